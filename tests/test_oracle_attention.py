@@ -1,0 +1,190 @@
+"""Pins of the oracle's packed layout and of its attention (Section 3.1, Eq. 1,
+over keys/values dequantized by Eq. 3).  CPU only."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import mixkvq_oracle as O
+
+
+def _f16(raw, off):
+    return float(np.frombuffer(raw[off:off + 2].tobytes(), dtype=np.float16)[0])
+
+
+def _u32(raw, off):
+    return int(np.frombuffer(raw[off:off + 4].tobytes(), dtype=np.uint32)[0])
+
+
+def brute_force_from_bytes(cfg, recs, res_k, res_v, n_res, q16, scale):
+    """Decode attention written as explicit Python loops that read the packed
+    block records bit by bit (layout as documented in block_layout) and apply
+    Eq. 3 and Eq. 1 in Python floats (binary64)."""
+    lay = O.block_layout(cfg)
+    P, nb, _ = recs.shape
+    out = np.zeros((cfg.B, cfg.Hq, cfg.D))
+    lse = np.zeros((cfg.B, cfg.Hq))
+    for p in range(P):
+        Kt, Vt = [], []
+        for blk in range(nb):
+            raw = recs[p, blk]
+            sel = [int(raw[lay.off_idx + i]) for i in range(cfg.ks)]
+            hi16, hi4 = sel[:cfg.k16], sel[cfg.k16:]
+            lo = [d for d in range(cfg.D) if d not in sel]
+            for t in range(cfg.R):
+                grp = t // cfg.Gk
+                krow = [0.0] * cfg.D
+                for i, d in enumerate(lo):
+                    w = _u32(raw, lay.off_klo + 4 * (t * lay.Wlo + i // 16))
+                    c = (w >> (2 * (i % 16))) & 3
+                    s = _f16(raw, lay.off_klo_s + 2 * (grp * lay.NLp + i))
+                    z = _f16(raw, lay.off_klo_z + 2 * (grp * lay.NLp + i))
+                    krow[d] = c * s + z
+                for i, d in enumerate(hi4):
+                    w = _u32(raw, lay.off_k4 + 4 * (t * lay.W4 + i // 8))
+                    c = (w >> (4 * (i % 8))) & 15
+                    s = _f16(raw, lay.off_k4_s + 2 * (grp * cfg.k4 + i))
+                    z = _f16(raw, lay.off_k4_z + 2 * (grp * cfg.k4 + i))
+                    krow[d] = c * s + z
+                for i, d in enumerate(hi16):
+                    krow[d] = _f16(raw, lay.off_k16 + 2 * (t * cfg.k16 + i))
+                vrow = [0.0] * cfg.D
+                for d in range(cfg.D):
+                    w = _u32(raw, lay.off_v + 4 * ((t // 16) * cfg.D + d))
+                    c = (w >> (2 * (t % 16))) & 3
+                    vg = d // cfg.Gv
+                    s = _f16(raw, lay.off_v_s + 2 * (t * lay.NVG + vg))
+                    z = _f16(raw, lay.off_v_z + 2 * (t * lay.NVG + vg))
+                    vrow[d] = c * s + z
+                Kt.append(krow)
+                Vt.append(vrow)
+        for t in range(n_res):
+            Kt.append([float(x) for x in res_k[p, t]])
+            Vt.append([float(x) for x in res_v[p, t]])
+        b, j = divmod(p, cfg.Hkv)
+        for hh in range(cfg.g):
+            h = j * cfg.g + hh
+            qv = [float(x) for x in q16[b, h]]
+            logits = [scale * sum(qv[d] * kr[d] for d in range(cfg.D)) for kr in Kt]
+            m = max(logits)
+            e = [math.exp(x - m) for x in logits]
+            l = sum(e)
+            for d in range(cfg.D):
+                out[b, h, d] = sum(e[t] * Vt[t][d] for t in range(len(Vt))) / l
+            lse[b, h] = m + math.log(l)
+    return out, lse
+
+
+def _tiny_cache(k4, k16, Gk=16, Gv=16, D=32, R=16, T=56, Hq=4, Hkv=2, B=2, seed=20, flush_mode=0):
+    rng = np.random.default_rng(seed)
+    cfg = O.OracleConfig(B=B, Hq=Hq, Hkv=Hkv, D=D, T_max=128, Gk=Gk, Gv=Gv, R=R, k4=k4, k16=k16,
+                         flush_mode=flush_mode)
+    K = (rng.standard_normal((B, Hkv, T, D)) * rng.uniform(0.5, 6, D)).astype(np.float16)
+    V = rng.standard_normal((B, Hkv, T, D)).astype(np.float16)
+    Qp = rng.standard_normal((B, Hq, 9, D)).astype(np.float16)
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    cache = O.OracleCache(cfg)
+    sel = cache.select_channels(Qp, K)
+    cache.append(K, V, sel)
+    return cfg, cache, K, V, q
+
+
+@pytest.mark.parametrize("k4,k16,Gk,Gv", [(8, 0, 16, 16), (0, 4, 8, 32), (8, 6, 16, 8), (0, 0, 16, 32)])
+def test_attention_equals_brute_force_over_packed_bytes(k4, k16, Gk, Gv):
+    cfg, cache, K, V, q = _tiny_cache(k4, k16, Gk, Gv)
+    assert cache.n_quant == 48 and cache.n_res == 8
+    out, lse = cache.decode_attention(q)
+    ref_out, ref_lse = brute_force_from_bytes(cfg, cache.packed_blocks(), cache.res_k, cache.res_v,
+                                              cache.n_res, q, 1.0 / math.sqrt(cfg.D))
+    assert np.allclose(out, ref_out, rtol=1e-11, atol=1e-12)
+    assert np.allclose(lse, ref_lse, rtol=1e-12, atol=1e-12)
+
+
+def _exact_attention(K, V, q, g, scale):
+    """softmax(q K^T / sqrt(D)) V on the fp16 inputs in binary64, via logsumexp."""
+    from scipy.special import logsumexp
+    B, Hq, D = q.shape
+    out = np.zeros((B, Hq, D))
+    lse = np.zeros((B, Hq))
+    for b in range(B):
+        for h in range(Hq):
+            kk = K[b, h // g].astype(np.float64)
+            x = kk @ q[b, h].astype(np.float64) * scale
+            lse[b, h] = logsumexp(x)
+            out[b, h] = np.exp(x - lse[b, h]) @ V[b, h // g].astype(np.float64)
+    return out, lse
+
+
+def test_everything_in_residual_window_is_exact_attention():
+    rng = np.random.default_rng(21)
+    cfg = O.OracleConfig(B=1, Hq=6, Hkv=2, D=32, T_max=64, Gk=16, Gv=16, R=32, k4=8, k16=0)
+    K = rng.standard_normal((1, 2, 32, 32)).astype(np.float16)
+    V = rng.standard_normal((1, 2, 32, 32)).astype(np.float16)
+    q = rng.standard_normal((1, 6, 32)).astype(np.float16)
+    cache = O.OracleCache(cfg)
+    cache.append(K, V)
+    assert cache.n_quant == 0 and cache.n_res == 32
+    out, lse = cache.decode_attention(q)
+    ro, rl = _exact_attention(K, V, q, 3, 1 / math.sqrt(32))
+    assert np.allclose(out, ro, rtol=1e-12, atol=1e-13) and np.allclose(lse, rl, rtol=1e-12)
+
+
+def test_full_fp16_channel_budget_gives_exact_logits():
+    """With every key channel in the fp16 tier the logits (hence lse) are those
+    of full-precision attention; the output differs only through 2-bit values."""
+    cfg, cache, K, V, q = _tiny_cache(k4=0, k16=32, T=64, flush_mode=1)
+    assert cache.n_res == 0
+    out, lse = cache.decode_attention(q)
+    _, rl = _exact_attention(K, V, q, cfg.g, 1 / math.sqrt(cfg.D))
+    assert np.allclose(lse, rl, rtol=1e-12, atol=1e-12)
+    # outputs: the same attention weights applied to the dequantized values
+    for p in range(cfg.B * cfg.Hkv):
+        _, Vh = cache.dequantized(p)
+        b, j = divmod(p, cfg.Hkv)
+        ro, _ = _exact_attention(K[b:b + 1, j:j + 1], Vh[None, None].astype(np.float64),
+                                 q[b:b + 1, j * cfg.g:(j + 1) * cfg.g], cfg.g, 1 / math.sqrt(cfg.D))
+        assert np.allclose(out[b, j * cfg.g:(j + 1) * cfg.g], ro[0], rtol=1e-11, atol=1e-12)
+
+
+def test_output_is_a_convex_combination_of_values():
+    cfg, cache, K, V, q = _tiny_cache(8, 0)
+    out, _ = cache.decode_attention(q)
+    for p in range(cfg.B * cfg.Hkv):
+        _, Vh = cache.dequantized(p)
+        b, j = divmod(p, cfg.Hkv)
+        o = out[b, j * cfg.g:(j + 1) * cfg.g]
+        assert np.all(o <= Vh.max(axis=0) + 1e-12) and np.all(o >= Vh.min(axis=0) - 1e-12)
+
+
+def test_split_softmax_merge_identity():
+    """Attention over token ranges merged by log-sum-exp weights equals attention
+    over the whole range (the identity the split-K GPU kernel relies on)."""
+    cfg, cache, K, V, q = _tiny_cache(8, 0, T=56)
+    out, lse = cache.decode_attention(q)
+    scale = 1 / math.sqrt(cfg.D)
+    for nsplit in (1, 2, 7):
+        for p in range(cfg.B * cfg.Hkv):
+            Kh, Vh = cache.dequantized(p)
+            b, j = divmod(p, cfg.Hkv)
+            for hh in range(cfg.g):
+                h = j * cfg.g + hh
+                bounds = np.linspace(0, Kh.shape[0], nsplit + 1).astype(int)
+                ms, ls, os_ = [], [], []
+                for a, e in zip(bounds[:-1], bounds[1:]):
+                    x = Kh[a:e] @ q[b, h].astype(np.float64) * scale
+                    m = x.max()
+                    w = np.exp(x - m)
+                    ms.append(m), ls.append(w.sum()), os_.append(w @ Vh[a:e])
+                M = max(ms)
+                L = sum(l * math.exp(m - M) for m, l in zip(ms, ls))
+                Ov = sum(o * math.exp(m - M) for m, o in zip(ms, os_)) / L
+                assert np.allclose(Ov, out[b, h], rtol=1e-11, atol=1e-13)
+                assert abs(M + math.log(L) - lse[b, h]) < 1e-11
+
+
+def test_accumulate_q_in_decode_adds_abs_query():
+    cfg, cache, K, V, q = _tiny_cache(8, 0)
+    before = cache.qacc.copy()
+    cache.decode_attention(q, accumulate_q=True)
+    add = np.abs(q.astype(np.float64)).reshape(cfg.B, cfg.Hkv, cfg.g, cfg.D).sum(axis=2) * 2.0 ** 24
+    assert np.array_equal((cache.qacc - before).astype(np.float64).reshape(cfg.B, cfg.Hkv, cfg.D), add)

@@ -1,0 +1,171 @@
+"""Pins of the oracle's cache state machine (Appendix D.1: residual buffer and
+lazy flush every R tokens) and of the closed forms used for reporting.  CPU only."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import mixkvq_oracle as O
+
+
+def _golden():
+    path = os.path.join(os.path.dirname(__file__), "golden", "paper_figures.txt")
+    vals = {}
+    for line in open(path):
+        line = line.split("#")[0].strip()
+        if "=" in line:
+            k, v = line.split("=")
+            vals[k.strip()] = float(v)
+    return vals
+
+
+def _cfg(R=16, flush_mode=0, **kw):
+    base = dict(B=1, Hq=2, Hkv=1, D=32, T_max=256, Gk=16, Gv=16, R=R, k4=8, k16=0, flush_mode=flush_mode)
+    base.update(kw)
+    return O.OracleConfig(**base)
+
+
+def _kv(rng, n, D=32):
+    return (rng.standard_normal((1, 1, n, D)).astype(np.float16),
+            rng.standard_normal((1, 1, n, D)).astype(np.float16))
+
+
+@pytest.mark.parametrize("n", [1, 15, 16, 17, 32, 33, 100, 128])
+def test_deferred_prefill_counts_closed_form(n):
+    """The newest <= R tokens stay in full precision: n_q = R (ceil(n/R) - 1)."""
+    rng = np.random.default_rng(30)
+    c = O.OracleCache(_cfg())
+    c.append(*_kv(rng, n))
+    assert c.n_quant == 16 * (-(-n // 16) - 1)
+    assert c.n_res == n - c.n_quant and 1 <= c.n_res <= 16
+    assert len(c.blocks[0]) == c.n_quant // 16
+
+
+def test_configured_prompts_leave_a_full_window():
+    for n, R, nq in ((1024, 32, 992), (32768, 128, 32640), (131072, 128, 130944)):
+        assert R * (-(-n // R) - 1) == nq
+
+
+@pytest.mark.parametrize("n", [1, 16, 17, 47, 48])
+def test_eager_counts(n):
+    rng = np.random.default_rng(31)
+    c = O.OracleCache(_cfg(flush_mode=1))
+    c.append(*_kv(rng, n))
+    assert c.n_quant == 16 * (n // 16) and c.n_res == n % 16
+
+
+@pytest.mark.parametrize("flush_mode", [0, 1])
+def test_one_by_one_equals_chunked(flush_mode):
+    rng = np.random.default_rng(32)
+    K, V = _kv(rng, 75)
+    Q = rng.standard_normal((1, 2, 11, 32)).astype(np.float16)
+    a = O.OracleCache(_cfg(flush_mode=flush_mode))
+    b = O.OracleCache(_cfg(flush_mode=flush_mode))
+    d = O.OracleCache(_cfg(flush_mode=flush_mode))
+    for c in (a, b, d):
+        c.accumulate_queries(Q)
+    a.append(K, V)
+    for t in range(75):
+        b.append(K[:, :, t:t + 1], V[:, :, t:t + 1])
+    for lo, hi in ((0, 5), (5, 40), (40, 41), (41, 75)):
+        d.append(K[:, :, lo:hi], V[:, :, lo:hi])
+    for c in (b, d):
+        assert (c.n_quant, c.n_res) == (a.n_quant, a.n_res)
+        assert np.array_equal(c.packed_blocks(), a.packed_blocks())
+        assert np.array_equal(c.res_k[:, :c.n_res], a.res_k[:, :a.n_res])
+        assert np.array_equal(c.res_v[:, :c.n_res], a.res_v[:, :a.n_res])
+
+
+def test_flush_rate_is_one_per_R_decode_steps():
+    """Appendix F: with R = 32 channel selection runs on 3.13 % (= 1/32) of decode steps."""
+    g = _golden()
+    rng = np.random.default_rng(33)
+    c = O.OracleCache(_cfg(R=32, Gk=32, T_max=32 * 40))
+    c.append(*_kv(rng, 32))
+    steps = 32 * 20
+    for _ in range(steps):
+        c.append(*_kv(rng, 1))
+    assert c.n_flush_calls * 32 == steps
+    assert abs(100.0 * c.n_flush_calls / steps - g["selection_call_rate_percent"]) <= 0.005 + 1e-9   # 3.125 printed as 3.13
+
+
+def test_each_decode_flush_reselects_from_running_accumulator():
+    rng = np.random.default_rng(34)
+    cfg = _cfg(R=16)
+    c = O.OracleCache(cfg)
+    K, V = _kv(rng, 16)
+    c.append(K, V)
+    q1 = np.zeros((1, 2, 32), dtype=np.float16)
+    q1[..., :8] = 1.0
+    c.decode_attention(q1, accumulate_q=True)
+    K2, V2 = _kv(rng, 16)
+    c.append(K2[:, :, :1], V2[:, :, :1])              # triggers the flush of the first block
+    assert c.blocks[0][0].sel.tolist() == list(range(8))
+    q2 = np.zeros((1, 2, 32), dtype=np.float16)
+    q2[..., 20:28] = 50.0
+    c.decode_attention(q2, accumulate_q=True)
+    c.append(K2[:, :, 1:], V2[:, :, 1:])
+    c.append(K[:, :, :1], V[:, :, :1])                # flush of the second block
+    assert c.blocks[0][1].sel.tolist() == list(range(20, 28))
+
+
+def test_windowed_accumulator_resets_on_flush():
+    rng = np.random.default_rng(35)
+    c = O.OracleCache(_cfg(R=16, qacc_reset_on_flush=1))
+    c.accumulate_queries(rng.standard_normal((1, 2, 4, 32)).astype(np.float16))
+    c.append(*_kv(rng, 16))
+    assert c.qacc.any()
+    c.append(*_kv(rng, 1))
+    assert not c.qacc.any() and not c.qcnt.any()
+
+
+def test_capacity_overflow_raises_and_leaves_cache_unchanged():
+    rng = np.random.default_rng(36)
+    c = O.OracleCache(_cfg(T_max=32))
+    c.append(*_kv(rng, 48))
+    assert c.n_quant == 32
+    with pytest.raises(OverflowError):
+        c.append(*_kv(rng, 17))
+    assert c.n_quant == 32 and c.n_res == 16
+
+
+def test_record_layout_closed_form():
+    cfg = O.OracleConfig(B=8, Hq=28, Hkv=4, D=128, T_max=32768, Gk=128, Gv=128, R=128, k4=16, k16=0)
+    lay = O.block_layout(cfg)
+    assert (lay.NL, lay.Wlo, lay.W4, lay.NG, lay.NVG) == (112, 7, 2, 1, 1)
+    # no padding in this configuration: the record is exactly the algorithmic bytes of 128 tokens
+    assert lay.rec_bytes == 9744
+    assert lay.rec_bytes * 255 + 128 * 128 * 4 + 7 * 128 * 4 == O.algorithmic_bytes_per_pair(cfg, 32640, 128)
+    for name in ("off_idx", "off_klo_s", "off_klo_z", "off_k4_s", "off_k4_z", "off_klo", "off_k4", "off_k16",
+                 "off_v", "off_v_s", "off_v_z"):
+        assert getattr(lay, name) % 16 == 0
+
+
+def test_algorithmic_bytes_per_configuration():
+    mk = lambda **kw: O.OracleConfig(T_max=1 << 20, **kw)
+    c0 = mk(B=1, Hq=1, Hkv=1, D=128, Gk=32, Gv=32, R=32, k4=8, k16=0)
+    c1 = mk(B=8, Hq=28, Hkv=4, D=128, Gk=128, Gv=128, R=128, k4=16, k16=0)
+    c2 = mk(B=64, Hq=40, Hkv=8, D=128, Gk=128, Gv=128, R=128, k4=0, k16=12)
+    c3 = mk(B=4, Hq=40, Hkv=8, D=128, Gk=128, Gv=128, R=128, k4=16, k16=0)
+    assert O.algorithmic_bytes_per_pair(c0, 992, 32) == 114360
+    assert O.algorithmic_bytes_per_pair(c1, 32640, 128) == 2553840
+    assert O.algorithmic_bytes_per_pair(c2, 32640, 128) == 3094436
+    assert O.algorithmic_bytes_per_pair(c3, 130944, 128) == 10036208
+
+
+def test_effective_bits_closed_form():
+    """Appendix C: B_eff = mean of b_i over the key channels, b_i in {16, 4, 2}."""
+    g = _golden()
+    assert O.effective_key_bits(128, 0, 16) == 2.25
+    assert O.effective_key_bits(128, 12, 0) == 3.3125
+    assert O.effective_key_bits(128, 0, 8) == 2.125
+    assert O.effective_key_bits(128, 128, 0) == 16 and O.effective_key_bits(128, 0, 0) == 2
+    # "16-bit -> 3.4-bit" saving
+    assert 100 * (1 - g["effective_bits_r1_qwen_7b"] / 16) > g["memory_saving_percent_floor"]
+
+
+def test_fp16_footprint_example_of_the_introduction():
+    g = _golden()
+    total = (g["kv_example_layers"] * g["kv_example_batch"] * g["kv_example_kv_heads"] * g["kv_example_tokens"]
+             * g["kv_example_head_dim"] * 2 * 2)
+    assert total / 2 ** 30 == g["kv_fp16_footprint_gb"]
