@@ -1,0 +1,141 @@
+/*
+ * libmixkvq: decode-time attention over a mixed-precision quantized KV cache
+ * (MixKVQ) for AMD MI355X (gfx950).  C ABI; no C++ or torch types cross it.
+ *
+ * Conventions for every call
+ *   - Returns MIXKVQ_OK (0) or a negative MIXKVQ_E* code; nothing throws or aborts
+ *     across this boundary.  On an error return the cache is unchanged.
+ *   - Pointers marked DEVICE are HIP device pointers owned by the caller (for
+ *     example torch allocations); pointers marked HOST are ordinary host memory.
+ *     The library allocates only the small host-side handle.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *     device work is enqueued asynchronously on it; no call synchronises or reads
+ *     device memory back.  Token counts depend only on the sequence of n_new
+ *     values, so the host-side state is exact without a read-back.
+ *   - All sequences of a batch advance in lock-step (same token count).
+ *   - Grouped-query mapping: query heads [j*g, (j+1)*g) use KV head j, g = Hq/Hkv.
+ *   - fp16 tensors are IEEE binary16; Inf/NaN inputs are outside the contract.
+ *   - Calls on one cache must be issued from one host thread at a time.
+ */
+#ifndef MIXKVQ_H
+#define MIXKVQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MIXKVQ_OK          0
+#define MIXKVQ_EINVAL    (-1)  /* bad shape, alignment, NULL pointer or unsupported configuration */
+#define MIXKVQ_ECAPACITY (-2)  /* the append would exceed T_max quantized tokens */
+#define MIXKVQ_EHIP      (-3)  /* a HIP call failed; mixkvq_strerror gives the HIP message */
+#define MIXKVQ_ENOMEM    (-4)  /* host allocation of the handle failed */
+#define MIXKVQ_EEMPTY    (-5)  /* decode attention on a cache that holds no token */
+
+typedef struct mixkvq_cache mixkvq_cache; /* opaque HOST handle: counts + the caller's device pointers */
+
+/* Caller-filled plain data.  Symbols follow the paper: R = residual length
+ * (Appendix D.1), G = group size (Section 5, "Settings"). */
+typedef struct {
+  int32_t B, Hq, Hkv;   /* batch, query heads, KV heads; Hq % Hkv == 0, Hq/Hkv <= 8 */
+  int32_t D;            /* head dimension; must be 128 */
+  int32_t T_max;        /* capacity of the quantized part in tokens; multiple of R */
+  int32_t Gk;           /* key group: Gk consecutive tokens of one channel; R % Gk == 0, Gk % 16 == 0 */
+  int32_t Gv;           /* value group: Gv consecutive channels of one token; D % Gv == 0, Gv % 16 == 0 */
+  int32_t R;            /* residual window length == flush unit; multiple of 16, <= 128 */
+  int32_t k4, k16;      /* salient key channels kept at 4 bit / as fp16; k4 % 8 == 0, k16 % 4 == 0, k4+k16 < D */
+  int32_t flush_mode;   /* 0 deferred: the newest <= R tokens stay fp16; 1 eager: flush as soon as R are buffered */
+  int32_t score_mode;   /* 0: A_d = I_d * S_d (Eq. 8); 1: A_d = S_d (error-only ablation) */
+  int32_t qacc_reset_on_flush; /* 0: |q| accumulator runs since sequence start; 1: cleared by every call that flushes */
+} mixkvq_config;
+
+/* Bytes of each caller-owned device buffer. */
+typedef struct {
+  uint64_t blocks;     /* [B*Hkv][T_max/R] block records, see mixkvq_block_layout */
+  uint64_t res_k;      /* [B*Hkv][R][D] fp16 residual keys   */
+  uint64_t res_v;      /* [B*Hkv][R][D] fp16 residual values */
+  uint64_t qacc;       /* [B*Hkv][D] u64 sums of |q| in units of 2^-24, then [B*Hkv] u64 counts */
+  uint64_t workspace;  /* split-K partials and selection scratch */
+} mixkvq_sizes;
+
+typedef struct {
+  void *blocks, *res_k, *res_v, *qacc, *workspace; /* DEVICE, 256-byte aligned */
+} mixkvq_buffers;
+
+/* Byte offsets of the planes inside one block record (R tokens of one
+ * (batch, KV head) pair).  Every plane starts on a 16-byte boundary, padding is 0.
+ *   idx    u8  [k16+k4]      fp16-tier channels ascending, then 4-bit-tier channels ascending
+ *   klo_s  f16 [NG][NLp]     scales of the 2-bit key channels (the non-salient channels, ascending)
+ *   klo_z  f16 [NG][NLp]     zero-points (group minima, Eq. 2)
+ *   k4_s   f16 [NG][k4]      4-bit tier scales, tier order;  k4_z likewise
+ *   klo    u32 [R][Wlo]      16 two-bit codes per word along channels, code i in bits [2i, 2i+2)
+ *   k4     u32 [R][k4/8]     8 four-bit codes per word, code i in bits [4i, 4i+4)
+ *   k16    f16 [R][k16]      raw values of the fp16 tier
+ *   v      u32 [R/16][D]     16 two-bit codes per word along TOKENS for one channel
+ *   v_s    f16 [R][D/Gv]     value scales per (token, channel group);  v_z likewise
+ * NL = D-k4-k16, Wlo = ceil(NL/16), NLp = 16*Wlo, NG = R/Gk, NVG = D/Gv, W4 = k4/8. */
+typedef struct {
+  int32_t NL, Wlo, NLp, NG, NVG, W4;
+  int32_t off_idx, off_klo_s, off_klo_z, off_k4_s, off_k4_z, off_klo, off_k4, off_k16, off_v, off_v_s, off_v_z;
+  int32_t rec_bytes;
+} mixkvq_block_layout_t;
+
+/* Validates cfg and fills the record layout.  HOST pointers.  EINVAL on a bad configuration. */
+int mixkvq_block_layout(const mixkvq_config* cfg, mixkvq_block_layout_t* out);
+
+/* Sizes of the five device buffers for cfg.  HOST pointers. */
+int mixkvq_cache_sizes(const mixkvq_config* cfg, mixkvq_sizes* out);
+
+/* Creates the host handle over caller-owned device buffers (each at least as large as
+ * mixkvq_cache_sizes says, 256-byte aligned).  The cache starts empty; call
+ * mixkvq_cache_reset once before first use to clear the |q| accumulator. */
+int mixkvq_cache_create(const mixkvq_config* cfg, const mixkvq_buffers* bufs, mixkvq_cache** out);
+void mixkvq_cache_destroy(mixkvq_cache* c);
+
+/* Empties the cache (token counts to 0) and zeroes the |q| accumulator on `stream`. */
+int mixkvq_cache_reset(mixkvq_cache* c, void* stream);
+
+/* Host-only: quantized and residual token counts.  Either out pointer may be NULL. */
+int mixkvq_cache_state(const mixkvq_cache* c, int64_t* n_quantized, int32_t* n_residual);
+
+/* Channel selection (Section 4.2, Eq. 6-8, with a top-k channel budget instead of thresholds).
+ *   q  DEVICE fp16 [B][Hq][Lq][D] after rotary embedding, element strides q_strides = {batch, head, token},
+ *      channel stride 1; may be NULL with Lq = 0 (use the running accumulator only).
+ *   k  DEVICE fp16 [B][Hkv][L][D] after rotary embedding, strides k_strides likewise; L >= 1.
+ * Adds sum|q| over the Lq tokens and over the g query heads of each KV head into the cache's accumulator
+ * (Eq. 6; Appendix D), takes max-min of every key channel over the L tokens (Eq. 7), scores
+ * A_d = sum|q|_d * range_d (Eq. 8 up to constants shared by the head), and writes the k16+k4 best
+ * channels per (b, KV head) to sel DEVICE u8 [B][Hkv][k16+k4]: first the k16 best, ascending, then the
+ * next k4, ascending.  Ties go to the lower channel index.  The token counts are unchanged. */
+int mixkvq_select_channels(mixkvq_cache* c, const void* q, int32_t Lq, const int64_t q_strides[3],
+                           const void* k, int32_t L, const int64_t k_strides[3],
+                           uint8_t* sel, void* stream);
+
+/* Prefill (n_new = prompt length) and per-step (n_new = 1) append (Appendix D.1).
+ *   k_new, v_new  DEVICE fp16 [B][Hkv][n_new][D], element strides kv_strides = {batch, head, token}.
+ *   sel           DEVICE u8 [B][Hkv][k16+k4] or NULL.
+ * Tokens enter the fp16 residual window; whole R-token blocks leave it per flush_mode and are quantized
+ * (Eq. 2: keys per channel in groups of Gk tokens, 2 bit, the selected channels at 4 bit or fp16; values per
+ * token in groups of Gv channels, 2 bit) into block records.  With sel != NULL every block flushed by this
+ * call uses that selection; with sel == NULL each block is scored from the accumulator and its own R tokens.
+ * ECAPACITY if the quantized part would exceed T_max. */
+int mixkvq_quantize_append(mixkvq_cache* c, const void* k_new, const void* v_new, int32_t n_new,
+                           const int64_t kv_strides[3], const uint8_t* sel, void* stream);
+
+/* One query token per sequence (Section 3.1, Eq. 1, over keys/values dequantized by Eq. 3).
+ *   q    DEVICE fp16 [B][Hq][D] contiguous;  out DEVICE fp16 [B][Hq][D];  lse DEVICE fp32 [B][Hq] or NULL
+ *        (natural-log sum of exp of the scaled logits).
+ *   scale <= 0 means 1/sqrt(D).  accumulate_q != 0 also adds |q| to the accumulator (Appendix D.2).
+ * EEMPTY if the cache holds no token. */
+int mixkvq_decode_attention(mixkvq_cache* c, const void* q, void* out, float* lse,
+                            float scale, int32_t accumulate_q, void* stream);
+
+/* Message for a return code (for EHIP: the last HIP error string seen by this thread). */
+const char* mixkvq_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MIXKVQ_H */

@@ -69,14 +69,14 @@ class OracleConfig:
 def group_params(x16: np.ndarray, bits: int, axis: int):
     """Scale and zero-point of Eq. 2-3 for groups laid along `axis`.
 
-    z = min(X) (stored as fp16; -0 canonicalised to +0),
+    z = min(X) (stored as fp16; a -0 minimum or maximum is taken as +0),
     s = (max(X) - min(X)) / (2^B - 1): binary32 subtract, binary32 divide,
     then round-to-nearest-even to fp16 (the stored value)."""
     assert x16.dtype == np.float16
-    mn = x16.min(axis=axis)
-    mx = x16.max(axis=axis)
-    z16 = (mn.astype(np.float32) + np.float32(0.0)).astype(np.float16)
-    d32 = mx.astype(np.float32) - mn.astype(np.float32)
+    mn = x16.min(axis=axis).astype(np.float32) + np.float32(0.0)   # "+ 0" turns -0 into +0
+    mx = x16.max(axis=axis).astype(np.float32) + np.float32(0.0)
+    z16 = mn.astype(np.float16)
+    d32 = mx - mn
     s32 = d32 / np.float32((1 << bits) - 1)
     s16 = s32.astype(np.float16)
     return s16, z16

@@ -1,0 +1,237 @@
+// Host side of libmixkvq: configuration checks, the block-record layout, the
+// cache state machine (residual window and lazy flush of Appendix D.1) and the
+// C ABI.  All device work is enqueued by the launchers in the kernel files.
+#include <new>
+#include <string.h>
+#include "mixkvq_internal.h"
+
+namespace mixkvq {
+
+static thread_local char g_hip_msg[256] = "no HIP error recorded";
+
+static int hip_fail(hipError_t e) {
+  snprintf(g_hip_msg, sizeof(g_hip_msg), "HIP error %d: %s", (int)e, hipGetErrorString(e));
+  (void)hipGetLastError();
+  return MIXKVQ_EHIP;
+}
+#define MIXKVQ_TRY_HIP(expr)                          \
+  do {                                                \
+    hipError_t e__ = (expr);                          \
+    if (e__ != hipSuccess) return hip_fail(e__);      \
+  } while (0)
+
+static inline int al16(int n) { return (n + 15) / 16 * 16; }
+
+int compute_layout(const mixkvq_config& c, Layout* out) {
+  if (c.B < 1 || c.Hq < 1 || c.Hkv < 1 || c.Hq % c.Hkv != 0) return MIXKVQ_EINVAL;
+  if (c.Hq / c.Hkv > 8) return MIXKVQ_EINVAL;
+  if (c.D != kD) return MIXKVQ_EINVAL;
+  if (c.R < 16 || c.R > kMaxR || c.R % 16 != 0) return MIXKVQ_EINVAL;
+  if (c.Gk < 16 || c.Gk % 16 != 0 || c.R % c.Gk != 0) return MIXKVQ_EINVAL;
+  if (c.Gv < 16 || c.Gv % 16 != 0 || c.D % c.Gv != 0) return MIXKVQ_EINVAL;
+  if (c.k4 < 0 || c.k16 < 0 || c.k4 % 8 != 0 || c.k16 % 4 != 0 || c.k4 + c.k16 >= c.D) return MIXKVQ_EINVAL;
+  if (c.T_max < c.R || c.T_max % c.R != 0) return MIXKVQ_EINVAL;
+  if (c.flush_mode < 0 || c.flush_mode > 1 || c.score_mode < 0 || c.score_mode > 1) return MIXKVQ_EINVAL;
+  if ((int64_t)c.B * c.Hkv > (1 << 20)) return MIXKVQ_EINVAL;
+  Layout l;
+  memset(&l, 0, sizeof(l));
+  const int ks = c.k4 + c.k16;
+  l.NL = c.D - ks;
+  l.Wlo = (l.NL + 15) / 16;
+  l.NLp = 16 * l.Wlo;
+  l.NG = c.R / c.Gk;
+  l.NVG = c.D / c.Gv;
+  l.W4 = c.k4 / 8;
+  int off = 0;
+  auto plane = [&](int32_t* dst, int bytes) { *dst = off; off += al16(bytes); };
+  plane(&l.off_idx, ks);
+  plane(&l.off_klo_s, l.NG * l.NLp * 2);
+  plane(&l.off_klo_z, l.NG * l.NLp * 2);
+  plane(&l.off_k4_s, l.NG * c.k4 * 2);
+  plane(&l.off_k4_z, l.NG * c.k4 * 2);
+  plane(&l.off_klo, c.R * l.Wlo * 4);
+  plane(&l.off_k4, c.R * l.W4 * 4);
+  plane(&l.off_k16, c.R * c.k16 * 2);
+  plane(&l.off_v, (c.R / 16) * c.D * 4);
+  plane(&l.off_v_s, c.R * l.NVG * 2);
+  plane(&l.off_v_z, c.R * l.NVG * 2);
+  l.rec_bytes = off;
+  if (l.rec_bytes > kMaxRec) return MIXKVQ_EINVAL;
+  *out = l;
+  return MIXKVQ_OK;
+}
+
+int max_splits_for(int P) {
+  int s = (kSplitTargetWGs + P - 1) / P;
+  if (s < 1) s = 1;
+  if (s > kMaxSplits) s = kMaxSplits;
+  return s;
+}
+
+static inline uint64_t al256(uint64_t n) { return (n + 255) / 256 * 256; }
+
+}  // namespace mixkvq
+
+using namespace mixkvq;
+
+struct mixkvq_cache {
+  CacheView v;
+  int64_t n_quant;
+  int32_t n_res;
+};
+
+extern "C" {
+
+int mixkvq_block_layout(const mixkvq_config* cfg, mixkvq_block_layout_t* out) {
+  if (!cfg || !out) return MIXKVQ_EINVAL;
+  Layout l;
+  int rc = compute_layout(*cfg, &l);
+  if (rc != MIXKVQ_OK) return rc;
+  *out = l;
+  return MIXKVQ_OK;
+}
+
+int mixkvq_cache_sizes(const mixkvq_config* cfg, mixkvq_sizes* out) {
+  if (!cfg || !out) return MIXKVQ_EINVAL;
+  Layout l;
+  int rc = compute_layout(*cfg, &l);
+  if (rc != MIXKVQ_OK) return rc;
+  const uint64_t P = (uint64_t)cfg->B * cfg->Hkv;
+  out->blocks = al256(P * (uint64_t)(cfg->T_max / cfg->R) * (uint64_t)l.rec_bytes);
+  out->res_k = al256(P * (uint64_t)cfg->R * cfg->D * 2);
+  out->res_v = out->res_k;
+  out->qacc = al256(P * (uint64_t)(cfg->D + 1) * 8);
+  uint64_t a = decode_workspace_bytes(*cfg), b = select_workspace_bytes(*cfg);
+  out->workspace = al256(a > b ? a : b);
+  return MIXKVQ_OK;
+}
+
+int mixkvq_cache_create(const mixkvq_config* cfg, const mixkvq_buffers* bufs, mixkvq_cache** out) {
+  if (!cfg || !bufs || !out) return MIXKVQ_EINVAL;
+  Layout l;
+  int rc = compute_layout(*cfg, &l);
+  if (rc != MIXKVQ_OK) return rc;
+  const void* ptrs[5] = {bufs->blocks, bufs->res_k, bufs->res_v, bufs->qacc, bufs->workspace};
+  for (const void* p : ptrs)
+    if (!p || ((uintptr_t)p & 255u)) return MIXKVQ_EINVAL;
+  mixkvq_cache* c = new (std::nothrow) mixkvq_cache;
+  if (!c) return MIXKVQ_ENOMEM;
+  c->v.cfg = *cfg;
+  c->v.lay = l;
+  c->v.P = cfg->B * cfg->Hkv;
+  c->v.g = cfg->Hq / cfg->Hkv;
+  c->v.NB = cfg->T_max / cfg->R;
+  c->v.blocks = (uint8_t*)bufs->blocks;
+  c->v.res_k = (__half*)bufs->res_k;
+  c->v.res_v = (__half*)bufs->res_v;
+  c->v.qacc = (unsigned long long*)bufs->qacc;
+  c->v.qcnt = c->v.qacc + (size_t)c->v.P * cfg->D;
+  c->v.ws = (uint8_t*)bufs->workspace;
+  c->n_quant = 0;
+  c->n_res = 0;
+  *out = c;
+  return MIXKVQ_OK;
+}
+
+void mixkvq_cache_destroy(mixkvq_cache* c) { delete c; }
+
+int mixkvq_cache_reset(mixkvq_cache* c, void* stream) {
+  if (!c) return MIXKVQ_EINVAL;
+  MIXKVQ_TRY_HIP(launch_zero_qacc(c->v, (hipStream_t)stream));
+  c->n_quant = 0;
+  c->n_res = 0;
+  return MIXKVQ_OK;
+}
+
+int mixkvq_cache_state(const mixkvq_cache* c, int64_t* n_quantized, int32_t* n_residual) {
+  if (!c) return MIXKVQ_EINVAL;
+  if (n_quantized) *n_quantized = c->n_quant;
+  if (n_residual) *n_residual = c->n_res;
+  return MIXKVQ_OK;
+}
+
+int mixkvq_select_channels(mixkvq_cache* c, const void* q, int32_t Lq, const int64_t q_strides[3],
+                           const void* k, int32_t L, const int64_t k_strides[3], uint8_t* sel, void* stream) {
+  if (!c || !k || !k_strides || !sel || L < 1 || Lq < 0) return MIXKVQ_EINVAL;
+  if (Lq > 0 && (!q || !q_strides)) return MIXKVQ_EINVAL;
+  if (c->v.cfg.k4 + c->v.cfg.k16 == 0) return MIXKVQ_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  if (Lq > 0) {
+    Strides3 qs{q_strides[0], q_strides[1], q_strides[2]};
+    MIXKVQ_TRY_HIP(launch_qabs_accumulate(c->v, (const __half*)q, Lq, qs, s));
+  }
+  Strides3 ks{k_strides[0], k_strides[1], k_strides[2]};
+  MIXKVQ_TRY_HIP(launch_select(c->v, (const __half*)k, L, ks, sel, s));
+  return MIXKVQ_OK;
+}
+
+int mixkvq_quantize_append(mixkvq_cache* c, const void* k_new, const void* v_new, int32_t n_new,
+                           const int64_t kv_strides[3], const uint8_t* sel, void* stream) {
+  if (!c || n_new < 0) return MIXKVQ_EINVAL;
+  if (n_new == 0) return MIXKVQ_OK;
+  if (!k_new || !v_new || !kv_strides) return MIXKVQ_EINVAL;
+  // rows are moved with 16-byte accesses
+  if (((uintptr_t)k_new & 15u) || ((uintptr_t)v_new & 15u)) return MIXKVQ_EINVAL;
+  for (int i = 0; i < 3; ++i)
+    if (kv_strides[i] % 8 != 0) return MIXKVQ_EINVAL;
+  const mixkvq_config& cfg = c->v.cfg;
+  const int R = cfg.R;
+  const int64_t total = (int64_t)c->n_res + n_new;
+  // Deferred: a full window is flushed just before the next token enters, so 1..R tokens remain.
+  // Eager: a window is flushed as soon as it is full, so 0..R-1 tokens remain.
+  int64_t F = cfg.flush_mode == 0 ? (total + R - 1) / R - 1 : total / R;
+  if (F < 0) F = 0;
+  if (c->n_quant + F * R > cfg.T_max) return MIXKVQ_ECAPACITY;
+  if (F > (1 << 24)) return MIXKVQ_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  Strides3 kvs{kv_strides[0], kv_strides[1], kv_strides[2]};
+  const int r0 = c->n_res;
+  if (F > 0) {
+    MIXKVQ_TRY_HIP(launch_flush(c->v, (const __half*)k_new, (const __half*)v_new, kvs, r0,
+                                (int)(c->n_quant / R), (int)F, sel, s));
+  }
+  // Tokens that stay in the window.  Stream position x of (old residual ++ new tokens) maps to
+  // new-token index x - r0; after F flushes positions [F*R, total) remain.
+  const int64_t rest_first = F * R;
+  const int n_rest = (int)(total - rest_first);
+  if (F == 0) {
+    MIXKVQ_TRY_HIP(launch_residual_copy(c->v, (const __half*)k_new, (const __half*)v_new, kvs, 0, r0, n_new, s));
+  } else if (n_rest > 0) {
+    MIXKVQ_TRY_HIP(launch_residual_copy(c->v, (const __half*)k_new, (const __half*)v_new, kvs,
+                                        (int)(rest_first - r0), 0, n_rest, s));
+  }
+  if (F > 0 && cfg.qacc_reset_on_flush) MIXKVQ_TRY_HIP(launch_zero_qacc(c->v, s));
+  c->n_quant += F * R;
+  c->n_res = n_rest;
+  return MIXKVQ_OK;
+}
+
+int mixkvq_decode_attention(mixkvq_cache* c, const void* q, void* out, float* lse, float scale,
+                            int32_t accumulate_q, void* stream) {
+  if (!c || !q || !out) return MIXKVQ_EINVAL;
+  if (c->n_quant == 0 && c->n_res == 0) return MIXKVQ_EEMPTY;
+  const mixkvq_config& cfg = c->v.cfg;
+  hipStream_t s = (hipStream_t)stream;
+  if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)cfg.D);
+  if (accumulate_q) {
+    Strides3 qs{(int64_t)cfg.Hq * cfg.D, (int64_t)cfg.D, (int64_t)cfg.D};
+    MIXKVQ_TRY_HIP(launch_qabs_accumulate(c->v, (const __half*)q, 1, qs, s));
+  }
+  MIXKVQ_TRY_HIP(launch_decode(c->v, (const __half*)q, (__half*)out, lse, scale, (int)(c->n_quant / cfg.R),
+                               c->n_res, s));
+  return MIXKVQ_OK;
+}
+
+const char* mixkvq_strerror(int code) {
+  switch (code) {
+    case MIXKVQ_OK: return "ok";
+    case MIXKVQ_EINVAL: return "invalid argument or unsupported configuration";
+    case MIXKVQ_ECAPACITY: return "append would exceed the cache capacity T_max";
+    case MIXKVQ_EHIP: return mixkvq::g_hip_msg;
+    case MIXKVQ_ENOMEM: return "host allocation failed";
+    case MIXKVQ_EEMPTY: return "the cache holds no token";
+    default: return "unknown mixkvq error code";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,221 @@
+// Split-K decode attention over the mixed-precision cache (Section 3.1, Eq. 1, with
+// keys and values dequantized on the fly by Eq. 3) and the log-sum-exp merge of the
+// splits.
+#include "mixkvq_internal.h"
+
+namespace mixkvq {
+
+constexpr int kDecThreads = 256;
+constexpr int kMaxG = 8;
+constexpr int kPartStride = kD + 2;   // floats per (split, head): O[D], m, l
+
+size_t decode_workspace_bytes(const mixkvq_config& c) {
+  const int P = c.B * c.Hkv;
+  return (size_t)P * max_splits_for(P) * (c.Hq / c.Hkv) * kPartStride * sizeof(float);
+}
+
+// ---------------------------------------------------------------------------
+// Reference-grade split kernel: plain vector ALU, one workgroup per (pair, split).
+// Threads play two roles per block of R tokens: (token, head-half) for q.K and the
+// softmax update, (channel, head-half) for P.V.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kDecThreads)
+decode_split_kernel(CacheView cv, const __half* __restrict__ q, float scale, int n_blocks, int n_res, int n_splits,
+                    float* __restrict__ part) {
+  __shared__ __align__(16) unsigned char sRec[kMaxRec];
+  __shared__ float sQ[kMaxG][kD];
+  __shared__ float sP[kMaxG][kMaxR];
+  __shared__ float sM[kMaxG], sL[kMaxG], sAlpha[kMaxG];
+  __shared__ unsigned char sLoList[kD];
+  __shared__ unsigned char sIsHi[kD];
+
+  const mixkvq_config& cfg = cv.cfg;
+  const Layout& lay = cv.lay;
+  const int R = cfg.R, Gk = cfg.Gk, Gv = cfg.Gv, k4 = cfg.k4, k16 = cfg.k16, ks = k4 + k16, g = cv.g;
+  const int p = blockIdx.x, split = blockIdx.y, tid = threadIdx.x;
+  const int b = p / cfg.Hkv, j = p % cfg.Hkv;
+  const int lane_lo = tid & (kD - 1), half = tid >> 7;   // role index and head half
+  const int h0 = half * 4;                               // heads h0 .. h0+3 (< g)
+
+  for (int i = tid; i < g * kD; i += kDecThreads)
+    sQ[i / kD][i % kD] = __half2float(q[((size_t)b * cfg.Hq + (size_t)j * g) * kD + i]);
+  if (tid < kMaxG) { sM[tid] = -INFINITY; sL[tid] = 0.f; }
+
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};   // O[h0+i][channel lane_lo]
+
+  const int blk0 = (int)((long long)n_blocks * split / n_splits);
+  const int blk1 = (int)((long long)n_blocks * (split + 1) / n_splits);
+  const bool owns_res = (split == n_splits - 1) && n_res > 0;
+  const int n_iter = (blk1 - blk0) + (owns_res ? 1 : 0);
+
+  for (int it = 0; it < n_iter; ++it) {
+    const bool is_res = it == blk1 - blk0;
+    const int nt = is_res ? n_res : R;
+    __syncthreads();
+    const uint8_t* rec = cv.blocks + ((size_t)p * cv.NB + blk0 + it) * lay.rec_bytes;
+    if (!is_res) {
+      for (int i = tid; i < lay.rec_bytes / 16; i += kDecThreads)
+        reinterpret_cast<uint4*>(sRec)[i] = reinterpret_cast<const uint4*>(rec)[i];
+      if (tid < kD) sIsHi[tid] = 0;
+      __syncthreads();
+      if (tid < ks) sIsHi[sRec[lay.off_idx + tid]] = 1;
+      __syncthreads();
+      if (tid < kD && !sIsHi[tid]) {
+        int pos = 0;
+        for (int e = 0; e < tid; ++e) pos += !sIsHi[e];
+        sLoList[pos] = (unsigned char)tid;
+      }
+      __syncthreads();
+    }
+
+    // ---- logits: thread (token t = lane_lo, heads h0..h0+3) ----
+    if (lane_lo < nt && h0 < g) {
+      const int t = lane_lo;
+      float s[4] = {0.f, 0.f, 0.f, 0.f};
+      if (is_res) {
+        const __half* row = cv.res_k + ((size_t)p * R + t) * kD;
+        for (int d = 0; d < kD; ++d) {
+          const float kv = __half2float(row[d]);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) s[i] += sQ[(h0 + i) & 7][d] * kv;
+        }
+      } else {
+        const int grp = t / Gk;
+        const unsigned* klo = reinterpret_cast<const unsigned*>(sRec + lay.off_klo) + t * lay.Wlo;
+        const __half* ls = reinterpret_cast<const __half*>(sRec + lay.off_klo_s) + grp * lay.NLp;
+        const __half* lz = reinterpret_cast<const __half*>(sRec + lay.off_klo_z) + grp * lay.NLp;
+        for (int jj = 0; jj < lay.NL; ++jj) {
+          const unsigned c = (klo[jj >> 4] >> (2 * (jj & 15))) & 3u;
+          const float kv = (float)c * __half2float(ls[jj]) + __half2float(lz[jj]);
+          const int d = sLoList[jj];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) s[i] += sQ[(h0 + i) & 7][d] * kv;
+        }
+        const unsigned* k4w = reinterpret_cast<const unsigned*>(sRec + lay.off_k4) + t * lay.W4;
+        const __half* hs = reinterpret_cast<const __half*>(sRec + lay.off_k4_s) + grp * k4;
+        const __half* hz = reinterpret_cast<const __half*>(sRec + lay.off_k4_z) + grp * k4;
+        for (int jj = 0; jj < k4; ++jj) {
+          const unsigned c = (k4w[jj >> 3] >> (4 * (jj & 7))) & 15u;
+          const float kv = (float)c * __half2float(hs[jj]) + __half2float(hz[jj]);
+          const int d = sRec[lay.off_idx + k16 + jj];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) s[i] += sQ[(h0 + i) & 7][d] * kv;
+        }
+        const __half* k16p = reinterpret_cast<const __half*>(sRec + lay.off_k16) + t * k16;
+        for (int jj = 0; jj < k16; ++jj) {
+          const float kv = __half2float(k16p[jj]);
+          const int d = sRec[lay.off_idx + jj];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) s[i] += sQ[(h0 + i) & 7][d] * kv;
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (h0 + i < g) sP[h0 + i][t] = s[i] * scale;
+    }
+    __syncthreads();
+
+    // ---- online softmax: wave w owns heads w and w+4 ----
+    {
+      const int wave = tid >> 6, lane = tid & 63;
+      for (int h = wave; h < g; h += 4) {
+        float x0 = lane < nt ? sP[h][lane] : -INFINITY;
+        float x1 = lane + 64 < nt ? sP[h][lane + 64] : -INFINITY;
+        float mx = fmaxf(x0, x1);
+        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+        const float m_old = sM[h];
+        const float m_new = fmaxf(m_old, mx);
+        const float e0 = lane < nt ? __expf(x0 - m_new) : 0.f;
+        const float e1 = lane + 64 < nt ? __expf(x1 - m_new) : 0.f;
+        float sum = e0 + e1;
+        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+        if (lane < nt) sP[h][lane] = e0;
+        if (lane + 64 < nt) sP[h][lane + 64] = e1;
+        if (lane == 0) {
+          const float alpha = __expf(m_old - m_new);   // exp(-inf) = 0 on the first block
+          sAlpha[h] = alpha;
+          sM[h] = m_new;
+          sL[h] = sL[h] * alpha + sum;
+        }
+      }
+    }
+    __syncthreads();
+
+    // ---- P.V: thread (channel d = lane_lo, heads h0..h0+3) ----
+    if (h0 < g) {
+      const int d = lane_lo;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] *= sAlpha[(h0 + i) & 7];
+      if (is_res) {
+        for (int t = 0; t < nt; ++t) {
+          const float vv = __half2float(cv.res_v[((size_t)p * R + t) * kD + d]);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) acc[i] += sP[(h0 + i) & 7][t] * vv;
+        }
+      } else {
+        const int vg = d / Gv;
+        const unsigned* vw = reinterpret_cast<const unsigned*>(sRec + lay.off_v);
+        const __half* vs = reinterpret_cast<const __half*>(sRec + lay.off_v_s);
+        const __half* vz = reinterpret_cast<const __half*>(sRec + lay.off_v_z);
+        for (int tg = 0; tg < R / 16; ++tg) {
+          const unsigned w = vw[tg * kD + d];
+#pragma unroll
+          for (int i16 = 0; i16 < 16; ++i16) {
+            const int t = tg * 16 + i16;
+            const float vv = (float)((w >> (2 * i16)) & 3u) * __half2float(vs[t * lay.NVG + vg]) +
+                             __half2float(vz[t * lay.NVG + vg]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[i] += sP[(h0 + i) & 7][t] * vv;
+          }
+        }
+      }
+    }
+  }
+  __syncthreads();
+  // ---- partial result of this split ----
+  float* out = part + ((size_t)p * n_splits + split) * g * kPartStride;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (h0 + i < g) out[(h0 + i) * kPartStride + lane_lo] = acc[i];
+  if (tid < g) {
+    out[tid * kPartStride + kD] = sM[tid];
+    out[tid * kPartStride + kD + 1] = sL[tid];
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Merge of the splits: m* = max m_i, l* = sum l_i e^(m_i - m*), O = sum O_i e^(m_i - m*) / l*.
+// One workgroup per (batch, query head), one thread per channel.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kD) decode_merge_kernel(const float* __restrict__ part, int n_splits, int g, int Hq,
+                                                         __half* __restrict__ out, float* __restrict__ lse) {
+  const int bh = blockIdx.x, b = bh / Hq, h = bh % Hq, d = threadIdx.x;
+  const int Hkv = Hq / g, j = h / g, hh = h % g;
+  const int p = b * Hkv + j;
+  const float* base = part + ((size_t)p * n_splits * g + hh) * kPartStride;
+  const size_t stride = (size_t)g * kPartStride;
+  float m = -INFINITY;
+  for (int s = 0; s < n_splits; ++s) m = fmaxf(m, base[s * stride + kD]);
+  float l = 0.f, o = 0.f;
+  for (int s = 0; s < n_splits; ++s) {
+    const float ms = base[s * stride + kD];
+    const float w = ms == -INFINITY ? 0.f : __expf(ms - m);
+    l += base[s * stride + kD + 1] * w;
+    o += base[s * stride + d] * w;
+  }
+  out[(size_t)bh * kD + d] = __float2half_rn(o / l);
+  if (lse && d == 0) lse[bh] = m + __logf(l);
+}
+
+hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float* lse, float scale, int n_blocks,
+                         int n_res, hipStream_t s) {
+  int n_splits = max_splits_for(v.P);
+  if (n_splits > n_blocks) n_splits = n_blocks;   // the residual window rides with the last split
+  if (n_splits < 1) n_splits = 1;
+  float* part = reinterpret_cast<float*>(v.ws);
+  decode_split_kernel<<<dim3(v.P, n_splits), dim3(kDecThreads), 0, s>>>(v, q, scale, n_blocks, n_res, n_splits, part);
+  decode_merge_kernel<<<dim3(v.cfg.B * v.cfg.Hq), dim3(kD), 0, s>>>(part, n_splits, v.g, v.cfg.Hq, out, lse);
+  return hipGetLastError();
+}
+
+}  // namespace mixkvq

@@ -1,0 +1,248 @@
+"""GPU parity: the HIP path behind the C ABI against the CPU oracle, on the same
+seeded inputs.  Indices, packed codes, scales, zero-points, residual rows and the
+|q| accumulator must be bit-exact; attention outputs within
+2e-3 + 1e-2*|oracle| (fp32 accumulation against the fp64 oracle)."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as S
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import gpu_common
+    return gpu_common
+
+
+def _kw(w: S.Workload, T_max=None, **over):
+    kw = dict(B=w.B, Hq=w.Hq, Hkv=w.Hkv, D=w.D, T_max=T_max or w.T, Gk=w.Gk, Gv=w.Gv, R=w.R, k4=w.k4, k16=w.k16)
+    kw.update(over)
+    return kw
+
+
+# ---------------------------------------------------------------------------
+# configuration 0, whole: 1 head, 1024 tokens, G = 32, 8 salient channels at 4 bit
+# ---------------------------------------------------------------------------
+def test_cfg0_end_to_end(H):
+    w = S.WORKLOADS[0]
+    K, V, Qp, q = S.cfg0_tensors()
+    oc, gc = H.make_pair(**_kw(w))
+    sel_ref = oc.select_channels(Qp, K)
+    sel = gc.select_channels(H.dev(Qp), H.dev(K))
+    assert np.array_equal(sel.cpu().numpy(), sel_ref)
+    assert {5, 37, 70, 101} <= set(sel_ref[0, 0].tolist())
+    oc.append(K, V, sel_ref)
+    gc.quantize_append(H.dev(K), H.dev(V), sel=sel)
+    H.check_state(oc, gc)
+    assert gc.state() == (992, 32)
+    H.check_attention(oc, gc, q)
+
+
+# ---------------------------------------------------------------------------
+# slices of the large configurations: several blocks, ragged residual tail
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("cfg_id,B,T", [(1, 2, 1000), (2, 1, 777), (3, 1, 1300), (1, 1, 4096)])
+def test_prefill_slice(H, cfg_id, B, T):
+    w = S.scaled_workload(cfg_id, B=B, T=T)
+    K, V, _ = S.heavy_tailed_kv(cfg_id, B, w.Hkv, T)
+    Qp = S.outlier_queries(cfg_id, B, w.Hq, 64)
+    q = S.outlier_queries(cfg_id, B, w.Hq, 1, stream=3)[:, :, 0]
+    oc, gc = H.make_pair(**_kw(w, T_max=(T + w.R - 1) // w.R * w.R))
+    sel_ref = oc.select_channels(Qp, K)
+    sel = gc.select_channels(H.dev(Qp), H.dev(K))
+    assert np.array_equal(sel.cpu().numpy(), sel_ref)
+    oc.append(K, V, sel_ref)
+    gc.quantize_append(H.dev(K), H.dev(V), sel=sel)
+    H.check_state(oc, gc)
+    H.check_attention(oc, gc, q, accumulate_q=True)
+    H.check_state(oc, gc)
+
+
+@pytest.mark.parametrize("g,k4,k16,Gk,Gv,R", [(1, 0, 0, 16, 16, 16), (5, 8, 4, 32, 64, 64), (8, 0, 32, 128, 128, 128),
+                                              (7, 24, 0, 64, 32, 128), (2, 8, 0, 16, 128, 48)])
+def test_shapes_and_tiers(H, g, k4, k16, Gk, Gv, R):
+    rng = np.random.default_rng(100 + g)
+    B, Hkv, T = 2, 2, 5 * R + 7
+    kw = dict(B=B, Hq=Hkv * g, Hkv=Hkv, D=128, T_max=8 * R, Gk=Gk, Gv=Gv, R=R, k4=k4, k16=k16)
+    K = (rng.standard_normal((B, Hkv, T, 128)) * rng.uniform(0.3, 8, 128)).astype(np.float16)
+    V = rng.standard_normal((B, Hkv, T, 128)).astype(np.float16)
+    Qp = rng.standard_normal((B, Hkv * g, 33, 128)).astype(np.float16)
+    q = rng.standard_normal((B, Hkv * g, 128)).astype(np.float16)
+    oc, gc = H.make_pair(**kw)
+    if k4 + k16:
+        sel_ref = oc.select_channels(Qp, K)
+        sel = gc.select_channels(H.dev(Qp), H.dev(K))
+        assert np.array_equal(sel.cpu().numpy(), sel_ref)
+    else:
+        sel_ref, sel = None, None
+    oc.append(K, V, sel_ref)
+    gc.quantize_append(H.dev(K), H.dev(V), sel=sel)
+    H.check_state(oc, gc)
+    H.check_attention(oc, gc, q)
+    H.check_attention(oc, gc, q, scale=0.31)
+
+
+# ---------------------------------------------------------------------------
+# decode loop: per-step append, |q| accumulation, re-selection at every flush
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("flush_mode,qreset", [(0, 0), (1, 0), (0, 1)])
+def test_decode_steps_with_flushes(H, flush_mode, qreset):
+    rng = np.random.default_rng(7)
+    B, Hkv, g, R = 2, 2, 5, 32
+    kw = dict(B=B, Hq=Hkv * g, Hkv=Hkv, D=128, T_max=8 * R, Gk=32, Gv=128, R=R, k4=16, k16=0, flush_mode=flush_mode,
+              qacc_reset_on_flush=qreset)
+    oc, gc = H.make_pair(**kw)
+    n0 = 45
+    K = (rng.standard_normal((B, Hkv, n0, 128)) * rng.uniform(0.3, 8, 128)).astype(np.float16)
+    V = rng.standard_normal((B, Hkv, n0, 128)).astype(np.float16)
+    Qp = rng.standard_normal((B, Hkv * g, n0, 128)).astype(np.float16)
+    sel_ref = oc.select_channels(Qp, K)
+    sel = gc.select_channels(H.dev(Qp), H.dev(K))
+    assert np.array_equal(sel.cpu().numpy(), sel_ref)
+    oc.append(K, V, sel_ref)
+    gc.quantize_append(H.dev(K), H.dev(V), sel=sel)
+    for step in range(100):
+        k1 = (rng.standard_normal((B, Hkv, 1, 128)) * rng.uniform(0.3, 8, 128)).astype(np.float16)
+        v1 = rng.standard_normal((B, Hkv, 1, 128)).astype(np.float16)
+        q1 = (rng.standard_normal((B, Hkv * g, 128)) * rng.uniform(0.2, 5, 128)).astype(np.float16)
+        oc.append(k1, v1)
+        gc.quantize_append(H.dev(k1), H.dev(v1))
+        H.check_attention(oc, gc, q1, accumulate_q=True)
+        if step % 16 == 15 or step == 99:
+            H.check_state(oc, gc)
+    assert oc.n_flush_calls >= 3
+
+
+def test_chunked_append_without_selection_matches_oracle(H):
+    """sel = NULL on a multi-token append: every flushed block is scored on its own."""
+    rng = np.random.default_rng(8)
+    kw = dict(B=1, Hq=4, Hkv=2, D=128, T_max=1024, Gk=64, Gv=128, R=128, k4=16, k16=0)
+    oc, gc = H.make_pair(**kw)
+    Qp = (rng.standard_normal((1, 4, 50, 128)) * rng.uniform(0.2, 5, 128)).astype(np.float16)
+    oc.accumulate_queries(Qp)
+    K = (rng.standard_normal((1, 2, 700, 128)) * rng.uniform(0.3, 8, (2, 1, 128))).astype(np.float16)
+    V = rng.standard_normal((1, 2, 700, 128)).astype(np.float16)
+    gc.select_channels(H.dev(Qp), H.dev(K))        # only to feed the accumulator
+    for lo, hi in ((0, 100), (100, 101), (101, 600), (600, 700)):
+        oc.append(K[:, :, lo:hi], V[:, :, lo:hi])
+        # strided views of the big tensors exercise the stride arguments
+        gc.quantize_append(H.dev(K)[:, :, lo:hi], H.dev(V)[:, :, lo:hi])
+        H.check_state(oc, gc)
+
+
+# ---------------------------------------------------------------------------
+# edge cases
+# ---------------------------------------------------------------------------
+def test_everything_in_the_residual_window(H):
+    rng = np.random.default_rng(9)
+    kw = dict(B=2, Hq=14, Hkv=2, D=128, T_max=128, Gk=128, Gv=128, R=128, k4=16, k16=0)
+    for n in (1, 5, 128):
+        oc, gc = H.make_pair(**kw)
+        K = rng.standard_normal((2, 2, n, 128)).astype(np.float16)
+        V = rng.standard_normal((2, 2, n, 128)).astype(np.float16)
+        q = rng.standard_normal((2, 14, 128)).astype(np.float16)
+        oc.append(K, V)
+        gc.quantize_append(H.dev(K), H.dev(V))
+        assert gc.state() == (0, n)
+        H.check_state(oc, gc)
+        H.check_attention(oc, gc, q)
+
+
+def test_eager_mode_with_empty_window_and_single_block(H):
+    rng = np.random.default_rng(10)
+    kw = dict(B=1, Hq=7, Hkv=1, D=128, T_max=256, Gk=128, Gv=128, R=128, k4=16, k16=0, flush_mode=1)
+    oc, gc = H.make_pair(**kw)
+    K = rng.standard_normal((1, 1, 128, 128)).astype(np.float16)
+    V = rng.standard_normal((1, 1, 128, 128)).astype(np.float16)
+    q = rng.standard_normal((1, 7, 128)).astype(np.float16)
+    oc.append(K, V)
+    gc.quantize_append(H.dev(K), H.dev(V))
+    assert gc.state() == (128, 0)
+    H.check_state(oc, gc)
+    H.check_attention(oc, gc, q)
+
+
+def test_degenerate_groups(H):
+    """Constant groups (scale 0), all-zero tensors with both signs of zero, extreme magnitudes, subnormals."""
+    rng = np.random.default_rng(11)
+    kw = dict(B=1, Hq=2, Hkv=1, D=128, T_max=256, Gk=32, Gv=32, R=64, k4=8, k16=4, flush_mode=1)
+    oc, gc = H.make_pair(**kw)
+    K = rng.standard_normal((1, 1, 128, 128)).astype(np.float16)
+    V = rng.standard_normal((1, 1, 128, 128)).astype(np.float16)
+    K[0, 0, :32, :] = 1.5                               # constant groups
+    K[0, 0, 32:64, ::2] = -0.0                          # mixed zero signs
+    K[0, 0, 32:64, 1::2] = 0.0
+    K[0, 0, 64:96, 3] = 65504.0                         # largest fp16 against the rest
+    K[0, 0, 96:, 7] = (rng.integers(-30, 30, 32) * 2.0 ** -24).astype(np.float16)   # subnormals only
+    V[0, 0, 5, :] = -0.0
+    V[0, 0, 6, :64] = 60000.0
+    V[0, 0, 6, 64:] = -60000.0
+    V[0, 0, 7, :] = (rng.integers(-3, 3, 128) * 2.0 ** -24).astype(np.float16)
+    Qp = rng.standard_normal((1, 2, 8, 128)).astype(np.float16)
+    sel_ref = oc.select_channels(Qp, K)
+    sel = gc.select_channels(H.dev(Qp), H.dev(K))
+    assert np.array_equal(sel.cpu().numpy(), sel_ref)
+    oc.append(K, V, sel_ref)
+    gc.quantize_append(H.dev(K), H.dev(V), sel=sel)
+    H.check_state(oc, gc)
+
+
+def test_error_only_score_mode_and_ties(H):
+    rng = np.random.default_rng(12)
+    kw = dict(B=1, Hq=2, Hkv=1, D=128, T_max=128, Gk=64, Gv=128, R=64, k4=8, k16=8, score_mode=1)
+    oc, gc = H.make_pair(**kw)
+    K = rng.integers(-4, 5, (1, 1, 64, 128)).astype(np.float16)   # many equal ranges -> ties
+    Qp = rng.standard_normal((1, 2, 4, 128)).astype(np.float16)
+    assert np.array_equal(gc.select_channels(H.dev(Qp), H.dev(K)).cpu().numpy(), oc.select_channels(Qp, K))
+    kw["score_mode"] = 0
+    oc, gc = H.make_pair(**kw)
+    Qz = np.zeros((1, 2, 4, 128), dtype=np.float16)               # all scores 0 -> lowest indices win
+    ref = oc.select_channels(Qz, K)
+    assert ref[0, 0].tolist() == list(range(16))
+    assert np.array_equal(gc.select_channels(H.dev(Qz), H.dev(K)).cpu().numpy(), ref)
+
+
+def test_capacity_and_empty_errors_leave_the_cache_unchanged(H):
+    import paper_2512_19206_amd as M
+    rng = np.random.default_rng(13)
+    kw = dict(B=1, Hq=1, Hkv=1, D=128, T_max=64, Gk=32, Gv=32, R=32, k4=8, k16=0)
+    oc, gc = H.make_pair(**kw)
+    q = H.dev(rng.standard_normal((1, 1, 128)).astype(np.float16))
+    with pytest.raises(M.MixKVQError) as e:
+        gc.decode_attention(q)
+    assert e.value.code == -5
+    K = rng.standard_normal((1, 1, 96, 128)).astype(np.float16)
+    oc.append(K, K)
+    gc.quantize_append(H.dev(K), H.dev(K))
+    assert gc.state() == (64, 32)
+    with pytest.raises(M.MixKVQError) as e:
+        gc.quantize_append(H.dev(K[:, :, :1]), H.dev(K[:, :, :1]))
+    assert e.value.code == -2
+    assert gc.state() == (64, 32)
+    H.check_state(oc, gc)
+    # misaligned rows are refused
+    with pytest.raises(M.MixKVQError):
+        gc.quantize_append(H.dev(K)[:, :, :1, 1:], H.dev(K)[:, :, :1, 1:])
+
+
+def test_results_are_deterministic(H):
+    rng = np.random.default_rng(14)
+    w = S.scaled_workload(1, B=1, T=2048)
+    K, V, _ = S.heavy_tailed_kv(1, 1, w.Hkv, 2048)
+    Qp = S.outlier_queries(1, 1, w.Hq, 32)
+    q = H.dev(S.outlier_queries(1, 1, w.Hq, 1, stream=3)[:, :, 0])
+    outs, recs = [], []
+    for _ in range(3):
+        _, gc = H.make_pair(**_kw(w))
+        sel = gc.select_channels(H.dev(Qp), H.dev(K))
+        gc.quantize_append(H.dev(K), H.dev(V), sel=sel)
+        out, lse = gc.decode_attention(q)
+        torch.cuda.synchronize()
+        outs.append(out.cpu().numpy().view(np.uint16))
+        recs.append(gc.block_records()[:, :gc.state()[0] // w.R].cpu().numpy())
+    assert all(np.array_equal(outs[0], o) for o in outs[1:])
+    assert all(np.array_equal(recs[0], r) for r in recs[1:])

@@ -1,0 +1,102 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared entry
+point, and its host-only functions (record layout, buffer sizes, argument
+validation) agree with the oracle.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from oracle import mixkvq_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def M():
+    import paper_2512_19206_amd as M
+    if not os.path.exists(M.LIB_PATH):
+        from paper_2512_19206_amd.build import build_library
+        build_library()
+    return M
+
+
+def _declared_symbols():
+    names = set()
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if fn.endswith(".h"):
+            text = open(os.path.join(ROOT, "include", fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(mixkvq_[a-z_0-9]+)\s*\(", text))
+    return names
+
+
+def test_library_exports_every_declared_symbol(M):
+    lib = M.load_library()
+    declared = _declared_symbols()
+    assert declared, "no declarations found"
+    assert declared == set(M.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+CONFIGS = [
+    dict(B=1, Hq=1, Hkv=1, D=128, T_max=1024, Gk=32, Gv=32, R=32, k4=8, k16=0),
+    dict(B=8, Hq=28, Hkv=4, D=128, T_max=32768, Gk=128, Gv=128, R=128, k4=16, k16=0),
+    dict(B=64, Hq=40, Hkv=8, D=128, T_max=32768, Gk=128, Gv=128, R=128, k4=0, k16=12),
+    dict(B=2, Hq=8, Hkv=2, D=128, T_max=256, Gk=16, Gv=16, R=64, k4=8, k16=4),
+    dict(B=1, Hq=2, Hkv=2, D=128, T_max=128, Gk=64, Gv=64, R=128, k4=0, k16=0),
+]
+
+
+@pytest.mark.parametrize("kw", CONFIGS)
+def test_record_layout_matches_oracle(M, kw):
+    lay = M.block_layout(M.make_config(**kw))
+    ref = O.block_layout(O.OracleConfig(**kw))
+    for name, _ in lay._fields_:
+        assert getattr(lay, name) == getattr(ref, name), name
+
+
+@pytest.mark.parametrize("kw", CONFIGS)
+def test_buffer_sizes(M, kw):
+    cfg = M.make_config(**kw)
+    sz, lay = M.cache_sizes(cfg), M.block_layout(cfg)
+    P = kw["B"] * kw["Hkv"]
+    assert sz.blocks >= P * (kw["T_max"] // kw["R"]) * lay.rec_bytes
+    assert sz.res_k >= P * kw["R"] * 128 * 2 and sz.res_v == sz.res_k
+    assert sz.qacc >= P * 129 * 8
+    assert sz.workspace >= P * 128 * 16
+    for f in ("blocks", "res_k", "res_v", "qacc", "workspace"):
+        assert getattr(sz, f) % 256 == 0
+
+
+@pytest.mark.parametrize("bad", [
+    dict(D=64), dict(Hq=3, Hkv=2), dict(Hq=18, Hkv=2), dict(R=24), dict(R=256, T_max=256), dict(Gk=48),
+    dict(Gv=24), dict(k4=4), dict(k16=2), dict(k4=64, k16=64), dict(T_max=100), dict(flush_mode=2),
+    dict(score_mode=-1), dict(B=0),
+])
+def test_bad_configurations_are_rejected(M, bad):
+    kw = dict(CONFIGS[1])
+    kw.update(bad)
+    cfg = M.make_config(**kw)
+    lay = M.BlockLayout()
+    assert M.load_library().mixkvq_block_layout(C.byref(cfg), C.byref(lay)) == -1
+    sz = M.Sizes()
+    assert M.load_library().mixkvq_cache_sizes(C.byref(cfg), C.byref(sz)) == -1
+
+
+def test_null_arguments_and_error_strings(M):
+    lib = M.load_library()
+    assert lib.mixkvq_block_layout(None, None) == -1
+    assert lib.mixkvq_cache_state(None, None, None) == -1
+    assert lib.mixkvq_decode_attention(None, None, None, None, 0.0, 0, None) == -1
+    assert lib.mixkvq_quantize_append(None, None, None, 1, None, None, None) == -1
+    for code in (0, -1, -2, -3, -4, -5, -99):
+        assert len(lib.mixkvq_strerror(code)) > 0
+    # cache_create rejects NULL and misaligned device pointers before touching the device
+    cfg = M.make_config(**CONFIGS[0])
+    h = C.c_void_p()
+    bufs = M.binding.Buffers(0, 0, 0, 0, 0)
+    assert lib.mixkvq_cache_create(C.byref(cfg), C.byref(bufs), C.byref(h)) == -1
+    bufs = M.binding.Buffers(256, 256, 256, 256, 260)
+    assert lib.mixkvq_cache_create(C.byref(cfg), C.byref(bufs), C.byref(h)) == -1
