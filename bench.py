@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the MixKVQ decode hot path on one MI355X.
+
+A step = one pass of the whole hot path for one batch: mixkvq_quantize_append of
+one new token per sequence (with the block flush, channel re-selection and
+quantize-and-pack whenever the residual window is full) followed by
+mixkvq_decode_attention with |q| accumulation.  Inputs are synthetic and already
+resident in HBM when the timed region starts.
+
+Prints ONE JSON line (see the fields below).  `value` is effective bandwidth:
+algorithmic bytes of a decode step (minimal representation of the method: packed
+codes, fp16 scale/zero per group, fp16-tier values, index bytes, the fp16 residual
+window, q in and out) divided by the measured time per step.
+"""
+import argparse
+import ctypes
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+LLC_BYTES = 256 << 20   # last-level (Infinity) cache
+
+
+def algorithmic_bytes(w, n_q, r):
+    """Bytes one decode step must move, all (batch, KV head) pairs."""
+    D, ks, g = w.D, w.k4 + w.k16, w.Hq // w.Hkv
+    nb, ng = n_q // w.R, n_q // w.Gk
+    per_pair = (n_q * (D - ks) // 4 + ng * (D - ks) * 4 + n_q * w.k4 // 2 + ng * w.k4 * 4 + n_q * w.k16 * 2
+                + nb * ks + n_q * D // 4 + n_q * (D // w.Gv) * 4 + r * D * 4 + g * D * 4)
+    return per_pair * w.B * w.Hkv
+
+
+class HipEvents:
+    """hipEvent pairs straight from the HIP runtime (they must be recorded on the
+    stream the kernel runs on, inside the library call)."""
+
+    def __init__(self, n):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.pairs = []
+        for _ in range(n):
+            a, b = ctypes.c_void_p(), ctypes.c_void_p()
+            assert self.hip.hipEventCreate(ctypes.byref(a)) == 0 and self.hip.hipEventCreate(ctypes.byref(b)) == 0
+            self.pairs.append((a, b))
+
+    def elapsed_ms(self):
+        out = []
+        for a, b in self.pairs:
+            ms = ctypes.c_float()
+            assert self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+            out.append(ms.value)
+        return out
+
+    def destroy(self):
+        for a, b in self.pairs:
+            self.hip.hipEventDestroy(a)
+            self.hip.hipEventDestroy(b)
+
+
+def build_inputs(cfg_id, w, host_batch):
+    """K, V [B, Hkv, T, D], prompt queries and per-step tensors on the device.
+    `host_batch` batch entries are drawn on the host; the others are device-side
+    copies with the channel order rolled (so that channel selection differs)."""
+    import numpy as np
+    import torch
+    import synth_inputs as S
+    hb = min(host_batch, w.B)
+    K, V, _ = S.heavy_tailed_kv(cfg_id, hb, w.Hkv, w.T)
+    Qp = S.outlier_queries(cfg_id, hb, w.Hq, 256)
+    qs = S.outlier_queries(cfg_id, hb, w.Hq, 8, stream=3)
+    dk = torch.empty((w.B, w.Hkv, w.T, w.D), dtype=torch.float16, device="cuda")
+    dv = torch.empty_like(dk)
+    dqp = torch.empty((w.B, w.Hq, 256, w.D), dtype=torch.float16, device="cuda")
+    dq = torch.empty((8, w.B, w.Hq, w.D), dtype=torch.float16, device="cuda")
+    hk, hv, hq, hs = (torch.from_numpy(a).cuda() for a in (K, V, Qp, qs))
+    for b in range(w.B):
+        src, roll = b % hb, 7 * (b // hb)
+        dk[b] = torch.roll(hk[src], roll, dims=-1)
+        dv[b] = torch.roll(hv[src], roll, dims=-1)
+        dqp[b] = torch.roll(hq[src], roll, dims=-1)
+        dq[:, b] = torch.roll(hs[src], roll, dims=-1).permute(1, 0, 2)
+    host = dict(K=K, V=V, Qp=Qp, qs=qs)
+    return dk, dv, dqp, dq, host
+
+
+def cpu_baseline(cfg_id, w, host, budget_s=20.0):
+    """The oracle's decode step (append one token, attention) timed on the host for
+    one batch entry at full context."""
+    import numpy as np
+    from oracle import mixkvq_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    cfg = O.OracleConfig(B=1, Hq=w.Hq, Hkv=w.Hkv, D=w.D, T_max=w.T + w.R, Gk=w.Gk, Gv=w.Gv, R=w.R, k4=w.k4, k16=w.k16)
+    oc = O.OracleCache(cfg)
+    K, V, Qp, qs = host["K"][:1], host["V"][:1], host["Qp"][:1], host["qs"][:1]
+    sel = oc.select_channels(Qp, K)
+    oc.append(K, V, sel)                       # prefill: not timed
+    n, t0 = 0, time.perf_counter()
+    while True:
+        q1 = np.ascontiguousarray(qs[:, :, n % qs.shape[2]])
+        oc.append(K[:, :, n:n + 1], V[:, :, n:n + 1])
+        oc.decode_attention(q1, accumulate_q=True)
+        n += 1
+        el = time.perf_counter() - t0
+        if el > budget_s or n >= 8:
+            break
+    import dataclasses
+    w1 = dataclasses.replace(w, B=1)
+    nbytes = algorithmic_bytes(w1, oc.n_quant, oc.n_res)
+    return {"value": round(nbytes * n / el / 1e9, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{n} decode steps of 1 of {w.B} batch entries (all {w.Hkv} KV heads, {w.T} tokens), "
+                      f"{el / n * 1e3:.0f} ms per step"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1024)
+    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--config", type=int, default=1, help="BASELINE configuration id (1, 2 or 3)")
+    ap.add_argument("--copies", type=int, default=0, help="independent cache copies rotated over (0 = enough for 2x LLC)")
+    ap.add_argument("--host-batch", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the hot path has no collective); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2512_19206_amd as M
+    import synth_inputs as S
+    assert torch.cuda.is_available(), "bench.py needs the GPU (there is no CPU fallback)"
+    M.load_library()
+
+    w = S.WORKLOADS[args.config]
+    n_q0 = w.R * (-(-w.T // w.R) - 1)
+    step_bytes = algorithmic_bytes(w, n_q0, w.T - n_q0)
+    copies = args.copies or max(1, math.ceil(2 * LLC_BYTES / step_bytes))
+    total_steps = args.steps * 2 + args.warmup
+    per_copy = -(-total_steps // copies)
+    T_max = (w.T + per_copy + 2 * w.R) // w.R * w.R
+
+    dk, dv, dqp, dq, host = build_inputs(args.config, w, args.host_batch)
+    kw = dict(B=w.B, Hq=w.Hq, Hkv=w.Hkv, D=w.D, T_max=T_max, Gk=w.Gk, Gv=w.Gv, R=w.R, k4=w.k4, k16=w.k16)
+    caches = []
+    for c in range(copies):
+        gc = M.Cache(M.make_config(**kw))
+        sel = M.mixkvq_select_channels(gc, dqp, dk)
+        M.mixkvq_quantize_append(gc, dk, dv, sel=sel)
+        caches.append(gc)
+    torch.cuda.synchronize()
+    k1 = dk[:, :, :64]   # new tokens are drawn from the prompt tensors (same distribution)
+    v1 = dv[:, :, :64]
+    out = torch.empty((w.B, w.Hq, w.D), dtype=torch.float16, device="cuda")
+    lse = torch.empty((w.B, w.Hq), dtype=torch.float32, device="cuda")
+
+    def step(i):
+        gc = caches[i % copies]
+        t = i % 64
+        M.mixkvq_quantize_append(gc, k1[:, :, t:t + 1], v1[:, :, t:t + 1])
+        M.mixkvq_decode_attention(gc, dq[i % 8], out=out, lse=lse, accumulate_q=True)
+
+    i = 0
+    for _ in range(args.warmup):
+        step(i)
+        i += 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(i)
+        i += 1
+    torch.cuda.synchronize()
+    el = time.perf_counter() - t0
+    ms_per_step = el / args.steps * 1e3
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # second pass over the same kind of steps with HIP events around the split-K attention kernel
+    n_ev = min(args.steps, 512)
+    ev = HipEvents(n_ev)
+    for n in range(n_ev):
+        gc = caches[i % copies]
+        gc.set_timing_events(*ev.pairs[n])
+        step(i)
+        gc.set_timing_events(None, None)
+        i += 1
+    torch.cuda.synchronize()
+    k_ms = ev.elapsed_ms()
+    ev.destroy()
+    k_avg_ms = sum(k_ms) / len(k_ms)
+    achieved = step_bytes / (k_avg_ms * 1e-3) / 1e9
+    nq_end, r_end = caches[0].state()
+
+    result = {
+        "metric": "quantized-KV decode attention: effective HBM GB/s at 32K ctx", "value": round(value, 2),
+        "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "us_per_step": round(ms_per_step * 1e3, 2),
+        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "T": w.T, "Gk": w.Gk, "Gv": w.Gv,
+                   "R": w.R, "k4": w.k4, "k16": w.k16, "cache_copies": copies,
+                   "algorithmic_bytes_per_step": step_bytes,
+                   "step": "quantize_append(1 token, flush every R) + decode_attention(accumulate_q)"},
+        "roofline": {"bound": "hbm", "kernel": "decode_split_kernel", "achieved": round(achieved, 2),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "kernel_avg_us": round(k_avg_ms * 1e3, 2), "kernel_min_us": round(min(k_ms) * 1e3, 2),
+                     "launches_timed": n_ev, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(args.config, w, host)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -132,6 +132,11 @@ int mixkvq_quantize_append(mixkvq_cache* c, const void* k_new, const void* v_new
 int mixkvq_decode_attention(mixkvq_cache* c, const void* q, void* out, float* lse,
                             float scale, int32_t accumulate_q, void* stream);
 
+/* Profiling aid.  With a pair of hipEvent_t handles (HOST, created by the caller with timing enabled), every
+ * following mixkvq_decode_attention on this cache records start_event just before and stop_event just after
+ * its split-K attention kernel, on the call's stream.  Pass NULL, NULL to switch it off. */
+int mixkvq_set_timing_events(mixkvq_cache* c, void* start_event, void* stop_event);
+
 /* Message for a return code (for EHIP: the last HIP error string seen by this thread). */
 const char* mixkvq_strerror(int code);
 

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libmixkvq.so")
 
 EXPORTS = ("mixkvq_block_layout", "mixkvq_cache_sizes", "mixkvq_cache_create", "mixkvq_cache_destroy",
            "mixkvq_cache_reset", "mixkvq_cache_state", "mixkvq_select_channels", "mixkvq_quantize_append",
-           "mixkvq_decode_attention", "mixkvq_strerror")
+           "mixkvq_decode_attention", "mixkvq_set_timing_events", "mixkvq_strerror")
 
 
 class Config(C.Structure):
@@ -68,6 +68,7 @@ def load_library() -> C.CDLL:
     lib.mixkvq_select_channels.argtypes = [vp, vp, i32, i64p, vp, i32, i64p, vp, vp]
     lib.mixkvq_quantize_append.argtypes = [vp, vp, vp, i32, i64p, vp, vp]
     lib.mixkvq_decode_attention.argtypes = [vp, vp, vp, vp, C.c_float, i32, vp]
+    lib.mixkvq_set_timing_events.argtypes = [vp, vp, vp]
     lib.mixkvq_strerror.argtypes = [i32]
     lib.mixkvq_strerror.restype = C.c_char_p
     for name in EXPORTS:
@@ -175,6 +176,10 @@ class Cache:
         _check(self.lib.mixkvq_decode_attention(self.handle, q.data_ptr(), out.data_ptr(), lse.data_ptr(),
                                                 float(scale), int(bool(accumulate_q)), _stream_ptr(stream)))
         return out, lse
+
+    def set_timing_events(self, start_event, stop_event):
+        """start_event, stop_event: raw hipEvent_t handles (ints) or None, None."""
+        _check(self.lib.mixkvq_set_timing_events(self.handle, start_event, stop_event))
 
     # helpers for tests: views of the raw buffers
     def block_records(self) -> torch.Tensor:

@@ -78,6 +78,7 @@ struct mixkvq_cache {
   CacheView v;
   int64_t n_quant;
   int32_t n_res;
+  hipEvent_t ev_start = nullptr, ev_stop = nullptr;   // optional timing of the split kernel
 };
 
 extern "C" {
@@ -218,7 +219,14 @@ int mixkvq_decode_attention(mixkvq_cache* c, const void* q, void* out, float* ls
     MIXKVQ_TRY_HIP(launch_qabs_accumulate(c->v, (const __half*)q, 1, qs, s));
   }
   MIXKVQ_TRY_HIP(launch_decode(c->v, (const __half*)q, (__half*)out, lse, scale, (int)(c->n_quant / cfg.R),
-                               c->n_res, s));
+                               c->n_res, s, c->ev_start, c->ev_stop));
+  return MIXKVQ_OK;
+}
+
+int mixkvq_set_timing_events(mixkvq_cache* c, void* start_event, void* stop_event) {
+  if (!c || ((start_event == nullptr) != (stop_event == nullptr))) return MIXKVQ_EINVAL;
+  c->ev_start = (hipEvent_t)start_event;
+  c->ev_stop = (hipEvent_t)stop_event;
   return MIXKVQ_OK;
 }
 

@@ -208,12 +208,14 @@ __global__ void __launch_bounds__(kD) decode_merge_kernel(const float* __restric
 }
 
 hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float* lse, float scale, int n_blocks,
-                         int n_res, hipStream_t s) {
+                         int n_res, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
   int n_splits = max_splits_for(v.P);
   if (n_splits > n_blocks) n_splits = n_blocks;   // the residual window rides with the last split
   if (n_splits < 1) n_splits = 1;
   float* part = reinterpret_cast<float*>(v.ws);
+  if (ev_start) (void)hipEventRecord(ev_start, s);
   decode_split_kernel<<<dim3(v.P, n_splits), dim3(kDecThreads), 0, s>>>(v, q, scale, n_blocks, n_res, n_splits, part);
+  if (ev_stop) (void)hipEventRecord(ev_stop, s);
   decode_merge_kernel<<<dim3(v.cfg.B * v.cfg.Hq), dim3(kD), 0, s>>>(part, n_splits, v.g, v.cfg.Hq, out, lse);
   return hipGetLastError();
 }
