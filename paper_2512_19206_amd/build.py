@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmixkvq.so")
-SOURCES = ["api.hip", "select_kernels.hip", "quantize_kernels.hip", "decode_kernels.hip"]
+SOURCES = ["api.hip", "select_kernels.hip", "quantize_kernels.hip", "decode_kernels.hip", "decode_mfma.hip"]
 
 
 def hipcc_path() -> str:
@@ -23,7 +23,7 @@ def build_library(verbose: bool = False) -> str:
     """Compile every HIP source for gfx950 and link the shared library."""
     cmd = [hipcc_path(), "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wall", "-Wno-unused-function",
+           "-Wall", "-Wno-unused-function", "-fno-strict-aliasing",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC,
            "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:

@@ -214,12 +214,8 @@ int mixkvq_decode_attention(mixkvq_cache* c, const void* q, void* out, float* ls
   const mixkvq_config& cfg = c->v.cfg;
   hipStream_t s = (hipStream_t)stream;
   if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)cfg.D);
-  if (accumulate_q) {
-    Strides3 qs{(int64_t)cfg.Hq * cfg.D, (int64_t)cfg.D, (int64_t)cfg.D};
-    MIXKVQ_TRY_HIP(launch_qabs_accumulate(c->v, (const __half*)q, 1, qs, s));
-  }
   MIXKVQ_TRY_HIP(launch_decode(c->v, (const __half*)q, (__half*)out, lse, scale, (int)(c->n_quant / cfg.R),
-                               c->n_res, s, c->ev_start, c->ev_stop));
+                               c->n_res, accumulate_q, s, c->ev_start, c->ev_stop));
   return MIXKVQ_OK;
 }
 

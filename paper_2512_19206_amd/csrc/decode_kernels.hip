@@ -11,7 +11,7 @@ constexpr int kPartStride = kD + 2;   // floats per (split, head): O[D], m, l
 
 size_t decode_workspace_bytes(const mixkvq_config& c) {
   const int P = c.B * c.Hkv;
-  return (size_t)P * max_splits_for(P) * (c.Hq / c.Hkv) * kPartStride * sizeof(float);
+  return (size_t)P * (max_splits_for(P) + 1) * (c.Hq / c.Hkv) * kPartStride * sizeof(float);
 }
 
 // ---------------------------------------------------------------------------
@@ -207,12 +207,28 @@ __global__ void __launch_bounds__(kD) decode_merge_kernel(const float* __restric
   if (lse && d == 0) lse[bh] = m + __logf(l);
 }
 
+bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, int n_blocks, int n_res, int n_splits,
+                            float* part, int accumulate_q, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop,
+                            hipError_t* err);
+
 hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float* lse, float scale, int n_blocks,
-                         int n_res, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
+                         int n_res, int accumulate_q, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
   int n_splits = max_splits_for(v.P);
   if (n_splits > n_blocks) n_splits = n_blocks;   // the residual window rides with the last split
   if (n_splits < 1) n_splits = 1;
   float* part = reinterpret_cast<float*>(v.ws);
+  hipError_t e = hipSuccess;
+  if (try_launch_decode_mfma(v, q, scale, n_blocks, n_res, n_splits, part, accumulate_q, s, ev_start, ev_stop, &e)) {
+    // matrix-core path: n_splits partials from the quantized blocks + one from the residual window
+    if (e != hipSuccess) return e;
+    decode_merge_kernel<<<dim3(v.cfg.B * v.cfg.Hq), dim3(kD), 0, s>>>(part, n_splits + 1, v.g, v.cfg.Hq, out, lse);
+    return hipGetLastError();
+  }
+  if (accumulate_q) {
+    Strides3 qs{(int64_t)v.cfg.Hq * kD, (int64_t)kD, (int64_t)kD};
+    e = launch_qabs_accumulate(v, q, 1, qs, s);
+    if (e != hipSuccess) return e;
+  }
   if (ev_start) (void)hipEventRecord(ev_start, s);
   decode_split_kernel<<<dim3(v.P, n_splits), dim3(kDecThreads), 0, s>>>(v, q, scale, n_blocks, n_res, n_splits, part);
   if (ev_stop) (void)hipEventRecord(ev_stop, s);

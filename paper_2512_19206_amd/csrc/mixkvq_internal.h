@@ -44,7 +44,8 @@ hipError_t launch_flush(const CacheView& v, const __half* k_new, const __half* v
 hipError_t launch_residual_copy(const CacheView& v, const __half* k_new, const __half* v_new, Strides3 kvs,
                                 int src_first, int dst_first, int n, hipStream_t s);
 hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float* lse, float scale,
-                         int n_blocks, int n_res, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop);
+                         int n_blocks, int n_res, int accumulate_q, hipStream_t s, hipEvent_t ev_start,
+                         hipEvent_t ev_stop);
 
 size_t decode_workspace_bytes(const mixkvq_config& c);
 size_t select_workspace_bytes(const mixkvq_config& c);
