@@ -1,6 +1,7 @@
 // Split-K decode attention over the mixed-precision cache (Section 3.1, Eq. 1, with
 // keys and values dequantized on the fly by Eq. 3) and the log-sum-exp merge of the
 // splits.
+#include <stdlib.h>
 #include "mixkvq_internal.h"
 
 namespace mixkvq {
@@ -9,9 +10,22 @@ constexpr int kDecThreads = 256;
 constexpr int kMaxG = 8;
 constexpr int kPartStride = kD + 2;   // floats per (split, head): O[D], m, l
 
-size_t decode_workspace_bytes(const mixkvq_config& c) {
+size_t decode_partials_bytes(const mixkvq_config& c) {
   const int P = c.B * c.Hkv;
-  return (size_t)P * (max_splits_for(P) + 1) * (c.Hq / c.Hkv) * kPartStride * sizeof(float);
+  const size_t n = (size_t)P * (max_splits_for(P) + 1) * (c.Hq / c.Hkv) * kPartStride * sizeof(float);
+  return (n + 255) / 256 * 256;
+}
+// partials, then one arrival counter per pair (kept at zero between launches)
+size_t decode_workspace_bytes(const mixkvq_config& c) { return decode_partials_bytes(c) + (size_t)c.B * c.Hkv * sizeof(unsigned); }
+
+__global__ void zero_u32_kernel(unsigned* p, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+hipError_t launch_zero_counters(const CacheView& v, hipStream_t s) {
+  unsigned* counters = reinterpret_cast<unsigned*>(v.ws + decode_partials_bytes(v.cfg));
+  zero_u32_kernel<<<dim3((v.P + 255) / 256), dim3(256), 0, s>>>(counters, v.P);
+  return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
@@ -195,8 +209,10 @@ __global__ void __launch_bounds__(kD) decode_merge_kernel(const float* __restric
   const float* base = part + ((size_t)p * n_splits * g + hh) * kPartStride;
   const size_t stride = (size_t)g * kPartStride;
   float m = -INFINITY;
+#pragma unroll 8
   for (int s = 0; s < n_splits; ++s) m = fmaxf(m, base[s * stride + kD]);
   float l = 0.f, o = 0.f;
+#pragma unroll 8
   for (int s = 0; s < n_splits; ++s) {
     const float ms = base[s * stride + kD];
     const float w = ms == -INFINITY ? 0.f : __expf(ms - m);
@@ -208,22 +224,30 @@ __global__ void __launch_bounds__(kD) decode_merge_kernel(const float* __restric
 }
 
 bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, int n_blocks, int n_res, int n_splits,
-                            float* part, int accumulate_q, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop,
-                            hipError_t* err);
+                            float* part, unsigned* counters, __half* out, float* lse, int accumulate_q, hipStream_t s,
+                            hipEvent_t ev_start, hipEvent_t ev_stop, hipError_t* err);
 
 hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float* lse, float scale, int n_blocks,
                          int n_res, int accumulate_q, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
-  int n_splits = max_splits_for(v.P);
-  if (n_splits > n_blocks) n_splits = n_blocks;   // the residual window rides with the last split
+  // split count: enough workgroups to fill the chip (tunable through MIXKVQ_DECODE_WGS for experiments),
+  // never above the ceiling the workspace was sized for
+  static const int target_wgs = [] {
+    const char* e = getenv("MIXKVQ_DECODE_WGS");
+    int t = e ? atoi(e) : 0;
+    return t > 0 ? t : kDecodeTargetWGs;
+  }();
+  int n_splits = target_wgs / v.P - 1;   // one more workgroup per pair takes the residual window
+  if (n_splits > max_splits_for(v.P)) n_splits = max_splits_for(v.P);
+  if (n_splits > n_blocks) n_splits = n_blocks;
   if (n_splits < 1) n_splits = 1;
   float* part = reinterpret_cast<float*>(v.ws);
   hipError_t e = hipSuccess;
-  if (try_launch_decode_mfma(v, q, scale, n_blocks, n_res, n_splits, part, accumulate_q, s, ev_start, ev_stop, &e)) {
-    // matrix-core path: n_splits partials from the quantized blocks + one from the residual window
-    if (e != hipSuccess) return e;
-    decode_merge_kernel<<<dim3(v.cfg.B * v.cfg.Hq), dim3(kD), 0, s>>>(part, n_splits + 1, v.g, v.cfg.Hq, out, lse);
-    return hipGetLastError();
-  }
+  // matrix-core path: one launch (n_splits partials from the quantized blocks, one from the residual
+  // window, merged by the last workgroup of each pair)
+  unsigned* counters = reinterpret_cast<unsigned*>(v.ws + decode_partials_bytes(v.cfg));
+  if (try_launch_decode_mfma(v, q, scale, n_blocks, n_res, n_splits, part, counters, out, lse, accumulate_q, s,
+                             ev_start, ev_stop, &e))
+    return e;
   if (accumulate_q) {
     Strides3 qs{(int64_t)v.cfg.Hq * kD, (int64_t)kD, (int64_t)kD};
     e = launch_qabs_accumulate(v, q, 1, qs, s);

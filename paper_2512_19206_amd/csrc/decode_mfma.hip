@@ -100,23 +100,26 @@ __device__ __forceinline__ u32x4 unpack4(unsigned w) {
 template <int K4, int K16>
 struct Tiers {
   static constexpr int NL = kD - K4 - K16;
-  static constexpr int Wlo = (NL + 15) / 16;
+  static constexpr int Wlo = (NL + 15) / 16;   // 2-bit words per token
   static constexpr int NLp = Wlo * 16;
-  static constexpr int NLU = (NL + 7) / 8;     // 8-slot units of the 2-bit plane
-  static constexpr int W4 = K4 / 8;            // 8-slot units (= words) of the 4-bit plane
-  static_assert(NLU + W4 <= 16, "the 2-bit and 4-bit tiers must fit four MFMA steps");
+  static constexpr int NU = (Wlo + 3) / 4;     // word rounds: lane group kg takes 2-bit word 4u + kg in round u
+  static constexpr int W4 = K4 / 8;            // 4-bit words per token
+  static_assert(W4 <= 4, "the 4-bit tier must fit one MFMA step");
   static_assert(K16 <= 32, "the fp16 tier must fit one MFMA step");
 };
 
-// unit (8 slots) handled by lane group kg in MFMA step s = 2u + x: linear index ui = 8u + 2kg + x;
-// ui < NLU: half x of 2-bit word 4u+kg; NLU <= ui < NLU+W4: 4-bit word ui-NLU; else empty.
+// Contraction slots.  Every lane group runs the same code; a lane group whose word does not
+// exist reads a clamped address and meets a zero in the small operand.
+//   2-bit tier, step 2u+x (u < NU, x = 0,1): lane group kg unpacks half x of word c = 4u+kg;
+//       VGPR e pairs channels j and j+8 of the 2-bit list, j = 16c + 4x + e, position factor 4^sc2(4x+e)
+//   4-bit tier, one step: lane group kg unpacks word kg; VGPR e pairs tier entries 8kg+e, 8kg+e+4
+//   fp16 tier, one step: lane group kg takes tier entries 8kg .. 8kg+7 as they are
 
 template <int K4, int K16, int NVG, int NKL>
-__global__ void __launch_bounds__(kMfmaThreads, 2)
-decode_mfma_kernel(CacheView cv, const __half* __restrict__ q, float scale_log2e, int n_blocks, int n_res, int n_splits,
-                   float* __restrict__ part, int accumulate_q) {
+__device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __restrict__ q, float scale_log2e,
+                                          int n_blocks, int n_splits, float* __restrict__ part, unsigned char* smem) {
   using T = Tiers<K4, K16>;
-  extern __shared__ __align__(16) unsigned char smem[];
+  constexpr int NU = T::NU;
   // scalars of the by-value view (kept in SGPRs; no references into the kernel argument)
   const int R = cv.cfg.R, g = cv.g, Hq = cv.cfg.Hq, Hkv = cv.cfg.Hkv, Gk = cv.cfg.Gk, NB = cv.NB;
   const int rec_bytes = cv.lay.rec_bytes, off_idx = cv.lay.off_idx, off_klo_s = cv.lay.off_klo_s,
@@ -124,7 +127,7 @@ decode_mfma_kernel(CacheView cv, const __half* __restrict__ q, float scale_log2e
             off_klo = cv.lay.off_klo, off_k4 = cv.lay.off_k4, off_k16 = cv.lay.off_k16, off_v = cv.lay.off_v,
             off_v_s = cv.lay.off_v_s;
   const unsigned char* const blocks = cv.blocks;
-  const int p = blockIdx.x, split = blockIdx.y, tid = threadIdx.x;
+  const int p = blockIdx.x, split = blockIdx.y - 1, tid = threadIdx.x;
   const int b = p / Hkv, jkv = p % Hkv;
   const int wave = tid >> 6, lane = tid & 63, n = lane & 15, kg = lane >> 4;
   const int head = n & 7, role = n >> 3;     // role 0: head of q*s, role 1: tail
@@ -133,37 +136,26 @@ decode_mfma_kernel(CacheView cv, const __half* __restrict__ q, float scale_log2e
   __half* sQn = reinterpret_cast<__half*>(smem);                   // [8][128] normalised q
   int* sEq = reinterpret_cast<int*>(smem + 2048);                   // [8] exponents
   unsigned char* wbase = smem + 2048 + 64 + wave * kWaveLds;        // this wave's private region
-  unsigned char* sK = wbase;                                        // record bytes [0, off_v)
+  unsigned char* sK = wbase;                                        // record bytes [0, NKL KiB)
   unsigned char* sVm = wbase + kKPartMax;                           // v_s, v_z planes
   unsigned char* sLo = wbase + kKPartMax + kVMetaMax;               // 2-bit channel list [128], then salient idx [<=64]
-
-  // ---- normalise q per head: qn = q * 2^-Eq with max|qn| in [1/2, 1) ----
-  if (tid < 8 * 32) {
-    const int h = tid >> 5, l32 = tid & 31;
-    float v[4];
-    float mx = 0.f;
-    for (int i = 0; i < 4; ++i) {
-      v[i] = h < g ? __half2float(q[((size_t)b * Hq + jkv * g + h) * kD + l32 * 4 + i]) : 0.f;
-      mx = fmaxf(mx, fabsf(v[i]));
-    }
-    for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 32));
-    int ef = (int)((__float_as_uint(mx) >> 23) & 0xff) - 127 + 15;   // fp16 exponent field of the maximum
-    if (ef < 1) ef = 1;
-    const int eq = ef - 14;
-    for (int i = 0; i < 4; ++i) sQn[h * kD + l32 * 4 + i] = __float2half_rn(ldexpf(v[i], -eq));
-    if (l32 == 0) sEq[h] = eq;
-  }
-  __syncthreads();
-  const int Eq = sEq[head];
 
   const int blk_lo = (int)((long long)n_blocks * split / n_splits);
   const int blk_hi = (int)((long long)n_blocks * (split + 1) / n_splits);
 
   // ---- per-lane constants -------------------------------------------------
-  const int m_ = n;                                   // A-operand row
-  const int tokbase = 16 * (m_ >> 2) + (m_ & 3);      // token of row m in tile (h, x): 64h + tokbase + {0,8,4,12}[x]
-  const int nck = off_v >> 4;                     // 16-byte chunks of the key part
-  const int nvm = (rec_bytes - off_v_s) >> 4; // chunks of the value scale/zero planes
+  const int tokbase = 16 * (n >> 2) + (n & 3);    // token of A-row n in tile (h, x): 64h + tokbase + {0,8,4,12}[x]
+  const int rec_chunks = rec_bytes >> 4;
+  const int nvm = (rec_bytes - off_v_s) >> 4;     // 16-byte chunks of the value scale/zero planes
+  // LDS byte offsets of this lane's words in token `tokbase` (clamped to existing words)
+  int lo_word_off[NU];
+#pragma unroll
+  for (int u = 0; u < NU; ++u) {
+    const int c = 4 * u + kg < T::Wlo ? 4 * u + kg : T::Wlo - 1;
+    lo_word_off[u] = off_klo + 4 * (tokbase * T::Wlo + c);
+  }
+  const int h4_word_off = off_k4 + 4 * (tokbase * T::W4 + (kg < T::W4 ? kg : 0));
+  const int k16_off = off_k16 + 2 * (tokbase * K16 + (8 * kg < K16 ? 8 * kg : 0));
 
   // running state (log2 domain)
   float m_run = -INFINITY, l_run = 0.f;
@@ -179,31 +171,31 @@ decode_mfma_kernel(CacheView cv, const __half* __restrict__ q, float scale_log2e
     for (int c = 0; c < 4; ++c) O[a][c] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   // q in slot order (rebuilt when the block's channel selection changes)
-  unsigned qn[4][4];                  // [step][vgpr]: normalised q pairs
-  unsigned q16[4];                    // fp16-tier q pairs of this lane's chunk (role 0 only)
+  unsigned qlo[2 * NU][4];            // [step][vgpr]: normalised q pairs of the 2-bit tier
+  unsigned qh4[4], q16[4];            // 4-bit tier pairs; fp16-tier pairs (role 0 only)
   unsigned sel_prev[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) sel_prev[i] = 0xffffffffu;
 #pragma unroll
-  for (int s = 0; s < 4; ++s)
+  for (int s = 0; s < 2 * NU; ++s)
 #pragma unroll
-    for (int e = 0; e < 4; ++e) qn[s][e] = 0u;
+    for (int e = 0; e < 4; ++e) qlo[s][e] = 0u;
 #pragma unroll
-  for (int e = 0; e < 4; ++e) q16[e] = 0u;
+  for (int e = 0; e < 4; ++e) { qh4[e] = 0u; q16[e] = 0u; }
 
   // prefetch registers
   u32x4 kreg[NKL];
   u32x4 vmreg;
   u32x4 vreg[2][2];   // [h][x]
 
-  // Loads of one block into the prefetch registers.  Indices beyond the end of a plane are
-  // clamped (the data is loaded twice and stored once) so that every load is unconditional.
-#define MIXKVQ_ISSUE_K_LOADS(BLK)                                                                             \
+  // Loads of one block.  Chunk indices are clamped to the record so that every lane loads and
+  // stores unconditionally (a clamped lane repeats the record's last chunk).
+#define MIXKVQ_ISSUE_K_LOADS(BLK)                                                                           \
   {                                                                                                          \
     const unsigned char* rec_ = blocks + ((size_t)p * NB + (BLK)) * rec_bytes;                              \
     _Pragma("unroll") for (int c = 0; c < NKL; ++c) {                                                       \
       const int idx_ = c * 64 + lane;                                                                        \
-      kreg[c] = reinterpret_cast<const u32x4*>(rec_)[idx_ < nck ? idx_ : nck - 1];                          \
+      kreg[c] = reinterpret_cast<const u32x4*>(rec_)[idx_ < rec_chunks ? idx_ : rec_chunks - 1];            \
     }                                                                                                        \
     vmreg = reinterpret_cast<const u32x4*>(rec_ + off_v_s)[lane < nvm ? lane : nvm - 1];                    \
   }
@@ -221,28 +213,50 @@ decode_mfma_kernel(CacheView cv, const __half* __restrict__ q, float scale_log2e
     MIXKVQ_ISSUE_V_LOADS(blk)
   }
 
+  // ---- normalise q per head: qn = q * 2^-Eq with max|qn| in [1/2, 1) ----
+  {
+    const int h = tid >> 5, l32 = tid & 31;
+    float v[4];
+    float mx = 0.f;
+    for (int i = 0; i < 4; ++i) {
+      v[i] = h < g ? __half2float(q[((size_t)b * Hq + jkv * g + h) * kD + l32 * 4 + i]) : 0.f;
+      mx = fmaxf(mx, fabsf(v[i]));
+    }
+    for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 32));
+    int ef = (int)((__float_as_uint(mx) >> 23) & 0xff) - 127 + 15;   // fp16 exponent field of the maximum
+    if (ef < 1) ef = 1;
+    const int eq = ef - 14;
+    for (int i = 0; i < 4; ++i) sQn[h * kD + l32 * 4 + i] = __float2half_rn(ldexpf(v[i], -eq));
+    if (l32 == 0) sEq[h] = eq;
+  }
+  __syncthreads();
+  const int Eq = sEq[head];
+
+
   for (; blk < blk_hi; blk += kWaves) {
     // ---- stage the key part and value metadata in LDS (wave-private: no barrier needed) ----
 #pragma unroll
-    for (int c = 0; c < NKL; ++c) {
-      const int idx = c * 64 + lane;
-      if (idx < nck) reinterpret_cast<u32x4*>(sK)[idx] = kreg[c];
-    }
-    if (lane < nvm) reinterpret_cast<u32x4*>(sVm)[lane] = vmreg;
+    for (int c = 0; c < NKL; ++c) reinterpret_cast<u32x4*>(sK)[c * 64 + lane] = kreg[c];
+    reinterpret_cast<u32x4*>(sVm)[lane < nvm ? lane : nvm - 1] = vmreg;
     if (blk + kWaves < blk_hi) MIXKVQ_ISSUE_K_LOADS(blk + kWaves)
 
     // ---- channel selection of this block: rebuild q in slot order if it changed ----
+    bool rebuild = false;
     if (K4 + K16 > 0) {
-      bool changed = false;
 #pragma unroll
       for (int i = 0; i < (K4 + K16 + 3) / 4; ++i) {
         const unsigned wv = reinterpret_cast<const unsigned*>(sK + off_idx)[i];
-        changed |= wv != sel_prev[i];
+        rebuild |= wv != sel_prev[i];
         sel_prev[i] = wv;
       }
-      if (__builtin_amdgcn_readfirstlane((int)changed)) {
+    } else {
+      rebuild = sel_prev[0] != 0u;
+      sel_prev[0] = 0u;
+    }
+    if (__builtin_amdgcn_readfirstlane((int)rebuild)) {
+      unsigned char* sIdx = sLo + kD;
+      if (K4 + K16 > 0) {
         // list of 2-bit channels: lanes cover channels lane and lane+64
-        unsigned char* sIdx = sLo + kD;
         if (lane < K4 + K16) sIdx[lane] = sK[off_idx + lane];
         unsigned long long m0 = 0, m1 = 0;   // bitmap of salient channels
 #pragma unroll
@@ -250,192 +264,173 @@ decode_mfma_kernel(CacheView cv, const __half* __restrict__ q, float scale_log2e
           const int ch = sK[off_idx + i];
           if (ch < 64) m0 |= 1ull << ch; else m1 |= 1ull << (ch - 64);
         }
-        {
-          const int ch0 = lane, ch1 = lane + 64;
-          if (!((m0 >> ch0) & 1)) sLo[ch0 - __popcll(m0 & ((1ull << ch0) - 1))] = (unsigned char)ch0;
-          if (!((m1 >> lane) & 1))
-            sLo[ch1 - __popcll(m0) - __popcll(m1 & ((1ull << lane) - 1))] = (unsigned char)ch1;
-        }
-        // gather
-        const __half* qrow = sQn + head * kD;
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-          for (int x = 0; x < 2; ++x) {
-            const int ui = 8 * u + 2 * kg + x;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              float lo = 0.f, hi = 0.f;
-              if (ui < T::NLU) {
-                const int j0 = 16 * (4 * u + kg) + 4 * x + e, j1 = j0 + 8;
-                if (j0 < T::NL) lo = __half2float(qrow[sLo[j0]]);
-                if (j1 < T::NL) hi = __half2float(qrow[sLo[j1]]);
-              } else if (ui - T::NLU < T::W4) {
-                const int a0 = 8 * (ui - T::NLU) + e;
-                lo = __half2float(qrow[sIdx[K16 + a0]]);
-                hi = __half2float(qrow[sIdx[K16 + a0 + 4]]);
-              }
-              if (!live) { lo = 0.f; hi = 0.f; }
-              qn[2 * u + x][e] = cvt_pk(lo, hi);
-            }
-          }
-        if (K16 > 0) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int a0 = 8 * kg + 2 * e;
-            float lo = 0.f, hi = 0.f;
-            if (live && role == 0) {
-              if (a0 < K16) lo = __half2float(qrow[sIdx[a0]]);
-              if (a0 + 1 < K16) hi = __half2float(qrow[sIdx[a0 + 1]]);
-            }
-            q16[e] = cvt_pk(lo, hi);
-          }
-        }
+        if (!((m0 >> lane) & 1)) sLo[lane - __popcll(m0 & ((1ull << lane) - 1))] = (unsigned char)lane;
+        if (!((m1 >> lane) & 1))
+          sLo[lane + 64 - __popcll(m0) - __popcll(m1 & ((1ull << lane) - 1))] = (unsigned char)(lane + 64);
+      } else {
+        sLo[lane] = (unsigned char)lane;
+        sLo[lane + 64] = (unsigned char)(lane + 64);
       }
-    } else if (sel_prev[0] == 0xffffffffu) {
-      sel_prev[0] = 0;
       const __half* qrow = sQn + head * kD;
 #pragma unroll
-      for (int u = 0; u < 2; ++u)
+      for (int u = 0; u < NU; ++u)
 #pragma unroll
         for (int x = 0; x < 2; ++x)
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const int j0 = 16 * (4 * u + kg) + 4 * x + e;
-            float lo = live ? __half2float(qrow[j0]) : 0.f, hi = live ? __half2float(qrow[j0 + 8]) : 0.f;
-            qn[2 * u + x][e] = cvt_pk(lo, hi);
+            const int j0 = 16 * (4 * u + kg) + 4 * x + e, j1 = j0 + 8;
+            float lo = 0.f, hi = 0.f;
+            if (live && j0 < T::NL) lo = __half2float(qrow[sLo[j0]]);
+            if (live && j1 < T::NL) hi = __half2float(qrow[sLo[j1]]);
+            qlo[2 * u + x][e] = cvt_pk(lo, hi);
           }
+      if (K4 > 0) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float lo = 0.f, hi = 0.f;
+          if (live && kg < T::W4) {
+            lo = __half2float(qrow[sIdx[K16 + 8 * kg + e]]);
+            hi = __half2float(qrow[sIdx[K16 + 8 * kg + e + 4]]);
+          }
+          qh4[e] = cvt_pk(lo, hi);
+        }
+      }
+      if (K16 > 0) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int a0 = 8 * kg + 2 * e;
+          float lo = 0.f, hi = 0.f;
+          if (live && role == 0) {
+            if (a0 < K16) lo = __half2float(qrow[sIdx[a0]]);
+            if (a0 + 1 < K16) hi = __half2float(qrow[sIdx[a0 + 1]]);
+          }
+          q16[e] = cvt_pk(lo, hi);
+        }
+      }
     }
 
     // operands that live across the super-groups of one key group
-    u32x4 Bq[4];
+    u32x4 Blo[2 * NU], Bh4;
     float zdot = 0.f, C = 0.f, Cz = 0.f, zc = 0.f;
 #pragma unroll
     for (int hsg = 0; hsg < 2; ++hsg) {       // super-groups of 64 tokens
       if (64 * hsg < R) {
-      if ((64 * hsg) % Gk == 0) {
-        const int grp = (64 * hsg) / Gk;
-      // ---- small key operand of this group: Qs = qg * s, bias = sum q z ----------------
-      unsigned sp[4][4];     // scales of this lane's slots, paired like the codes
-      zdot = 0.f;
-      unsigned smax2 = 0u;
+        if ((64 * hsg) % Gk == 0) {
+          const int grp = (64 * hsg) / Gk;
+          // ---- small key operand of this group: Qs = q * s (head and tail), bias = sum q z ----
+          unsigned sp[2 * NU][4], sp4[4];   // scales of this lane's slots, paired like the codes
+          float zd = 0.f;
+          unsigned smax2 = 0u;
 #pragma unroll
-      for (int u = 0; u < 2; ++u)
+          for (int u = 0; u < NU; ++u) {
+            const int c = 4 * u + kg < T::Wlo ? 4 * u + kg : T::Wlo - 1;
+            const uint4* ps = reinterpret_cast<const uint4*>(sK + off_klo_s + 2 * (grp * T::NLp + 16 * c));
+            const uint4* pz = reinterpret_cast<const uint4*>(sK + off_klo_z + 2 * (grp * T::NLp + 16 * c));
+            const uint4 s0 = ps[0], s1 = ps[1], z0 = pz[0], z1 = pz[1];
+            const unsigned sl[4] = {s0.x, s0.y, s0.z, s0.w}, sh[4] = {s1.x, s1.y, s1.z, s1.w};
+            const unsigned zl[4] = {z0.x, z0.y, z0.z, z0.w}, zh[4] = {z1.x, z1.y, z1.z, z1.w};
 #pragma unroll
-        for (int x = 0; x < 2; ++x) {
-          const int ui = 8 * u + 2 * kg + x;
-          // byte offsets of the two 4-entry runs (A: low halves, B: high halves) inside the record
-          int oa_s, ob_s, oa_z, ob_z;
-          if (ui < T::NLU) {
-            const int j0 = 16 * (4 * u + kg) + 4 * x;
-            oa_s = off_klo_s + 2 * (grp * T::NLp + j0);
-            ob_s = oa_s + 16;
-            oa_z = off_klo_z + 2 * (grp * T::NLp + j0);
-            ob_z = oa_z + 16;
-          } else if (ui - T::NLU < T::W4) {
-            const int a0 = 8 * (ui - T::NLU);
-            oa_s = off_k4_s + 2 * (grp * K4 + a0);
-            ob_s = oa_s + 8;
-            oa_z = off_k4_z + 2 * (grp * K4 + a0);
-            ob_z = oa_z + 8;
-          } else {   // empty unit: q is 0 there; read any finite scale
-            oa_s = ob_s = off_klo_s;
-            oa_z = ob_z = off_klo_z;
+            for (int x = 0; x < 2; ++x)
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const int r = 4 * x + e;      // pair (entry r, entry r + 8) of the word's 16 channels
+                const unsigned selb = (r & 1) ? 0x07060302u : 0x05040100u;
+                sp[2 * u + x][e] = __builtin_amdgcn_perm(sh[r >> 1], sl[r >> 1], selb);
+                zd = dot2(qlo[2 * u + x][e], __builtin_amdgcn_perm(zh[r >> 1], zl[r >> 1], selb), zd);
+                smax2 = pk_max(smax2, sp[2 * u + x][e]);
+              }
           }
-          const uint2 sa = *reinterpret_cast<const uint2*>(sK + oa_s), sb = *reinterpret_cast<const uint2*>(sK + ob_s);
-          const uint2 za = *reinterpret_cast<const uint2*>(sK + oa_z), zb = *reinterpret_cast<const uint2*>(sK + ob_z);
-          const int s = 2 * u + x;
-          sp[s][0] = __builtin_amdgcn_perm(sb.x, sa.x, 0x05040100u);
-          sp[s][1] = __builtin_amdgcn_perm(sb.x, sa.x, 0x07060302u);
-          sp[s][2] = __builtin_amdgcn_perm(sb.y, sa.y, 0x05040100u);
-          sp[s][3] = __builtin_amdgcn_perm(sb.y, sa.y, 0x07060302u);
-          zdot = dot2(qn[s][0], __builtin_amdgcn_perm(zb.x, za.x, 0x05040100u), zdot);
-          zdot = dot2(qn[s][1], __builtin_amdgcn_perm(zb.x, za.x, 0x07060302u), zdot);
-          zdot = dot2(qn[s][2], __builtin_amdgcn_perm(zb.y, za.y, 0x05040100u), zdot);
-          zdot = dot2(qn[s][3], __builtin_amdgcn_perm(zb.y, za.y, 0x07060302u), zdot);
+          if (K4 > 0) {
+            const int w = kg < T::W4 ? kg : 0;
+            const uint4 s0 = *reinterpret_cast<const uint4*>(sK + off_k4_s + 2 * (grp * K4 + 8 * w));
+            const uint4 z0 = *reinterpret_cast<const uint4*>(sK + off_k4_z + 2 * (grp * K4 + 8 * w));
+            const unsigned sl[4] = {s0.x, s0.y, s0.z, s0.w}, zl[4] = {z0.x, z0.y, z0.z, z0.w};
 #pragma unroll
-          for (int e = 0; e < 4; ++e) smax2 = pk_max(smax2, sp[s][e]);
+            for (int e = 0; e < 4; ++e) {     // pair (entry e, entry e + 4)
+              const unsigned selb = (e & 1) ? 0x07060302u : 0x05040100u;
+              sp4[e] = __builtin_amdgcn_perm(sl[2 + (e >> 1)], sl[e >> 1], selb);
+              zd = dot2(qh4[e], __builtin_amdgcn_perm(zl[2 + (e >> 1)], zl[e >> 1], selb), zd);
+              smax2 = pk_max(smax2, sp4[e]);
+            }
+          }
+          zd = xkg_sum(zd);
+          zdot = role ? 0.f : zd;
+          // block exponent: scales are multiplied by 2^e0 so that the largest lands in [2^14, 2^15) (e0 <= 15),
+          // and by 4^-sc, the position factor of the code they meet in the product
+          float smax = fmaxf(half_lo(smax2), half_hi(smax2));
+          smax = xkg_max(smax);
+          int efs = (int)((__float_as_uint(smax) >> 23) & 0xff) - 127 + 15;
+          if (efs < 1) efs = 1;
+          efs = __builtin_amdgcn_readfirstlane(efs);
+          const int e0 = 29 - efs < 15 ? 29 - efs : 15;
+#pragma unroll
+          for (int s = 0; s < 2 * NU; ++s)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const unsigned mult = ((unsigned)(15 + e0 - 2 * sc2(4 * (s & 1) + e)) << 10) * 0x00010001u;
+              const unsigned sn = pk_mul(sp[s][e], mult);                 // fp16 pair s * 2^(e0 - 2 sc)
+              const unsigned hi = pk_mul(qlo[s][e], sn);
+              const unsigned lo = pk_fma_neg(qlo[s][e], sn, hi);
+              Blo[s][e] = role ? lo : hi;
+            }
+          if (K4 > 0) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const unsigned mult = ((unsigned)(15 + e0 - 2 * sc4(e)) << 10) * 0x00010001u;
+              const unsigned sn = pk_mul(sp4[e], mult);
+              const unsigned hi = pk_mul(qh4[e], sn);
+              const unsigned lo = pk_fma_neg(qh4[e], sn, hi);
+              Bh4[e] = role ? lo : hi;
+            }
+          }
+          // logits in the log2 domain: x2 = S * C + Z * Cz
+          Cz = ldexpf(scale_log2e, Eq);
+          C = ldexpf(scale_log2e, 24 - e0 + Eq);
+          zc = zdot * Cz;
         }
-      zdot = xkg_sum(zdot);
-      if (role) zdot = 0.f;
-      // block exponent: scales are multiplied by 2^e0 so that the largest lands in [2^14, 2^15) (e0 <= 15),
-      // and by 4^-sc, the position factor of the code they meet in the product
-      float smax = fmaxf(half_lo(smax2), half_hi(smax2));
-      smax = xkg_max(smax);
-      int efs = (int)((__float_as_uint(smax) >> 23) & 0xff) - 127 + 15;
-      if (efs < 1) efs = 1;
-      efs = __builtin_amdgcn_readfirstlane(efs);
-      const int e0 = 29 - efs < 15 ? 29 - efs : 15;
-#pragma unroll
-      for (int s = 0; s < 4; ++s)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int ui = 8 * (s >> 1) + 2 * kg + (s & 1);
-          const int sc = ui < T::NLU ? sc2(4 * (s & 1) + e) : sc4(e);
-          const unsigned mult = ((unsigned)(15 + e0 - 2 * sc) << 10) * 0x00010001u;   // fp16 pair 2^(e0 - 2 sc)
-          const unsigned sn = pk_mul(sp[s][e], mult);
-          const unsigned hi = pk_mul(qn[s][e], sn);
-          const unsigned lo = pk_fma_neg(qn[s][e], sn, hi);
-          Bq[s][e] = role ? lo : hi;
-        }
-      // logits in the log2 domain: x2 = S * C + Z * Cz
-      Cz = ldexpf(scale_log2e, Eq);
-      C = ldexpf(scale_log2e, 24 - e0 + Eq);
-      zc = zdot * Cz;
 
-      }
-      {
         // ---- S^T tiles: tile x holds tokens 64*hsg + 16*(row/4) + row%4 + {0,8,4,12}[x] ----
-        f32x4 S[4];
+        constexpr int offx[4] = {0, 8, 4, 12};
+        unsigned wlo[NU][4], wh4[4];
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
-          const int off_x = (x == 0 ? 0 : x == 1 ? 8 : x == 2 ? 4 : 12);
-          const int tok = 64 * hsg + tokbase + off_x;
-          f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+          const int tk = 64 * hsg + offx[x];
 #pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            u32x4 a0 = {0u, 0u, 0u, 0u}, a1 = {0u, 0u, 0u, 0u};
-            const int ui0 = 8 * u + 2 * kg;
-            if (8 * u + 7 < T::NLU) {          // every lane group has a full 2-bit word here
-              const unsigned w = *reinterpret_cast<const unsigned*>(sK + off_klo + 4 * (tok * T::Wlo + 4 * u + kg));
-              unpack2(w, a0, a1);
-            } else {
-              if (ui0 < T::NLU) {
-                const unsigned w = *reinterpret_cast<const unsigned*>(sK + off_klo + 4 * (tok * T::Wlo + 4 * u + kg));
-                u32x4 t0, t1;
-                unpack2(w, t0, t1);
-                a0 = t0;
-                if (ui0 + 1 < T::NLU) a1 = t1;
-              }
-              if (T::W4 > 0) {
-                if (ui0 >= T::NLU && ui0 - T::NLU < T::W4)
-                  a0 = unpack4(*reinterpret_cast<const unsigned*>(sK + off_k4 + 4 * (tok * T::W4 + ui0 - T::NLU)));
-                if (ui0 + 1 >= T::NLU && ui0 + 1 - T::NLU < T::W4)
-                  a1 = unpack4(*reinterpret_cast<const unsigned*>(sK + off_k4 + 4 * (tok * T::W4 + ui0 + 1 - T::NLU)));
-              }
-            }
-            acc = mfma(a0, Bq[2 * u], acc);
-            acc = mfma(a1, Bq[2 * u + 1], acc);
-          }
-          S[x] = acc;
+          for (int u = 0; u < NU; ++u)
+            wlo[u][x] = *reinterpret_cast<const unsigned*>(sK + lo_word_off[u] + 4 * tk * T::Wlo);
+          if (K4 > 0) wh4[x] = *reinterpret_cast<const unsigned*>(sK + h4_word_off + 4 * tk * T::W4);
+        }
+        f32x4 S[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) S[x] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+          u32x4 a0[4], a1[4];
+#pragma unroll
+          for (int x = 0; x < 4; ++x) unpack2(wlo[u][x], a0[x], a1[x]);
+#pragma unroll
+          for (int x = 0; x < 4; ++x) S[x] = mfma(a0[x], Blo[2 * u], S[x]);
+#pragma unroll
+          for (int x = 0; x < 4; ++x) S[x] = mfma(a1[x], Blo[2 * u + 1], S[x]);
+        }
+        if (K4 > 0) {
+#pragma unroll
+          for (int x = 0; x < 4; ++x) S[x] = mfma(unpack4(wh4[x]), Bh4, S[x]);
         }
         f32x4 S16[4];
         if (K16 > 0) {
+          const u32x4 bq = {q16[0], q16[1], q16[2], q16[3]};
 #pragma unroll
           for (int x = 0; x < 4; ++x) {
-            const int off_x = (x == 0 ? 0 : x == 1 ? 8 : x == 2 ? 4 : 12);
-            const int tok = 64 * hsg + tokbase + off_x;
-            u32x4 a = {0u, 0u, 0u, 0u};
-            if (8 * kg < K16) {
-              const unsigned char* src = sK + off_k16 + 2 * (tok * K16 + 8 * kg);
-              const uint2 v0 = *reinterpret_cast<const uint2*>(src);
-              a[0] = v0.x; a[1] = v0.y;
-              if (8 * kg + 4 < K16) {
-                const uint2 v1 = *reinterpret_cast<const uint2*>(src + 8);
-                a[2] = v1.x; a[3] = v1.y;
-              }
-            }
-            u32x4 bq = {q16[0], q16[1], q16[2], q16[3]};
+            const unsigned char* src = sK + k16_off + 2 * (64 * hsg + offx[x]) * K16;
+            const uint2 v0 = *reinterpret_cast<const uint2*>(src);
+            const uint2 v1 = *reinterpret_cast<const uint2*>(src + 8);
+            // entries beyond the tier are cleared: they belong to the next token's row or the next plane
+            u32x4 a;
+            a[0] = 8 * kg < K16 ? v0.x : 0u;
+            a[1] = 8 * kg + 2 < K16 ? v0.y : 0u;
+            a[2] = 8 * kg + 4 < K16 ? v1.x : 0u;
+            a[3] = 8 * kg + 6 < K16 ? v1.y : 0u;
             S16[x] = mfma(a, bq, f32x4{zdot, zdot, zdot, zdot});
           }
         }
@@ -467,83 +462,85 @@ decode_mfma_kernel(CacheView cv, const __half* __restrict__ q, float scale_log2e
           m_run = m_new;
         }
 
-        // ---- p, value-side small operand Ps = p * s_v * 4^-sc ----
-        // this lane's tokens: 64*hsg + 16*kg + r, r = i + {0,8,4,12}[x]; their scale/zero-point entries
-        unsigned vs[NVG][8], vz[NVG][8];   // fp16 pairs: entry r -> [r/2] half r%2
+        // ---- p (fp16, with the position factor 4^-sc of the value code it meets), Ps = p * s_v ----
+        // this lane's tokens: 64*hsg + 16*kg + r; PV step st pairs r = i + 4st (tile 2st) with r + 8 (tile 2st+1)
+        unsigned p16[2][4];
+        float lsum = 0.f;
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int sc = sc2(4 * st + i);
+            const float msc = m_run + 2.f * sc;
+            p16[st][i] = cvt_pk(__builtin_amdgcn_exp2f(x2[2 * st][i] - msc), __builtin_amdgcn_exp2f(x2[2 * st + 1][i] - msc));
+            const unsigned w4sc = ((unsigned)(15 + 2 * sc) << 10) * 0x00010001u;   // fp16 pair 4^sc
+            lsum = dot2(p16[st][i], w4sc, lsum);
+          }
+        l_run += lsum;
+        u32x4 Bp[NVG][2];
         {
           const int t0 = 64 * hsg + 16 * kg;
           if (NVG == 1) {
             const uint4* ps = reinterpret_cast<const uint4*>(sVm + 2 * t0);
             const uint4* pz = reinterpret_cast<const uint4*>(sVm + 2 * R + 2 * t0);
             const uint4 s0 = ps[0], s1 = ps[1], z0 = pz[0], z1 = pz[1];
-            vs[0][0] = s0.x; vs[0][1] = s0.y; vs[0][2] = s0.z; vs[0][3] = s0.w;
-            vs[0][4] = s1.x; vs[0][5] = s1.y; vs[0][6] = s1.z; vs[0][7] = s1.w;
-            vz[0][0] = z0.x; vz[0][1] = z0.y; vz[0][2] = z0.z; vz[0][3] = z0.w;
-            vz[0][4] = z1.x; vz[0][5] = z1.y; vz[0][6] = z1.z; vz[0][7] = z1.w;
+            const unsigned sl[4] = {s0.x, s0.y, s0.z, s0.w}, sh[4] = {s1.x, s1.y, s1.z, s1.w};
+            const unsigned zl[4] = {z0.x, z0.y, z0.z, z0.w}, zh[4] = {z1.x, z1.y, z1.z, z1.w};
+#pragma unroll
+            for (int st = 0; st < 2; ++st)
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                const int r = i + 4 * st;
+                const unsigned selb = (r & 1) ? 0x07060302u : 0x05040100u;
+                Bp[0][st][i] = pk_mul(p16[st][i], __builtin_amdgcn_perm(sh[r >> 1], sl[r >> 1], selb));
+                zacc[0][sc2(r)] = dot2(p16[st][i], __builtin_amdgcn_perm(zh[r >> 1], zl[r >> 1], selb), zacc[0][sc2(r)]);
+              }
           } else {
-            // [token][2] layout: token r at dword r, value group a in half a
+            // [token][2] layout: one dword per token, value group a in half a
             const uint4* ps = reinterpret_cast<const uint4*>(sVm + 4 * t0);
             const uint4* pz = reinterpret_cast<const uint4*>(sVm + 4 * R + 4 * t0);
+            unsigned sw[16], zw[16];
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
               const uint4 sv = ps[c], zv = pz[c];
-              const unsigned sw[4] = {sv.x, sv.y, sv.z, sv.w}, zw[4] = {zv.x, zv.y, zv.z, zv.w};
-#pragma unroll
-              for (int k2 = 0; k2 < 2; ++k2) {
-                // tokens 4c+2k2, 4c+2k2+1 -> pair index (4c+2k2)/2
-                vs[0][2 * c + k2] = __builtin_amdgcn_perm(sw[2 * k2 + 1], sw[2 * k2], 0x05040100u);
-                vs[NVG - 1][2 * c + k2] = __builtin_amdgcn_perm(sw[2 * k2 + 1], sw[2 * k2], 0x07060302u);
-                vz[0][2 * c + k2] = __builtin_amdgcn_perm(zw[2 * k2 + 1], zw[2 * k2], 0x05040100u);
-                vz[NVG - 1][2 * c + k2] = __builtin_amdgcn_perm(zw[2 * k2 + 1], zw[2 * k2], 0x07060302u);
-              }
+              sw[4 * c] = sv.x; sw[4 * c + 1] = sv.y; sw[4 * c + 2] = sv.z; sw[4 * c + 3] = sv.w;
+              zw[4 * c] = zv.x; zw[4 * c + 1] = zv.y; zw[4 * c + 2] = zv.z; zw[4 * c + 3] = zv.w;
             }
+#pragma unroll
+            for (int a = 0; a < NVG; ++a)
+#pragma unroll
+              for (int st = 0; st < 2; ++st)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                  const int r = i + 4 * st;
+                  const unsigned selb = a ? 0x07060302u : 0x05040100u;
+                  Bp[a][st][i] = pk_mul(p16[st][i], __builtin_amdgcn_perm(sw[r + 8], sw[r], selb));
+                  zacc[a][sc2(r)] = dot2(p16[st][i], __builtin_amdgcn_perm(zw[r + 8], zw[r], selb), zacc[a][sc2(r)]);
+                }
           }
         }
-        u32x4 Bp[NVG][2];   // [value group][PV step]: step 0 pairs tiles (0,1), step 1 pairs tiles (2,3)
-        float lsum = 0.f;
-#pragma unroll
-        for (int st = 0; st < 2; ++st)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int sc = st == 0 ? i : sc2(4 + i);
-            const float pa = __builtin_amdgcn_exp2f(x2[2 * st][i] - m_run - 2.f * sc);       // tile 2st:   token r = i + (st ? 4 : 0)
-            const float pb = __builtin_amdgcn_exp2f(x2[2 * st + 1][i] - m_run - 2.f * sc);   // tile 2st+1: token r + 8
-            lsum = fmaf(pa + pb, (float)(1 << (2 * sc)), lsum);
-            const int ra = i + (st ? 4 : 0), rb = ra + 8;
-#pragma unroll
-            for (int a = 0; a < NVG; ++a) {
-              const float sa = (ra & 1) ? half_hi(vs[a][ra >> 1]) : half_lo(vs[a][ra >> 1]);
-              const float sb = (rb & 1) ? half_hi(vs[a][rb >> 1]) : half_lo(vs[a][rb >> 1]);
-              const float za = (ra & 1) ? half_hi(vz[a][ra >> 1]) : half_lo(vz[a][ra >> 1]);
-              const float zb = (rb & 1) ? half_hi(vz[a][rb >> 1]) : half_lo(vz[a][rb >> 1]);
-              Bp[a][st][i] = cvt_pk(pa * sa, pb * sb);
-              zacc[a][sc] = fmaf(pa, za, fmaf(pb, zb, zacc[a][sc]));
-            }
-          }
-        l_run += lsum;
 
         // ---- O^T += V_codes^T . Ps^T ----
 #pragma unroll
         for (int xp = 0; xp < 2; ++xp) {
           const u32x4 vw = vreg[hsg][xp];
-          const unsigned w4[4] = {vw.x, vw.y, vw.z, vw.w};
+          const int a = NVG == 1 ? 0 : xp;
 #pragma unroll
           for (int qq = 0; qq < 4; ++qq) {
             u32x4 a0, a1;
-            unpack2(w4[qq], a0, a1);
-            const int a = NVG == 1 ? 0 : xp;
+            unpack2(vw[qq], a0, a1);
             O[xp][qq] = mfma(a0, Bp[a][0], O[xp][qq]);
             O[xp][qq] = mfma(a1, Bp[a][1], O[xp][qq]);
           }
         }
       }
-      }
     }
     if (blk + kWaves < blk_hi) MIXKVQ_ISSUE_V_LOADS(blk + kWaves)
   }
+#undef MIXKVQ_ISSUE_K_LOADS
+#undef MIXKVQ_ISSUE_V_LOADS
 
   // ---- wave results -> workgroup partial ------------------------------------------
-  // sums over the four lane groups of a column
   l_run = xkg_sum(l_run);
   float zsum[NVG];
 #pragma unroll
@@ -594,12 +591,13 @@ decode_mfma_kernel(CacheView cv, const __half* __restrict__ q, float scale_log2e
 // Residual window (fp16 keys and values) and the |q| accumulator: one workgroup
 // per pair, plain vector ALU; it writes partial number n_splits.
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(256)
-decode_residual_kernel(CacheView cv, const __half* __restrict__ q, float scale, int n_res, int n_splits,
-                       float* __restrict__ part, int accumulate_q) {
-  __shared__ float sQ[8][kD];
-  __shared__ float sP[8][kMaxR];
-  __shared__ float sM[8], sL[8];
+__device__ __forceinline__ void residual_part(const CacheView& cv, const __half* __restrict__ q, float scale, int n_res,
+                                              int n_splits, float* __restrict__ part, int accumulate_q,
+                                              unsigned char* smem) {
+  float (*sQ)[kD] = reinterpret_cast<float (*)[kD]>(smem);
+  float (*sP)[kMaxR] = reinterpret_cast<float (*)[kMaxR]>(smem + 8 * kD * 4);
+  float* sM = reinterpret_cast<float*>(smem + 8 * kD * 4 + 8 * kMaxR * 4);
+  float* sL = sM + 8;
   const mixkvq_config& cfg = cv.cfg;
   const int R = cfg.R, g = cv.g;
   const int p = blockIdx.x, tid = threadIdx.x;
@@ -669,10 +667,85 @@ decode_residual_kernel(CacheView cv, const __half* __restrict__ q, float scale, 
   }
 }
 
+// ---------------------------------------------------------------------------
+// Log-sum-exp merge of the partials of one pair (one workgroup per pair):
+// m* = max m_i, l* = sum l_i e^(m_i - m*), O = sum O_i e^(m_i - m*) / l*.
+// A separate launch: the kernel boundary makes the partials visible across the chip's L2 slices
+// without device-wide fences inside the attention kernel.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+decode_merge_pair_kernel(CacheView cv, const float* __restrict__ part, int n_parts, __half* __restrict__ out,
+                         float* __restrict__ lse) {
+  __shared__ __align__(16) unsigned char smem[64 + ((kMaxSplits + 1) * 8 * 2 + 16) * 4];
+  const int p = blockIdx.x, tid = threadIdx.x, g = cv.g;
+  const int b = p / cv.cfg.Hkv, j = p % cv.cfg.Hkv;
+  const size_t stride = (size_t)g * kPartStrideM;
+  const float* pbase = part + (size_t)p * n_parts * g * kPartStrideM;
+  float* sW = reinterpret_cast<float*>(smem + 64);          // [n_parts][g] weights e^(m_i - m*), m_i first
+  float* sML = sW + (kMaxSplits + 1) * 8;                   // [g] m*, then [g] l*
+  // every (part, head) maximum and sum: all loads are independent and issued together
+  float my_m = -INFINITY, my_l = 0.f;
+  if (tid < n_parts * g) {
+    const int sidx = tid / g, h = tid % g;
+    my_m = pbase[sidx * stride + h * kPartStrideM + kD];
+    my_l = pbase[sidx * stride + h * kPartStrideM + kD + 1];
+    sW[tid] = my_m;
+  }
+  __syncthreads();
+  if (tid < n_parts * g) {
+    const int h = tid % g;
+    float m = -INFINITY;
+    for (int s2 = 0; s2 < n_parts; ++s2) m = fmaxf(m, sW[s2 * g + h]);
+    if (tid < g) sML[h] = m;
+    my_l *= my_m == -INFINITY ? 0.f : __expf(my_m - m);
+    my_m = my_m == -INFINITY ? 0.f : __expf(my_m - m);      // now the weight
+  }
+  __syncthreads();
+  if (tid < n_parts * g) sW[tid] = my_m;
+  float* sLp = sML + 16;                                     // [n_parts][g] weighted l
+  if (tid < n_parts * g) sLp[tid] = my_l;
+  __syncthreads();
+  if (tid < g) {
+    float l = 0.f;
+    for (int s2 = 0; s2 < n_parts; ++s2) l += sLp[s2 * g + tid];
+    sML[8 + tid] = l;
+  }
+  __syncthreads();
+  const int d = tid & 127;
+  for (int h = tid >> 7; h < g; h += 2) {
+    float o = 0.f;
+    for (int s0 = 0; s0 < n_parts; s0 += 16) {
+      float v[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) v[i] = s0 + i < n_parts ? pbase[(s0 + i) * stride + h * kPartStrideM + d] : 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o = fmaf(v[i], s0 + i < n_parts ? sW[(s0 + i) * g + h] : 0.f, o);
+    }
+    const size_t bh = (size_t)b * cv.cfg.Hq + (size_t)j * g + h;
+    out[bh * kD + d] = __float2half_rn(o / sML[8 + h]);
+    if (lse && d == 0) lse[bh] = sML[h] + __logf(sML[8 + h]);
+  }
+}
+
+// One launch per decode step: workgroups (pair, split < n_splits) run the matrix-core part over their
+// blocks, workgroup (pair, n_splits) the residual window and the |q| accumulator.
+template <int K4, int K16, int NVG, int NKL>
+__global__ void __launch_bounds__(kMfmaThreads, 2)
+decode_fused_kernel(CacheView cv, const __half* __restrict__ q, float scale, int n_blocks, int n_res, int n_splits,
+                    float* __restrict__ part, int accumulate_q) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  // the residual workgroups come first in dispatch order so that they do not form a tail
+  if (blockIdx.y == 0)
+    residual_part(cv, q, scale, n_res, n_splits, part, accumulate_q, smem);
+  else
+    mfma_part<K4, K16, NVG, NKL>(cv, q, scale * 1.4426950408889634f, n_blocks, n_splits, part, smem);
+}
+
 template <int K4, int K16, int NVG, int NKL>
 static hipError_t launch_one(const CacheView& v, const __half* q, float scale, int n_blocks, int n_res, int n_splits,
-                             float* part, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
-  auto kern = decode_mfma_kernel<K4, K16, NVG, NKL>;
+                             float* part, unsigned* counters, __half* out, float* lse, int accumulate_q,
+                             hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
+  auto kern = decode_fused_kernel<K4, K16, NVG, NKL>;
   const size_t lds = 2048 + 64 + (size_t)kWaves * kWaveLds;
   static bool attr_set = false;
   if (!attr_set) {
@@ -681,16 +754,16 @@ static hipError_t launch_one(const CacheView& v, const __half* q, float scale, i
     attr_set = true;
   }
   if (ev_start) (void)hipEventRecord(ev_start, s);
-  kern<<<dim3(v.P, n_splits), dim3(kMfmaThreads), lds, s>>>(v, q, scale * 1.4426950408889634f, n_blocks, n_res, n_splits,
-                                                            part, 0);
+  kern<<<dim3(v.P, n_splits + 1), dim3(kMfmaThreads), lds, s>>>(v, q, scale, n_blocks, n_res, n_splits, part, accumulate_q);
   if (ev_stop) (void)hipEventRecord(ev_stop, s);
+  decode_merge_pair_kernel<<<dim3(v.P), dim3(256), 0, s>>>(v, part, n_splits + 1, out, lse);
   return hipGetLastError();
 }
 
 // Returns true and launches when the configuration is one the matrix-core kernel covers.
 bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, int n_blocks, int n_res, int n_splits,
-                            float* part, int accumulate_q, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop,
-                            hipError_t* err) {
+                            float* part, unsigned* counters, __half* out, float* lse, int accumulate_q, hipStream_t s,
+                            hipEvent_t ev_start, hipEvent_t ev_stop, hipError_t* err) {
   const mixkvq_config& c = v.cfg;
   if (c.R % 64 != 0 || c.Gk % 64 != 0 || c.Gv % 64 != 0 || n_blocks < 1) return false;
   if (v.lay.off_v > kKPartMax || v.lay.rec_bytes - v.lay.off_v_s > kVMetaMax) return false;
@@ -700,7 +773,8 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
   bool ok = true;
 #define MIXKVQ_CASE(K4_, K16_, NVG_, NKL_)                                                                          \
   if (c.k4 == K4_ && c.k16 == K16_ && nvg == NVG_ && nkl <= NKL_)                                                   \
-    e = launch_one<K4_, K16_, NVG_, NKL_>(v, q, scale, n_blocks, n_res, n_splits, part, s, ev_start, ev_stop);     \
+    e = launch_one<K4_, K16_, NVG_, NKL_>(v, q, scale, n_blocks, n_res, n_splits, part, counters, out, lse,       \
+                                          accumulate_q, s, ev_start, ev_stop);                                         \
   else
   MIXKVQ_CASE(16, 0, 1, 6)
   MIXKVQ_CASE(0, 12, 1, 8)
@@ -715,10 +789,6 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
   ok = false;
 #undef MIXKVQ_CASE
   if (!ok) return false;
-  if (e == hipSuccess) {
-    decode_residual_kernel<<<dim3(v.P), dim3(256), 0, s>>>(v, q, scale, n_res, n_splits, part, accumulate_q);
-    e = hipGetLastError();
-  }
   *err = e;
   return true;
 }

@@ -10,7 +10,8 @@ namespace mixkvq {
 constexpr int kD = 128;             // head dimension of the hot path
 constexpr int kMaxR = 128;          // largest residual window / flush unit
 constexpr int kMaxSplits = 64;      // split-K ceiling per (batch, KV head) pair
-constexpr int kSplitTargetWGs = 1024;
+constexpr int kSplitTargetWGs = 1024;   // sizes the workspace: split ceiling = kSplitTargetWGs / pairs
+constexpr int kDecodeTargetWGs = 512;   // workgroups the decode launch aims for
 constexpr int kMaxRec = 24576;      // largest supported block record in bytes (it is staged whole in LDS)
 
 struct Layout : mixkvq_block_layout_t {};
@@ -48,6 +49,8 @@ hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float
                          hipEvent_t ev_stop);
 
 size_t decode_workspace_bytes(const mixkvq_config& c);
+size_t decode_partials_bytes(const mixkvq_config& c);
+hipError_t launch_zero_counters(const CacheView& v, hipStream_t s);
 size_t select_workspace_bytes(const mixkvq_config& c);
 
 // ---- small device helpers used by several kernels ----
