@@ -132,6 +132,7 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="BASELINE configuration id (1, 2 or 3)")
     ap.add_argument("--copies", type=int, default=0, help="independent cache copies rotated over (0 = enough for 2x LLC)")
     ap.add_argument("--host-batch", type=int, default=2)
+    ap.add_argument("--tokens", type=int, default=0, help="override the context length of the configuration")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -145,6 +146,8 @@ def main():
     M.load_library()
 
     w = S.WORKLOADS[args.config]
+    if args.tokens:
+        w = S.scaled_workload(args.config, T=args.tokens)
     n_q0 = w.R * (-(-w.T // w.R) - 1)
     step_bytes = algorithmic_bytes(w, n_q0, w.T - n_q0)
     copies = args.copies or max(1, math.ceil(2 * LLC_BYTES / step_bytes))

@@ -74,8 +74,10 @@ __device__ __forceinline__ float xkg_sum(float v) {
   return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 // value of lane+8 inside each row of 16 lanes (0 for lanes 8..15)
-__device__ __forceinline__ float row_shl8(float v) {
-  return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(v), 0x108, 0xF, 0xF, true));
+__device__ __forceinline__ unsigned row_shl8u(unsigned v) { return __builtin_amdgcn_update_dpp(0u, v, 0x108, 0xF, 0xF, true); }
+// value of lane (i+8)%16 inside each row of 16 lanes
+__device__ __forceinline__ float row_ror8(float v) {
+  return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(v), 0x128, 0xF, 0xF, true));
 }
 
 // position exponent of code r%8 of a 16-code word after unpacking: value = c * 4^sc * 2^-24
@@ -159,12 +161,21 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 
   // running state (log2 domain)
   float m_run = -INFINITY, l_run = 0.f;
-  float zacc[NVG][5];
+  float zacc[NVG][4];   // sum p' z per register index; its position factor is a per-lane constant
+  // position exponent of pair i in this lane half: step 0 (lanes 0..7 of a row) or step 1 (lanes 8..15)
+  float sc2f[4];
+  unsigned w4sc[4];     // fp16 pair (4^sc, 4^sc)
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int sc = role ? sc2(4 + i) : i;
+    sc2f[i] = 2.f * sc;
+    w4sc[i] = ((unsigned)(15 + 2 * sc) << 10) * 0x00010001u;
+  }
   f32x4 O[2][4];   // [x'][q]: channels 64x' + 16kg + 4i + q
 #pragma unroll
   for (int a = 0; a < NVG; ++a)
 #pragma unroll
-    for (int c = 0; c < 5; ++c) zacc[a][c] = 0.f;
+    for (int c = 0; c < 4; ++c) zacc[a][c] = 0.f;
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -300,7 +311,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         for (int e = 0; e < 4; ++e) {
           const int a0 = 8 * kg + 2 * e;
           float lo = 0.f, hi = 0.f;
-          if (live && role == 0) {
+          if (live) {
             if (a0 < K16) lo = __half2float(qrow[sIdx[a0]]);
             if (a0 + 1 < K16) hi = __half2float(qrow[sIdx[a0 + 1]]);
           }
@@ -354,7 +365,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
             }
           }
           zd = xkg_sum(zd);
-          zdot = role ? 0.f : zd;
+          zdot = zd;
           // block exponent: scales are multiplied by 2^e0 so that the largest lands in [2^14, 2^15) (e0 <= 15),
           // and by 4^-sc, the position factor of the code they meet in the product
           float smax = fmaxf(half_lo(smax2), half_hi(smax2));
@@ -435,18 +446,26 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
           }
         }
 
-        // ---- logits, running maximum ----
-        float x2[4][4];
+        // ---- logits.  Only columns 0..7 carry heads, so two tiles share one register: lanes 0..7 of a
+        // row of 16 keep tile 0 (resp. 1), lanes 8..15 take tile 2 (resp. 3).  ror8 adds head and tail. ----
+        float xa[4], xb[4];     // packed logits: xa = tiles (0 | 2), xb = tiles (1 | 3)
         float mx = -INFINITY;
 #pragma unroll
-        for (int x = 0; x < 4; ++x)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const float s = S[x][i] + row_shl8(S[x][i]);
-            x2[x][i] = K16 > 0 ? fmaf(s, C, S16[x][i] * Cz) : fmaf(s, C, zc);
-            mx = fmaxf(mx, x2[x][i]);
+        for (int i = 0; i < 4; ++i) {
+          const float c0 = S[0][i] + row_ror8(S[0][i]), c2 = S[2][i] + row_ror8(S[2][i]);
+          const float c1 = S[1][i] + row_ror8(S[1][i]), c3 = S[3][i] + row_ror8(S[3][i]);
+          const float sa = role ? c2 : c0, sb = role ? c3 : c1;
+          if (K16 > 0) {
+            xa[i] = fmaf(sa, C, (role ? S16[2][i] : S16[0][i]) * Cz);
+            xb[i] = fmaf(sb, C, (role ? S16[3][i] : S16[1][i]) * Cz);
+          } else {
+            xa[i] = fmaf(sa, C, zc);
+            xb[i] = fmaf(sb, C, zc);
           }
+          mx = fmaxf(mx, fmaxf(xa[i], xb[i]));
+        }
         mx = xkg_max(mx);
+        mx = fmaxf(mx, row_ror8(mx));
         const float m_new = fmaxf(m_run, mx);
         if (__builtin_amdgcn_readfirstlane((int)__any(m_new > m_run))) {
           const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // exp2(-inf) = 0 on the first block
@@ -454,7 +473,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 #pragma unroll
           for (int a = 0; a < NVG; ++a)
 #pragma unroll
-            for (int c = 0; c < 5; ++c) zacc[a][c] *= alpha;
+            for (int c = 0; c < 4; ++c) zacc[a][c] *= alpha;
 #pragma unroll
           for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -462,61 +481,51 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
           m_run = m_new;
         }
 
-        // ---- p (fp16, with the position factor 4^-sc of the value code it meets), Ps = p * s_v ----
-        // this lane's tokens: 64*hsg + 16*kg + r; PV step st pairs r = i + 4st (tile 2st) with r + 8 (tile 2st+1)
-        unsigned p16[2][4];
-        float lsum = 0.f;
+        // ---- p in fp16 with the position factor 4^-sc of the value code it meets.  In lanes 0..7 pair i is
+        // (token i, token i+8) of this lane group's 16 tokens = PV step 0; in lanes 8..15 it is (4+i, 12+i) = step 1.
+        unsigned pk[4];
 #pragma unroll
-        for (int st = 0; st < 2; ++st)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int sc = sc2(4 * st + i);
-            const float msc = m_run + 2.f * sc;
-            p16[st][i] = cvt_pk(__builtin_amdgcn_exp2f(x2[2 * st][i] - msc), __builtin_amdgcn_exp2f(x2[2 * st + 1][i] - msc));
-            const unsigned w4sc = ((unsigned)(15 + 2 * sc) << 10) * 0x00010001u;   // fp16 pair 4^sc
-            lsum = dot2(p16[st][i], w4sc, lsum);
-          }
-        l_run += lsum;
+        for (int i = 0; i < 4; ++i) {
+          const float msc = m_run + sc2f[i];
+          pk[i] = cvt_pk(__builtin_amdgcn_exp2f(xa[i] - msc), __builtin_amdgcn_exp2f(xb[i] - msc));
+          l_run = dot2(pk[i], w4sc[i], l_run);
+        }
+        // value scales / zero-points of the tokens this lane half pairs: entries 4*role + i and 8 + 4*role + i
         u32x4 Bp[NVG][2];
         {
           const int t0 = 64 * hsg + 16 * kg;
           if (NVG == 1) {
-            const uint4* ps = reinterpret_cast<const uint4*>(sVm + 2 * t0);
-            const uint4* pz = reinterpret_cast<const uint4*>(sVm + 2 * R + 2 * t0);
-            const uint4 s0 = ps[0], s1 = ps[1], z0 = pz[0], z1 = pz[1];
-            const unsigned sl[4] = {s0.x, s0.y, s0.z, s0.w}, sh[4] = {s1.x, s1.y, s1.z, s1.w};
-            const unsigned zl[4] = {z0.x, z0.y, z0.z, z0.w}, zh[4] = {z1.x, z1.y, z1.z, z1.w};
+            const unsigned char* ps = sVm + 2 * (t0 + 4 * role);
+            const unsigned char* pz = sVm + 2 * R + 2 * (t0 + 4 * role);
+            const uint2 sl = *reinterpret_cast<const uint2*>(ps), sh = *reinterpret_cast<const uint2*>(ps + 16);
+            const uint2 zl = *reinterpret_cast<const uint2*>(pz), zh = *reinterpret_cast<const uint2*>(pz + 16);
+            const unsigned slv[2] = {sl.x, sl.y}, shv[2] = {sh.x, sh.y}, zlv[2] = {zl.x, zl.y}, zhv[2] = {zh.x, zh.y};
 #pragma unroll
-            for (int st = 0; st < 2; ++st)
-#pragma unroll
-              for (int i = 0; i < 4; ++i) {
-                const int r = i + 4 * st;
-                const unsigned selb = (r & 1) ? 0x07060302u : 0x05040100u;
-                Bp[0][st][i] = pk_mul(p16[st][i], __builtin_amdgcn_perm(sh[r >> 1], sl[r >> 1], selb));
-                zacc[0][sc2(r)] = dot2(p16[st][i], __builtin_amdgcn_perm(zh[r >> 1], zl[r >> 1], selb), zacc[0][sc2(r)]);
-              }
+            for (int i = 0; i < 4; ++i) {
+              const unsigned selb = (i & 1) ? 0x07060302u : 0x05040100u;
+              const unsigned pm = pk_mul(pk[i], __builtin_amdgcn_perm(shv[i >> 1], slv[i >> 1], selb));
+              Bp[0][0][i] = pm;
+              Bp[0][1][i] = row_shl8u(pm);
+              zacc[0][i] = dot2(pk[i], __builtin_amdgcn_perm(zhv[i >> 1], zlv[i >> 1], selb), zacc[0][i]);
+            }
           } else {
             // [token][2] layout: one dword per token, value group a in half a
-            const uint4* ps = reinterpret_cast<const uint4*>(sVm + 4 * t0);
-            const uint4* pz = reinterpret_cast<const uint4*>(sVm + 4 * R + 4 * t0);
-            unsigned sw[16], zw[16];
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-              const uint4 sv = ps[c], zv = pz[c];
-              sw[4 * c] = sv.x; sw[4 * c + 1] = sv.y; sw[4 * c + 2] = sv.z; sw[4 * c + 3] = sv.w;
-              zw[4 * c] = zv.x; zw[4 * c + 1] = zv.y; zw[4 * c + 2] = zv.z; zw[4 * c + 3] = zv.w;
-            }
+            const unsigned char* ps = sVm + 4 * (t0 + 4 * role);
+            const unsigned char* pz = sVm + 4 * R + 4 * (t0 + 4 * role);
+            const uint4 sl = *reinterpret_cast<const uint4*>(ps), sh = *reinterpret_cast<const uint4*>(ps + 32);
+            const uint4 zl = *reinterpret_cast<const uint4*>(pz), zh = *reinterpret_cast<const uint4*>(pz + 32);
+            const unsigned slv[4] = {sl.x, sl.y, sl.z, sl.w}, shv[4] = {sh.x, sh.y, sh.z, sh.w};
+            const unsigned zlv[4] = {zl.x, zl.y, zl.z, zl.w}, zhv[4] = {zh.x, zh.y, zh.z, zh.w};
 #pragma unroll
             for (int a = 0; a < NVG; ++a)
 #pragma unroll
-              for (int st = 0; st < 2; ++st)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                  const int r = i + 4 * st;
-                  const unsigned selb = a ? 0x07060302u : 0x05040100u;
-                  Bp[a][st][i] = pk_mul(p16[st][i], __builtin_amdgcn_perm(sw[r + 8], sw[r], selb));
-                  zacc[a][sc2(r)] = dot2(p16[st][i], __builtin_amdgcn_perm(zw[r + 8], zw[r], selb), zacc[a][sc2(r)]);
-                }
+              for (int i = 0; i < 4; ++i) {
+                const unsigned selb = a ? 0x07060302u : 0x05040100u;
+                const unsigned pm = pk_mul(pk[i], __builtin_amdgcn_perm(shv[i], slv[i], selb));
+                Bp[a][0][i] = pm;
+                Bp[a][1][i] = row_shl8u(pm);
+                zacc[a][i] = dot2(pk[i], __builtin_amdgcn_perm(zhv[i], zlv[i], selb), zacc[a][i]);
+              }
           }
         }
 
@@ -542,13 +551,15 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 
   // ---- wave results -> workgroup partial ------------------------------------------
   l_run = xkg_sum(l_run);
+  l_run += row_ror8(l_run);          // the two lane halves hold different tokens of the same head
   float zsum[NVG];
 #pragma unroll
   for (int a = 0; a < NVG; ++a) {
     float z = 0.f;
 #pragma unroll
-    for (int c = 0; c < 5; ++c) z = fmaf(zacc[a][c], (float)(1 << (2 * c)), z);
-    zsum[a] = xkg_sum(z);
+    for (int c = 0; c < 4; ++c) z = fmaf(zacc[a][c], __builtin_amdgcn_exp2f(sc2f[c]), z);
+    z = xkg_sum(z);
+    zsum[a] = z + row_ror8(z);
   }
   __syncthreads();   // every wave is done with its private LDS region
   float* sM = reinterpret_cast<float*>(smem + 2048 + 64);          // [waves][8]
@@ -616,14 +627,22 @@ __device__ __forceinline__ void residual_part(const CacheView& cv, const __half*
   if (t < n_res && h0 < g) {
     float s[4] = {0.f, 0.f, 0.f, 0.f};
     const __half* row = cv.res_k + ((size_t)p * R + t) * kD;
-    for (int d8 = 0; d8 < kD; d8 += 8) {
-      const uint4 raw = *reinterpret_cast<const uint4*>(row + d8);
+#pragma unroll 1
+    for (int d32 = 0; d32 < kD; d32 += 32) {       // four independent 16-byte loads per round
+      uint4 rows[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) rows[c] = *reinterpret_cast<const uint4*>(row + d32 + 8 * c);
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc) {
+      const int d8 = d32 + 8 * cc;
+      const uint4 raw = rows[cc];
       const unsigned ww[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const float k0 = half_lo(ww[c]), k1 = half_hi(ww[c]);
 #pragma unroll
         for (int i = 0; i < 4; ++i) s[i] = fmaf(sQ[(h0 + i) & 7][d8 + 2 * c + 1], k1, fmaf(sQ[(h0 + i) & 7][d8 + 2 * c], k0, s[i]));
+      }
       }
     }
 #pragma unroll
@@ -652,10 +671,18 @@ __device__ __forceinline__ void residual_part(const CacheView& cv, const __half*
   float* out = part + ((size_t)p * (n_splits + 1) + n_splits) * g * kPartStrideM;
   if (h0 < g) {
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int tt = 0; tt < n_res; ++tt) {
-      const float vv = __half2float(cv.res_v[((size_t)p * R + tt) * kD + d]);
+    const __half* vcol = cv.res_v + (size_t)p * R * kD + d;
+#pragma unroll 1
+    for (int t0 = 0; t0 < n_res; t0 += 8) {       // eight independent loads per round
+      __half vv[8];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) acc[i] = fmaf(sP[(h0 + i) & 7][tt], vv, acc[i]);
+      for (int c = 0; c < 8; ++c) vv[c] = vcol[(size_t)(t0 + c < n_res ? t0 + c : n_res - 1) * kD];
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        const float v = t0 + c < n_res ? __half2float(vv[c]) : 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i] = fmaf(sP[(h0 + i) & 7][t0 + c], v, acc[i]);
+      }
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i)
