@@ -67,18 +67,20 @@ typedef struct {
 /* Byte offsets of the planes inside one block record (R tokens of one
  * (batch, KV head) pair).  Every plane starts on a 16-byte boundary, padding is 0.
  *   idx    u8  [k16+k4]      fp16-tier channels ascending, then 4-bit-tier channels ascending
+ *   kmax   f16 [NG]          largest stored scale among the group's 2-bit and 4-bit channels (derived metadata)
  *   klo_s  f16 [NG][NLp]     scales of the 2-bit key channels (the non-salient channels, ascending)
  *   klo_z  f16 [NG][NLp]     zero-points (group minima, Eq. 2)
  *   k4_s   f16 [NG][k4]      4-bit tier scales, tier order;  k4_z likewise
- *   klo    u32 [R][Wlo]      16 two-bit codes per word along channels, code i in bits [2i, 2i+2)
- *   k4     u32 [R][k4/8]     8 four-bit codes per word, code i in bits [4i, 4i+4)
+ *   klo    u32 [R][Wlo]      16 two-bit codes per word along channels; even codes fill the low half-word, odd
+ *                            codes the high one: code i in bits [16(i&1) + 2(i>>1), +2)
+ *   k4     u32 [R][k4/8]     8 four-bit codes per word, code i in bits [16(i&1) + 4(i>>1), +4)
  *   k16    f16 [R][k16]      raw values of the fp16 tier
- *   v      u32 [R/16][D]     16 two-bit codes per word along TOKENS for one channel
+ *   v      u32 [R/16][D]     16 two-bit codes per word along TOKENS for one channel, same bit order as klo
  *   v_s    f16 [R][D/Gv]     value scales per (token, channel group);  v_z likewise
  * NL = D-k4-k16, Wlo = ceil(NL/16), NLp = 16*Wlo, NG = R/Gk, NVG = D/Gv, W4 = k4/8. */
 typedef struct {
   int32_t NL, Wlo, NLp, NG, NVG, W4;
-  int32_t off_idx, off_klo_s, off_klo_z, off_k4_s, off_k4_z, off_klo, off_k4, off_k16, off_v, off_v_s, off_v_z;
+  int32_t off_idx, off_kmax, off_klo_s, off_klo_z, off_k4_s, off_k4_z, off_klo, off_k4, off_k16, off_v, off_v_s, off_v_z;
   int32_t rec_bytes;
 } mixkvq_block_layout_t;
 

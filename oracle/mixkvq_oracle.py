@@ -192,6 +192,7 @@ class BlockLayout:
     NVG: int     # value groups per token
     W4: int      # u32 words per token for the 4-bit key plane
     off_idx: int
+    off_kmax: int
     off_klo_s: int
     off_klo_z: int
     off_k4_s: int
@@ -209,14 +210,17 @@ def block_layout(cfg: OracleConfig) -> BlockLayout:
     """Byte offsets of the planes inside one block record.  Every plane starts
     on a 16-byte boundary; padding bytes are zero.
       idx    u8  [ks]               fp16-tier channels ascending, then 4-bit tier ascending
+      kmax   f16 [NG]               largest stored scale of the group's 2-bit and 4-bit channels (derived
+                                    metadata: lets a reader normalise the scales without scanning them)
       klo_s  f16 [NG][NLp]          scales of the 2-bit key channels (ascending non-salient channels)
       klo_z  f16 [NG][NLp]          zero-points
       k4_s   f16 [NG][k4]           scales of the 4-bit tier (tier order)
       k4_z   f16 [NG][k4]
-      klo    u32 [R][Wlo]           16 two-bit codes per word along channels, code i in bits [2i, 2i+2)
-      k4     u32 [R][k4/8]          8 four-bit codes per word, code i in bits [4i, 4i+4)
+      klo    u32 [R][Wlo]           16 two-bit codes per word along channels; even codes fill the low half-word,
+                                    odd codes the high one: code i in bits [16(i&1) + 2(i>>1), +2)
+      k4     u32 [R][k4/8]          8 four-bit codes per word, code i in bits [16(i&1) + 4(i>>1), +4)
       k16    f16 [R][k16]           raw fp16 values of the fp16 tier
-      v      u32 [R/16][D]          16 two-bit codes per word along TOKENS for one channel
+      v      u32 [R/16][D]          16 two-bit codes per word along TOKENS for one channel, same bit order as klo
       v_s    f16 [R][D/Gv]          value scales per (token, channel group)
       v_z    f16 [R][D/Gv]
     """
@@ -229,7 +233,7 @@ def block_layout(cfg: OracleConfig) -> BlockLayout:
     W4 = cfg.k4 // 8
     off = 0
     offs = {}
-    for name, size in (("idx", cfg.ks), ("klo_s", NG * NLp * 2), ("klo_z", NG * NLp * 2),
+    for name, size in (("idx", cfg.ks), ("kmax", NG * 2), ("klo_s", NG * NLp * 2), ("klo_z", NG * NLp * 2),
                        ("k4_s", NG * cfg.k4 * 2), ("k4_z", NG * cfg.k4 * 2),
                        ("klo", R * Wlo * 4), ("k4", R * W4 * 4), ("k16", R * cfg.k16 * 2),
                        ("v", (R // 16) * D * 4), ("v_s", R * NVG * 2), ("v_z", R * NVG * 2)):
@@ -269,11 +273,14 @@ def quantize_block(cfg: OracleConfig, K16: np.ndarray, V16: np.ndarray, sel: np.
 
 
 def _pack_along_last(codes: np.ndarray, bits: int) -> np.ndarray:
-    """Pack codes [..., n] (n a multiple of 32/bits) into u32 [..., n*bits/32],
-    code i of a word in bits [bits*i, bits*i + bits)."""
+    """Pack codes [..., n] (n a multiple of 32/bits) into u32 [..., n*bits/32].
+    Code i of a word goes to bits [16*(i&1) + bits*(i>>1), + bits): even codes in
+    the low half-word, odd codes in the high half-word (an adjacent pair of
+    codes then sits at the same position of the two halves)."""
     per = 32 // bits
     c = codes.astype(np.uint32).reshape(codes.shape[:-1] + (codes.shape[-1] // per, per))
-    shifts = (np.arange(per, dtype=np.uint32) * np.uint32(bits))
+    i = np.arange(per, dtype=np.uint32)
+    shifts = np.uint32(16) * (i & 1) + np.uint32(bits) * (i >> 1)
     return np.bitwise_or.reduce(c << shifts, axis=-1).astype(np.uint32)
 
 
@@ -287,6 +294,8 @@ def pack_block(cfg: OracleConfig, blk: QuantBlock) -> np.ndarray:
         rec[off:off + b.size] = b
 
     put(lay.off_idx, blk.sel)
+    allscales = np.concatenate([blk.lo_s, blk.k4_s], axis=1)          # [NG, NL + k4] fp16, all >= 0
+    put(lay.off_kmax, allscales.max(axis=1).astype(np.float16))
     pad = lay.NLp - lay.NL
     s = np.pad(blk.lo_s, ((0, 0), (0, pad)))
     z = np.pad(blk.lo_z, ((0, 0), (0, pad)))

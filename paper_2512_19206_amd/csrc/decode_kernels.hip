@@ -99,7 +99,7 @@ decode_split_kernel(CacheView cv, const __half* __restrict__ q, float scale, int
         const __half* ls = reinterpret_cast<const __half*>(sRec + lay.off_klo_s) + grp * lay.NLp;
         const __half* lz = reinterpret_cast<const __half*>(sRec + lay.off_klo_z) + grp * lay.NLp;
         for (int jj = 0; jj < lay.NL; ++jj) {
-          const unsigned c = (klo[jj >> 4] >> (2 * (jj & 15))) & 3u;
+          const unsigned c = (klo[jj >> 4] >> (16 * (jj & 1) + 2 * ((jj & 15) >> 1))) & 3u;
           const float kv = (float)c * __half2float(ls[jj]) + __half2float(lz[jj]);
           const int d = sLoList[jj];
 #pragma unroll
@@ -109,7 +109,7 @@ decode_split_kernel(CacheView cv, const __half* __restrict__ q, float scale, int
         const __half* hs = reinterpret_cast<const __half*>(sRec + lay.off_k4_s) + grp * k4;
         const __half* hz = reinterpret_cast<const __half*>(sRec + lay.off_k4_z) + grp * k4;
         for (int jj = 0; jj < k4; ++jj) {
-          const unsigned c = (k4w[jj >> 3] >> (4 * (jj & 7))) & 15u;
+          const unsigned c = (k4w[jj >> 3] >> (16 * (jj & 1) + 4 * ((jj & 7) >> 1))) & 15u;
           const float kv = (float)c * __half2float(hs[jj]) + __half2float(hz[jj]);
           const int d = sRec[lay.off_idx + k16 + jj];
 #pragma unroll
@@ -176,7 +176,7 @@ decode_split_kernel(CacheView cv, const __half* __restrict__ q, float scale, int
 #pragma unroll
           for (int i16 = 0; i16 < 16; ++i16) {
             const int t = tg * 16 + i16;
-            const float vv = (float)((w >> (2 * i16)) & 3u) * __half2float(vs[t * lay.NVG + vg]) +
+            const float vv = (float)((w >> (16 * (i16 & 1) + 2 * (i16 >> 1))) & 3u) * __half2float(vs[t * lay.NVG + vg]) +
                              __half2float(vz[t * lay.NVG + vg]);
 #pragma unroll
             for (int i = 0; i < 4; ++i) acc[i] += sP[(h0 + i) & 7][t] * vv;

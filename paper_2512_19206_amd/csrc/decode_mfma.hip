@@ -91,7 +91,7 @@ __device__ __forceinline__ void unpack2(unsigned w, u32x4& a0, u32x4& a1) {
   a0[0] = w & 0x00030003u; a0[1] = w & 0x000C000Cu; a0[2] = w & 0x00300030u; a0[3] = w & 0x00C000C0u;
   a1[0] = w & 0x03000300u; a1[1] = w6 & 0x00300030u; a1[2] = w6 & 0x00C000C0u; a1[3] = w6 & 0x03000300u;
 }
-// four-bit word -> one A operand: pairs (0,4) (1,5) (2,6) (3,7)
+// four-bit word -> one A operand: code pairs (0,1) (2,3) (4,5) (6,7)
 __device__ __forceinline__ u32x4 unpack4(unsigned w) {
   const unsigned w8 = w >> 8;
   u32x4 a;
@@ -113,8 +113,8 @@ struct Tiers {
 // Contraction slots.  Every lane group runs the same code; a lane group whose word does not
 // exist reads a clamped address and meets a zero in the small operand.
 //   2-bit tier, step 2u+x (u < NU, x = 0,1): lane group kg unpacks half x of word c = 4u+kg;
-//       VGPR e pairs channels j and j+8 of the 2-bit list, j = 16c + 4x + e, position factor 4^sc2(4x+e)
-//   4-bit tier, one step: lane group kg unpacks word kg; VGPR e pairs tier entries 8kg+e, 8kg+e+4
+//       VGPR e pairs channels j and j+1 of the 2-bit list, j = 16c + 8x + 2e, position factor 4^sc2(4x+e)
+//   4-bit tier, one step: lane group kg unpacks word kg; VGPR e pairs tier entries 8kg+2e, 8kg+2e+1
 //   fp16 tier, one step: lane group kg takes tier entries 8kg .. 8kg+7 as they are
 
 template <int K4, int K16, int NVG, int NKL>
@@ -126,7 +126,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   const int R = cv.cfg.R, g = cv.g, Hq = cv.cfg.Hq, Hkv = cv.cfg.Hkv, Gk = cv.cfg.Gk, NB = cv.NB;
   const int rec_bytes = cv.lay.rec_bytes, off_idx = cv.lay.off_idx, off_klo_s = cv.lay.off_klo_s,
             off_klo_z = cv.lay.off_klo_z, off_k4_s = cv.lay.off_k4_s, off_k4_z = cv.lay.off_k4_z,
-            off_klo = cv.lay.off_klo, off_k4 = cv.lay.off_k4, off_k16 = cv.lay.off_k16, off_v = cv.lay.off_v,
+            off_kmax = cv.lay.off_kmax, off_klo = cv.lay.off_klo, off_k4 = cv.lay.off_k4, off_k16 = cv.lay.off_k16, off_v = cv.lay.off_v,
             off_v_s = cv.lay.off_v_s;
   const unsigned char* const blocks = cv.blocks;
   const int p = blockIdx.x, split = blockIdx.y - 1, tid = threadIdx.x;
@@ -146,7 +146,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   const int blk_hi = (int)((long long)n_blocks * (split + 1) / n_splits);
 
   // ---- per-lane constants -------------------------------------------------
-  const int tokbase = 16 * (n >> 2) + (n & 3);    // token of A-row n in tile (h, x): 64h + tokbase + {0,8,4,12}[x]
+  const int tokbase = 16 * (n >> 2) + 2 * (n & 3);   // token of A-row n in tile (h, x): 64h + tokbase + {0,1,8,9}[x]
   const int rec_chunks = rec_bytes >> 4;
   const int nvm = (rec_bytes - off_v_s) >> 4;     // 16-byte chunks of the value scale/zero planes
   // LDS byte offsets of this lane's words in token `tokbase` (clamped to existing words)
@@ -289,7 +289,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         for (int x = 0; x < 2; ++x)
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const int j0 = 16 * (4 * u + kg) + 4 * x + e, j1 = j0 + 8;
+            const int j0 = 16 * (4 * u + kg) + 8 * x + 2 * e, j1 = j0 + 1;
             float lo = 0.f, hi = 0.f;
             if (live && j0 < T::NL) lo = __half2float(qrow[sLo[j0]]);
             if (live && j1 < T::NL) hi = __half2float(qrow[sLo[j1]]);
@@ -300,8 +300,8 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         for (int e = 0; e < 4; ++e) {
           float lo = 0.f, hi = 0.f;
           if (live && kg < T::W4) {
-            lo = __half2float(qrow[sIdx[K16 + 8 * kg + e]]);
-            hi = __half2float(qrow[sIdx[K16 + 8 * kg + e + 4]]);
+            lo = __half2float(qrow[sIdx[K16 + 8 * kg + 2 * e]]);
+            hi = __half2float(qrow[sIdx[K16 + 8 * kg + 2 * e + 1]]);
           }
           qh4[e] = cvt_pk(lo, hi);
         }
@@ -329,48 +329,40 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         if ((64 * hsg) % Gk == 0) {
           const int grp = (64 * hsg) / Gk;
           // ---- small key operand of this group: Qs = q * s (head and tail), bias = sum q z ----
-          unsigned sp[2 * NU][4], sp4[4];   // scales of this lane's slots, paired like the codes
+          unsigned sp[2 * NU][4], sp4[4];   // scales of this lane's slots: adjacent pairs, as stored
           float zd = 0.f;
-          unsigned smax2 = 0u;
 #pragma unroll
           for (int u = 0; u < NU; ++u) {
             const int c = 4 * u + kg < T::Wlo ? 4 * u + kg : T::Wlo - 1;
             const uint4* ps = reinterpret_cast<const uint4*>(sK + off_klo_s + 2 * (grp * T::NLp + 16 * c));
             const uint4* pz = reinterpret_cast<const uint4*>(sK + off_klo_z + 2 * (grp * T::NLp + 16 * c));
-            const uint4 s0 = ps[0], s1 = ps[1], z0 = pz[0], z1 = pz[1];
-            const unsigned sl[4] = {s0.x, s0.y, s0.z, s0.w}, sh[4] = {s1.x, s1.y, s1.z, s1.w};
-            const unsigned zl[4] = {z0.x, z0.y, z0.z, z0.w}, zh[4] = {z1.x, z1.y, z1.z, z1.w};
 #pragma unroll
-            for (int x = 0; x < 2; ++x)
+            for (int x = 0; x < 2; ++x) {
+              const uint4 sv = ps[x], zv = pz[x];
+              const unsigned sw[4] = {sv.x, sv.y, sv.z, sv.w}, zw[4] = {zv.x, zv.y, zv.z, zv.w};
 #pragma unroll
               for (int e = 0; e < 4; ++e) {
-                const int r = 4 * x + e;      // pair (entry r, entry r + 8) of the word's 16 channels
-                const unsigned selb = (r & 1) ? 0x07060302u : 0x05040100u;
-                sp[2 * u + x][e] = __builtin_amdgcn_perm(sh[r >> 1], sl[r >> 1], selb);
-                zd = dot2(qlo[2 * u + x][e], __builtin_amdgcn_perm(zh[r >> 1], zl[r >> 1], selb), zd);
-                smax2 = pk_max(smax2, sp[2 * u + x][e]);
+                sp[2 * u + x][e] = sw[e];
+                zd = dot2(qlo[2 * u + x][e], zw[e], zd);
               }
+            }
           }
           if (K4 > 0) {
             const int w = kg < T::W4 ? kg : 0;
-            const uint4 s0 = *reinterpret_cast<const uint4*>(sK + off_k4_s + 2 * (grp * K4 + 8 * w));
-            const uint4 z0 = *reinterpret_cast<const uint4*>(sK + off_k4_z + 2 * (grp * K4 + 8 * w));
-            const unsigned sl[4] = {s0.x, s0.y, s0.z, s0.w}, zl[4] = {z0.x, z0.y, z0.z, z0.w};
+            const uint4 sv = *reinterpret_cast<const uint4*>(sK + off_k4_s + 2 * (grp * K4 + 8 * w));
+            const uint4 zv = *reinterpret_cast<const uint4*>(sK + off_k4_z + 2 * (grp * K4 + 8 * w));
+            const unsigned sw[4] = {sv.x, sv.y, sv.z, sv.w}, zw[4] = {zv.x, zv.y, zv.z, zv.w};
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {     // pair (entry e, entry e + 4)
-              const unsigned selb = (e & 1) ? 0x07060302u : 0x05040100u;
-              sp4[e] = __builtin_amdgcn_perm(sl[2 + (e >> 1)], sl[e >> 1], selb);
-              zd = dot2(qh4[e], __builtin_amdgcn_perm(zl[2 + (e >> 1)], zl[e >> 1], selb), zd);
-              smax2 = pk_max(smax2, sp4[e]);
+            for (int e = 0; e < 4; ++e) {
+              sp4[e] = sw[e];
+              zd = dot2(qh4[e], zw[e], zd);
             }
           }
           zd = xkg_sum(zd);
           zdot = zd;
           // block exponent: scales are multiplied by 2^e0 so that the largest lands in [2^14, 2^15) (e0 <= 15),
           // and by 4^-sc, the position factor of the code they meet in the product
-          float smax = fmaxf(half_lo(smax2), half_hi(smax2));
-          smax = xkg_max(smax);
-          int efs = (int)((__float_as_uint(smax) >> 23) & 0xff) - 127 + 15;
+          int efs = (int)(*reinterpret_cast<const unsigned short*>(sK + off_kmax + 2 * grp) >> 10);   // exponent field
           if (efs < 1) efs = 1;
           efs = __builtin_amdgcn_readfirstlane(efs);
           const int e0 = 29 - efs < 15 ? 29 - efs : 15;
@@ -400,8 +392,8 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
           zc = zdot * Cz;
         }
 
-        // ---- S^T tiles: tile x holds tokens 64*hsg + 16*(row/4) + row%4 + {0,8,4,12}[x] ----
-        constexpr int offx[4] = {0, 8, 4, 12};
+        // ---- S^T tiles: tile x holds tokens 64*hsg + 16*(row/4) + 2*(row%4) + {0,1,8,9}[x] ----
+        constexpr int offx[4] = {0, 1, 8, 9};
         unsigned wlo[NU][4], wh4[4];
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
@@ -482,7 +474,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         }
 
         // ---- p in fp16 with the position factor 4^-sc of the value code it meets.  In lanes 0..7 pair i is
-        // (token i, token i+8) of this lane group's 16 tokens = PV step 0; in lanes 8..15 it is (4+i, 12+i) = step 1.
+        // (token 2i, token 2i+1) of this lane group's 16 tokens = PV step 0; in lanes 8..15 it is (8+2i, 9+2i) = step 1.
         unsigned pk[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -490,41 +482,38 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
           pk[i] = cvt_pk(__builtin_amdgcn_exp2f(xa[i] - msc), __builtin_amdgcn_exp2f(xb[i] - msc));
           l_run = dot2(pk[i], w4sc[i], l_run);
         }
-        // value scales / zero-points of the tokens this lane half pairs: entries 4*role + i and 8 + 4*role + i
+        // value scales / zero-points of the tokens this lane half pairs
         u32x4 Bp[NVG][2];
         {
           const int t0 = 64 * hsg + 16 * kg;
           if (NVG == 1) {
-            const unsigned char* ps = sVm + 2 * (t0 + 4 * role);
-            const unsigned char* pz = sVm + 2 * R + 2 * (t0 + 4 * role);
-            const uint2 sl = *reinterpret_cast<const uint2*>(ps), sh = *reinterpret_cast<const uint2*>(ps + 16);
-            const uint2 zl = *reinterpret_cast<const uint2*>(pz), zh = *reinterpret_cast<const uint2*>(pz + 16);
-            const unsigned slv[2] = {sl.x, sl.y}, shv[2] = {sh.x, sh.y}, zlv[2] = {zl.x, zl.y}, zhv[2] = {zh.x, zh.y};
+            // pair i of this lane half = tokens (8*role + 2i, 8*role + 2i + 1): dword 4*role + i of the run
+            const uint4 sv = *reinterpret_cast<const uint4*>(sVm + 2 * t0 + 16 * role);
+            const uint4 zv = *reinterpret_cast<const uint4*>(sVm + 2 * R + 2 * t0 + 16 * role);
+            const unsigned sw[4] = {sv.x, sv.y, sv.z, sv.w}, zw[4] = {zv.x, zv.y, zv.z, zv.w};
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-              const unsigned selb = (i & 1) ? 0x07060302u : 0x05040100u;
-              const unsigned pm = pk_mul(pk[i], __builtin_amdgcn_perm(shv[i >> 1], slv[i >> 1], selb));
+              const unsigned pm = pk_mul(pk[i], sw[i]);
               Bp[0][0][i] = pm;
               Bp[0][1][i] = row_shl8u(pm);
-              zacc[0][i] = dot2(pk[i], __builtin_amdgcn_perm(zhv[i >> 1], zlv[i >> 1], selb), zacc[0][i]);
+              zacc[0][i] = dot2(pk[i], zw[i], zacc[0][i]);
             }
           } else {
-            // [token][2] layout: one dword per token, value group a in half a
-            const unsigned char* ps = sVm + 4 * (t0 + 4 * role);
-            const unsigned char* pz = sVm + 4 * R + 4 * (t0 + 4 * role);
-            const uint4 sl = *reinterpret_cast<const uint4*>(ps), sh = *reinterpret_cast<const uint4*>(ps + 32);
-            const uint4 zl = *reinterpret_cast<const uint4*>(pz), zh = *reinterpret_cast<const uint4*>(pz + 32);
-            const unsigned slv[4] = {sl.x, sl.y, sl.z, sl.w}, shv[4] = {sh.x, sh.y, sh.z, sh.w};
-            const unsigned zlv[4] = {zl.x, zl.y, zl.z, zl.w}, zhv[4] = {zh.x, zh.y, zh.z, zh.w};
+            // [token][2] layout: one dword per token, value group a in half a; tokens 8*role .. 8*role+7
+            const uint4* ps = reinterpret_cast<const uint4*>(sVm + 4 * t0 + 32 * role);
+            const uint4* pz = reinterpret_cast<const uint4*>(sVm + 4 * R + 4 * t0 + 32 * role);
+            const uint4 s0 = ps[0], s1 = ps[1], z0 = pz[0], z1 = pz[1];
+            const unsigned sw[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+            const unsigned zw[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
 #pragma unroll
             for (int a = 0; a < NVG; ++a)
 #pragma unroll
               for (int i = 0; i < 4; ++i) {
                 const unsigned selb = a ? 0x07060302u : 0x05040100u;
-                const unsigned pm = pk_mul(pk[i], __builtin_amdgcn_perm(shv[i], slv[i], selb));
+                const unsigned pm = pk_mul(pk[i], __builtin_amdgcn_perm(sw[2 * i + 1], sw[2 * i], selb));
                 Bp[a][0][i] = pm;
                 Bp[a][1][i] = row_shl8u(pm);
-                zacc[a][i] = dot2(pk[i], __builtin_amdgcn_perm(zhv[i], zlv[i], selb), zacc[a][i]);
+                zacc[a][i] = dot2(pk[i], __builtin_amdgcn_perm(zw[2 * i + 1], zw[2 * i], selb), zacc[a][i]);
               }
           }
         }

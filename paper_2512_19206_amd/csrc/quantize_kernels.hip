@@ -71,6 +71,7 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
   __shared__ unsigned char sLoList[kD];    // 2-bit channels, ascending
   __shared__ unsigned char sHiList[kD];    // fp16 tier then 4-bit tier
   __shared__ float sS[8 * kD], sZ[8 * kD]; // [group][channel] scale / zero-point of the channel's tier
+  __shared__ unsigned sKmax[8];            // per group: largest stored scale (fp16 bits; scales are >= 0)
 
   const mixkvq_config& cfg = cv.cfg;
   const Layout& lay = cv.lay;
@@ -83,6 +84,7 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
   for (int i = tid; i < lay.off_klo / 4; i += kFlushThreads) reinterpret_cast<unsigned*>(rec)[i] = 0u;
 
   load_tile(sT, cv.res_k, k_new, st, p, cfg.Hkv, R, r0, f * R);
+  if (tid < 8) sKmax[tid] = 0u;
   __syncthreads();
 
   // ---- channel tiers --------------------------------------------------
@@ -144,6 +146,7 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
     sS[grp * kD + d] = gp.s;
     sZ[grp * kD + d] = gp.z;
     const int pos = sPos[d];
+    atomicMax(&sKmax[grp], (unsigned)gp.s16);
     if (tier == 0) {
       reinterpret_cast<unsigned short*>(rec + lay.off_klo_s)[grp * lay.NLp + pos] = gp.s16;
       reinterpret_cast<unsigned short*>(rec + lay.off_klo_z)[grp * lay.NLp + pos] = gp.z16;
@@ -153,6 +156,7 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
     }
   }
   __syncthreads();
+  if (tid < NG) reinterpret_cast<unsigned short*>(rec + lay.off_kmax)[tid] = (unsigned short)sKmax[tid];
 
   // ---- 2-bit key words: [token][Wlo] ------------------------------------
   for (int it = tid; it < R * lay.Wlo; it += kFlushThreads) {
@@ -163,7 +167,7 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
       const int jj = wd * 16 + i;
       if (jj < lay.NL) {
         const int d = sLoList[jj];
-        w |= encode(__half2float(sT[t * kRowStride + d]), sZ[grp * kD + d], sS[grp * kD + d], 3.f) << (2 * i);
+        w |= encode(__half2float(sT[t * kRowStride + d]), sZ[grp * kD + d], sS[grp * kD + d], 3.f) << (16 * (i & 1) + 2 * (i >> 1));
       }
     }
     reinterpret_cast<unsigned*>(rec + lay.off_klo)[it] = w;
@@ -175,7 +179,7 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int d = sHiList[k16 + wd * 8 + i];
-      w |= encode(__half2float(sT[t * kRowStride + d]), sZ[grp * kD + d], sS[grp * kD + d], 15.f) << (4 * i);
+      w |= encode(__half2float(sT[t * kRowStride + d]), sZ[grp * kD + d], sS[grp * kD + d], 15.f) << (16 * (i & 1) + 4 * (i >> 1));
     }
     reinterpret_cast<unsigned*>(rec + lay.off_k4)[it] = w;
   }
@@ -215,7 +219,7 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int t = tg * 16 + i;
-      w |= encode(__half2float(sT[t * kRowStride + d]), sVZ[t * NVG + vg], sVS[t * NVG + vg], 3.f) << (2 * i);
+      w |= encode(__half2float(sT[t * kRowStride + d]), sVZ[t * NVG + vg], sVS[t * NVG + vg], 3.f) << (16 * (i & 1) + 2 * (i >> 1));
     }
     reinterpret_cast<unsigned*>(rec + lay.off_v)[it] = w;
   }

@@ -16,6 +16,15 @@ def _u32(raw, off):
     return int(np.frombuffer(raw[off:off + 4].tobytes(), dtype=np.uint32)[0])
 
 
+def _bit2(i):
+    """Bit offset of two-bit code i of a word: even codes low half-word, odd codes high half-word."""
+    return 16 * (i & 1) + 2 * (i >> 1)
+
+
+def _bit4(i):
+    return 16 * (i & 1) + 4 * (i >> 1)
+
+
 def brute_force_from_bytes(cfg, recs, res_k, res_v, n_res, q16, scale):
     """Decode attention written as explicit Python loops that read the packed
     block records bit by bit (layout as documented in block_layout) and apply
@@ -36,13 +45,13 @@ def brute_force_from_bytes(cfg, recs, res_k, res_v, n_res, q16, scale):
                 krow = [0.0] * cfg.D
                 for i, d in enumerate(lo):
                     w = _u32(raw, lay.off_klo + 4 * (t * lay.Wlo + i // 16))
-                    c = (w >> (2 * (i % 16))) & 3
+                    c = (w >> _bit2(i % 16)) & 3
                     s = _f16(raw, lay.off_klo_s + 2 * (grp * lay.NLp + i))
                     z = _f16(raw, lay.off_klo_z + 2 * (grp * lay.NLp + i))
                     krow[d] = c * s + z
                 for i, d in enumerate(hi4):
                     w = _u32(raw, lay.off_k4 + 4 * (t * lay.W4 + i // 8))
-                    c = (w >> (4 * (i % 8))) & 15
+                    c = (w >> _bit4(i % 8)) & 15
                     s = _f16(raw, lay.off_k4_s + 2 * (grp * cfg.k4 + i))
                     z = _f16(raw, lay.off_k4_z + 2 * (grp * cfg.k4 + i))
                     krow[d] = c * s + z
@@ -51,7 +60,7 @@ def brute_force_from_bytes(cfg, recs, res_k, res_v, n_res, q16, scale):
                 vrow = [0.0] * cfg.D
                 for d in range(cfg.D):
                     w = _u32(raw, lay.off_v + 4 * ((t // 16) * cfg.D + d))
-                    c = (w >> (2 * (t % 16))) & 3
+                    c = (w >> _bit2(t % 16)) & 3
                     vg = d // cfg.Gv
                     s = _f16(raw, lay.off_v_s + 2 * (t * lay.NVG + vg))
                     z = _f16(raw, lay.off_v_z + 2 * (t * lay.NVG + vg))

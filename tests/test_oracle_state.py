@@ -133,10 +133,10 @@ def test_record_layout_closed_form():
     cfg = O.OracleConfig(B=8, Hq=28, Hkv=4, D=128, T_max=32768, Gk=128, Gv=128, R=128, k4=16, k16=0)
     lay = O.block_layout(cfg)
     assert (lay.NL, lay.Wlo, lay.W4, lay.NG, lay.NVG) == (112, 7, 2, 1, 1)
-    # no padding in this configuration: the record is exactly the algorithmic bytes of 128 tokens
-    assert lay.rec_bytes == 9744
-    assert lay.rec_bytes * 255 + 128 * 128 * 4 + 7 * 128 * 4 == O.algorithmic_bytes_per_pair(cfg, 32640, 128)
-    for name in ("off_idx", "off_klo_s", "off_klo_z", "off_k4_s", "off_k4_z", "off_klo", "off_k4", "off_k16",
+    # the record is the algorithmic bytes of 128 tokens plus the 16-byte plane of derived scale maxima
+    assert lay.rec_bytes == 9744 + 16
+    assert (lay.rec_bytes - 16) * 255 + 128 * 128 * 4 + 7 * 128 * 4 == O.algorithmic_bytes_per_pair(cfg, 32640, 128)
+    for name in ("off_idx", "off_kmax", "off_klo_s", "off_klo_z", "off_k4_s", "off_k4_z", "off_klo", "off_k4", "off_k16",
                  "off_v", "off_v_s", "off_v_z"):
         assert getattr(lay, name) % 16 == 0
 
