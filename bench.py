@@ -172,8 +172,7 @@ def main():
     def step(i):
         gc = caches[i % copies]
         t = i % 64
-        M.mixkvq_quantize_append(gc, k1[:, :, t:t + 1], v1[:, :, t:t + 1])
-        M.mixkvq_decode_attention(gc, dq[i % 8], out=out, lse=lse, accumulate_q=True)
+        M.mixkvq_decode_step(gc, k1[:, :, t:t + 1], v1[:, :, t:t + 1], dq[i % 8], out=out, lse=lse, accumulate_q=True)
 
     i = 0
     for _ in range(args.warmup):
@@ -214,7 +213,7 @@ def main():
         "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "T": w.T, "Gk": w.Gk, "Gv": w.Gv,
                    "R": w.R, "k4": w.k4, "k16": w.k16, "cache_copies": copies,
                    "algorithmic_bytes_per_step": step_bytes,
-                   "step": "quantize_append(1 token, flush every R) + decode_attention(accumulate_q)"},
+                   "step": "decode_step = quantize_append(1 token, flush every R) + decode_attention(accumulate_q)"},
         "roofline": {"bound": "hbm", "kernel": "decode_fused_kernel", "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "kernel_avg_us": round(k_avg_ms * 1e3, 2), "kernel_min_us": round(min(k_ms) * 1e3, 2),

@@ -134,6 +134,14 @@ int mixkvq_quantize_append(mixkvq_cache* c, const void* k_new, const void* v_new
 int mixkvq_decode_attention(mixkvq_cache* c, const void* q, void* out, float* lse,
                             float scale, int32_t accumulate_q, void* stream);
 
+/* One decode step in the fewest launches: the same result and cache state as
+ * mixkvq_quantize_append(c, k_new, v_new, 1, kv_strides, NULL, stream) followed by
+ * mixkvq_decode_attention(c, q, out, lse, scale, accumulate_q, stream), with the same argument rules and
+ * errors (Appendix D.1: the new key/value enter the residual buffer; Eq. 1 over the cache).  When the append
+ * flushes no block, the attention launch moves the new rows into the window itself. */
+int mixkvq_decode_step(mixkvq_cache* c, const void* k_new, const void* v_new, const int64_t kv_strides[3],
+                       const void* q, void* out, float* lse, float scale, int32_t accumulate_q, void* stream);
+
 /* Profiling aid.  With a pair of hipEvent_t handles (HOST, created by the caller with timing enabled), every
  * following mixkvq_decode_attention on this cache records start_event just before and stop_event just after
  * its split-K attention kernel, on the call's stream.  Pass NULL, NULL to switch it off. */

@@ -12,5 +12,9 @@ def mixkvq_quantize_append(cache: Cache, k_new, v_new, sel=None, stream=None):
     return cache.quantize_append(k_new, v_new, sel=sel, stream=stream)
 
 
+def mixkvq_decode_step(cache: Cache, k_new, v_new, q, out=None, lse=None, scale=0.0, accumulate_q=False, stream=None):
+    return cache.decode_step(k_new, v_new, q, out=out, lse=lse, scale=scale, accumulate_q=accumulate_q, stream=stream)
+
+
 def mixkvq_decode_attention(cache: Cache, q, out=None, lse=None, scale=0.0, accumulate_q=False, stream=None):
     return cache.decode_attention(q, out=out, lse=lse, scale=scale, accumulate_q=accumulate_q, stream=stream)

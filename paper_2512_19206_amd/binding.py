@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libmixkvq.so")
 
 EXPORTS = ("mixkvq_block_layout", "mixkvq_cache_sizes", "mixkvq_cache_create", "mixkvq_cache_destroy",
            "mixkvq_cache_reset", "mixkvq_cache_state", "mixkvq_select_channels", "mixkvq_quantize_append",
-           "mixkvq_decode_attention", "mixkvq_set_timing_events", "mixkvq_strerror")
+           "mixkvq_decode_attention", "mixkvq_decode_step", "mixkvq_set_timing_events", "mixkvq_strerror")
 
 
 class Config(C.Structure):
@@ -69,6 +69,7 @@ def load_library() -> C.CDLL:
     lib.mixkvq_select_channels.argtypes = [vp, vp, i32, i64p, vp, i32, i64p, vp, vp]
     lib.mixkvq_quantize_append.argtypes = [vp, vp, vp, i32, i64p, vp, vp]
     lib.mixkvq_decode_attention.argtypes = [vp, vp, vp, vp, C.c_float, i32, vp]
+    lib.mixkvq_decode_step.argtypes = [vp, vp, vp, i64p, vp, vp, vp, C.c_float, i32, vp]
     lib.mixkvq_set_timing_events.argtypes = [vp, vp, vp]
     lib.mixkvq_strerror.argtypes = [i32]
     lib.mixkvq_strerror.restype = C.c_char_p
@@ -176,6 +177,18 @@ class Cache:
             lse = torch.empty(q.shape[:2], dtype=torch.float32, device=self.device)
         _check(self.lib.mixkvq_decode_attention(self.handle, q.data_ptr(), out.data_ptr(), lse.data_ptr(),
                                                 float(scale), int(bool(accumulate_q)), _stream_ptr(stream)))
+        return out, lse
+
+    def decode_step(self, k_new, v_new, q, out=None, lse=None, scale=0.0, accumulate_q=False, stream=None):
+        """k_new, v_new: fp16 [B, Hkv, 1, D]; q: fp16 [B, Hq, D] contiguous.  Append + attention in one call."""
+        assert q.is_contiguous() and k_new.stride() == v_new.stride() and k_new.shape[2] == 1
+        if out is None:
+            out = torch.empty_like(q)
+        if lse is None:
+            lse = torch.empty(q.shape[:2], dtype=torch.float32, device=self.device)
+        _check(self.lib.mixkvq_decode_step(self.handle, k_new.data_ptr(), v_new.data_ptr(), _strides3(k_new),
+                                           q.data_ptr(), out.data_ptr(), lse.data_ptr(), float(scale),
+                                           int(bool(accumulate_q)), _stream_ptr(stream)))
         return out, lse
 
     def set_timing_events(self, start_event, stop_event):

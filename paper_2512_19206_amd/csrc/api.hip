@@ -217,7 +217,33 @@ int mixkvq_decode_attention(mixkvq_cache* c, const void* q, void* out, float* ls
   hipStream_t s = (hipStream_t)stream;
   if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)cfg.D);
   MIXKVQ_TRY_HIP(launch_decode(c->v, (const __half*)q, (__half*)out, lse, scale, (int)(c->n_quant / cfg.R),
-                               c->n_res, accumulate_q, s, c->ev_start, c->ev_stop));
+                               c->n_res, accumulate_q, NewToken{nullptr, nullptr, {0, 0, 0}, 0}, s, c->ev_start,
+                               c->ev_stop));
+  return MIXKVQ_OK;
+}
+
+int mixkvq_decode_step(mixkvq_cache* c, const void* k_new, const void* v_new, const int64_t kv_strides[3],
+                       const void* q, void* out, float* lse, float scale, int32_t accumulate_q, void* stream) {
+  if (!c || !k_new || !v_new || !kv_strides || !q || !out) return MIXKVQ_EINVAL;
+  if (((uintptr_t)k_new & 15u) || ((uintptr_t)v_new & 15u)) return MIXKVQ_EINVAL;
+  for (int i = 0; i < 3; ++i)
+    if (kv_strides[i] % 8 != 0) return MIXKVQ_EINVAL;
+  const mixkvq_config& cfg = c->v.cfg;
+  const int R = cfg.R;
+  const int total = c->n_res + 1;
+  const bool flushes = cfg.flush_mode == 0 ? total > R : total >= R;
+  if (flushes) {   // the append flushes a block: take the general path for it
+    int rc = mixkvq_quantize_append(c, k_new, v_new, 1, kv_strides, nullptr, stream);
+    if (rc != MIXKVQ_OK) return rc;
+    return mixkvq_decode_attention(c, q, out, lse, scale, accumulate_q, stream);
+  }
+  hipStream_t s = (hipStream_t)stream;
+  if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)cfg.D);
+  NewToken nt{(const __half*)k_new, (const __half*)v_new, Strides3{kv_strides[0], kv_strides[1], kv_strides[2]},
+              c->n_res};
+  MIXKVQ_TRY_HIP(launch_decode(c->v, (const __half*)q, (__half*)out, lse, scale, (int)(c->n_quant / R), total,
+                               accumulate_q, nt, s, c->ev_start, c->ev_stop));
+  c->n_res = total;
   return MIXKVQ_OK;
 }
 

@@ -224,11 +224,12 @@ __global__ void __launch_bounds__(kD) decode_merge_kernel(const float* __restric
 }
 
 bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, int n_blocks, int n_res, int n_splits,
-                            float* part, unsigned* counters, __half* out, float* lse, int accumulate_q, hipStream_t s,
-                            hipEvent_t ev_start, hipEvent_t ev_stop, hipError_t* err);
+                            float* part, unsigned* counters, __half* out, float* lse, int accumulate_q, NewToken nt,
+                            hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop, hipError_t* err);
 
 hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float* lse, float scale, int n_blocks,
-                         int n_res, int accumulate_q, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
+                         int n_res, int accumulate_q, NewToken nt, hipStream_t s, hipEvent_t ev_start,
+                         hipEvent_t ev_stop) {
   // split count: enough workgroups to fill the chip (tunable through MIXKVQ_DECODE_WGS for experiments),
   // never above the ceiling the workspace was sized for
   static const int target_wgs = [] {
@@ -245,9 +246,13 @@ hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float
   // matrix-core path: one launch (n_splits partials from the quantized blocks, one from the residual
   // window, merged by the last workgroup of each pair)
   unsigned* counters = reinterpret_cast<unsigned*>(v.ws + decode_partials_bytes(v.cfg));
-  if (try_launch_decode_mfma(v, q, scale, n_blocks, n_res, n_splits, part, counters, out, lse, accumulate_q, s,
+  if (try_launch_decode_mfma(v, q, scale, n_blocks, n_res, n_splits, part, counters, out, lse, accumulate_q, nt, s,
                              ev_start, ev_stop, &e))
     return e;
+  if (nt.k) {   // this path does not move the new token itself
+    e = launch_residual_copy(v, nt.k, nt.v, nt.st, 0, nt.row, 1, s);
+    if (e != hipSuccess) return e;
+  }
   if (accumulate_q) {
     Strides3 qs{(int64_t)v.cfg.Hq * kD, (int64_t)kD, (int64_t)kD};
     e = launch_qabs_accumulate(v, q, 1, qs, s);

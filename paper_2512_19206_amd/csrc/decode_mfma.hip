@@ -117,13 +117,15 @@ struct Tiers {
 //   4-bit tier, one step: lane group kg unpacks word kg; VGPR e pairs tier entries 8kg+2e, 8kg+2e+1
 //   fp16 tier, one step: lane group kg takes tier entries 8kg .. 8kg+7 as they are
 
-template <int K4, int K16, int NVG, int NKL>
+template <int K4, int K16, int NVG, int NKL, int RG>
 __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __restrict__ q, float scale_log2e,
                                           int n_blocks, int n_splits, float* __restrict__ part, unsigned char* smem) {
   using T = Tiers<K4, K16>;
   constexpr int NU = T::NU;
   // scalars of the by-value view (kept in SGPRs; no references into the kernel argument)
-  const int R = cv.cfg.R, g = cv.g, Hq = cv.cfg.Hq, Hkv = cv.cfg.Hkv, Gk = cv.cfg.Gk, NB = cv.NB;
+  // RG = 1: R = Gk = 128 known at compile time (one straight-line body per block record)
+  const int R = RG ? 128 : cv.cfg.R, Gk = RG ? 128 : cv.cfg.Gk;
+  const int g = cv.g, Hq = cv.cfg.Hq, Hkv = cv.cfg.Hkv, NB = cv.NB;
   const int rec_bytes = cv.lay.rec_bytes, off_idx = cv.lay.off_idx, off_klo_s = cv.lay.off_klo_s,
             off_klo_z = cv.lay.off_klo_z, off_k4_s = cv.lay.off_k4_s, off_k4_z = cv.lay.off_k4_z,
             off_kmax = cv.lay.off_kmax, off_klo = cv.lay.off_klo, off_k4 = cv.lay.off_k4, off_k16 = cv.lay.off_k16, off_v = cv.lay.off_v,
@@ -593,7 +595,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void residual_part(const CacheView& cv, const __half* __restrict__ q, float scale, int n_res,
                                               int n_splits, float* __restrict__ part, int accumulate_q,
-                                              unsigned char* smem) {
+                                              const NewToken& nt, unsigned char* smem) {
   float (*sQ)[kD] = reinterpret_cast<float (*)[kD]>(smem);
   float (*sP)[kMaxR] = reinterpret_cast<float (*)[kMaxR]>(smem + 8 * kD * 4);
   float* sM = reinterpret_cast<float*>(smem + 8 * kD * 4 + 8 * kMaxR * 4);
@@ -604,6 +606,12 @@ __device__ __forceinline__ void residual_part(const CacheView& cv, const __half*
   const int b = p / cfg.Hkv, j = p % cfg.Hkv;
   const __half* qp = q + ((size_t)b * cfg.Hq + (size_t)j * g) * kD;
   for (int i = tid; i < g * kD; i += 256) sQ[i / kD][i % kD] = __half2float(qp[i]);
+  if (nt.k && tid < 32) {   // fused append: this step's key and value rows enter the window first
+    const int64_t src = (int64_t)b * nt.st.b + (int64_t)j * nt.st.h + (tid & 15) * 8;
+    const size_t dst = ((size_t)p * R + nt.row) * kD + (tid & 15) * 8;
+    if (tid < 16) *reinterpret_cast<uint4*>(cv.res_k + dst) = *reinterpret_cast<const uint4*>(nt.k + src);
+    else *reinterpret_cast<uint4*>(cv.res_v + dst) = *reinterpret_cast<const uint4*>(nt.v + src);
+  }
   if (accumulate_q && tid < kD) {
     unsigned long long acc = 0;
     for (int h = 0; h < g; ++h) acc += fix24_abs(h2bits(qp[h * kD + tid]));
@@ -745,23 +753,23 @@ decode_merge_pair_kernel(CacheView cv, const float* __restrict__ part, int n_par
 
 // One launch per decode step: workgroups (pair, split < n_splits) run the matrix-core part over their
 // blocks, workgroup (pair, n_splits) the residual window and the |q| accumulator.
-template <int K4, int K16, int NVG, int NKL>
+template <int K4, int K16, int NVG, int NKL, int RG>
 __global__ void __launch_bounds__(kMfmaThreads, 2)
 decode_fused_kernel(CacheView cv, const __half* __restrict__ q, float scale, int n_blocks, int n_res, int n_splits,
-                    float* __restrict__ part, int accumulate_q) {
+                    float* __restrict__ part, int accumulate_q, NewToken nt) {
   extern __shared__ __align__(16) unsigned char smem[];
   // the residual workgroups come first in dispatch order so that they do not form a tail
   if (blockIdx.y == 0)
-    residual_part(cv, q, scale, n_res, n_splits, part, accumulate_q, smem);
+    residual_part(cv, q, scale, n_res, n_splits, part, accumulate_q, nt, smem);
   else
-    mfma_part<K4, K16, NVG, NKL>(cv, q, scale * 1.4426950408889634f, n_blocks, n_splits, part, smem);
+    mfma_part<K4, K16, NVG, NKL, RG>(cv, q, scale * 1.4426950408889634f, n_blocks, n_splits, part, smem);
 }
 
-template <int K4, int K16, int NVG, int NKL>
+template <int K4, int K16, int NVG, int NKL, int RG>
 static hipError_t launch_one(const CacheView& v, const __half* q, float scale, int n_blocks, int n_res, int n_splits,
-                             float* part, unsigned* counters, __half* out, float* lse, int accumulate_q,
+                             float* part, unsigned* counters, __half* out, float* lse, int accumulate_q, NewToken nt,
                              hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
-  auto kern = decode_fused_kernel<K4, K16, NVG, NKL>;
+  auto kern = decode_fused_kernel<K4, K16, NVG, NKL, RG>;
   const size_t lds = 2048 + 64 + (size_t)kWaves * kWaveLds;
   static bool attr_set = false;
   if (!attr_set) {
@@ -770,7 +778,7 @@ static hipError_t launch_one(const CacheView& v, const __half* q, float scale, i
     attr_set = true;
   }
   if (ev_start) (void)hipEventRecord(ev_start, s);
-  kern<<<dim3(v.P, n_splits + 1), dim3(kMfmaThreads), lds, s>>>(v, q, scale, n_blocks, n_res, n_splits, part, accumulate_q);
+  kern<<<dim3(v.P, n_splits + 1), dim3(kMfmaThreads), lds, s>>>(v, q, scale, n_blocks, n_res, n_splits, part, accumulate_q, nt);
   if (ev_stop) (void)hipEventRecord(ev_stop, s);
   decode_merge_pair_kernel<<<dim3(v.P), dim3(256), 0, s>>>(v, part, n_splits + 1, out, lse);
   return hipGetLastError();
@@ -778,8 +786,8 @@ static hipError_t launch_one(const CacheView& v, const __half* q, float scale, i
 
 // Returns true and launches when the configuration is one the matrix-core kernel covers.
 bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, int n_blocks, int n_res, int n_splits,
-                            float* part, unsigned* counters, __half* out, float* lse, int accumulate_q, hipStream_t s,
-                            hipEvent_t ev_start, hipEvent_t ev_stop, hipError_t* err) {
+                            float* part, unsigned* counters, __half* out, float* lse, int accumulate_q, NewToken nt,
+                            hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop, hipError_t* err) {
   const mixkvq_config& c = v.cfg;
   if (c.R % 64 != 0 || c.Gk % 64 != 0 || c.Gv % 64 != 0 || n_blocks < 1) return false;
   if (v.lay.off_v > kKPartMax || v.lay.rec_bytes - v.lay.off_v_s > kVMetaMax) return false;
@@ -787,21 +795,24 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
   const int nkl = (v.lay.off_v / 16 + 63) / 64;
   hipError_t e = hipErrorInvalidValue;
   bool ok = true;
-#define MIXKVQ_CASE(K4_, K16_, NVG_, NKL_)                                                                          \
-  if (c.k4 == K4_ && c.k16 == K16_ && nvg == NVG_ && nkl <= NKL_)                                                   \
-    e = launch_one<K4_, K16_, NVG_, NKL_>(v, q, scale, n_blocks, n_res, n_splits, part, counters, out, lse,       \
-                                          accumulate_q, s, ev_start, ev_stop);                                         \
+#define MIXKVQ_CASE(K4_, K16_, NVG_, NKL_, RG_)                                                                     \
+  if (c.k4 == K4_ && c.k16 == K16_ && nvg == NVG_ && nkl <= NKL_ && (RG_ == 0 || (c.R == 128 && c.Gk == 128)))     \
+    e = launch_one<K4_, K16_, NVG_, NKL_, RG_>(v, q, scale, n_blocks, n_res, n_splits, part, counters, out, lse,   \
+                                               accumulate_q, nt, s, ev_start, ev_stop);                            \
   else
-  MIXKVQ_CASE(16, 0, 1, 6)
-  MIXKVQ_CASE(0, 12, 1, 8)
-  MIXKVQ_CASE(0, 0, 1, 6)
-  MIXKVQ_CASE(8, 0, 1, 6)
-  MIXKVQ_CASE(24, 0, 1, 6)
-  MIXKVQ_CASE(32, 0, 1, 6)
-  MIXKVQ_CASE(16, 0, 2, 6)
-  MIXKVQ_CASE(0, 12, 2, 8)
-  MIXKVQ_CASE(8, 4, 1, 8)
-  MIXKVQ_CASE(0, 32, 1, 8)
+  MIXKVQ_CASE(16, 0, 1, 6, 1)
+  MIXKVQ_CASE(0, 12, 1, 8, 1)
+  MIXKVQ_CASE(8, 0, 1, 6, 1)
+  MIXKVQ_CASE(16, 0, 1, 6, 0)
+  MIXKVQ_CASE(0, 12, 1, 8, 0)
+  MIXKVQ_CASE(0, 0, 1, 6, 0)
+  MIXKVQ_CASE(8, 0, 1, 6, 0)
+  MIXKVQ_CASE(24, 0, 1, 6, 0)
+  MIXKVQ_CASE(32, 0, 1, 6, 0)
+  MIXKVQ_CASE(16, 0, 2, 6, 0)
+  MIXKVQ_CASE(0, 12, 2, 8, 0)
+  MIXKVQ_CASE(8, 4, 1, 8, 0)
+  MIXKVQ_CASE(0, 32, 1, 8, 0)
   ok = false;
 #undef MIXKVQ_CASE
   if (!ok) return false;

@@ -18,6 +18,10 @@ struct Layout : mixkvq_block_layout_t {};
 
 struct Strides3 { int64_t b, h, t; };
 
+// One new token per sequence that the decode launch itself moves into residual-window row `row`
+// (k == nullptr: none).
+struct NewToken { const __half* k; const __half* v; Strides3 st; int row; };
+
 // Device-visible view of a cache: plain data passed by value to kernels.
 struct CacheView {
   mixkvq_config cfg;
@@ -45,7 +49,7 @@ hipError_t launch_flush(const CacheView& v, const __half* k_new, const __half* v
 hipError_t launch_residual_copy(const CacheView& v, const __half* k_new, const __half* v_new, Strides3 kvs,
                                 int src_first, int dst_first, int n, hipStream_t s);
 hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float* lse, float scale,
-                         int n_blocks, int n_res, int accumulate_q, hipStream_t s, hipEvent_t ev_start,
+                         int n_blocks, int n_res, int accumulate_q, NewToken nt, hipStream_t s, hipEvent_t ev_start,
                          hipEvent_t ev_stop);
 
 size_t decode_workspace_bytes(const mixkvq_config& c);

@@ -117,6 +117,37 @@ def test_decode_steps_with_flushes(H, flush_mode, qreset):
     assert oc.n_flush_calls >= 3
 
 
+@pytest.mark.parametrize("R,Gk,k4,k16,flush_mode", [(64, 64, 16, 0, 0), (128, 128, 0, 12, 0), (32, 32, 8, 0, 1)])
+def test_fused_decode_step(H, R, Gk, k4, k16, flush_mode):
+    """mixkvq_decode_step = append of one token + attention, across block flushes."""
+    rng = np.random.default_rng(17)
+    B, Hkv, g = 2, 2, 7
+    kw = dict(B=B, Hq=Hkv * g, Hkv=Hkv, D=128, T_max=6 * R, Gk=Gk, Gv=128, R=R, k4=k4, k16=k16, flush_mode=flush_mode)
+    oc, gc = H.make_pair(**kw)
+    n0 = 2 * R + 11
+    K = (rng.standard_normal((B, Hkv, n0, 128)) * rng.uniform(0.3, 8, 128)).astype(np.float16)
+    V = rng.standard_normal((B, Hkv, n0, 128)).astype(np.float16)
+    Qp = rng.standard_normal((B, Hkv * g, 16, 128)).astype(np.float16)
+    sel_ref = oc.select_channels(Qp, K)
+    sel = gc.select_channels(H.dev(Qp), H.dev(K))
+    oc.append(K, V, sel_ref)
+    gc.quantize_append(H.dev(K), H.dev(V), sel=sel)
+    for step in range(2 * R + 5):
+        k1 = (rng.standard_normal((B, Hkv, 1, 128)) * rng.uniform(0.3, 8, 128)).astype(np.float16)
+        v1 = rng.standard_normal((B, Hkv, 1, 128)).astype(np.float16)
+        q1 = (rng.standard_normal((B, Hkv * g, 128)) * rng.uniform(0.2, 5, 128)).astype(np.float16)
+        oc.append(k1, v1)
+        ro, rl = oc.decode_attention(q1, accumulate_q=True)
+        out, lse = gc.decode_step(H.dev(k1), H.dev(v1), H.dev(q1), accumulate_q=True)
+        torch.cuda.synchronize()
+        err = np.abs(out.float().cpu().numpy() - ro)
+        assert np.all(err <= H.ATOL + H.RTOL * np.abs(ro)), (step, float(err.max()))
+        assert np.all(np.abs(lse.cpu().numpy() - rl) <= H.LSE_ATOL + 1e-4 * np.abs(rl))
+        if step % 37 == 36 or step == 2 * R + 4:
+            H.check_state(oc, gc)
+    assert oc.n_flush_calls >= 2
+
+
 def test_chunked_append_without_selection_matches_oracle(H):
     """sel = NULL on a multi-token append: every flushed block is scored on its own."""
     rng = np.random.default_rng(8)
