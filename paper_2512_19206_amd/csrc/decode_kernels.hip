@@ -237,7 +237,7 @@ hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float
     int t = e ? atoi(e) : 0;
     return t > 0 ? t : kDecodeTargetWGs;
   }();
-  int n_splits = target_wgs / v.P - 1;   // one more workgroup per pair takes the residual window
+  int n_splits = target_wgs / v.P;
   if (n_splits > max_splits_for(v.P)) n_splits = max_splits_for(v.P);
   if (n_splits > n_blocks) n_splits = n_blocks;
   if (n_splits < 1) n_splits = 1;

@@ -119,7 +119,8 @@ struct Tiers {
 
 template <int K4, int K16, int NVG, int NKL, int RG>
 __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __restrict__ q, float scale_log2e,
-                                          int n_blocks, int n_splits, float* __restrict__ part, unsigned char* smem) {
+                                          int n_blocks, int n_res, int n_splits, float* __restrict__ part,
+                                          int accumulate_q, const NewToken& nt, unsigned char* smem) {
   using T = Tiers<K4, K16>;
   constexpr int NU = T::NU;
   // scalars of the by-value view (kept in SGPRs; no references into the kernel argument)
@@ -131,7 +132,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
             off_kmax = cv.lay.off_kmax, off_klo = cv.lay.off_klo, off_k4 = cv.lay.off_k4, off_k16 = cv.lay.off_k16, off_v = cv.lay.off_v,
             off_v_s = cv.lay.off_v_s;
   const unsigned char* const blocks = cv.blocks;
-  const int p = blockIdx.x, split = blockIdx.y - 1, tid = threadIdx.x;
+  const int p = blockIdx.x, split = blockIdx.y, tid = threadIdx.x;
   const int b = p / Hkv, jkv = p % Hkv;
   const int wave = tid >> 6, lane = tid & 63, n = lane & 15, kg = lane >> 4;
   const int head = n & 7, role = n >> 3;     // role 0: head of q*s, role 1: tail
@@ -144,8 +145,21 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   unsigned char* sVm = wbase + kKPartMax;                           // v_s, v_z planes
   unsigned char* sLo = wbase + kKPartMax + kVMetaMax;               // 2-bit channel list [128], then salient idx [<=64]
 
-  const int blk_lo = (int)((long long)n_blocks * split / n_splits);
-  const int blk_hi = (int)((long long)n_blocks * (split + 1) / n_splits);
+  // Work units of the pair: its block records, then the residual window in sub-units of 32 tokens, dealt
+  // round-robin over all wavefronts of the pair's workgroups.
+  const int gw = split * kWaves + wave, n_gw = n_splits * kWaves;
+  // The wavefronts of a workgroup take neighbouring records at the same time (wavefront w of workgroup s
+  // takes units s*4 + w, then + 4*n_splits, ...): the chip streams a few long contiguous ranges.
+  const int blk_lo = gw;
+  const int blk_hi = n_blocks;
+  const int blk_step = n_gw;
+  // residual window: sub-units of 32 tokens follow the records in the same round-robin deal
+  const int n_sub = (n_res + 31) >> 5;
+  int my_sub = -1;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    if (j < n_sub && (n_blocks + j) % n_gw == gw) my_sub = j;
+  const bool bookkeeper = n_sub > 0 ? my_sub == n_sub - 1 : gw == 0;   // the new token lies in the last sub-unit
 
   // ---- per-lane constants -------------------------------------------------
   const int tokbase = 16 * (n >> 2) + 2 * (n & 3);   // token of A-row n in tile (h, x): 64h + tokbase + {0,1,8,9}[x]
@@ -220,7 +234,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         vreg[h][x] = *reinterpret_cast<const u32x4*>(vw_ + (4 * (h * 64 < R ? h : 0) + kg) * kD + 64 * x + 4 * n); \
   }
 
-  int blk = blk_lo + wave;
+  int blk = blk_lo;
   if (blk < blk_hi) {
     MIXKVQ_ISSUE_K_LOADS(blk)
     MIXKVQ_ISSUE_V_LOADS(blk)
@@ -246,12 +260,107 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   const int Eq = sEq[head];
 
 
-  for (; blk < blk_hi; blk += kWaves) {
+  // ---- residual window (fp16 keys/values): 32 tokens per wavefront, before its block records ----
+  if (bookkeeper) {   // this step's new token enters the window; |q| joins the accumulator (one writer per pair)
+    if (nt.k && lane < 32) {
+      const int64_t src = (int64_t)b * nt.st.b + (int64_t)jkv * nt.st.h + (lane & 15) * 8;
+      const size_t dst = ((size_t)p * R + nt.row) * kD + (lane & 15) * 8;
+      if (lane < 16) *reinterpret_cast<uint4*>(cv.res_k + dst) = *reinterpret_cast<const uint4*>(nt.k + src);
+      else *reinterpret_cast<uint4*>(cv.res_v + dst) = *reinterpret_cast<const uint4*>(nt.v + src);
+    }
+    if (accumulate_q) {
+#pragma unroll
+      for (int hc = 0; hc < 2; ++hc) {
+        const int d = lane + 64 * hc;
+        unsigned long long acc = 0;
+        for (int h = 0; h < g; ++h) acc += fix24_abs(h2bits(q[((size_t)b * Hq + jkv * g + h) * kD + d]));
+        cv.qacc[(size_t)p * kD + d] += acc;
+      }
+      if (lane == 0) cv.qcnt[p] += (unsigned long long)g;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");   // the new rows are read back below
+  }
+  if (my_sub >= 0) {
+    const int t0 = 32 * my_sub;
+    const __half* rk = cv.res_k + ((size_t)p * R + t0) * kD;
+    const __half* rv = cv.res_v + ((size_t)p * R + t0) * kD;
+    constexpr int kVStride = 264;     // bytes per staged value row (+8 against bank conflicts)
+    const int tokb = 8 * (n >> 2) + 2 * (n & 3);      // A-row n of tile x: token t0 + tokb + x
+    // all loads of the sub-unit at once: 2 key tiles x 4 steps, 32 value rows
+    u32x4 kr[2][4];
+    uint4 vr[8];
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+      for (int st = 0; st < 4; ++st)
+        kr[x][st] = *reinterpret_cast<const u32x4*>(rk + (size_t)(tokb + x) * kD + 8 * kg + 32 * st);
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int ci = it * 64 + lane;
+      vr[it] = *reinterpret_cast<const uint4*>(rv + (size_t)(ci >> 4) * kD + 8 * (ci & 15));
+    }
+    const float Cres = ldexpf(scale_log2e, Eq);
+    f32x4 S0 = {0.f, 0.f, 0.f, 0.f}, S1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+      u32x4 bq;       // normalised q in natural channel order; columns 8..15 stay zero
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        bq[e] = (role == 0 && live) ? *reinterpret_cast<const unsigned*>(sQn + head * kD + 32 * st + 8 * kg + 2 * e) : 0u;
+      S0 = mfma(kr[0][st], bq, S0);
+      S1 = mfma(kr[1][st], bq, S1);
+    }
+    float xa[4], xb[4];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int tok = t0 + 8 * kg + 2 * i;      // token of xa; xb is the next one
+      xa[i] = (role == 0 && tok < n_res) ? S0[i] * Cres : -INFINITY;
+      xb[i] = (role == 0 && tok + 1 < n_res) ? S1[i] * Cres : -INFINITY;
+      mx = fmaxf(mx, fmaxf(xa[i], xb[i]));
+    }
+    mx = xkg_max(mx);
+    mx = fmaxf(mx, row_ror8(mx));       // finite: token t0 is valid
+    m_run = mx;                          // nothing has been accumulated yet
+    u32x4 Bp;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      Bp[i] = cvt_pk(__builtin_amdgcn_exp2f(xa[i] - m_run), __builtin_amdgcn_exp2f(xb[i] - m_run));
+      l_run = dot2(Bp[i], 0x3c003c00u, l_run);
+    }
+    // values through LDS (rows beyond the window are zeroed), read back transposed: A row = channel,
+    // slot pair = adjacent tokens
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int ci = it * 64 + lane, rowi = ci >> 4, c16 = ci & 15;
+      uint4 v = vr[it];
+      if (t0 + rowi >= n_res) v = make_uint4(0u, 0u, 0u, 0u);
+      uint2* dst = reinterpret_cast<uint2*>(sK + rowi * kVStride + 16 * c16);
+      dst[0] = make_uint2(v.x, v.y);
+      dst[1] = make_uint2(v.z, v.w);
+    }
+#pragma unroll
+    for (int xp = 0; xp < 2; ++xp)
+#pragma unroll
+      for (int qq = 0; qq < 4; ++qq) {
+        u32x4 a;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const unsigned short* cp = reinterpret_cast<const unsigned short*>(sK + (8 * kg + 2 * e) * kVStride) + 64 * xp + 4 * n + qq;
+          a[e] = (unsigned)cp[0] | ((unsigned)cp[kVStride / 2] << 16);
+        }
+        // the block loop accumulates sum p' c 4^sc 2^-24 and is scaled by 2^24 at the end
+        const f32x4 t = mfma(a, Bp, f32x4{0.f, 0.f, 0.f, 0.f});
+        O[xp][qq] = t * 5.9604644775390625e-8f;
+      }
+  }
+
+  for (; blk < blk_hi; blk += blk_step) {
     // ---- stage the key part and value metadata in LDS (wave-private: no barrier needed) ----
 #pragma unroll
     for (int c = 0; c < NKL; ++c) reinterpret_cast<u32x4*>(sK)[c * 64 + lane] = kreg[c];
     reinterpret_cast<u32x4*>(sVm)[lane < nvm ? lane : nvm - 1] = vmreg;
-    if (blk + kWaves < blk_hi) MIXKVQ_ISSUE_K_LOADS(blk + kWaves)
+    if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_K_LOADS(blk + blk_step)
 
     // ---- channel selection of this block: rebuild q in slot order if it changed ----
     bool rebuild = false;
@@ -535,7 +644,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         }
       }
     }
-    if (blk + kWaves < blk_hi) MIXKVQ_ISSUE_V_LOADS(blk + kWaves)
+    if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_V_LOADS(blk + blk_step)
   }
 #undef MIXKVQ_ISSUE_K_LOADS
 #undef MIXKVQ_ISSUE_V_LOADS
@@ -579,115 +688,13 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
     __syncthreads();
   }
   // natural-log domain for the merge kernel: m_e = m2 * ln2
-  float* out = part + ((size_t)p * (n_splits + 1) + split) * g * kPartStrideM;
+  float* out = part + ((size_t)p * n_splits + split) * g * kPartStrideM;
   for (int i = tid; i < g * kD; i += kMfmaThreads) out[(i / kD) * kPartStrideM + (i % kD)] = sO[i];
   if (tid < g) {
     float mw = -INFINITY;
     for (int w = 0; w < kWaves; ++w) mw = fmaxf(mw, sM[w * 8 + tid]);
     out[tid * kPartStrideM + kD] = mw * 0.6931471805599453f;
     out[tid * kPartStrideM + kD + 1] = sO[8 * kD + tid];
-  }
-}
-
-// ---------------------------------------------------------------------------
-// Residual window (fp16 keys and values) and the |q| accumulator: one workgroup
-// per pair, plain vector ALU; it writes partial number n_splits.
-// ---------------------------------------------------------------------------
-__device__ __forceinline__ void residual_part(const CacheView& cv, const __half* __restrict__ q, float scale, int n_res,
-                                              int n_splits, float* __restrict__ part, int accumulate_q,
-                                              const NewToken& nt, unsigned char* smem) {
-  float (*sQ)[kD] = reinterpret_cast<float (*)[kD]>(smem);
-  float (*sP)[kMaxR] = reinterpret_cast<float (*)[kMaxR]>(smem + 8 * kD * 4);
-  float* sM = reinterpret_cast<float*>(smem + 8 * kD * 4 + 8 * kMaxR * 4);
-  float* sL = sM + 8;
-  const mixkvq_config& cfg = cv.cfg;
-  const int R = cfg.R, g = cv.g;
-  const int p = blockIdx.x, tid = threadIdx.x;
-  const int b = p / cfg.Hkv, j = p % cfg.Hkv;
-  const __half* qp = q + ((size_t)b * cfg.Hq + (size_t)j * g) * kD;
-  for (int i = tid; i < g * kD; i += 256) sQ[i / kD][i % kD] = __half2float(qp[i]);
-  if (nt.k && tid < 32) {   // fused append: this step's key and value rows enter the window first
-    const int64_t src = (int64_t)b * nt.st.b + (int64_t)j * nt.st.h + (tid & 15) * 8;
-    const size_t dst = ((size_t)p * R + nt.row) * kD + (tid & 15) * 8;
-    if (tid < 16) *reinterpret_cast<uint4*>(cv.res_k + dst) = *reinterpret_cast<const uint4*>(nt.k + src);
-    else *reinterpret_cast<uint4*>(cv.res_v + dst) = *reinterpret_cast<const uint4*>(nt.v + src);
-  }
-  if (accumulate_q && tid < kD) {
-    unsigned long long acc = 0;
-    for (int h = 0; h < g; ++h) acc += fix24_abs(h2bits(qp[h * kD + tid]));
-    cv.qacc[(size_t)p * kD + tid] += acc;     // one writer per element
-    if (tid == 0) cv.qcnt[p] += (unsigned long long)g;
-  }
-  __syncthreads();
-  // logits: thread (token, head half)
-  const int t = tid & 127, h0 = (tid >> 7) * 4;
-  if (t < n_res && h0 < g) {
-    float s[4] = {0.f, 0.f, 0.f, 0.f};
-    const __half* row = cv.res_k + ((size_t)p * R + t) * kD;
-#pragma unroll 1
-    for (int d32 = 0; d32 < kD; d32 += 32) {       // four independent 16-byte loads per round
-      uint4 rows[4];
-#pragma unroll
-      for (int c = 0; c < 4; ++c) rows[c] = *reinterpret_cast<const uint4*>(row + d32 + 8 * c);
-#pragma unroll
-      for (int cc = 0; cc < 4; ++cc) {
-      const int d8 = d32 + 8 * cc;
-      const uint4 raw = rows[cc];
-      const unsigned ww[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const float k0 = half_lo(ww[c]), k1 = half_hi(ww[c]);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) s[i] = fmaf(sQ[(h0 + i) & 7][d8 + 2 * c + 1], k1, fmaf(sQ[(h0 + i) & 7][d8 + 2 * c], k0, s[i]));
-      }
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      if (h0 + i < g) sP[h0 + i][t] = s[i] * scale;
-  }
-  __syncthreads();
-  {
-    const int wave = tid >> 6, lane = tid & 63;
-    for (int h = wave; h < g; h += 4) {
-      const float x0 = lane < n_res ? sP[h][lane] : -INFINITY;
-      const float x1 = lane + 64 < n_res ? sP[h][lane + 64] : -INFINITY;
-      float mx = fmaxf(x0, x1);
-      for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-      const float e0 = lane < n_res ? __expf(x0 - mx) : 0.f;
-      const float e1 = lane + 64 < n_res ? __expf(x1 - mx) : 0.f;
-      float sum = e0 + e1;
-      for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-      if (lane < n_res) sP[h][lane] = e0;
-      if (lane + 64 < n_res) sP[h][lane + 64] = e1;
-      if (lane == 0) { sM[h] = mx; sL[h] = sum; }
-    }
-  }
-  __syncthreads();
-  const int d = tid & 127;
-  float* out = part + ((size_t)p * (n_splits + 1) + n_splits) * g * kPartStrideM;
-  if (h0 < g) {
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    const __half* vcol = cv.res_v + (size_t)p * R * kD + d;
-#pragma unroll 1
-    for (int t0 = 0; t0 < n_res; t0 += 8) {       // eight independent loads per round
-      __half vv[8];
-#pragma unroll
-      for (int c = 0; c < 8; ++c) vv[c] = vcol[(size_t)(t0 + c < n_res ? t0 + c : n_res - 1) * kD];
-#pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        const float v = t0 + c < n_res ? __half2float(vv[c]) : 0.f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) acc[i] = fmaf(sP[(h0 + i) & 7][t0 + c], v, acc[i]);
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      if (h0 + i < g) out[(h0 + i) * kPartStrideM + d] = acc[i];
-  }
-  if (tid < g) {
-    out[tid * kPartStrideM + kD] = n_res > 0 ? sM[tid] : -INFINITY;
-    out[tid * kPartStrideM + kD + 1] = n_res > 0 ? sL[tid] : 0.f;
   }
 }
 
@@ -751,18 +758,15 @@ decode_merge_pair_kernel(CacheView cv, const float* __restrict__ part, int n_par
   }
 }
 
-// One launch per decode step: workgroups (pair, split < n_splits) run the matrix-core part over their
-// blocks, workgroup (pair, n_splits) the residual window and the |q| accumulator.
+// One launch per decode step: the workgroups (pair, split) share the pair's block records and its
+// residual window.
 template <int K4, int K16, int NVG, int NKL, int RG>
 __global__ void __launch_bounds__(kMfmaThreads, 2)
 decode_fused_kernel(CacheView cv, const __half* __restrict__ q, float scale, int n_blocks, int n_res, int n_splits,
                     float* __restrict__ part, int accumulate_q, NewToken nt) {
   extern __shared__ __align__(16) unsigned char smem[];
-  // the residual workgroups come first in dispatch order so that they do not form a tail
-  if (blockIdx.y == 0)
-    residual_part(cv, q, scale, n_res, n_splits, part, accumulate_q, nt, smem);
-  else
-    mfma_part<K4, K16, NVG, NKL, RG>(cv, q, scale * 1.4426950408889634f, n_blocks, n_splits, part, smem);
+  mfma_part<K4, K16, NVG, NKL, RG>(cv, q, scale * 1.4426950408889634f, n_blocks, n_res, n_splits, part, accumulate_q, nt,
+                                   smem);
 }
 
 template <int K4, int K16, int NVG, int NKL, int RG>
@@ -778,9 +782,9 @@ static hipError_t launch_one(const CacheView& v, const __half* q, float scale, i
     attr_set = true;
   }
   if (ev_start) (void)hipEventRecord(ev_start, s);
-  kern<<<dim3(v.P, n_splits + 1), dim3(kMfmaThreads), lds, s>>>(v, q, scale, n_blocks, n_res, n_splits, part, accumulate_q, nt);
+  kern<<<dim3(v.P, n_splits), dim3(kMfmaThreads), lds, s>>>(v, q, scale, n_blocks, n_res, n_splits, part, accumulate_q, nt);
   if (ev_stop) (void)hipEventRecord(ev_stop, s);
-  decode_merge_pair_kernel<<<dim3(v.P), dim3(256), 0, s>>>(v, part, n_splits + 1, out, lse);
+  decode_merge_pair_kernel<<<dim3(v.P), dim3(256), 0, s>>>(v, part, n_splits, out, lse);
   return hipGetLastError();
 }
 
