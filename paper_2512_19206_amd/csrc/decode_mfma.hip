@@ -36,6 +36,21 @@ constexpr int kVMetaMax = 1024;                 // value scales + zero-points of
 constexpr int kWaveLds = kKPartMax + kVMetaMax + 256;   // + channel lists
 constexpr int kPartStrideM = kD + 2;
 
+#ifdef MIXKVQ_PHASE_CLOCKS
+// Profiling aid, not part of the default build: 100 MHz timestamps of each wavefront's phases.
+__device__ unsigned long long g_phase_clock[4096 * 16];
+#define MIXKVQ_PHASE(K_)                                                                              \
+  if (lane == 0)                                                                                      \
+    g_phase_clock[((blockIdx.y * gridDim.x + blockIdx.x) * kWaves + wave) % 4096 * 16 + (K_)] = wall_clock64();
+// slots 12 and 13: the shader clock at the first and the last phase
+#define MIXKVQ_PHASE_CYCLES(K_)                                                                       \
+  if (lane == 0)                                                                                      \
+    g_phase_clock[((blockIdx.y * gridDim.x + blockIdx.x) * kWaves + wave) % 4096 * 16 + (K_)] = clock64();
+#else
+#define MIXKVQ_PHASE(K_)
+#define MIXKVQ_PHASE_CYCLES(K_)
+#endif
+
 __device__ __forceinline__ f32x4 mfma(u32x4 a, u32x4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
@@ -99,6 +114,19 @@ __device__ __forceinline__ u32x4 unpack4(unsigned w) {
   return a;
 }
 
+// Eight channel numbers at `list8` -> four fp16 pairs of the row `qrow`; entries from `n_valid` on give zero.
+__device__ __forceinline__ void gather8(const unsigned char* list8, const unsigned short* qrow, int n_valid,
+                                        unsigned (&out)[4]) {
+  unsigned w[2];
+  __builtin_memcpy(w, list8, 8);     // the fp16-tier list may start at any byte
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const unsigned pr = w[e >> 1] >> (16 * (e & 1));
+    const unsigned lo = qrow[pr & 127u], hi = qrow[(pr >> 8) & 127u];
+    out[e] = (2 * e < n_valid ? lo : 0u) | ((2 * e + 1 < n_valid ? hi : 0u) << 16);
+  }
+}
+
 template <int K4, int K16>
 struct Tiers {
   static constexpr int NL = kD - K4 - K16;
@@ -140,7 +168,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 
   __half* sQn = reinterpret_cast<__half*>(smem);                   // [8][128] normalised q
   int* sEq = reinterpret_cast<int*>(smem + 2048);                   // [8] exponents
-  unsigned char* wbase = smem + 2048 + 64 + wave * kWaveLds;        // this wave's private region
+  unsigned char* wbase = smem + 2048 + 256 + wave * kWaveLds;        // this wave's private region
   unsigned char* sK = wbase;                                        // record bytes [0, NKL KiB)
   unsigned char* sVm = wbase + kKPartMax;                           // v_s, v_z planes
   unsigned char* sLo = wbase + kKPartMax + kVMetaMax;               // 2-bit channel list [128], then salient idx [<=64]
@@ -159,7 +187,9 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 #pragma unroll
   for (int j = 0; j < 4; ++j)
     if (j < n_sub && (n_blocks + j) % n_gw == gw) my_sub = j;
-  const bool bookkeeper = n_sub > 0 ? my_sub == n_sub - 1 : gw == 0;   // the new token lies in the last sub-unit
+  // one wavefront per pair (the next in the deal, never one with a sub-unit unless the pair has a single
+  // workgroup) stores this step's new token and adds |q| to the accumulator, after its units
+  const bool bookkeeper = (n_blocks + n_sub) % n_gw == gw;
 
   // ---- per-lane constants -------------------------------------------------
   const int tokbase = 16 * (n >> 2) + 2 * (n & 3);   // token of A-row n in tile (h, x): 64h + tokbase + {0,1,8,9}[x]
@@ -200,9 +230,10 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   // q in slot order (rebuilt when the block's channel selection changes)
   unsigned qlo[2 * NU][4];            // [step][vgpr]: normalised q pairs of the 2-bit tier
   unsigned qh4[4], q16[4];            // 4-bit tier pairs; fp16-tier pairs (role 0 only)
-  unsigned sel_prev[8];
+  constexpr int kSelWords = K4 + K16 > 0 ? (K4 + K16 + 3) / 4 : 1;
+  unsigned sel_prev[kSelWords];     // wave-uniform: the selection q was last laid out for
 #pragma unroll
-  for (int i = 0; i < 8; ++i) sel_prev[i] = 0xffffffffu;
+  for (int i = 0; i < kSelWords; ++i) sel_prev[i] = 0xffffffffu;
 #pragma unroll
   for (int s = 0; s < 2 * NU; ++s)
 #pragma unroll
@@ -234,71 +265,113 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         vreg[h][x] = *reinterpret_cast<const u32x4*>(vw_ + (4 * (h * 64 < R ? h : 0) + kg) * kD + 64 * x + 4 * n); \
   }
 
-  int blk = blk_lo;
-  if (blk < blk_hi) {
-    MIXKVQ_ISSUE_K_LOADS(blk)
-    MIXKVQ_ISSUE_V_LOADS(blk)
+  // q in slot order from the selection words SELW (wave-uniform): the list of 2-bit channels and the salient
+  // list go to LDS, then every lane gathers the q entries of its contraction slots without branches.
+#define MIXKVQ_REBUILD_Q(SELW)                                                                                 \
+  {                                                                                                            \
+    unsigned char* sIdx = sLo + kD;                                                                            \
+    if (K4 + K16 > 0) {                                                                                        \
+      if (lane == 0) {                                                                                         \
+        _Pragma("unroll") for (int i = 0; i < kSelWords; ++i) reinterpret_cast<unsigned*>(sIdx)[i] = SELW[i];  \
+      }                                                                                                        \
+      unsigned long long m0 = 0, m1 = 0; /* bitmap of salient channels (scalar arithmetic) */                  \
+      _Pragma("unroll") for (int i = 0; i < K4 + K16; ++i) {                                                   \
+        const unsigned ch = (SELW[i >> 2] >> (8 * (i & 3))) & 0xffu;                                           \
+        m0 |= ch < 64u ? 1ull << (ch & 63u) : 0ull;                                                            \
+        m1 |= ch < 64u ? 0ull : 1ull << (ch & 63u);                                                            \
+      }                                                                                                        \
+      /* lanes cover channels lane and lane + 64 */                                                            \
+      if (!((m0 >> lane) & 1)) sLo[lane - __popcll(m0 & ((1ull << lane) - 1))] = (unsigned char)lane;          \
+      if (!((m1 >> lane) & 1))                                                                                 \
+        sLo[lane + 64 - __popcll(m0) - __popcll(m1 & ((1ull << lane) - 1))] = (unsigned char)(lane + 64);      \
+    } else {                                                                                                   \
+      sLo[lane] = (unsigned char)lane;                                                                         \
+      sLo[lane + 64] = (unsigned char)(lane + 64);                                                             \
+    }                                                                                                          \
+    const unsigned short* qrow = reinterpret_cast<const unsigned short*>(sQn) + head * kD;                     \
+    _Pragma("unroll") for (int u = 0; u < NU; ++u) _Pragma("unroll") for (int x = 0; x < 2; ++x) {             \
+      const int j = 16 * (4 * u + kg) + 8 * x;                                                                 \
+      gather8(sLo + (j < kD ? j : 0), qrow, live ? T::NL - j : 0, qlo[2 * u + x]);                             \
+    }                                                                                                          \
+    if (K4 > 0) gather8(sIdx + K16 + 8 * (kg < T::W4 ? kg : 0), qrow, live && kg < T::W4 ? 8 : 0, qh4);        \
+    if (K16 > 0) gather8(sIdx + (8 * kg < K16 ? 8 * kg : 0), qrow, live ? K16 - 8 * kg : 0, q16);              \
   }
+
+  MIXKVQ_PHASE(0)
+  MIXKVQ_PHASE_CYCLES(12)
+  // Loads go out in the order of use (they return in order): q, the first record's channel selection, the
+  // residual sub-unit, the first record.
+  int blk = blk_lo;
+  uint2 qraw = make_uint2(0u, 0u);
+  {
+    const int h = tid >> 5, l32 = tid & 31;
+    if (h < g) qraw = *reinterpret_cast<const uint2*>(q + ((size_t)b * Hq + jkv * g + h) * kD + l32 * 4);
+  }
+  unsigned sel_first[kSelWords];
+#pragma unroll
+  for (int i = 0; i < kSelWords; ++i) sel_first[i] = 0u;
+  if (K4 + K16 > 0 && blk < blk_hi) {
+    const unsigned* recw = reinterpret_cast<const unsigned*>(blocks + ((size_t)p * NB + blk) * rec_bytes + off_idx);
+#pragma unroll
+    for (int i = 0; i < kSelWords; ++i) sel_first[i] = recw[i];
+  }
+  // Residual sub-unit of this wavefront: 2 key tiles x 4 contraction steps, 32 value rows.  This step's new
+  // token is read from the caller's tensors.
+  const int sub_t0 = 32 * (my_sub > 0 ? my_sub : 0);
+  const int tokb = 8 * (n >> 2) + 2 * (n & 3);      // A-row n of tile x: token sub_t0 + tokb + x
+  u32x4 kr[2][4], vr[8];
+  if (my_sub >= 0) {
+    const __half* rk = cv.res_k + (size_t)p * R * kD;
+    const __half* rv = cv.res_v + (size_t)p * R * kD;
+    const int64_t nt_off = (int64_t)b * nt.st.b + (int64_t)jkv * nt.st.h;
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      const int row = sub_t0 + tokb + x;
+      const __half* src = (nt.k && row == nt.row) ? nt.k + nt_off : rk + (size_t)row * kD;
+#pragma unroll
+      for (int st = 0; st < 4; ++st) kr[x][st] = *reinterpret_cast<const u32x4*>(src + 8 * kg + 32 * st);
+    }
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int ci = it * 64 + lane, row = sub_t0 + (ci >> 4);
+      const __half* src = (nt.k && row == nt.row) ? nt.v + nt_off : rv + (size_t)row * kD;
+      vr[it] = *reinterpret_cast<const u32x4*>(src + 8 * (ci & 15));
+    }
+  }
+  if (blk < blk_hi) MIXKVQ_ISSUE_K_LOADS(blk)
 
   // ---- normalise q per head: qn = q * 2^-Eq with max|qn| in [1/2, 1) ----
   {
     const int h = tid >> 5, l32 = tid & 31;
-    float v[4];
-    float mx = 0.f;
-    for (int i = 0; i < 4; ++i) {
-      v[i] = h < g ? __half2float(q[((size_t)b * Hq + jkv * g + h) * kD + l32 * 4 + i]) : 0.f;
-      mx = fmaxf(mx, fabsf(v[i]));
-    }
+    const h2 q01 = __builtin_bit_cast(h2, qraw.x), q23 = __builtin_bit_cast(h2, qraw.y);
+    const float v[4] = {(float)q01[0], (float)q01[1], (float)q23[0], (float)q23[1]};
+    float mx = fmaxf(fmaxf(fabsf(v[0]), fabsf(v[1])), fmaxf(fabsf(v[2]), fabsf(v[3])));
     for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 32));
     int ef = (int)((__float_as_uint(mx) >> 23) & 0xff) - 127 + 15;   // fp16 exponent field of the maximum
     if (ef < 1) ef = 1;
     const int eq = ef - 14;
-    for (int i = 0; i < 4; ++i) sQn[h * kD + l32 * 4 + i] = __float2half_rn(ldexpf(v[i], -eq));
+    uint2 qn;
+    qn.x = cvt_pk(ldexpf(v[0], -eq), ldexpf(v[1], -eq));
+    qn.y = cvt_pk(ldexpf(v[2], -eq), ldexpf(v[3], -eq));
+    *reinterpret_cast<uint2*>(sQn + h * kD + l32 * 4) = qn;
     if (l32 == 0) sEq[h] = eq;
   }
   __syncthreads();
   const int Eq = sEq[head];
-
+  MIXKVQ_PHASE(1)
+  // q in the slot order of the first record, while that record is still on its way (its value words are
+  // asked for only now: the first answers come the sooner the less every wavefront asks for at once)
+  if (blk < blk_hi) {
+    MIXKVQ_ISSUE_V_LOADS(blk)
+#pragma unroll
+    for (int i = 0; i < kSelWords; ++i) sel_prev[i] = __builtin_amdgcn_readfirstlane(sel_first[i]);
+    MIXKVQ_REBUILD_Q(sel_prev)
+  }
 
   // ---- residual window (fp16 keys/values): 32 tokens per wavefront, before its block records ----
-  if (bookkeeper) {   // this step's new token enters the window; |q| joins the accumulator (one writer per pair)
-    if (nt.k && lane < 32) {
-      const int64_t src = (int64_t)b * nt.st.b + (int64_t)jkv * nt.st.h + (lane & 15) * 8;
-      const size_t dst = ((size_t)p * R + nt.row) * kD + (lane & 15) * 8;
-      if (lane < 16) *reinterpret_cast<uint4*>(cv.res_k + dst) = *reinterpret_cast<const uint4*>(nt.k + src);
-      else *reinterpret_cast<uint4*>(cv.res_v + dst) = *reinterpret_cast<const uint4*>(nt.v + src);
-    }
-    if (accumulate_q) {
-#pragma unroll
-      for (int hc = 0; hc < 2; ++hc) {
-        const int d = lane + 64 * hc;
-        unsigned long long acc = 0;
-        for (int h = 0; h < g; ++h) acc += fix24_abs(h2bits(q[((size_t)b * Hq + jkv * g + h) * kD + d]));
-        cv.qacc[(size_t)p * kD + d] += acc;
-      }
-      if (lane == 0) cv.qcnt[p] += (unsigned long long)g;
-    }
-    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");   // the new rows are read back below
-  }
   if (my_sub >= 0) {
-    const int t0 = 32 * my_sub;
-    const __half* rk = cv.res_k + ((size_t)p * R + t0) * kD;
-    const __half* rv = cv.res_v + ((size_t)p * R + t0) * kD;
+    const int t0 = sub_t0;
     constexpr int kVStride = 264;     // bytes per staged value row (+8 against bank conflicts)
-    const int tokb = 8 * (n >> 2) + 2 * (n & 3);      // A-row n of tile x: token t0 + tokb + x
-    // all loads of the sub-unit at once: 2 key tiles x 4 steps, 32 value rows
-    u32x4 kr[2][4];
-    uint4 vr[8];
-#pragma unroll
-    for (int x = 0; x < 2; ++x)
-#pragma unroll
-      for (int st = 0; st < 4; ++st)
-        kr[x][st] = *reinterpret_cast<const u32x4*>(rk + (size_t)(tokb + x) * kD + 8 * kg + 32 * st);
-#pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const int ci = it * 64 + lane;
-      vr[it] = *reinterpret_cast<const uint4*>(rv + (size_t)(ci >> 4) * kD + 8 * (ci & 15));
-    }
     const float Cres = ldexpf(scale_log2e, Eq);
     f32x4 S0 = {0.f, 0.f, 0.f, 0.f}, S1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -333,11 +406,11 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
       const int ci = it * 64 + lane, rowi = ci >> 4, c16 = ci & 15;
-      uint4 v = vr[it];
-      if (t0 + rowi >= n_res) v = make_uint4(0u, 0u, 0u, 0u);
+      u32x4 v = vr[it];
+      if (t0 + rowi >= n_res) v = u32x4{0u, 0u, 0u, 0u};
       uint2* dst = reinterpret_cast<uint2*>(sK + rowi * kVStride + 16 * c16);
-      dst[0] = make_uint2(v.x, v.y);
-      dst[1] = make_uint2(v.z, v.w);
+      dst[0] = make_uint2(v[0], v[1]);
+      dst[1] = make_uint2(v[2], v[3]);
     }
 #pragma unroll
     for (int xp = 0; xp < 2; ++xp)
@@ -355,6 +428,8 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
       }
   }
 
+  MIXKVQ_PHASE(2)
+  [[maybe_unused]] int phase_i = 3;
   for (; blk < blk_hi; blk += blk_step) {
     // ---- stage the key part and value metadata in LDS (wave-private: no barrier needed) ----
 #pragma unroll
@@ -363,72 +438,16 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
     if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_K_LOADS(blk + blk_step)
 
     // ---- channel selection of this block: rebuild q in slot order if it changed ----
-    bool rebuild = false;
-    if (K4 + K16 > 0) {
+    {
+      bool rebuild = false;
+      unsigned selw[kSelWords];
 #pragma unroll
-      for (int i = 0; i < (K4 + K16 + 3) / 4; ++i) {
-        const unsigned wv = reinterpret_cast<const unsigned*>(sK + off_idx)[i];
-        rebuild |= wv != sel_prev[i];
-        sel_prev[i] = wv;
+      for (int i = 0; i < kSelWords; ++i) {
+        selw[i] = K4 + K16 > 0 ? __builtin_amdgcn_readfirstlane(reinterpret_cast<const unsigned*>(sK + off_idx)[i]) : 0u;
+        rebuild |= selw[i] != sel_prev[i];
+        sel_prev[i] = selw[i];
       }
-    } else {
-      rebuild = sel_prev[0] != 0u;
-      sel_prev[0] = 0u;
-    }
-    if (__builtin_amdgcn_readfirstlane((int)rebuild)) {
-      unsigned char* sIdx = sLo + kD;
-      if (K4 + K16 > 0) {
-        // list of 2-bit channels: lanes cover channels lane and lane+64
-        if (lane < K4 + K16) sIdx[lane] = sK[off_idx + lane];
-        unsigned long long m0 = 0, m1 = 0;   // bitmap of salient channels
-#pragma unroll
-        for (int i = 0; i < K4 + K16; ++i) {
-          const int ch = sK[off_idx + i];
-          if (ch < 64) m0 |= 1ull << ch; else m1 |= 1ull << (ch - 64);
-        }
-        if (!((m0 >> lane) & 1)) sLo[lane - __popcll(m0 & ((1ull << lane) - 1))] = (unsigned char)lane;
-        if (!((m1 >> lane) & 1))
-          sLo[lane + 64 - __popcll(m0) - __popcll(m1 & ((1ull << lane) - 1))] = (unsigned char)(lane + 64);
-      } else {
-        sLo[lane] = (unsigned char)lane;
-        sLo[lane + 64] = (unsigned char)(lane + 64);
-      }
-      const __half* qrow = sQn + head * kD;
-#pragma unroll
-      for (int u = 0; u < NU; ++u)
-#pragma unroll
-        for (int x = 0; x < 2; ++x)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int j0 = 16 * (4 * u + kg) + 8 * x + 2 * e, j1 = j0 + 1;
-            float lo = 0.f, hi = 0.f;
-            if (live && j0 < T::NL) lo = __half2float(qrow[sLo[j0]]);
-            if (live && j1 < T::NL) hi = __half2float(qrow[sLo[j1]]);
-            qlo[2 * u + x][e] = cvt_pk(lo, hi);
-          }
-      if (K4 > 0) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          float lo = 0.f, hi = 0.f;
-          if (live && kg < T::W4) {
-            lo = __half2float(qrow[sIdx[K16 + 8 * kg + 2 * e]]);
-            hi = __half2float(qrow[sIdx[K16 + 8 * kg + 2 * e + 1]]);
-          }
-          qh4[e] = cvt_pk(lo, hi);
-        }
-      }
-      if (K16 > 0) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int a0 = 8 * kg + 2 * e;
-          float lo = 0.f, hi = 0.f;
-          if (live) {
-            if (a0 < K16) lo = __half2float(qrow[sIdx[a0]]);
-            if (a0 + 1 < K16) hi = __half2float(qrow[sIdx[a0 + 1]]);
-          }
-          q16[e] = cvt_pk(lo, hi);
-        }
-      }
+      if (rebuild) MIXKVQ_REBUILD_Q(selw)
     }
 
     // operands that live across the super-groups of one key group
@@ -645,9 +664,31 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
       }
     }
     if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_V_LOADS(blk + blk_step)
+    MIXKVQ_PHASE(phase_i < 11 ? phase_i : 11)
+    ++phase_i;
   }
+  if (bookkeeper) {
+    if (nt.k && lane < 32) {
+      const int64_t src = (int64_t)b * nt.st.b + (int64_t)jkv * nt.st.h + (lane & 15) * 8;
+      const size_t dst = ((size_t)p * R + nt.row) * kD + (lane & 15) * 8;
+      if (lane < 16) *reinterpret_cast<uint4*>(cv.res_k + dst) = *reinterpret_cast<const uint4*>(nt.k + src);
+      else *reinterpret_cast<uint4*>(cv.res_v + dst) = *reinterpret_cast<const uint4*>(nt.v + src);
+    }
+    if (accumulate_q) {
+#pragma unroll
+      for (int hc = 0; hc < 2; ++hc) {
+        const int d = lane + 64 * hc;
+        unsigned long long acc = 0;
+        for (int h = 0; h < g; ++h) acc += fix24_abs(h2bits(q[((size_t)b * Hq + jkv * g + h) * kD + d]));
+        cv.qacc[(size_t)p * kD + d] += acc;
+      }
+      if (lane == 0) cv.qcnt[p] += (unsigned long long)g;
+    }
+  }
+  MIXKVQ_PHASE(14)
 #undef MIXKVQ_ISSUE_K_LOADS
 #undef MIXKVQ_ISSUE_V_LOADS
+#undef MIXKVQ_REBUILD_Q
 
   // ---- wave results -> workgroup partial ------------------------------------------
   l_run = xkg_sum(l_run);
@@ -661,41 +702,54 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
     z = xkg_sum(z);
     zsum[a] = z + row_ror8(z);
   }
-  __syncthreads();   // every wave is done with its private LDS region
+  // each wavefront leaves its result in its own LDS region; after one barrier all threads merge the four
+  // in a fixed order
+  float* wO = reinterpret_cast<float*>(wbase);        // [8][128] O, then [8] l
   float* sM = reinterpret_cast<float*>(smem + 2048 + 64);          // [waves][8]
-  float* sO = sM + kWaves * 8;                                     // [8][128] + [8] l
-  if (kg == 0 && role == 0) sM[wave * 8 + head] = m_run;
-  for (int i = tid; i < 8 * kD + 8; i += kMfmaThreads) sO[i] = 0.f;
-  __syncthreads();
-  float m_wg = -INFINITY;
+  if (role == 0 && live) {
 #pragma unroll
-  for (int w = 0; w < kWaves; ++w) m_wg = fmaxf(m_wg, sM[w * 8 + head]);
-  const float wscale = m_run == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run - m_wg);
-  for (int w = 0; w < kWaves; ++w) {   // one wave at a time: the sum order is fixed
-    if (wave == w && role == 0 && live) {
+    for (int xp = 0; xp < 2; ++xp)
 #pragma unroll
-      for (int xp = 0; xp < 2; ++xp)
+      for (int qq = 0; qq < 4; ++qq)
 #pragma unroll
-        for (int qq = 0; qq < 4; ++qq)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int ch = 64 * xp + 16 * kg + 4 * i + qq;
-            const int a = NVG == 1 ? 0 : xp;
-            sO[head * kD + ch] += fmaf(O[xp][qq][i], 16777216.f, zsum[a]) * wscale;
-          }
-      if (kg == 0) sO[8 * kD + head] += l_run * wscale;
+        for (int i = 0; i < 4; ++i) {
+          const int ch = 64 * xp + 16 * kg + 4 * i + qq;
+          const int a = NVG == 1 ? 0 : xp;
+          wO[head * kD + ch] = fmaf(O[xp][qq][i], 16777216.f, zsum[a]);
+        }
+    if (kg == 0) {
+      wO[8 * kD + head] = l_run;
+      sM[wave * 8 + head] = m_run;
     }
-    __syncthreads();
   }
+  __syncthreads();
   // natural-log domain for the merge kernel: m_e = m2 * ln2
   float* out = part + ((size_t)p * n_splits + split) * g * kPartStrideM;
-  for (int i = tid; i < g * kD; i += kMfmaThreads) out[(i / kD) * kPartStrideM + (i % kD)] = sO[i];
-  if (tid < g) {
-    float mw = -INFINITY;
-    for (int w = 0; w < kWaves; ++w) mw = fmaxf(mw, sM[w * 8 + tid]);
-    out[tid * kPartStrideM + kD] = mw * 0.6931471805599453f;
-    out[tid * kPartStrideM + kD + 1] = sO[8 * kD + tid];
+  const float* r0 = reinterpret_cast<const float*>(smem + 2048 + 256);
+  constexpr int kWaveF = kWaveLds / 4;
+  for (int i = tid; i < g * (kD + 1); i += kMfmaThreads) {
+    // elements g*kD .. are the l sums
+    const int h = i < g * kD ? i / kD : i - g * kD;
+    const int src = i < g * kD ? i : 8 * kD + h;
+    float mw[kWaves], m_wg = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      mw[w] = sM[w * 8 + h];
+      m_wg = fmaxf(m_wg, mw[w]);
+    }
+    float acc = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w)
+      acc += mw[w] == -INFINITY ? 0.f : r0[w * kWaveF + src] * __builtin_amdgcn_exp2f(mw[w] - m_wg);
+    if (i < g * kD) {
+      out[h * kPartStrideM + (i % kD)] = acc;
+    } else {
+      out[h * kPartStrideM + kD] = m_wg * 0.6931471805599453f;
+      out[h * kPartStrideM + kD + 1] = acc;
+    }
   }
+  MIXKVQ_PHASE(15)
+  MIXKVQ_PHASE_CYCLES(13)
 }
 
 // ---------------------------------------------------------------------------
@@ -774,7 +828,7 @@ static hipError_t launch_one(const CacheView& v, const __half* q, float scale, i
                              float* part, unsigned* counters, __half* out, float* lse, int accumulate_q, NewToken nt,
                              hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
   auto kern = decode_fused_kernel<K4, K16, NVG, NKL, RG>;
-  const size_t lds = 2048 + 64 + (size_t)kWaves * kWaveLds;
+  const size_t lds = 2048 + 256 + (size_t)kWaves * kWaveLds;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -825,3 +879,10 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
 }
 
 }  // namespace mixkvq
+
+#ifdef MIXKVQ_PHASE_CLOCKS
+extern "C" int mixkvq_debug_phase_clocks(void* host_dst, size_t bytes) {
+  (void)hipDeviceSynchronize();
+  return (int)hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(mixkvq::g_phase_clock), bytes);
+}
+#endif
