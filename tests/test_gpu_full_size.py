@@ -1,0 +1,85 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch
+configuration bench.py times (same inputs, same calls, default split count).
+
+The library runs the whole batch; the oracle recomputes sampled (batch, KV head)
+pairs one by one from the same seeded inputs: channel selection, every packed
+block record of the pair, the residual window and the |q| accumulator bit for bit,
+attention outputs of the pair's query heads within the stated tolerance."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_common
+    return gpu_common
+
+
+def _host_pair(host, w, b, j, hb):
+    """Host copies of what bench.build_inputs put on the device for batch entry b, KV head j."""
+    g = w.Hq // w.Hkv
+    src, roll = b % hb, 7 * (b // hb)
+    K = np.roll(host["K"][src, j], roll, axis=-1)[None, None]
+    V = np.roll(host["V"][src, j], roll, axis=-1)[None, None]
+    Qp = np.roll(host["Qp"][src, j * g:(j + 1) * g], roll, axis=-1)[None]
+    qs = np.roll(host["qs"][src, j * g:(j + 1) * g], roll, axis=-1)[None]     # [1, g, 8, D]
+    return K, V, Qp, qs
+
+
+@pytest.mark.parametrize("cfg_id,host_batch,samples,n_steps", [
+    (1, 2, [(0, 0), (1, 3), (5, 2), (7, 1)], 3),
+    (3, 1, [(0, 0), (3, 5)], 2),
+    (2, 1, [(0, 7), (37, 2)], 2),
+])
+def test_full_size_sampled_pairs(H, cfg_id, host_batch, samples, n_steps):
+    import bench
+    import paper_2512_19206_amd as M
+    import synth_inputs as S
+    from oracle import mixkvq_oracle as O
+    w = S.WORKLOADS[cfg_id]
+    g = w.Hq // w.Hkv
+    print(f"full size: {w.name} B={w.B} Hq={w.Hq} Hkv={w.Hkv} T={w.T}", flush=True)
+    dk, dv, dqp, dq, host = bench.build_inputs(cfg_id, w, host_batch)
+    hb = min(host_batch, w.B)
+    kw = dict(D=w.D, T_max=w.T + 2 * w.R, Gk=w.Gk, Gv=w.Gv, R=w.R, k4=w.k4, k16=w.k16)
+    gc = M.Cache(M.make_config(B=w.B, Hq=w.Hq, Hkv=w.Hkv, **kw))
+    sel = M.mixkvq_select_channels(gc, dqp, dk)
+    M.mixkvq_quantize_append(gc, dk, dv, sel=sel)
+    outs = []
+    for t in range(n_steps):
+        out, lse = M.mixkvq_decode_step(gc, dk[:, :, t:t + 1], dv[:, :, t:t + 1], dq[t], accumulate_q=True)
+        outs.append((out.float().cpu().numpy(), lse.cpu().numpy()))
+    torch.cuda.synchronize()
+    nq, r = gc.state()
+    sel_h = sel.cpu().numpy()
+    acc, cnt = gc.query_accumulator()
+    acc_h, cnt_h = acc.cpu().numpy().astype(np.uint64), cnt.cpu().numpy().astype(np.uint64)
+    rk, rv = gc.residual()
+
+    for b, j in samples:
+        print(f"  oracle for pair (b={b}, kv head={j})", flush=True)
+        p = b * w.Hkv + j
+        K, V, Qp, qs = _host_pair(host, w, b, j, hb)
+        oc = O.OracleCache(O.OracleConfig(B=1, Hq=g, Hkv=1, **kw))
+        sel_ref = oc.select_channels(Qp, K)
+        assert np.array_equal(sel_h[b, j], sel_ref[0, 0]), f"selection differs for pair ({b}, {j})"
+        oc.append(K, V, sel_ref)
+        for t in range(n_steps):
+            oc.append(K[:, :, t:t + 1], V[:, :, t:t + 1])
+            ro, rl = oc.decode_attention(np.ascontiguousarray(qs[:, :, t]), accumulate_q=True)
+            go, gl = outs[t][0][b, j * g:(j + 1) * g], outs[t][1][b, j * g:(j + 1) * g]
+            err = np.abs(go - ro[0])
+            assert np.all(err <= H.ATOL + H.RTOL * np.abs(ro[0])), (b, j, t, float(err.max()))
+            assert np.all(np.abs(gl - rl[0]) <= H.LSE_ATOL + 1e-4 * np.abs(rl[0])), (b, j, t)
+        assert (nq, r) == (oc.n_quant, oc.n_res)
+        nb = nq // w.R
+        got = gc.block_records()[p, :nb].cpu().numpy()
+        assert np.array_equal(got, oc.packed_blocks()[0]), f"block records differ for pair ({b}, {j})"
+        assert np.array_equal(rk[p, :r].cpu().numpy().view(np.uint16), oc.res_k[0, :r].view(np.uint16))
+        assert np.array_equal(rv[p, :r].cpu().numpy().view(np.uint16), oc.res_v[0, :r].view(np.uint16))
+        assert np.array_equal(acc_h[p], oc.qacc[0]) and cnt_h[p] == oc.qcnt[0]
