@@ -27,6 +27,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 LLC_BYTES = 256 << 20   # last-level (Infinity) cache
 
+# HBM bytes per launch of the decode kernel from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), each scaled by what
+# the same counter read for a 512 MiB device copy in the same run (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0);
+# the readings and commands are in profiles/decode_fused_kernel_cfg1.txt.  Only for the default workload.
+MEASURED_TRAFFIC_BYTES = {("cfg1_gqa7b_b8_32k", 32768): 39612.8 * 1024 * 2.0 + 1867.7 * 1024 * 1.0}
+
 
 def algorithmic_bytes(w, n_q, r):
     """Bytes one decode step must move, all (batch, KV head) pairs."""
@@ -134,6 +139,8 @@ def main():
     ap.add_argument("--host-batch", type=int, default=2)
     ap.add_argument("--tokens", type=int, default=0, help="override the context length of the configuration")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also run 4 plain device copies of this many MiB (reference reading for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the hot path has no collective); --gpus must be 1", file=sys.stderr)
@@ -168,6 +175,14 @@ def main():
     v1 = dv[:, :, :64]
     out = torch.empty((w.B, w.Hq, w.D), dtype=torch.float16, device="cuda")
     lse = torch.empty((w.B, w.Hq), dtype=torch.float32, device="cuda")
+
+    if args.calibration_copy_mib:
+        src = torch.full((args.calibration_copy_mib << 20,), 3, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     def step(i):
         gc = caches[i % copies]
@@ -217,7 +232,9 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "decode_fused_kernel", "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "kernel_avg_us": round(k_avg_ms * 1e3, 2), "kernel_min_us": round(min(k_ms) * 1e3, 2),
-                     "launches_timed": n_ev, "traffic": None},
+                     "launches_timed": n_ev,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, w.T)), "traffic_unit": "bytes per launch",
+                     "algorithmic_bytes_per_launch": step_bytes},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args.config, w, host)
