@@ -145,6 +145,95 @@ struct Tiers {
 //   4-bit tier, one step: lane group kg unpacks word kg; VGPR e pairs tier entries 8kg+2e, 8kg+2e+1
 //   fp16 tier, one step: lane group kg takes tier entries 8kg .. 8kg+7 as they are
 
+// ---------------------------------------------------------------------------
+// Log-sum-exp merge of the partials of one pair (one workgroup per pair):
+// m* = max m_i, l* = sum l_i e^(m_i - m*), O = sum O_i e^(m_i - m*) / l*.
+// A launch of its own: the kernel boundary makes the partials visible across the chip's L2 slices.  (Merging
+// in the attention kernel by the last workgroup of a pair to arrive was measured slower: with agent-scope
+// stores, counter and loads the chain store-acknowledge -> atomic -> loads costs more than this launch, and
+// device-wide fences cost far more.)
+// ---------------------------------------------------------------------------
+constexpr int kMergeLds = 64 + ((kMaxSplits + 1) * 8 * 2 + 16) * 4;
+
+__global__ void __launch_bounds__(256)
+decode_merge_pair_kernel(CacheView cv, const float* __restrict__ part, int n_parts, __half* __restrict__ out,
+                         float* __restrict__ lse) {
+  __shared__ __align__(16) unsigned char smem[kMergeLds];
+  const int p = blockIdx.x, tid = threadIdx.x, g = cv.g;
+  const int b = p / cv.cfg.Hkv, j = p % cv.cfg.Hkv;
+  const size_t stride = (size_t)g * kPartStrideM;
+  const float* pbase = part + (size_t)p * n_parts * g * kPartStrideM;
+  float* sW = reinterpret_cast<float*>(smem + 64);          // [n_parts][g] weights e^(m_i - m*), m_i first
+  float* sML = sW + (kMaxSplits + 1) * 8;                   // [g] m*, then [g] l*
+  // Every load of the first 16 parts goes out before anything waits: the (part, head) maxima and sums, and
+  // this thread's output channel of up to four heads.
+  constexpr int kItems = (kMaxSplits * 8 + 255) / 256;      // (part, head) items per thread
+  float my_m[kItems], my_l[kItems];
+#pragma unroll
+  for (int it = 0; it < kItems; ++it) {
+    const int t = tid + 256 * it;
+    my_m[it] = -INFINITY;
+    my_l[it] = 0.f;
+    if (t < n_parts * g) {
+      const int sidx = t / g, h = t % g;
+      my_m[it] = pbase[sidx * stride + h * kPartStrideM + kD];
+      my_l[it] = pbase[sidx * stride + h * kPartStrideM + kD + 1];
+    }
+  }
+  const int d = tid & 127, h0 = tid >> 7;
+  float v0[4][16];
+#pragma unroll
+  for (int hh = 0; hh < 4; ++hh)
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      v0[hh][i] = (h0 + 2 * hh < g && i < n_parts) ? pbase[i * stride + (h0 + 2 * hh) * kPartStrideM + d] : 0.f;
+#pragma unroll
+  for (int it = 0; it < kItems; ++it)
+    if (tid + 256 * it < n_parts * g) sW[tid + 256 * it] = my_m[it];
+  __syncthreads();
+  if (tid < g) {
+    float m = -INFINITY;
+    for (int s2 = 0; s2 < n_parts; ++s2) m = fmaxf(m, sW[s2 * g + tid]);
+    sML[tid] = m;
+  }
+  __syncthreads();
+  float* sLp = sML + 16;                                     // [n_parts][g] weighted l
+#pragma unroll
+  for (int it = 0; it < kItems; ++it) {
+    const int t = tid + 256 * it;
+    if (t < n_parts * g) {
+      const float wgt = my_m[it] == -INFINITY ? 0.f : __expf(my_m[it] - sML[t % g]);
+      sW[t] = wgt;
+      sLp[t] = my_l[it] * wgt;
+    }
+  }
+  __syncthreads();
+  if (tid < g) {
+    float l = 0.f;
+    for (int s2 = 0; s2 < n_parts; ++s2) l += sLp[s2 * g + tid];
+    sML[8 + tid] = l;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int hh = 0; hh < 4; ++hh) {
+    const int h = h0 + 2 * hh;
+    if (h >= g) break;
+    float o = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o = fmaf(v0[hh][i], i < n_parts ? sW[i * g + h] : 0.f, o);
+    for (int s0 = 16; s0 < n_parts; s0 += 16) {
+      float v[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) v[i] = s0 + i < n_parts ? pbase[(s0 + i) * stride + h * kPartStrideM + d] : 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o = fmaf(v[i], s0 + i < n_parts ? sW[(s0 + i) * g + h] : 0.f, o);
+    }
+    const size_t bh = (size_t)b * cv.cfg.Hq + (size_t)j * g + h;
+    out[bh * kD + d] = __float2half_rn(o / sML[8 + h]);
+    if (lse && d == 0) lse[bh] = sML[h] + __logf(sML[8 + h]);
+  }
+}
+
 template <int K4, int K16, int NVG, int NKL, int RG>
 __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __restrict__ q, float scale_log2e,
                                           int n_blocks, int n_res, int n_splits, float* __restrict__ part,
@@ -750,66 +839,6 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   }
   MIXKVQ_PHASE(15)
   MIXKVQ_PHASE_CYCLES(13)
-}
-
-// ---------------------------------------------------------------------------
-// Log-sum-exp merge of the partials of one pair (one workgroup per pair):
-// m* = max m_i, l* = sum l_i e^(m_i - m*), O = sum O_i e^(m_i - m*) / l*.
-// A separate launch: the kernel boundary makes the partials visible across the chip's L2 slices
-// without device-wide fences inside the attention kernel.
-// ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(256)
-decode_merge_pair_kernel(CacheView cv, const float* __restrict__ part, int n_parts, __half* __restrict__ out,
-                         float* __restrict__ lse) {
-  __shared__ __align__(16) unsigned char smem[64 + ((kMaxSplits + 1) * 8 * 2 + 16) * 4];
-  const int p = blockIdx.x, tid = threadIdx.x, g = cv.g;
-  const int b = p / cv.cfg.Hkv, j = p % cv.cfg.Hkv;
-  const size_t stride = (size_t)g * kPartStrideM;
-  const float* pbase = part + (size_t)p * n_parts * g * kPartStrideM;
-  float* sW = reinterpret_cast<float*>(smem + 64);          // [n_parts][g] weights e^(m_i - m*), m_i first
-  float* sML = sW + (kMaxSplits + 1) * 8;                   // [g] m*, then [g] l*
-  // every (part, head) maximum and sum: all loads are independent and issued together
-  float my_m = -INFINITY, my_l = 0.f;
-  if (tid < n_parts * g) {
-    const int sidx = tid / g, h = tid % g;
-    my_m = pbase[sidx * stride + h * kPartStrideM + kD];
-    my_l = pbase[sidx * stride + h * kPartStrideM + kD + 1];
-    sW[tid] = my_m;
-  }
-  __syncthreads();
-  if (tid < n_parts * g) {
-    const int h = tid % g;
-    float m = -INFINITY;
-    for (int s2 = 0; s2 < n_parts; ++s2) m = fmaxf(m, sW[s2 * g + h]);
-    if (tid < g) sML[h] = m;
-    my_l *= my_m == -INFINITY ? 0.f : __expf(my_m - m);
-    my_m = my_m == -INFINITY ? 0.f : __expf(my_m - m);      // now the weight
-  }
-  __syncthreads();
-  if (tid < n_parts * g) sW[tid] = my_m;
-  float* sLp = sML + 16;                                     // [n_parts][g] weighted l
-  if (tid < n_parts * g) sLp[tid] = my_l;
-  __syncthreads();
-  if (tid < g) {
-    float l = 0.f;
-    for (int s2 = 0; s2 < n_parts; ++s2) l += sLp[s2 * g + tid];
-    sML[8 + tid] = l;
-  }
-  __syncthreads();
-  const int d = tid & 127;
-  for (int h = tid >> 7; h < g; h += 2) {
-    float o = 0.f;
-    for (int s0 = 0; s0 < n_parts; s0 += 16) {
-      float v[16];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) v[i] = s0 + i < n_parts ? pbase[(s0 + i) * stride + h * kPartStrideM + d] : 0.f;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o = fmaf(v[i], s0 + i < n_parts ? sW[(s0 + i) * g + h] : 0.f, o);
-    }
-    const size_t bh = (size_t)b * cv.cfg.Hq + (size_t)j * g + h;
-    out[bh * kD + d] = __float2half_rn(o / sML[8 + h]);
-    if (lse && d == 0) lse[bh] = sML[h] + __logf(sML[8 + h]);
-  }
 }
 
 // One launch per decode step: the workgroups (pair, split) share the pair's block records and its

@@ -183,6 +183,29 @@ def test_everything_in_the_residual_window(H):
         H.check_attention(oc, gc, q)
 
 
+@pytest.mark.parametrize("B,Hkv,g,n_blocks,n_res", [(1, 1, 8, 70, 5), (1, 2, 7, 33, 64), (1, 1, 3, 200, 33)])
+def test_few_pairs_many_splits(H, B, Hkv, g, n_blocks, n_res):
+    """Few (batch, KV head) pairs: the split count reaches its ceiling (64 partials of up to 8 heads each to
+    merge) and the residual sub-units share wavefronts with block records."""
+    rng = np.random.default_rng(31)
+    R = 64
+    kw = dict(B=B, Hq=Hkv * g, Hkv=Hkv, D=128, T_max=R * (n_blocks + 2), Gk=64, Gv=128, R=R, k4=16, k16=0)
+    oc, gc = H.make_pair(**kw)
+    n = R * n_blocks + n_res
+    K = (rng.standard_normal((B, Hkv, n, 128)) * rng.uniform(0.3, 8, 128)).astype(np.float16)
+    V = rng.standard_normal((B, Hkv, n, 128)).astype(np.float16)
+    Qp = (rng.standard_normal((B, Hkv * g, 8, 128)) * rng.uniform(0.2, 5, 128)).astype(np.float16)
+    sel_ref = oc.select_channels(Qp, K)
+    sel = gc.select_channels(H.dev(Qp), H.dev(K))
+    oc.append(K, V, sel_ref)
+    gc.quantize_append(H.dev(K), H.dev(V), sel=sel)
+    assert gc.state() == (R * n_blocks, n_res)
+    for _ in range(2):
+        q = (rng.standard_normal((B, Hkv * g, 128)) * rng.uniform(0.2, 5, 128)).astype(np.float16)
+        H.check_attention(oc, gc, q, accumulate_q=True)
+    H.check_state(oc, gc)
+
+
 def test_eager_mode_with_empty_window_and_single_block(H):
     rng = np.random.default_rng(10)
     kw = dict(B=1, Hq=7, Hkv=1, D=128, T_max=256, Gk=128, Gv=128, R=128, k4=16, k16=0, flush_mode=1)
