@@ -129,12 +129,83 @@ def cpu_baseline(cfg_id, w, host, budget_s=20.0):
                       f"{el / n * 1e3:.0f} ms per step"}
 
 
+def prefill_bytes(w, Lq):
+    """(fp16 input bytes, bytes written) of one prefill pass: K, V and the prompt queries in; block records and the
+    residual window out."""
+    P = w.B * w.Hkv
+    kv = 2 * P * w.T * w.D * 2
+    qb = w.B * w.Hq * Lq * w.D * 2
+    n_q = w.R * (-(-w.T // w.R) - 1)
+    out = algorithmic_bytes(w, n_q, 0) - P * (w.Hq // w.Hkv) * w.D * 4 + P * (w.T - n_q) * w.D * 4
+    return kv + qb, out
+
+
+def bench_prefill(args, w, cfg_id):
+    """Configuration 4: full-prompt channel scoring + top-k + mixed-precision pack.  A step = cache reset,
+    mixkvq_select_channels(Q, K), mixkvq_quantize_append(K, V, sel) over the whole batch."""
+    import torch
+    import paper_2512_19206_amd as M
+    import synth_inputs as S
+    Lq = w.T
+    hb = 1
+    K, V, _ = S.heavy_tailed_kv(cfg_id, hb, w.Hkv, w.T)
+    Q = S.outlier_queries(cfg_id, hb, w.Hq, Lq)
+    dk = torch.empty((w.B, w.Hkv, w.T, w.D), dtype=torch.float16, device="cuda")
+    dv = torch.empty_like(dk)
+    dq = torch.empty((w.B, w.Hq, Lq, w.D), dtype=torch.float16, device="cuda")
+    hk, hv, hq = (torch.from_numpy(a).cuda() for a in (K, V, Q))
+    for b in range(w.B):
+        dk[b] = torch.roll(hk[0], 7 * b, dims=-1)
+        dv[b] = torch.roll(hv[0], 7 * b, dims=-1)
+        dq[b] = torch.roll(hq[0], 7 * b, dims=-1)
+    del hk, hv, hq
+    kw = dict(B=w.B, Hq=w.Hq, Hkv=w.Hkv, D=w.D, T_max=-(-w.T // w.R) * w.R, Gk=w.Gk, Gv=w.Gv, R=w.R, k4=w.k4, k16=w.k16)
+    gc = M.Cache(M.make_config(**kw))
+    sel = torch.empty((w.B, w.Hkv, w.k4 + w.k16), dtype=torch.uint8, device="cuda")
+
+    def step(with_q=True):
+        gc.reset()
+        M.mixkvq_select_channels(gc, dq if with_q else None, dk, sel=sel)
+        M.mixkvq_quantize_append(gc, dk, dv, sel=sel)
+
+    def timed(n, **kws):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            step(**kws)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
+    for _ in range(args.warmup):
+        step()
+    el = timed(args.steps)
+    el_noq = timed(args.steps, with_q=False)
+    in_b, out_b = prefill_bytes(w, Lq)
+    in_noq = in_b - w.B * w.Hq * Lq * w.D * 2
+    value = in_b / el / 1e9
+    result = {
+        "metric": "prefill quantization: GB/s of fp16 input consumed (K, V, prompt queries)", "value": round(value, 2),
+        "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(el * 1e3, 4),
+        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "T": w.T, "Lq": Lq, "Gk": w.Gk,
+                   "Gv": w.Gv, "R": w.R, "k4": w.k4, "k16": w.k16, "input_bytes": in_b, "written_bytes": out_b,
+                   "step": "cache_reset + select_channels(Q, K) + quantize_append(K, V, sel)"},
+        "without_prompt_queries": {"ms_per_step": round(el_noq * 1e3, 4), "value": round(in_noq / el_noq / 1e9, 2),
+                                   "unit": "GB/s", "input_bytes": in_noq},
+        "roofline": {"bound": "hbm", "kernel": "whole step (qabs_accumulate, key_range, flush_block: streaming kernels)",
+                     "achieved": round((in_b + out_b) / el / 1e9, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round((in_b + out_b) / el / 1e9 / HBM_PEAK_GBS, 4), "traffic": None},
+    }
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1024)
     ap.add_argument("--warmup", type=int, default=64)
-    ap.add_argument("--config", type=int, default=1, help="BASELINE configuration id (1, 2 or 3)")
+    ap.add_argument("--config", type=int, default=1, help="BASELINE configuration id (1, 2, 3: decode step; 4: prefill)")
     ap.add_argument("--copies", type=int, default=0, help="independent cache copies rotated over (0 = enough for 2x LLC)")
     ap.add_argument("--host-batch", type=int, default=2)
     ap.add_argument("--tokens", type=int, default=0, help="override the context length of the configuration")
@@ -155,6 +226,10 @@ def main():
     w = S.WORKLOADS[args.config]
     if args.tokens:
         w = S.scaled_workload(args.config, T=args.tokens)
+    if args.config == 4:
+        args.steps, args.warmup = min(args.steps, 8), min(args.warmup, 2)
+        bench_prefill(args, w, args.config)
+        return
     n_q0 = w.R * (-(-w.T // w.R) - 1)
     step_bytes = algorithmic_bytes(w, n_q0, w.T - n_q0)
     copies = args.copies or max(1, math.ceil(2 * LLC_BYTES / step_bytes))

@@ -23,36 +23,96 @@ hipError_t launch_zero_qacc(const CacheView& v, hipStream_t s) {
 
 // ---------------------------------------------------------------------------
 // Eq. 6: sum of |q| per KV head and channel, over tokens and the g query heads
-// of the group.  One thread per channel; 128-bit loads are not needed for the
-// decode case (one token), and the prefill case streams rows of 256 bytes.
+// of the group.  Streaming form: a workgroup takes kRowsPerWG rows of one query head;
+// 16 threads cover a row of 256 bytes with one 16-byte load each, 16 rows per pass,
+// four passes in flight.  Per-thread 64-bit sums, one LDS reduction over the 16 row
+// lanes, one 64-bit atomic per channel and workgroup (integers: any order is exact).
 // ---------------------------------------------------------------------------
-constexpr int kQTokensPerBlock = 64;
+constexpr int kStreamThreads = 256;
+constexpr int kRowsPerWG = 512;
 
-__global__ void __launch_bounds__(kD) qabs_accumulate_kernel(const __half* __restrict__ q, int Lq, Strides3 qs, int Hkv,
-                                                            int g, unsigned long long* __restrict__ qacc,
-                                                            unsigned long long* __restrict__ qcnt) {
-  const int p = blockIdx.x, b = p / Hkv, j = p % Hkv, d = threadIdx.x;
-  const int t0 = blockIdx.y * kQTokensPerBlock;
-  const int t1 = min(Lq, t0 + kQTokensPerBlock);
-  unsigned long long acc = 0;
-  for (int hh = 0; hh < g; ++hh) {
-    const __half* base = q + (int64_t)b * qs.b + (int64_t)(j * g + hh) * qs.h + d;
-    for (int t = t0; t < t1; ++t) acc += fix24_abs(h2bits(base[(int64_t)t * qs.t]));
+__device__ __forceinline__ void add8(unsigned long long (&acc)[8], uint4 v) {
+  const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    acc[2 * i] += fix24_abs((unsigned short)(w[i] & 0xffffu));
+    acc[2 * i + 1] += fix24_abs((unsigned short)(w[i] >> 16));
   }
+}
+
+__global__ void __launch_bounds__(kStreamThreads)
+qabs_accumulate_kernel(const __half* __restrict__ q, int Lq, Strides3 qs, int Hkv, int g,
+                       unsigned long long* __restrict__ qacc, unsigned long long* __restrict__ qcnt) {
+  __shared__ unsigned long long sAcc[16][kD];
+  const int p = blockIdx.x, b = p / Hkv, j = p % Hkv, tid = threadIdx.x;
+  const int hh = blockIdx.y % g, chunk = blockIdx.y / g;
+  const int c = tid & 15, r = tid >> 4;
+  const int t0 = chunk * kRowsPerWG, t1 = min(Lq, t0 + kRowsPerWG);
+  const __half* base = q + (int64_t)b * qs.b + (int64_t)(j * g + hh) * qs.h + 8 * c;
+  unsigned long long acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = 0ull;
+  int t = t0 + r;
+  for (; t + 48 < t1; t += 64) {
+    uint4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const uint4*>(base + (int64_t)(t + 16 * u) * qs.t);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) add8(acc, v[u]);
+  }
+  for (; t < t1; t += 16) add8(acc, *reinterpret_cast<const uint4*>(base + (int64_t)t * qs.t));
+#pragma unroll
+  for (int i = 0; i < 8; ++i) sAcc[r][8 * c + i] = acc[i];
+  __syncthreads();
+  if (tid < kD) {
+    unsigned long long sum = 0;
+#pragma unroll
+    for (int rr = 0; rr < 16; ++rr) sum += sAcc[rr][tid];
+    atomicAdd(&qacc[(size_t)p * kD + tid], sum);
+  }
+  if (tid == 0) atomicAdd(&qcnt[p], (unsigned long long)(t1 - t0));
+}
+
+// Fallback for tensors whose rows are not 16-byte aligned: one thread per channel.
+__global__ void __launch_bounds__(kD) qabs_accumulate_unaligned_kernel(const __half* __restrict__ q, int Lq, Strides3 qs,
+                                                                      int Hkv, int g,
+                                                                      unsigned long long* __restrict__ qacc,
+                                                                      unsigned long long* __restrict__ qcnt) {
+  const int p = blockIdx.x, b = p / Hkv, j = p % Hkv, d = threadIdx.x;
+  const int hh = blockIdx.y % g, chunk = blockIdx.y / g;
+  const int t0 = chunk * kRowsPerWG, t1 = min(Lq, t0 + kRowsPerWG);
+  const __half* base = q + (int64_t)b * qs.b + (int64_t)(j * g + hh) * qs.h + d;
+  unsigned long long acc = 0;
+  for (int t = t0; t < t1; ++t) acc += fix24_abs(h2bits(base[(int64_t)t * qs.t]));
   atomicAdd(&qacc[(size_t)p * kD + d], acc);
-  if (d == 0) atomicAdd(&qcnt[p], (unsigned long long)g * (unsigned long long)(t1 - t0));
+  if (d == 0) atomicAdd(&qcnt[p], (unsigned long long)(t1 - t0));
+}
+
+static bool rows_aligned16(const void* ptr, Strides3 st) {
+  return (reinterpret_cast<uintptr_t>(ptr) & 15u) == 0 && st.b % 8 == 0 && st.h % 8 == 0 && st.t % 8 == 0;
 }
 
 hipError_t launch_qabs_accumulate(const CacheView& v, const __half* q, int Lq, Strides3 qs, hipStream_t s) {
-  dim3 grid(v.P, (Lq + kQTokensPerBlock - 1) / kQTokensPerBlock);
-  qabs_accumulate_kernel<<<grid, dim3(kD), 0, s>>>(q, Lq, qs, v.cfg.Hkv, v.g, v.qacc, v.qcnt);
+  dim3 grid(v.P, v.g * ((Lq + kRowsPerWG - 1) / kRowsPerWG));
+  if (rows_aligned16(q, qs))
+    qabs_accumulate_kernel<<<grid, dim3(kStreamThreads), 0, s>>>(q, Lq, qs, v.cfg.Hkv, v.g, v.qacc, v.qcnt);
+  else
+    qabs_accumulate_unaligned_kernel<<<grid, dim3(kD), 0, s>>>(q, Lq, qs, v.cfg.Hkv, v.g, v.qacc, v.qcnt);
   return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
-// Eq. 7: per-channel min and max of the keys over L tokens (exact integers).
+// Eq. 7: per-channel min and max of the keys over L tokens.  Same streaming form; the
+// running min/max are kept on packed 16-bit keys that order like the fp16 values
+// (sign-magnitude -> two's complement), two channels per instruction, and only the
+// workgroup's result is converted to the exact integers the atomics work on.
 // ---------------------------------------------------------------------------
-constexpr int kKTokensPerBlock = 256;
+typedef short s16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ s16x2 order_key(unsigned w) {     // involution: also maps keys back to fp16 bits
+  const s16x2 v = __builtin_bit_cast(s16x2, w);
+  return v ^ ((v >> 15) & (short)0x7fff);
+}
 
 __global__ void range_init_kernel(long long* mn, long long* mx, int n) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -62,11 +122,69 @@ __global__ void range_init_kernel(long long* mn, long long* mx, int n) {
   }
 }
 
-__global__ void __launch_bounds__(kD) key_range_kernel(const __half* __restrict__ k, int L, Strides3 ks, int Hkv,
-                                                      long long* __restrict__ mn, long long* __restrict__ mx) {
+__global__ void __launch_bounds__(kStreamThreads)
+key_range_kernel(const __half* __restrict__ k, int L, Strides3 ks, int Hkv, long long* __restrict__ mn,
+                 long long* __restrict__ mx) {
+  __shared__ unsigned sLo[16][kD / 2], sHi[16][kD / 2];
+  const int p = blockIdx.x, b = p / Hkv, j = p % Hkv, tid = threadIdx.x;
+  const int c = tid & 15, r = tid >> 4;
+  const int t0 = blockIdx.y * kRowsPerWG, t1 = min(L, t0 + kRowsPerWG);
+  const __half* base = k + (int64_t)b * ks.b + (int64_t)j * ks.h + 8 * c;
+  s16x2 lo[4], hi[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    lo[i] = s16x2{(short)0x7fff, (short)0x7fff};
+    hi[i] = s16x2{(short)-0x8000, (short)-0x8000};
+  }
+  auto upd = [&](uint4 v) {
+    const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const s16x2 key = order_key(w[i]);
+      lo[i] = __builtin_elementwise_min(lo[i], key);
+      hi[i] = __builtin_elementwise_max(hi[i], key);
+    }
+  };
+  int t = t0 + r;
+  for (; t + 48 < t1; t += 64) {
+    uint4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const uint4*>(base + (int64_t)(t + 16 * u) * ks.t);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) upd(v[u]);
+  }
+  for (; t < t1; t += 16) upd(*reinterpret_cast<const uint4*>(base + (int64_t)t * ks.t));
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    sLo[r][4 * c + i] = __builtin_bit_cast(unsigned, lo[i]);
+    sHi[r][4 * c + i] = __builtin_bit_cast(unsigned, hi[i]);
+  }
+  __syncthreads();
+  if (tid < kD / 2) {
+    s16x2 l = __builtin_bit_cast(s16x2, sLo[0][tid]), h = __builtin_bit_cast(s16x2, sHi[0][tid]);
+#pragma unroll
+    for (int rr = 1; rr < 16; ++rr) {
+      l = __builtin_elementwise_min(l, __builtin_bit_cast(s16x2, sLo[rr][tid]));
+      h = __builtin_elementwise_max(h, __builtin_bit_cast(s16x2, sHi[rr][tid]));
+    }
+    const unsigned lb = __builtin_bit_cast(unsigned, order_key(__builtin_bit_cast(unsigned, l)));
+    const unsigned hb = __builtin_bit_cast(unsigned, order_key(__builtin_bit_cast(unsigned, h)));
+    const size_t o = (size_t)p * kD + 2 * tid;
+    if (t1 > t0) {
+      atomicMin(&mn[o], fix24((unsigned short)(lb & 0xffffu)));
+      atomicMin(&mn[o + 1], fix24((unsigned short)(lb >> 16)));
+      atomicMax(&mx[o], fix24((unsigned short)(hb & 0xffffu)));
+      atomicMax(&mx[o + 1], fix24((unsigned short)(hb >> 16)));
+    }
+  }
+}
+
+__global__ void __launch_bounds__(kD) key_range_unaligned_kernel(const __half* __restrict__ k, int L, Strides3 ks,
+                                                                int Hkv, long long* __restrict__ mn,
+                                                                long long* __restrict__ mx) {
   const int p = blockIdx.x, b = p / Hkv, j = p % Hkv, d = threadIdx.x;
-  const int t0 = blockIdx.y * kKTokensPerBlock;
-  const int t1 = min(L, t0 + kKTokensPerBlock);
+  const int t0 = blockIdx.y * kRowsPerWG;
+  const int t1 = min(L, t0 + kRowsPerWG);
   const __half* base = k + (int64_t)b * ks.b + (int64_t)j * ks.h + d;
   long long lo = 0x7fffffffffffffffll, hi = -0x7fffffffffffffffll - 1;
   for (int t = t0; t < t1; ++t) {
@@ -120,8 +238,11 @@ hipError_t launch_select(const CacheView& v, const __half* k, int L, Strides3 ks
   long long* mx = mn + (size_t)v.P * kD;
   const int n = v.P * kD;
   range_init_kernel<<<dim3((n + 255) / 256), dim3(256), 0, s>>>(mn, mx, n);
-  dim3 grid(v.P, (L + kKTokensPerBlock - 1) / kKTokensPerBlock);
-  key_range_kernel<<<grid, dim3(kD), 0, s>>>(k, L, ks, v.cfg.Hkv, mn, mx);
+  dim3 grid(v.P, (L + kRowsPerWG - 1) / kRowsPerWG);
+  if (rows_aligned16(k, ks))
+    key_range_kernel<<<grid, dim3(kStreamThreads), 0, s>>>(k, L, ks, v.cfg.Hkv, mn, mx);
+  else
+    key_range_unaligned_kernel<<<grid, dim3(kD), 0, s>>>(k, L, ks, v.cfg.Hkv, mn, mx);
   select_topk_kernel<<<dim3(v.P), dim3(kD), 0, s>>>(v.qacc, mn, mx, v.cfg.k16, v.cfg.k4, v.cfg.score_mode, sel);
   return hipGetLastError();
 }
