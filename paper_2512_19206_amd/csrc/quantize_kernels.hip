@@ -225,14 +225,384 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
   }
 }
 
+// ---------------------------------------------------------------------------
+// The same record, built for throughput (Gk a multiple of 16, Gv >= 16, 16-byte aligned rows):
+//   - both tiles are fetched with all loads in flight at once (the value tile waits in registers while the
+//     keys are encoded);
+//   - minima and maxima are taken on packed 16-bit keys that order like the fp16 values, two channels per
+//     instruction, first per chunk of 16 tokens (all threads), then per group / per block;
+//   - positions inside the tiers come from wavefront ballots;
+//   - in the encode loops a thread keeps the scale and zero-point of its channels (keys) or tokens (values)
+//     in registers and only the element itself comes from LDS.
+// Every rounding step is the one of flush_block_kernel: results are bit-identical.
+// ---------------------------------------------------------------------------
+typedef short fs16x2 __attribute__((ext_vector_type(2)));
+
+#ifdef MIXKVQ_PHASE_CLOCKS
+// Profiling aid, not part of the default build: 100 MHz timestamps of the phases of the first 1024 workgroups.
+__device__ unsigned long long g_flush_clock[1024 * 16];
+#define MIXKVQ_FPHASE(K_)                                                      \
+  if (threadIdx.x == 0 && blockIdx.x + gridDim.x * blockIdx.y < 1024)          \
+    g_flush_clock[(blockIdx.x + gridDim.x * blockIdx.y) * 16 + (K_)] = wall_clock64();
+#else
+#define MIXKVQ_FPHASE(K_)
+#endif
+
+__device__ __forceinline__ fs16x2 fkey(unsigned w) {   // fp16 pair -> keys ordered like the values (an involution)
+  const fs16x2 v = __builtin_bit_cast(fs16x2, w);
+  return v ^ ((v >> 15) & (short)0x7fff);
+}
+__device__ __forceinline__ float key_to_float(short key) {
+  const unsigned short bits = (unsigned short)(key ^ ((key >> 15) & (short)0x7fff));
+  return __half2float(__ushort_as_half(bits));
+}
+
+// Two-bit code of u = x - z with the reciprocal r of the scale (r = 0 for scale 0).  q0 = u*r is within 1e-6 of the
+// correctly rounded quotient (u/s < 4.3, rcp and the product are good to 1.8e-7 relative), so whenever q0 is
+// further than 2^-18 from every half-integer, rint(q0) IS the code Eq. 2 defines; `near` collects the other
+// cases, which the caller redoes with the IEEE division.
+__device__ __forceinline__ unsigned code2_fast(float x, float z, float r, bool& near) {
+  const float q0 = (x - z) * r;
+  const float fr = q0 - floorf(q0);
+  near |= fabsf(fr - 0.5f) < 3.814697265625e-6f;
+  return (unsigned)fminf(fmaxf(rintf(q0), 0.f), 3.f);
+}
+__device__ __forceinline__ float safe_rcp(float s) { return s > 0.f ? __builtin_amdgcn_rcpf(s) : 0.f; }
+
+__device__ __forceinline__ uint4 load_chunk(const __half* res, const __half* fresh, Strides3 st, int p, int Hkv, int R,
+                                            int r0, int pos0, int idx) {
+  const int t = idx >> 4, c = idx & 15;
+  return *reinterpret_cast<const uint4*>(token_row(res, fresh, st, p, Hkv, R, r0, pos0 + t) + c * 8);
+}
+
+__global__ void __launch_bounds__(kFlushThreads, 3)   // three workgroups per CU (LDS) = three wavefronts per SIMD
+flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __half* __restrict__ v_new, Strides3 st,
+                        int r0, int first_block, const uint8_t* __restrict__ sel_in) {
+  __shared__ __align__(16) __half sT[kMaxR * kRowStride];   // K tile, then V tile
+  __shared__ double sA[kD];
+  __shared__ unsigned char sTier[kD];      // 0: 2 bit, 1: 4 bit, 2: fp16
+  __shared__ unsigned char sPos[kD];       // position of the channel inside its tier
+  __shared__ unsigned char sLoList[kD];    // 2-bit channels, ascending
+  __shared__ unsigned char sHiList[kD];    // fp16 tier then 4-bit tier
+  __shared__ __align__(16) float sS[8 * kD], sZ[8 * kD];   // keys: [group][channel]; values: [token][value group]
+  __shared__ unsigned sKmax[8];
+  __shared__ unsigned sChunk[2][kMaxR / 16][kD / 2];   // (min, max) keys per 16-token chunk and channel pair
+  unsigned (*sCLo)[kD / 2] = sChunk[0];
+  unsigned (*sCHi)[kD / 2] = sChunk[1];
+  __shared__ int sCnt[3];                  // channels per tier in wavefront 0
+
+  const int R = cv.cfg.R, Gk = cv.cfg.Gk, Gv = cv.cfg.Gv, k4 = cv.cfg.k4, k16 = cv.cfg.k16, ks = k4 + k16;
+  const int Hkv = cv.cfg.Hkv, score_mode = cv.cfg.score_mode;
+  const int rec_bytes = cv.lay.rec_bytes, off_idx = cv.lay.off_idx, off_kmax = cv.lay.off_kmax,
+            off_klo_s = cv.lay.off_klo_s, off_klo_z = cv.lay.off_klo_z, off_k4_s = cv.lay.off_k4_s,
+            off_k4_z = cv.lay.off_k4_z, off_klo = cv.lay.off_klo, off_k4 = cv.lay.off_k4, off_k16 = cv.lay.off_k16,
+            off_v = cv.lay.off_v, off_v_s = cv.lay.off_v_s, off_v_z = cv.lay.off_v_z, NL = cv.lay.NL, NLp = cv.lay.NLp,
+            Wlo = cv.lay.Wlo, W4 = cv.lay.W4, NG = cv.lay.NG, NVG = cv.lay.NVG;
+  const int p = blockIdx.x, f = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  uint8_t* rec = cv.blocks + ((size_t)p * cv.NB + first_block + f) * rec_bytes;
+  const int n_chunks16 = R * 16;           // 16-byte pieces of a tile
+  const int n_ch = R / 16;                 // chunks of 16 tokens
+
+  MIXKVQ_FPHASE(0)
+  // ---- both tiles: every load in flight ------------------------------------------------------
+  uint4 kreg[8], vreg[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int idx = tid + kFlushThreads * i;
+    kreg[i] = make_uint4(0u, 0u, 0u, 0u);
+    if (idx < n_chunks16) kreg[i] = load_chunk(cv.res_k, k_new, st, p, Hkv, R, r0, f * R, idx);
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int idx = tid + kFlushThreads * i;
+    vreg[i] = make_uint4(0u, 0u, 0u, 0u);
+    if (idx < n_chunks16) vreg[i] = load_chunk(cv.res_v, v_new, st, p, Hkv, R, r0, f * R, idx);
+  }
+  // zero the small planes of the record (index bytes, tails of the scale/zero planes)
+  for (int i = tid; i < off_klo / 4; i += kFlushThreads) reinterpret_cast<unsigned*>(rec)[i] = 0u;
+  if (tid < 8) sKmax[tid] = 0u;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int idx = tid + kFlushThreads * i;
+    if (idx < n_chunks16) *reinterpret_cast<uint4*>(sT + (idx >> 4) * kRowStride + (idx & 15) * 8) = kreg[i];
+  }
+  __syncthreads();
+
+  MIXKVQ_FPHASE(1)
+  // ---- minimum / maximum per chunk of 16 tokens and channel pair -----------------------------
+  {
+    const int d2 = tid & 63;
+    const unsigned* sT32 = reinterpret_cast<const unsigned*>(sT);
+    for (int ch = tid >> 6; ch < n_ch; ch += 4) {
+      fs16x2 lo = fkey(sT32[(16 * ch) * (kRowStride / 2) + d2]), hi = lo;
+#pragma unroll
+      for (int t = 1; t < 16; ++t) {
+        const fs16x2 key = fkey(sT32[(16 * ch + t) * (kRowStride / 2) + d2]);
+        lo = __builtin_elementwise_min(lo, key);
+        hi = __builtin_elementwise_max(hi, key);
+      }
+      sCLo[ch][d2] = __builtin_bit_cast(unsigned, lo);
+      sCHi[ch][d2] = __builtin_bit_cast(unsigned, hi);
+    }
+  }
+  __syncthreads();
+
+  MIXKVQ_FPHASE(2)
+  // ---- channel tiers ------------------------------------------------------------------------
+  if (sel_in == nullptr && ks > 0) {
+    double A = 0.0;
+    if (tid < kD) {
+      const short* cl = reinterpret_cast<const short*>(&sCLo[0][0]);
+      const short* chh = reinterpret_cast<const short*>(&sCHi[0][0]);
+      short lo = cl[tid], hi = chh[tid];
+      for (int ch = 1; ch < n_ch; ++ch) {
+        const short a = cl[ch * kD + tid], b2 = chh[ch * kD + tid];
+        lo = a < lo ? a : lo;
+        hi = b2 > hi ? b2 : hi;
+      }
+      const long long rng = fix24((unsigned short)(hi ^ ((hi >> 15) & (short)0x7fff))) -
+                            fix24((unsigned short)(lo ^ ((lo >> 15) & (short)0x7fff)));
+      A = score_mode ? (double)rng : (double)cv.qacc[(size_t)p * kD + tid] * (double)rng;
+      sA[tid] = A;
+    }
+    __syncthreads();
+    if (tid < kD) {
+      int rank = 0;
+      for (int e = 0; e < kD; ++e) {
+        const double o = sA[e];
+        rank += (o > A) || (o == A && e < tid);
+      }
+      sTier[tid] = rank < k16 ? 2 : (rank < ks ? 1 : 0);
+    }
+  } else {
+    if (tid < kD) sTier[tid] = 0;
+    __syncthreads();
+    if (tid < ks) sTier[sel_in[(size_t)p * ks + tid]] = tid < k16 ? 2 : 1;
+  }
+  __syncthreads();
+  // position of every channel inside its tier: ballots over the two wavefronts that hold the channels
+  {
+    const int tier = tid < kD ? sTier[tid] : 3;
+    const unsigned long long m0 = __ballot(tier == 0), m1 = __ballot(tier == 1), m2 = __ballot(tier == 2);
+    if (tid == 0) {
+      sCnt[0] = __popcll(m0);
+      sCnt[1] = __popcll(m1);
+      sCnt[2] = __popcll(m2);
+    }
+    __syncthreads();
+    if (tid < kD) {
+      const unsigned long long mine = tier == 0 ? m0 : (tier == 1 ? m1 : m2);
+      const int pos = __popcll(mine & ((1ull << lane) - 1ull)) + (wave == 1 ? sCnt[tier] : 0);
+      sPos[tid] = (unsigned char)pos;
+      if (tier == 0) sLoList[pos] = (unsigned char)tid;
+      else {
+        const int slot = (tier == 2 ? 0 : k16) + pos;
+        sHiList[slot] = (unsigned char)tid;
+        rec[off_idx + slot] = (uint8_t)tid;
+      }
+    }
+  }
+  __syncthreads();
+
+  MIXKVQ_FPHASE(3)
+  // ---- key group parameters from the chunk extrema ------------------------------------------
+  {
+    const short* cl = reinterpret_cast<const short*>(&sCLo[0][0]);
+    const short* chh = reinterpret_cast<const short*>(&sCHi[0][0]);
+    const int cpg = Gk / 16;     // chunks per group
+    for (int it = tid; it < NG * kD; it += kFlushThreads) {
+      const int grp = it / kD, d = it % kD;
+      const unsigned char tier = sTier[d];
+      if (tier == 2) continue;
+      short lo = cl[(grp * cpg) * kD + d], hi = chh[(grp * cpg) * kD + d];
+      for (int c = 1; c < cpg; ++c) {
+        const short a = cl[(grp * cpg + c) * kD + d], b2 = chh[(grp * cpg + c) * kD + d];
+        lo = a < lo ? a : lo;
+        hi = b2 > hi ? b2 : hi;
+      }
+      const GroupParams gp = group_params(key_to_float(lo), key_to_float(hi), tier ? 15.f : 3.f);
+      sS[grp * kD + d] = gp.s;
+      sZ[grp * kD + d] = gp.z;
+      const int pos = sPos[d];
+      atomicMax(&sKmax[grp], (unsigned)gp.s16);
+      if (tier == 0) {
+        reinterpret_cast<unsigned short*>(rec + off_klo_s)[grp * NLp + pos] = gp.s16;
+        reinterpret_cast<unsigned short*>(rec + off_klo_z)[grp * NLp + pos] = gp.z16;
+      } else {
+        reinterpret_cast<unsigned short*>(rec + off_k4_s)[grp * k4 + pos] = gp.s16;
+        reinterpret_cast<unsigned short*>(rec + off_k4_z)[grp * k4 + pos] = gp.z16;
+      }
+    }
+  }
+  __syncthreads();
+  if (tid < NG) reinterpret_cast<unsigned short*>(rec + off_kmax)[tid] = (unsigned short)sKmax[tid];
+
+  MIXKVQ_FPHASE(4)
+  // ---- 2-bit key words [token][Wlo]: thread = (word column, token lane); the 16 channels of the column
+  //      and their parameters stay in registers ---------------------------------------------------------
+  {
+    const int wd = tid & 7, tl = tid >> 3;
+    if (wd < Wlo) {
+      int doff[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int jj = 16 * wd + i;
+        doff[i] = jj < NL ? (int)sLoList[jj] : -1;
+      }
+      for (int grp = 0; grp < NG; ++grp) {
+        float rc[16], zp[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int d = doff[i] < 0 ? 0 : doff[i];
+          rc[i] = doff[i] < 0 ? 0.f : safe_rcp(sS[grp * kD + d]);   // 0 gives code 0: the padding of the last word
+          zp[i] = sZ[grp * kD + d];
+        }
+        for (int tt = tl; tt < Gk; tt += 32) {
+          const int t = grp * Gk + tt;
+          const __half* row = sT + t * kRowStride;
+          unsigned w = 0;
+          bool near = false;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const float x = __half2float(row[doff[i] < 0 ? 0 : doff[i]]);
+            w |= code2_fast(x, zp[i], rc[i], near) << (16 * (i & 1) + 2 * (i >> 1));
+          }
+          if (__any(near)) {     // rare: some quotient sits next to a rounding boundary
+            w = 0;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int d = doff[i] < 0 ? 0 : doff[i];
+              const float x = __half2float(row[d]);
+              w |= encode(x, zp[i], doff[i] < 0 ? 0.f : sS[grp * kD + d], 3.f) << (16 * (i & 1) + 2 * (i >> 1));
+            }
+          }
+          reinterpret_cast<unsigned*>(rec + off_klo)[t * Wlo + wd] = w;
+        }
+      }
+    }
+  }
+  MIXKVQ_FPHASE(5)
+  // ---- 4-bit key words: [token][k4/8] -------------------------------------
+  for (int it = tid; it < R * W4; it += kFlushThreads) {
+    const int t = it / W4, wd = it % W4, grp = t / Gk;
+    unsigned w = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int d = sHiList[k16 + wd * 8 + i];
+      w |= encode(__half2float(sT[t * kRowStride + d]), sZ[grp * kD + d], sS[grp * kD + d], 15.f) << (16 * (i & 1) + 4 * (i >> 1));
+    }
+    reinterpret_cast<unsigned*>(rec + off_k4)[it] = w;
+  }
+  // ---- fp16 tier: [token][k16] ------------------------------------------
+  for (int it = tid; it < R * k16; it += kFlushThreads) {
+    const int t = it / k16, i = it % k16;
+    reinterpret_cast<__half*>(rec + off_k16)[it] = sT[t * kRowStride + sHiList[i]];
+  }
+  __syncthreads();
+
+  MIXKVQ_FPHASE(6)
+  // ---- values ---------------------------------------------------------------------------------
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int idx = tid + kFlushThreads * i;
+    if (idx < n_chunks16) *reinterpret_cast<uint4*>(sT + (idx >> 4) * kRowStride + (idx & 15) * 8) = vreg[i];
+  }
+  __syncthreads();
+  MIXKVQ_FPHASE(7)
+  float* sVS = sS;   // [token][NVG]
+  float* sVZ = sZ;
+  {
+    // per token and value group: 16 threads cover a row, a group is Gv/8 neighbouring threads.  The pair
+    // (min key, ~max key) is reduced with packed 16-bit minima over DPP lane exchanges inside the row of 16.
+    const int c = tid & 15, lpg = Gv / 8;
+    unsigned* sRow = &sChunk[0][0][0];     // [token][value group] packed (min key, ~max key); <= 128 * 8 entries
+    for (int row = tid >> 4; row < R; row += 16) {
+      const uint4 v = *reinterpret_cast<const uint4*>(sT + row * kRowStride + c * 8);
+      const fs16x2 k0 = fkey(v.x), k1 = fkey(v.y), k2 = fkey(v.z), k3 = fkey(v.w);
+      const fs16x2 lo2 = __builtin_elementwise_min(__builtin_elementwise_min(k0, k1), __builtin_elementwise_min(k2, k3));
+      const fs16x2 hi2 = __builtin_elementwise_max(__builtin_elementwise_max(k0, k1), __builtin_elementwise_max(k2, k3));
+      fs16x2 m;
+      m[0] = lo2[0] < lo2[1] ? lo2[0] : lo2[1];
+      m[1] = (short)~(hi2[0] > hi2[1] ? hi2[0] : hi2[1]);
+      int mi = __builtin_bit_cast(int, m);
+#define MIXKVQ_DPP_MIN(CTRL)                                                                                   \
+  mi = __builtin_bit_cast(int, __builtin_elementwise_min(                                                      \
+      __builtin_bit_cast(fs16x2, mi), __builtin_bit_cast(fs16x2, __builtin_amdgcn_update_dpp(mi, mi, CTRL, 0xf, 0xf, false))));
+      if (lpg >= 2) MIXKVQ_DPP_MIN(0xB1)     // quad_perm [1,0,3,2]
+      if (lpg >= 4) MIXKVQ_DPP_MIN(0x4E)     // quad_perm [2,3,0,1]
+      if (lpg >= 8) MIXKVQ_DPP_MIN(0x141)    // row_half_mirror
+      if (lpg >= 16) MIXKVQ_DPP_MIN(0x140)   // row_mirror
+#undef MIXKVQ_DPP_MIN
+      if (c % lpg == 0) sRow[row * NVG + c / lpg] = (unsigned)mi;
+    }
+    __syncthreads();
+    for (int it = tid; it < R * NVG; it += kFlushThreads) {
+      const unsigned mi = sRow[it];
+      const GroupParams gp = group_params(key_to_float((short)(mi & 0xffffu)), key_to_float((short)~(mi >> 16)), 3.f);
+      sVS[it] = gp.s;
+      sVZ[it] = gp.z;
+      reinterpret_cast<unsigned short*>(rec + off_v_s)[it] = gp.s16;
+      reinterpret_cast<unsigned short*>(rec + off_v_z)[it] = gp.z16;
+    }
+  }
+  __syncthreads();
+  MIXKVQ_FPHASE(8)
+  // value words [token group][channel], 16 codes along tokens: the 16 tokens' parameters in registers
+  {
+    const int d = tid & (kD - 1), vg = d / Gv;
+    for (int tg = tid >> 7; tg < n_ch; tg += 2) {
+      float sc[16], zp[16];
+      if (NVG == 1) {
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const float4 a = *reinterpret_cast<const float4*>(sVS + tg * 16 + 4 * i4);
+          const float4 b2 = *reinterpret_cast<const float4*>(sVZ + tg * 16 + 4 * i4);
+          sc[4 * i4] = a.x; sc[4 * i4 + 1] = a.y; sc[4 * i4 + 2] = a.z; sc[4 * i4 + 3] = a.w;
+          zp[4 * i4] = b2.x; zp[4 * i4 + 1] = b2.y; zp[4 * i4 + 2] = b2.z; zp[4 * i4 + 3] = b2.w;
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          sc[i] = sVS[(tg * 16 + i) * NVG + vg];
+          zp[i] = sVZ[(tg * 16 + i) * NVG + vg];
+        }
+      }
+      unsigned w = 0;
+      bool near = false;
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        w |= code2_fast(__half2float(sT[(tg * 16 + i) * kRowStride + d]), zp[i], safe_rcp(sc[i]), near)
+             << (16 * (i & 1) + 2 * (i >> 1));
+      if (__any(near)) {     // rare: some quotient sits next to a rounding boundary
+        w = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          w |= encode(__half2float(sT[(tg * 16 + i) * kRowStride + d]), zp[i], sc[i], 3.f) << (16 * (i & 1) + 2 * (i >> 1));
+      }
+      reinterpret_cast<unsigned*>(rec + off_v)[tg * kD + d] = w;
+    }
+  }
+  MIXKVQ_FPHASE(9)
+}
+
 hipError_t launch_flush(const CacheView& v, const __half* k_new, const __half* v_new, Strides3 kvs, int r0,
                         int first_block, int n_flush, const uint8_t* sel, hipStream_t s) {
+  // the throughput kernel needs 16-token chunks inside key groups, whole 16-byte pieces inside value groups and
+  // 16-byte aligned rows; anything else takes the general kernel
+  const bool aligned = ((reinterpret_cast<uintptr_t>(k_new) | reinterpret_cast<uintptr_t>(v_new)) & 15u) == 0 &&
+                       kvs.b % 8 == 0 && kvs.h % 8 == 0 && kvs.t % 8 == 0;
+  static const bool force_general = getenv("MIXKVQ_FLUSH_GENERAL") != nullptr;
+  const bool fast = aligned && v.cfg.Gk % 16 == 0 && v.cfg.Gv % 16 == 0 && !force_general;
   // grid.y is limited to 65535 blocks per launch
   for (int f0 = 0; f0 < n_flush; f0 += 32768) {
     const int nf = n_flush - f0 < 32768 ? n_flush - f0 : 32768;
     // shift the stream origin so that block index 0 of this launch is block f0 of the call
-    flush_block_kernel<<<dim3(v.P, nf), dim3(kFlushThreads), 0, s>>>(v, k_new, v_new, kvs, r0 - f0 * v.cfg.R,
-                                                                    first_block + f0, sel);
+    if (fast)
+      flush_block_fast_kernel<<<dim3(v.P, nf), dim3(kFlushThreads), 0, s>>>(v, k_new, v_new, kvs, r0 - f0 * v.cfg.R,
+                                                                           first_block + f0, sel);
+    else
+      flush_block_kernel<<<dim3(v.P, nf), dim3(kFlushThreads), 0, s>>>(v, k_new, v_new, kvs, r0 - f0 * v.cfg.R,
+                                                                      first_block + f0, sel);
   }
   return hipGetLastError();
 }
@@ -263,3 +633,10 @@ hipError_t launch_residual_copy(const CacheView& v, const __half* k_new, const _
 }
 
 }  // namespace mixkvq
+
+#ifdef MIXKVQ_PHASE_CLOCKS
+extern "C" int mixkvq_debug_flush_clocks(void* host_dst, size_t bytes) {
+  (void)hipDeviceSynchronize();
+  return (int)hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(mixkvq::g_flush_clock), bytes);
+}
+#endif
