@@ -206,6 +206,26 @@ def test_few_pairs_many_splits(H, B, Hkv, g, n_blocks, n_res):
     H.check_state(oc, gc)
 
 
+def test_quotients_on_rounding_boundaries(H):
+    """Integer-valued inputs make (x - z)/s land exactly on k + 1/2 (ties go to even) and right next to it: the
+    quantize kernel's reciprocal shortcut must hand these to the exact division."""
+    rng = np.random.default_rng(41)
+    kw = dict(B=1, Hq=4, Hkv=2, D=128, T_max=512, Gk=64, Gv=128, R=128, k4=16, k16=0)
+    oc, gc = H.make_pair(**kw)
+    n = 300
+    K = rng.integers(0, 7, size=(1, 2, n, 128)).astype(np.float16)          # range 6 -> scale 2 -> quotients k/2
+    K[..., :16] = rng.integers(0, 31, size=(1, 2, n, 16)).astype(np.float16)  # range 30 -> 4-bit scale 2
+    V = rng.integers(-3, 4, size=(1, 2, n, 128)).astype(np.float16)
+    V[:, :, ::3] *= np.float16(1.0009765625)                                 # neighbours of the ties
+    Qp = rng.standard_normal((1, 4, 8, 128)).astype(np.float16)
+    sel_ref = oc.select_channels(Qp, K)
+    sel = gc.select_channels(H.dev(Qp), H.dev(K))
+    assert np.array_equal(sel.cpu().numpy(), sel_ref)
+    oc.append(K, V, sel_ref)
+    gc.quantize_append(H.dev(K), H.dev(V), sel=sel)
+    H.check_state(oc, gc)
+
+
 def test_eager_mode_with_empty_window_and_single_block(H):
     rng = np.random.default_rng(10)
     kw = dict(B=1, Hq=7, Hkv=1, D=128, T_max=256, Gk=128, Gv=128, R=128, k4=16, k16=0, flush_mode=1)
