@@ -33,7 +33,10 @@ constexpr int kMfmaThreads = 256;
 constexpr int kWaves = kMfmaThreads / 64;
 constexpr int kKPartMax = 8192;                 // bytes of a record before the value plane (staged in LDS)
 constexpr int kVMetaMax = 1024;                 // value scales + zero-points of one block
-constexpr int kWaveLds = kKPartMax + kVMetaMax + 256;   // + channel lists
+constexpr int kQsStride = 168;                  // halfs per head row of the slot-ordered q table (160 slots + padding)
+constexpr int kQsBytes = 8 * kQsStride * 2;
+constexpr int kWaveLds = kKPartMax + kVMetaMax + 256 + kQsBytes;   // + channel lists + slot-ordered q
+constexpr int kHdrLds = 2048 + 256 + 2048;      // normalised q [8][128], exponents and wave maxima, q transposed [128][8]
 constexpr int kPartStrideM = kD + 2;
 
 #ifdef MIXKVQ_PHASE_CLOCKS
@@ -112,19 +115,6 @@ __device__ __forceinline__ u32x4 unpack4(unsigned w) {
   u32x4 a;
   a[0] = w & 0x000F000Fu; a[1] = w & 0x00F000F0u; a[2] = w8 & 0x000F000Fu; a[3] = w8 & 0x00F000F0u;
   return a;
-}
-
-// Eight channel numbers at `list8` -> four fp16 pairs of the row `qrow`; entries from `n_valid` on give zero.
-__device__ __forceinline__ void gather8(const unsigned char* list8, const unsigned short* qrow, int n_valid,
-                                        unsigned (&out)[4]) {
-  unsigned w[2];
-  __builtin_memcpy(w, list8, 8);     // the fp16-tier list may start at any byte
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const unsigned pr = w[e >> 1] >> (16 * (e & 1));
-    const unsigned lo = qrow[pr & 127u], hi = qrow[(pr >> 8) & 127u];
-    out[e] = (2 * e < n_valid ? lo : 0u) | ((2 * e + 1 < n_valid ? hi : 0u) << 16);
-  }
 }
 
 template <int K4, int K16>
@@ -257,10 +247,12 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 
   __half* sQn = reinterpret_cast<__half*>(smem);                   // [8][128] normalised q
   int* sEq = reinterpret_cast<int*>(smem + 2048);                   // [8] exponents
-  unsigned char* wbase = smem + 2048 + 256 + wave * kWaveLds;        // this wave's private region
+  __half* sQt = reinterpret_cast<__half*>(smem + 2048 + 256);       // [128][8]: the 8 heads of a channel in 16 bytes
+  unsigned char* wbase = smem + kHdrLds + wave * kWaveLds;           // this wave's private region
   unsigned char* sK = wbase;                                        // record bytes [0, NKL KiB)
   unsigned char* sVm = wbase + kKPartMax;                           // v_s, v_z planes
   unsigned char* sLo = wbase + kKPartMax + kVMetaMax;               // 2-bit channel list [128], then salient idx [<=64]
+  unsigned short* sQs = reinterpret_cast<unsigned short*>(wbase + kKPartMax + kVMetaMax + 256);   // [8][kQsStride]
 
   // Work units of the pair: its block records, then the residual window in sub-units of 32 tokens, dealt
   // round-robin over all wavefronts of the pair's workgroups.
@@ -354,8 +346,10 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         vreg[h][x] = *reinterpret_cast<const u32x4*>(vw_ + (4 * (h * 64 < R ? h : 0) + kg) * kD + 64 * x + 4 * n); \
   }
 
-  // q in slot order from the selection words SELW (wave-uniform): the list of 2-bit channels and the salient
-  // list go to LDS, then every lane gathers the q entries of its contraction slots without branches.
+  // q in slot order from the selection words SELW (wave-uniform).  The list of 2-bit channels and the salient
+  // list go to LDS; a table [head][slot] of q is filled from the transposed q (one 16-byte read per slot brings
+  // all heads of the slot's channel): slots 0..127 follow the 2-bit list (zero past its end), slots 128.. the
+  // salient list.  Every lane then reads the 8 entries of each of its contraction steps with one 16-byte read.
 #define MIXKVQ_REBUILD_Q(SELW)                                                                                 \
   {                                                                                                            \
     unsigned char* sIdx = sLo + kD;                                                                            \
@@ -377,13 +371,33 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
       sLo[lane] = (unsigned char)lane;                                                                         \
       sLo[lane + 64] = (unsigned char)(lane + 64);                                                             \
     }                                                                                                          \
-    const unsigned short* qrow = reinterpret_cast<const unsigned short*>(sQn) + head * kD;                     \
-    _Pragma("unroll") for (int u = 0; u < NU; ++u) _Pragma("unroll") for (int x = 0; x < 2; ++x) {             \
-      const int j = 16 * (4 * u + kg) + 8 * x;                                                                 \
-      gather8(sLo + (j < kD ? j : 0), qrow, live ? T::NL - j : 0, qlo[2 * u + x]);                             \
+    _Pragma("unroll") for (int cch = 0; cch < 3; ++cch) {                                                      \
+      const int slot = 64 * cch + lane;                                                                        \
+      const unsigned ch = cch < 2 ? sLo[slot & 127] : sIdx[lane & 31];                                         \
+      const bool valid = cch < 2 ? slot < T::NL : lane < K4 + K16;                                             \
+      u32x4 hv = *reinterpret_cast<const u32x4*>(sQt + (ch & 127u) * 8);                                       \
+      if (!valid) hv = u32x4{0u, 0u, 0u, 0u};                                                                  \
+      if (cch < 2 || lane < 32) {                                                                              \
+        _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                                        \
+          sQs[(2 * e) * kQsStride + slot] = (unsigned short)(hv[e] & 0xffffu);                                 \
+          sQs[(2 * e + 1) * kQsStride + slot] = (unsigned short)(hv[e] >> 16);                                 \
+        }                                                                                                      \
+      }                                                                                                        \
     }                                                                                                          \
-    if (K4 > 0) gather8(sIdx + K16 + 8 * (kg < T::W4 ? kg : 0), qrow, live && kg < T::W4 ? 8 : 0, qh4);        \
-    if (K16 > 0) gather8(sIdx + (8 * kg < K16 ? 8 * kg : 0), qrow, live ? K16 - 8 * kg : 0, q16);              \
+    const unsigned short* qrow = sQs + head * kQsStride;                                                       \
+    _Pragma("unroll") for (int u = 0; u < NU; ++u) _Pragma("unroll") for (int x = 0; x < 2; ++x) {             \
+      const u32x4 t_ = *reinterpret_cast<const u32x4*>(qrow + 16 * (4 * u + kg) + 8 * x);                      \
+      _Pragma("unroll") for (int e = 0; e < 4; ++e) qlo[2 * u + x][e] = t_[e];                                 \
+    }                                                                                                          \
+    if (K4 > 0) {                                                                                              \
+      unsigned t_[4];                                                                                          \
+      __builtin_memcpy(t_, qrow + 128 + K16 + 8 * (kg < T::W4 ? kg : 0), 16);                                  \
+      _Pragma("unroll") for (int e = 0; e < 4; ++e) qh4[e] = kg < T::W4 ? t_[e] : 0u;                          \
+    }                                                                                                          \
+    if (K16 > 0) {                                                                                             \
+      const u32x4 t_ = *reinterpret_cast<const u32x4*>(qrow + 128 + (8 * kg < K16 ? 8 * kg : 0));              \
+      _Pragma("unroll") for (int e = 0; e < 4; ++e) q16[e] = t_[e];                                            \
+    }                                                                                                          \
   }
 
   MIXKVQ_PHASE(0)
@@ -443,6 +457,11 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
     qn.x = cvt_pk(ldexpf(v[0], -eq), ldexpf(v[1], -eq));
     qn.y = cvt_pk(ldexpf(v[2], -eq), ldexpf(v[3], -eq));
     *reinterpret_cast<uint2*>(sQn + h * kD + l32 * 4) = qn;
+    unsigned short* qt = reinterpret_cast<unsigned short*>(sQt) + (l32 * 4) * 8 + h;
+    qt[0] = (unsigned short)(qn.x & 0xffffu);
+    qt[8] = (unsigned short)(qn.x >> 16);
+    qt[16] = (unsigned short)(qn.y & 0xffffu);
+    qt[24] = (unsigned short)(qn.y >> 16);
     if (l32 == 0) sEq[h] = eq;
   }
   __syncthreads();
@@ -814,7 +833,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   __syncthreads();
   // natural-log domain for the merge kernel: m_e = m2 * ln2
   float* out = part + ((size_t)p * n_splits + split) * g * kPartStrideM;
-  const float* r0 = reinterpret_cast<const float*>(smem + 2048 + 256);
+  const float* r0 = reinterpret_cast<const float*>(smem + kHdrLds);
   constexpr int kWaveF = kWaveLds / 4;
   for (int i = tid; i < g * (kD + 1); i += kMfmaThreads) {
     // elements g*kD .. are the l sums
@@ -857,7 +876,7 @@ static hipError_t launch_one(const CacheView& v, const __half* q, float scale, i
                              float* part, unsigned* counters, __half* out, float* lse, int accumulate_q, NewToken nt,
                              hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
   auto kern = decode_fused_kernel<K4, K16, NVG, NKL, RG>;
-  const size_t lds = 2048 + 256 + (size_t)kWaves * kWaveLds;
+  const size_t lds = kHdrLds + (size_t)kWaves * kWaveLds;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
