@@ -36,7 +36,7 @@ constexpr int kVMetaMax = 1024;                 // value scales + zero-points of
 constexpr int kQsStride = 168;                  // halfs per head row of the slot-ordered q table (160 slots + padding)
 constexpr int kQsBytes = 8 * kQsStride * 2;
 constexpr int kWaveLds = kKPartMax + kVMetaMax + 256 + kQsBytes;   // + channel lists + slot-ordered q
-constexpr int kHdrLds = 2048 + 256 + 2048;      // normalised q [8][128], exponents and wave maxima, q transposed [128][8]
+constexpr int kHdrLds = 2048 + 256 + 2048 + 2048;   // normalised q [8][128], exponents and wave maxima, q transposed [128][8], raw q [8][128]
 constexpr int kPartStrideM = kD + 2;
 
 #ifdef MIXKVQ_PHASE_CLOCKS
@@ -248,6 +248,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   __half* sQn = reinterpret_cast<__half*>(smem);                   // [8][128] normalised q
   int* sEq = reinterpret_cast<int*>(smem + 2048);                   // [8] exponents
   __half* sQt = reinterpret_cast<__half*>(smem + 2048 + 256);       // [128][8]: the 8 heads of a channel in 16 bytes
+  unsigned short* sQraw = reinterpret_cast<unsigned short*>(smem + 2048 + 256 + 2048);   // [8][128] q as given
   unsigned char* wbase = smem + kHdrLds + wave * kWaveLds;           // this wave's private region
   unsigned char* sK = wbase;                                        // record bytes [0, NKL KiB)
   unsigned char* sVm = wbase + kKPartMax;                           // v_s, v_z planes
@@ -269,7 +270,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   for (int j = 0; j < 4; ++j)
     if (j < n_sub && (n_blocks + j) % n_gw == gw) my_sub = j;
   // one wavefront per pair (the next in the deal, never one with a sub-unit unless the pair has a single
-  // workgroup) stores this step's new token and adds |q| to the accumulator, after its units
+  // workgroup) stores this step's new token and adds |q| to the accumulator
   const bool bookkeeper = (n_blocks + n_sub) % n_gw == gw;
 
   // ---- per-lane constants -------------------------------------------------
@@ -346,6 +347,16 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         vreg[h][x] = *reinterpret_cast<const u32x4*>(vw_ + (4 * (h * 64 < R ? h : 0) + kg) * kD + 64 * x + 4 * n); \
   }
 
+  // The value words of one half (64 tokens) of a record: asked for as soon as the previous record's matrix
+  // products have consumed the registers they land in, so that each half has most of a record's time to arrive.
+#define MIXKVQ_ISSUE_V_HALF(BLK, H)                                                                          \
+  {                                                                                                          \
+    const unsigned char* rec_ = blocks + ((size_t)p * NB + (BLK)) * rec_bytes;                              \
+    const unsigned* vw_ = reinterpret_cast<const unsigned*>(rec_ + off_v);                                  \
+    _Pragma("unroll") for (int x = 0; x < 2; ++x)                                                           \
+        vreg[H][x] = *reinterpret_cast<const u32x4*>(vw_ + (4 * (H) + kg) * kD + 64 * x + 4 * n);           \
+  }
+
   // q in slot order from the selection words SELW (wave-uniform).  The list of 2-bit channels and the salient
   // list go to LDS; a table [head][slot] of q is filled from the transposed q (one 16-byte read per slot brings
   // all heads of the slot's channel): slots 0..127 follow the 2-bit list (zero past its end), slots 128.. the
@@ -405,6 +416,20 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   // Loads go out in the order of use (they return in order): q, the first record's channel selection, the
   // residual sub-unit, the first record.
   int blk = blk_lo;
+  // the pair's bookkeeping wavefront: old accumulator values and the new token's rows, first in the queue
+  unsigned long long qacc_old[2] = {0ull, 0ull}, qcnt_old = 0ull;
+  uint4 nt_row = make_uint4(0u, 0u, 0u, 0u);
+  if (bookkeeper) {
+    if (accumulate_q) {
+      qacc_old[0] = cv.qacc[(size_t)p * kD + lane];
+      qacc_old[1] = cv.qacc[(size_t)p * kD + lane + 64];
+      if (lane == 0) qcnt_old = cv.qcnt[p];
+    }
+    if (nt.k && lane < 32) {
+      const int64_t src = (int64_t)b * nt.st.b + (int64_t)jkv * nt.st.h + (lane & 15) * 8;
+      nt_row = *reinterpret_cast<const uint4*>((lane < 16 ? nt.k : nt.v) + src);
+    }
+  }
   uint2 qraw = make_uint2(0u, 0u);
   {
     const int h = tid >> 5, l32 = tid & 31;
@@ -457,6 +482,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
     qn.x = cvt_pk(ldexpf(v[0], -eq), ldexpf(v[1], -eq));
     qn.y = cvt_pk(ldexpf(v[2], -eq), ldexpf(v[3], -eq));
     *reinterpret_cast<uint2*>(sQn + h * kD + l32 * 4) = qn;
+    if (accumulate_q) *reinterpret_cast<uint2*>(sQraw + h * kD + l32 * 4) = qraw;
     unsigned short* qt = reinterpret_cast<unsigned short*>(sQt) + (l32 * 4) * 8 + h;
     qt[0] = (unsigned short)(qn.x & 0xffffu);
     qt[8] = (unsigned short)(qn.x >> 16);
@@ -467,6 +493,22 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   __syncthreads();
   const int Eq = sEq[head];
   MIXKVQ_PHASE(1)
+  if (bookkeeper) {   // the new token enters the window; |q| of this step joins the accumulator (one writer per pair)
+    if (nt.k && lane < 32) {
+      const size_t dst = ((size_t)p * R + nt.row) * kD + (lane & 15) * 8;
+      *reinterpret_cast<uint4*>((lane < 16 ? cv.res_k : cv.res_v) + dst) = nt_row;
+    }
+    if (accumulate_q) {
+#pragma unroll
+      for (int hc = 0; hc < 2; ++hc) {
+        const int d = lane + 64 * hc;
+        unsigned long long acc = qacc_old[hc];
+        for (int h = 0; h < g; ++h) acc += fix24_abs(sQraw[h * kD + d]);
+        cv.qacc[(size_t)p * kD + d] = acc;
+      }
+      if (lane == 0) cv.qcnt[p] = qcnt_old + (unsigned long long)g;
+    }
+  }
   // q in the slot order of the first record, while that record is still on its way (its value words are
   // asked for only now: the first answers come the sooner the less every wavefront asks for at once)
   if (blk < blk_hi) {
@@ -769,33 +811,16 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
             O[xp][qq] = mfma(a1, Bp[a][1], O[xp][qq]);
           }
         }
+        if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_V_HALF(blk + blk_step, hsg)
       }
     }
-    if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_V_LOADS(blk + blk_step)
     MIXKVQ_PHASE(phase_i < 11 ? phase_i : 11)
     ++phase_i;
-  }
-  if (bookkeeper) {
-    if (nt.k && lane < 32) {
-      const int64_t src = (int64_t)b * nt.st.b + (int64_t)jkv * nt.st.h + (lane & 15) * 8;
-      const size_t dst = ((size_t)p * R + nt.row) * kD + (lane & 15) * 8;
-      if (lane < 16) *reinterpret_cast<uint4*>(cv.res_k + dst) = *reinterpret_cast<const uint4*>(nt.k + src);
-      else *reinterpret_cast<uint4*>(cv.res_v + dst) = *reinterpret_cast<const uint4*>(nt.v + src);
-    }
-    if (accumulate_q) {
-#pragma unroll
-      for (int hc = 0; hc < 2; ++hc) {
-        const int d = lane + 64 * hc;
-        unsigned long long acc = 0;
-        for (int h = 0; h < g; ++h) acc += fix24_abs(h2bits(q[((size_t)b * Hq + jkv * g + h) * kD + d]));
-        cv.qacc[(size_t)p * kD + d] += acc;
-      }
-      if (lane == 0) cv.qcnt[p] += (unsigned long long)g;
-    }
   }
   MIXKVQ_PHASE(14)
 #undef MIXKVQ_ISSUE_K_LOADS
 #undef MIXKVQ_ISSUE_V_LOADS
+#undef MIXKVQ_ISSUE_V_HALF
 #undef MIXKVQ_REBUILD_Q
 
   // ---- wave results -> workgroup partial ------------------------------------------
