@@ -117,6 +117,15 @@ __device__ __forceinline__ u32x4 unpack4(unsigned w) {
   return a;
 }
 
+// Lanes of a wavefront hand data to each other through the wavefront's own LDS region.  The hardware keeps a
+// wavefront's LDS operations in order, so no instruction is needed, but the compiler must be told that what a
+// lane reads may have been written by another lane (else it may reuse a value the lane loaded earlier).
+__device__ __forceinline__ void wave_lds_handoff() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 template <int K4, int K16>
 struct Tiers {
   static constexpr int NL = kD - K4 - K16;
@@ -382,6 +391,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
       sLo[lane] = (unsigned char)lane;                                                                         \
       sLo[lane + 64] = (unsigned char)(lane + 64);                                                             \
     }                                                                                                          \
+    wave_lds_handoff();                                                                                        \
     _Pragma("unroll") for (int cch = 0; cch < 3; ++cch) {                                                      \
       const int slot = 64 * cch + lane;                                                                        \
       const unsigned ch = cch < 2 ? sLo[slot & 127] : sIdx[lane & 31];                                         \
@@ -395,6 +405,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         }                                                                                                      \
       }                                                                                                        \
     }                                                                                                          \
+    wave_lds_handoff();                                                                                        \
     const unsigned short* qrow = sQs + head * kQsStride;                                                       \
     _Pragma("unroll") for (int u = 0; u < NU; ++u) _Pragma("unroll") for (int x = 0; x < 2; ++x) {             \
       const u32x4 t_ = *reinterpret_cast<const u32x4*>(qrow + 16 * (4 * u + kg) + 8 * x);                      \
@@ -562,6 +573,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
       dst[0] = make_uint2(v[0], v[1]);
       dst[1] = make_uint2(v[2], v[3]);
     }
+    wave_lds_handoff();
 #pragma unroll
     for (int xp = 0; xp < 2; ++xp)
 #pragma unroll
@@ -576,6 +588,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         const f32x4 t = mfma(a, Bp, f32x4{0.f, 0.f, 0.f, 0.f});
         O[xp][qq] = t * 5.9604644775390625e-8f;
       }
+    wave_lds_handoff();     // the staging area is the record buffer of the block loop
   }
 
   MIXKVQ_PHASE(2)
@@ -585,6 +598,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 #pragma unroll
     for (int c = 0; c < NKL; ++c) reinterpret_cast<u32x4*>(sK)[c * 64 + lane] = kreg[c];
     reinterpret_cast<u32x4*>(sVm)[lane < nvm ? lane : nvm - 1] = vmreg;
+    wave_lds_handoff();
     if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_K_LOADS(blk + blk_step)
 
     // ---- channel selection of this block: rebuild q in slot order if it changed ----
