@@ -233,7 +233,7 @@ def main():
     n_q0 = w.R * (-(-w.T // w.R) - 1)
     step_bytes = algorithmic_bytes(w, n_q0, w.T - n_q0)
     copies = args.copies or max(1, math.ceil(2 * LLC_BYTES / step_bytes))
-    total_steps = args.steps * 2 + args.warmup
+    total_steps = args.steps * 3 + args.warmup
     per_copy = -(-total_steps // copies)
     T_max = (w.T + per_copy + 2 * w.R) // w.R * w.R
 
@@ -291,6 +291,23 @@ def main():
     k_ms = ev.elapsed_ms()
     ev.destroy()
     k_avg_ms = sum(k_ms) / len(k_ms)
+
+    # third pass: every step between its own pair of events (whole step, flush steps included), for the
+    # mean / worst step and the share of the block flushes
+    n_ps = min(args.steps, 512)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_ps)]
+    flushed = []
+    for n in range(n_ps):
+        nq_before = caches[i % copies].state()[0]
+        evs[n][0].record()
+        step(i)
+        evs[n][1].record()
+        flushed.append(caches[i % copies].state()[0] != nq_before)
+        i += 1
+    torch.cuda.synchronize()
+    ps = [a.elapsed_time(b) * 1e3 for a, b in evs]
+    ps_flush = [t for t, f in zip(ps, flushed) if f]
+    ps_plain = [t for t, f in zip(ps, flushed) if not f]
     achieved = step_bytes / (k_avg_ms * 1e-3) / 1e9
     nq_end, r_end = caches[0].state()
 
@@ -311,6 +328,13 @@ def main():
                      "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, w.T)), "traffic_unit": "bytes per launch",
                      "algorithmic_bytes_per_launch": step_bytes},
     }
+    result["per_step_us"] = {
+        "steps": n_ps, "mean": round(sum(ps) / len(ps), 2), "worst": round(max(ps), 2),
+        "plain_steps_mean": round(sum(ps_plain) / max(1, len(ps_plain)), 2),
+        "flush_steps": len(ps_flush), "flush_steps_mean": round(sum(ps_flush) / max(1, len(ps_flush)), 2),
+        "amortised_with_flush_every_R": round((sum(ps_plain) / max(1, len(ps_plain)) * (w.R - 1)
+                                               + (sum(ps_flush) / len(ps_flush) if ps_flush else 0.0)) / w.R, 2),
+        "note": "each step between its own event pair (adds event overhead to every step)"}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args.config, w, host)
     print(json.dumps(result))

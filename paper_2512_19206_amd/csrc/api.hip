@@ -140,7 +140,6 @@ void mixkvq_cache_destroy(mixkvq_cache* c) { delete c; }
 int mixkvq_cache_reset(mixkvq_cache* c, void* stream) {
   if (!c) return MIXKVQ_EINVAL;
   MIXKVQ_TRY_HIP(launch_zero_qacc(c->v, (hipStream_t)stream));
-  MIXKVQ_TRY_HIP(launch_zero_counters(c->v, (hipStream_t)stream));
   c->n_quant = 0;
   c->n_res = 0;
   return MIXKVQ_OK;

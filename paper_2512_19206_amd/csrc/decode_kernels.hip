@@ -15,18 +15,7 @@ size_t decode_partials_bytes(const mixkvq_config& c) {
   const size_t n = (size_t)P * (max_splits_for(P) + 1) * (c.Hq / c.Hkv) * kPartStride * sizeof(float);
   return (n + 255) / 256 * 256;
 }
-// partials, then one arrival counter per pair (kept at zero between launches)
-size_t decode_workspace_bytes(const mixkvq_config& c) { return decode_partials_bytes(c) + (size_t)c.B * c.Hkv * sizeof(unsigned); }
-
-__global__ void zero_u32_kernel(unsigned* p, int n) {
-  int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0u;
-}
-hipError_t launch_zero_counters(const CacheView& v, hipStream_t s) {
-  unsigned* counters = reinterpret_cast<unsigned*>(v.ws + decode_partials_bytes(v.cfg));
-  zero_u32_kernel<<<dim3((v.P + 255) / 256), dim3(256), 0, s>>>(counters, v.P);
-  return hipGetLastError();
-}
+size_t decode_workspace_bytes(const mixkvq_config& c) { return decode_partials_bytes(c); }
 
 // ---------------------------------------------------------------------------
 // Reference-grade split kernel: plain vector ALU, one workgroup per (pair, split).
@@ -224,7 +213,7 @@ __global__ void __launch_bounds__(kD) decode_merge_kernel(const float* __restric
 }
 
 bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, int n_blocks, int n_res, int n_splits,
-                            float* part, unsigned* counters, __half* out, float* lse, int accumulate_q, NewToken nt,
+                            float* part, __half* out, float* lse, int accumulate_q, NewToken nt,
                             hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop, hipError_t* err);
 
 hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float* lse, float scale, int n_blocks,
@@ -245,8 +234,7 @@ hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float
   hipError_t e = hipSuccess;
   // matrix-core path: one launch (n_splits partials from the quantized blocks, one from the residual
   // window, merged by the last workgroup of each pair)
-  unsigned* counters = reinterpret_cast<unsigned*>(v.ws + decode_partials_bytes(v.cfg));
-  if (try_launch_decode_mfma(v, q, scale, n_blocks, n_res, n_splits, part, counters, out, lse, accumulate_q, nt, s,
+  if (try_launch_decode_mfma(v, q, scale, n_blocks, n_res, n_splits, part, out, lse, accumulate_q, nt, s,
                              ev_start, ev_stop, &e))
     return e;
   if (nt.k) {   // this path does not move the new token itself

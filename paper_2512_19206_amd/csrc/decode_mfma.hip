@@ -912,7 +912,7 @@ decode_fused_kernel(CacheView cv, const __half* __restrict__ q, float scale, int
 
 template <int K4, int K16, int NVG, int NKL, int RG>
 static hipError_t launch_one(const CacheView& v, const __half* q, float scale, int n_blocks, int n_res, int n_splits,
-                             float* part, unsigned* counters, __half* out, float* lse, int accumulate_q, NewToken nt,
+                             float* part, __half* out, float* lse, int accumulate_q, NewToken nt,
                              hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
   auto kern = decode_fused_kernel<K4, K16, NVG, NKL, RG>;
   const size_t lds = kHdrLds + (size_t)kWaves * kWaveLds;
@@ -931,7 +931,7 @@ static hipError_t launch_one(const CacheView& v, const __half* q, float scale, i
 
 // Returns true and launches when the configuration is one the matrix-core kernel covers.
 bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, int n_blocks, int n_res, int n_splits,
-                            float* part, unsigned* counters, __half* out, float* lse, int accumulate_q, NewToken nt,
+                            float* part, __half* out, float* lse, int accumulate_q, NewToken nt,
                             hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop, hipError_t* err) {
   const mixkvq_config& c = v.cfg;
   if (c.R % 64 != 0 || c.Gk % 64 != 0 || c.Gv % 64 != 0 || n_blocks < 1) return false;
@@ -942,7 +942,7 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
   bool ok = true;
 #define MIXKVQ_CASE(K4_, K16_, NVG_, NKL_, RG_)                                                                     \
   if (c.k4 == K4_ && c.k16 == K16_ && nvg == NVG_ && nkl <= NKL_ && (RG_ == 0 || (c.R == 128 && c.Gk == 128)))     \
-    e = launch_one<K4_, K16_, NVG_, NKL_, RG_>(v, q, scale, n_blocks, n_res, n_splits, part, counters, out, lse,   \
+    e = launch_one<K4_, K16_, NVG_, NKL_, RG_>(v, q, scale, n_blocks, n_res, n_splits, part, out, lse,   \
                                                accumulate_q, nt, s, ev_start, ev_stop);                            \
   else
   MIXKVQ_CASE(16, 0, 1, 6, 1)

@@ -54,7 +54,6 @@ hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float
 
 size_t decode_workspace_bytes(const mixkvq_config& c);
 size_t decode_partials_bytes(const mixkvq_config& c);
-hipError_t launch_zero_counters(const CacheView& v, hipStream_t s);
 size_t select_workspace_bytes(const mixkvq_config& c);
 
 // ---- small device helpers used by several kernels ----
