@@ -623,8 +623,10 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         if ((64 * hsg) % Gk == 0) {
           const int grp = (64 * hsg) / Gk;
           // ---- small key operand of this group: Qs = q * s (head and tail), bias = sum q z ----
+          // The bias runs on the matrix cores too: the zero-points of a step's 32 slots as every row of the
+          // large operand, q as the small one; all 16 rows of the result hold sum q z of the lane's head.
           unsigned sp[2 * NU][4], sp4[4];   // scales of this lane's slots: adjacent pairs, as stored
-          float zd = 0.f;
+          f32x4 zd4 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int u = 0; u < NU; ++u) {
             const int c = 4 * u + kg < T::Wlo ? 4 * u + kg : T::Wlo - 1;
@@ -635,10 +637,9 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
               const uint4 sv = ps[x], zv = pz[x];
               const unsigned sw[4] = {sv.x, sv.y, sv.z, sv.w}, zw[4] = {zv.x, zv.y, zv.z, zv.w};
 #pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                sp[2 * u + x][e] = sw[e];
-                zd = dot2(qlo[2 * u + x][e], zw[e], zd);
-              }
+              for (int e = 0; e < 4; ++e) sp[2 * u + x][e] = sw[e];
+              zd4 = mfma(u32x4{zw[0], zw[1], zw[2], zw[3]},
+                         u32x4{qlo[2 * u + x][0], qlo[2 * u + x][1], qlo[2 * u + x][2], qlo[2 * u + x][3]}, zd4);
             }
           }
           if (K4 > 0) {
@@ -647,13 +648,10 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
             const uint4 zv = *reinterpret_cast<const uint4*>(sK + off_k4_z + 2 * (grp * K4 + 8 * w));
             const unsigned sw[4] = {sv.x, sv.y, sv.z, sv.w}, zw[4] = {zv.x, zv.y, zv.z, zv.w};
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              sp4[e] = sw[e];
-              zd = dot2(qh4[e], zw[e], zd);
-            }
+            for (int e = 0; e < 4; ++e) sp4[e] = sw[e];
+            zd4 = mfma(u32x4{zw[0], zw[1], zw[2], zw[3]}, u32x4{qh4[0], qh4[1], qh4[2], qh4[3]}, zd4);
           }
-          zd = xkg_sum(zd);
-          zdot = zd;
+          zdot = zd4[0];
           // block exponent: scales are multiplied by 2^e0 so that the largest lands in [2^14, 2^15) (e0 <= 15),
           // and by 4^-sc, the position factor of the code they meet in the product
           int efs = (int)(*reinterpret_cast<const unsigned short*>(sK + off_kmax + 2 * grp) >> 10);   // exponent field
