@@ -658,24 +658,32 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
           if (efs < 1) efs = 1;
           efs = __builtin_amdgcn_readfirstlane(efs);
           const int e0 = 29 - efs < 15 ? 29 - efs : 15;
+          // every lane forms the head fp16(q s); the lanes of the tail columns then replace it by the exact
+          // remainder q s - head in ONE divergent region (cheaper than a select per register)
 #pragma unroll
           for (int s = 0; s < 2 * NU; ++s)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
               const unsigned mult = ((unsigned)(15 + e0 - 2 * sc2(4 * (s & 1) + e)) << 10) * 0x00010001u;
-              const unsigned sn = pk_mul(sp[s][e], mult);                 // fp16 pair s * 2^(e0 - 2 sc)
-              const unsigned hi = pk_mul(qlo[s][e], sn);
-              const unsigned lo = pk_fma_neg(qlo[s][e], sn, hi);
-              Blo[s][e] = role ? lo : hi;
+              sp[s][e] = pk_mul(sp[s][e], mult);                 // fp16 pair s * 2^(e0 - 2 sc)
+              Blo[s][e] = pk_mul(qlo[s][e], sp[s][e]);
             }
           if (K4 > 0) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
               const unsigned mult = ((unsigned)(15 + e0 - 2 * sc4(e)) << 10) * 0x00010001u;
-              const unsigned sn = pk_mul(sp4[e], mult);
-              const unsigned hi = pk_mul(qh4[e], sn);
-              const unsigned lo = pk_fma_neg(qh4[e], sn, hi);
-              Bh4[e] = role ? lo : hi;
+              sp4[e] = pk_mul(sp4[e], mult);
+              Bh4[e] = pk_mul(qh4[e], sp4[e]);
+            }
+          }
+          if (role) {
+#pragma unroll
+            for (int s = 0; s < 2 * NU; ++s)
+#pragma unroll
+              for (int e = 0; e < 4; ++e) Blo[s][e] = pk_fma_neg(qlo[s][e], sp[s][e], Blo[s][e]);
+            if (K4 > 0) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) Bh4[e] = pk_fma_neg(qh4[e], sp4[e], Bh4[e]);
             }
           }
           // logits in the log2 domain: x2 = S * C + Z * Cz
