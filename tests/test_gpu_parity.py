@@ -86,6 +86,64 @@ def test_shapes_and_tiers(H, g, k4, k16, Gk, Gv, R):
     H.check_attention(oc, gc, q, scale=0.31)
 
 
+def _random_configs(n, seed):
+    """Seeded random valid configurations: every matrix-core kernel variant (tiers x value groups x R/Gk) and
+    shapes that take the general kernels."""
+    rng = np.random.default_rng(seed)
+    mfma_tiers = [(16, 0), (0, 12), (8, 0), (0, 0), (24, 0), (32, 0), (8, 4), (0, 32)]
+    out = []
+    for i in range(n):
+        if i % 3 != 2:     # matrix-core path: R, Gk, Gv multiples of 64
+            k4, k16 = mfma_tiers[int(rng.integers(len(mfma_tiers)))]
+            R = int(rng.choice([64, 128]))
+            Gk = int(rng.choice([g for g in (64, 128) if R % g == 0]))
+            Gv = int(rng.choice([64, 128])) if (k4, k16) in ((16, 0), (0, 12)) else 128
+        else:              # anything the layout allows
+            k4, k16 = int(rng.choice([0, 8, 16, 40])), int(rng.choice([0, 4, 20]))
+            R = int(rng.choice([16, 32, 48, 80, 96, 112, 128]))
+            Gk = int(rng.choice([g for g in (16, 32, 48, 64, 80, 96, 112, 128) if R % g == 0]))
+            Gv = int(rng.choice([16, 32, 64, 128]))
+        g = int(rng.integers(1, 9))
+        out.append((g, k4, k16, Gk, Gv, R, int(rng.integers(1, 4)), int(rng.integers(0, R + 1)),
+                    int(rng.integers(0, 2)), 1000 + i))
+    return out
+
+
+@pytest.mark.parametrize("g,k4,k16,Gk,Gv,R,n_blocks,n_extra,flush_mode,seed", _random_configs(24, 5))
+def test_random_configurations(H, g, k4, k16, Gk, Gv, R, n_blocks, n_extra, flush_mode, seed):
+    rng = np.random.default_rng(seed)
+    B, Hkv = 1, 2
+    T = R * n_blocks + n_extra
+    kw = dict(B=B, Hq=Hkv * g, Hkv=Hkv, D=128, T_max=R * (n_blocks + 3), Gk=Gk, Gv=Gv, R=R, k4=k4, k16=k16,
+              flush_mode=flush_mode)
+    K = (rng.standard_normal((B, Hkv, T, 128)) * rng.uniform(0.3, 8, 128)).astype(np.float16)
+    V = (rng.standard_normal((B, Hkv, T, 128)) * rng.uniform(0.5, 2, (T, 1))).astype(np.float16)
+    Qp = (rng.standard_normal((B, Hkv * g, 9, 128)) * rng.uniform(0.2, 5, 128)).astype(np.float16)
+    oc, gc = H.make_pair(**kw)
+    sel_ref = sel = None
+    if k4 + k16:
+        sel_ref = oc.select_channels(Qp, K)
+        sel = gc.select_channels(H.dev(Qp), H.dev(K))
+        assert np.array_equal(sel.cpu().numpy(), sel_ref)
+    oc.append(K, V, sel_ref)
+    gc.quantize_append(H.dev(K), H.dev(V), sel=sel)
+    H.check_state(oc, gc)
+    if oc.n_quant + oc.n_res == 0:
+        return
+    for _ in range(3):      # decode steps: append + attention fused, flushes included
+        k1 = (rng.standard_normal((B, Hkv, 1, 128)) * rng.uniform(0.3, 8, 128)).astype(np.float16)
+        v1 = rng.standard_normal((B, Hkv, 1, 128)).astype(np.float16)
+        q1 = (rng.standard_normal((B, Hkv * g, 128)) * rng.uniform(0.2, 5, 128)).astype(np.float16)
+        oc.append(k1, v1)
+        ro, rl = oc.decode_attention(q1, accumulate_q=True)
+        out, lse = gc.decode_step(H.dev(k1), H.dev(v1), H.dev(q1), accumulate_q=True)
+        torch.cuda.synchronize()
+        err = np.abs(out.float().cpu().numpy() - ro)
+        assert np.all(err <= H.ATOL + H.RTOL * np.abs(ro)), float(err.max())
+        assert np.all(np.abs(lse.cpu().numpy() - rl) <= H.LSE_ATOL + 1e-4 * np.abs(rl))
+    H.check_state(oc, gc)
+
+
 # ---------------------------------------------------------------------------
 # decode loop: per-step append, |q| accumulation, re-selection at every flush
 # ---------------------------------------------------------------------------
