@@ -205,7 +205,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1024)
     ap.add_argument("--warmup", type=int, default=64)
-    ap.add_argument("--config", type=int, default=1, help="BASELINE configuration id (1, 2, 3: decode step; 4: prefill)")
+    ap.add_argument("--config", type=int, default=1, help="workload configuration (1, 2, 3: decode step; 4: prefill)")
     ap.add_argument("--copies", type=int, default=0, help="independent cache copies rotated over (0 = enough for 2x LLC)")
     ap.add_argument("--host-batch", type=int, default=2)
     ap.add_argument("--tokens", type=int, default=0, help="override the context length of the configuration")
