@@ -257,15 +257,18 @@ __device__ __forceinline__ float key_to_float(short key) {
   return __half2float(__ushort_as_half(bits));
 }
 
-// Two-bit code of u = x - z with the reciprocal r of the scale (r = 0 for scale 0).  q0 = u*r is within 1e-6 of the
-// correctly rounded quotient (u/s < 4.3, rcp and the product are good to 1.8e-7 relative), so whenever q0 is
-// further than 2^-18 from every half-integer, rint(q0) IS the code Eq. 2 defines; `near` collects the other
-// cases, which the caller redoes with the IEEE division.
-__device__ __forceinline__ unsigned code2_fast(float x, float z, float r, bool& near) {
+// Code of u = x - z with the reciprocal r of the scale (r = 0 for scale 0); TOP = 3 or 15.  q0 = u*r is within
+// (TOP + 1.3) * 2.4e-7 of the correctly rounded quotient (rcp and the product are good to 1.8e-7 relative, the
+// quotient itself to 6e-8), i.e. within 1e-6 for two-bit and 4e-6 for four-bit codes; so whenever q0 is further
+// than EPS (2^-18, 2^-16) from every half-integer, rint(q0) IS the code Eq. 2 defines.  `near` collects the
+// other cases, which the caller redoes with the IEEE division.  (u >= 0, so no lower clamp is needed.)
+template <int TOP>
+__device__ __forceinline__ unsigned code_fast(float x, float z, float r, bool& near) {
+  constexpr float kEps = TOP == 3 ? 3.814697265625e-6f : 1.52587890625e-5f;
   const float q0 = (x - z) * r;
-  const float fr = q0 - floorf(q0);
-  near |= fabsf(fr - 0.5f) < 3.814697265625e-6f;
-  return (unsigned)fminf(fmaxf(rintf(q0), 0.f), 3.f);
+  const float c = rintf(q0);
+  near |= fabsf(q0 - c) > 0.5f - kEps;
+  return (unsigned)fminf(c, (float)TOP);
 }
 __device__ __forceinline__ float safe_rcp(float s) { return s > 0.f ? __builtin_amdgcn_rcpf(s) : 0.f; }
 
@@ -285,6 +288,7 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   __shared__ unsigned char sLoList[kD];    // 2-bit channels, ascending
   __shared__ unsigned char sHiList[kD];    // fp16 tier then 4-bit tier
   __shared__ __align__(16) float sS[8 * kD], sZ[8 * kD];   // keys: [group][channel]; values: [token][value group]
+  __shared__ __align__(16) float sR[8 * kD];   // reciprocals of the scales in sS (0 for scale 0)
   __shared__ unsigned sKmax[8];
   __shared__ unsigned sChunk[2][kMaxR / 16][kD / 2];   // (min, max) keys per 16-token chunk and channel pair
   unsigned (*sCLo)[kD / 2] = sChunk[0];
@@ -423,6 +427,7 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
       const GroupParams gp = group_params(key_to_float(lo), key_to_float(hi), tier ? 15.f : 3.f);
       sS[grp * kD + d] = gp.s;
       sZ[grp * kD + d] = gp.z;
+      sR[grp * kD + d] = safe_rcp(gp.s);
       const int pos = sPos[d];
       atomicMax(&sKmax[grp], (unsigned)gp.s16);
       if (tier == 0) {
@@ -454,7 +459,7 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int d = doff[i] < 0 ? 0 : doff[i];
-          rc[i] = doff[i] < 0 ? 0.f : safe_rcp(sS[grp * kD + d]);   // 0 gives code 0: the padding of the last word
+          rc[i] = doff[i] < 0 ? 0.f : sR[grp * kD + d];   // 0 gives code 0: the padding of the last word
           zp[i] = sZ[grp * kD + d];
         }
         for (int tt = tl; tt < Gk; tt += 32) {
@@ -465,7 +470,7 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
             const float x = __half2float(row[doff[i] < 0 ? 0 : doff[i]]);
-            w |= code2_fast(x, zp[i], rc[i], near) << (16 * (i & 1) + 2 * (i >> 1));
+            w |= code_fast<3>(x, zp[i], rc[i], near) << (16 * (i & 1) + 2 * (i >> 1));
           }
           if (__any(near)) {     // rare: some quotient sits next to a rounding boundary
             w = 0;
@@ -486,10 +491,19 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   for (int it = tid; it < R * W4; it += kFlushThreads) {
     const int t = it / W4, wd = it % W4, grp = t / Gk;
     unsigned w = 0;
+    bool near = false;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int d = sHiList[k16 + wd * 8 + i];
-      w |= encode(__half2float(sT[t * kRowStride + d]), sZ[grp * kD + d], sS[grp * kD + d], 15.f) << (16 * (i & 1) + 4 * (i >> 1));
+      w |= code_fast<15>(__half2float(sT[t * kRowStride + d]), sZ[grp * kD + d], sR[grp * kD + d], near) << (16 * (i & 1) + 4 * (i >> 1));
+    }
+    if (__any(near)) {     // rare: some quotient sits next to a rounding boundary
+      w = 0;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int d = sHiList[k16 + wd * 8 + i];
+        w |= encode(__half2float(sT[t * kRowStride + d]), sZ[grp * kD + d], sS[grp * kD + d], 15.f) << (16 * (i & 1) + 4 * (i >> 1));
+      }
     }
     reinterpret_cast<unsigned*>(rec + off_k4)[it] = w;
   }
@@ -541,6 +555,7 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
       const GroupParams gp = group_params(key_to_float((short)(mi & 0xffffu)), key_to_float((short)~(mi >> 16)), 3.f);
       sVS[it] = gp.s;
       sVZ[it] = gp.z;
+      sR[it] = safe_rcp(gp.s);
       reinterpret_cast<unsigned short*>(rec + off_v_s)[it] = gp.s16;
       reinterpret_cast<unsigned short*>(rec + off_v_z)[it] = gp.z16;
     }
@@ -551,19 +566,19 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   {
     const int d = tid & (kD - 1), vg = d / Gv;
     for (int tg = tid >> 7; tg < n_ch; tg += 2) {
-      float sc[16], zp[16];
+      float rc[16], zp[16];
       if (NVG == 1) {
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
-          const float4 a = *reinterpret_cast<const float4*>(sVS + tg * 16 + 4 * i4);
+          const float4 a = *reinterpret_cast<const float4*>(sR + tg * 16 + 4 * i4);
           const float4 b2 = *reinterpret_cast<const float4*>(sVZ + tg * 16 + 4 * i4);
-          sc[4 * i4] = a.x; sc[4 * i4 + 1] = a.y; sc[4 * i4 + 2] = a.z; sc[4 * i4 + 3] = a.w;
+          rc[4 * i4] = a.x; rc[4 * i4 + 1] = a.y; rc[4 * i4 + 2] = a.z; rc[4 * i4 + 3] = a.w;
           zp[4 * i4] = b2.x; zp[4 * i4 + 1] = b2.y; zp[4 * i4 + 2] = b2.z; zp[4 * i4 + 3] = b2.w;
         }
       } else {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          sc[i] = sVS[(tg * 16 + i) * NVG + vg];
+          rc[i] = sR[(tg * 16 + i) * NVG + vg];
           zp[i] = sVZ[(tg * 16 + i) * NVG + vg];
         }
       }
@@ -571,13 +586,14 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
       bool near = false;
 #pragma unroll
       for (int i = 0; i < 16; ++i)
-        w |= code2_fast(__half2float(sT[(tg * 16 + i) * kRowStride + d]), zp[i], safe_rcp(sc[i]), near)
+        w |= code_fast<3>(__half2float(sT[(tg * 16 + i) * kRowStride + d]), zp[i], rc[i], near)
              << (16 * (i & 1) + 2 * (i >> 1));
       if (__any(near)) {     // rare: some quotient sits next to a rounding boundary
         w = 0;
 #pragma unroll
         for (int i = 0; i < 16; ++i)
-          w |= encode(__half2float(sT[(tg * 16 + i) * kRowStride + d]), zp[i], sc[i], 3.f) << (16 * (i & 1) + 2 * (i >> 1));
+          w |= encode(__half2float(sT[(tg * 16 + i) * kRowStride + d]), zp[i], sVS[(tg * 16 + i) * NVG + vg], 3.f)
+               << (16 * (i & 1) + 2 * (i >> 1));
       }
       reinterpret_cast<unsigned*>(rec + off_v)[tg * kD + d] = w;
     }
