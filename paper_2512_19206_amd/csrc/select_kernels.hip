@@ -31,12 +31,17 @@ hipError_t launch_zero_qacc(const CacheView& v, hipStream_t s) {
 constexpr int kStreamThreads = 256;
 constexpr int kRowsPerWG = 512;
 
-__device__ __forceinline__ void add8(unsigned long long (&acc)[8], uint4 v) {
+// The per-thread sums run in binary64, which is exact here: every |fp16| is a multiple of 2^-24 below 2^16, so up to
+// 2^13 of them add without rounding in a 53-bit significand (a thread adds at most kRowsPerWG / 16 = 32 per channel);
+// the sum times 2^24 is the exact integer.
+typedef _Float16 sh2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void add8(double (&acc)[8], uint4 v) {
   const unsigned w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    acc[2 * i] += fix24_abs((unsigned short)(w[i] & 0xffffu));
-    acc[2 * i + 1] += fix24_abs((unsigned short)(w[i] >> 16));
+    const sh2 h = __builtin_bit_cast(sh2, w[i]);
+    acc[2 * i] += __builtin_fabs((double)(float)h[0]);
+    acc[2 * i + 1] += __builtin_fabs((double)(float)h[1]);
   }
 }
 
@@ -49,9 +54,10 @@ qabs_accumulate_kernel(const __half* __restrict__ q, int Lq, Strides3 qs, int Hk
   const int c = tid & 15, r = tid >> 4;
   const int t0 = chunk * kRowsPerWG, t1 = min(Lq, t0 + kRowsPerWG);
   const __half* base = q + (int64_t)b * qs.b + (int64_t)(j * g + hh) * qs.h + 8 * c;
-  unsigned long long acc[8];
+  static_assert(kRowsPerWG / 16 <= 8192, "per-thread binary64 sums must stay exact");
+  double acc[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) acc[i] = 0ull;
+  for (int i = 0; i < 8; ++i) acc[i] = 0.0;
   int t = t0 + r;
   for (; t + 48 < t1; t += 64) {
     uint4 v[4];
@@ -62,7 +68,7 @@ qabs_accumulate_kernel(const __half* __restrict__ q, int Lq, Strides3 qs, int Hk
   }
   for (; t < t1; t += 16) add8(acc, *reinterpret_cast<const uint4*>(base + (int64_t)t * qs.t));
 #pragma unroll
-  for (int i = 0; i < 8; ++i) sAcc[r][8 * c + i] = acc[i];
+  for (int i = 0; i < 8; ++i) sAcc[r][8 * c + i] = (unsigned long long)(acc[i] * 16777216.0);
   __syncthreads();
   if (tid < kD) {
     unsigned long long sum = 0;
