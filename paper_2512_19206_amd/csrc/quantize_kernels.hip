@@ -21,8 +21,8 @@ struct GroupParams { float s, z; unsigned short s16, z16; };
 
 // Scale and zero-point of one group from its fp16 minimum and maximum (Eq. 2-3).
 __device__ __forceinline__ GroupParams group_params(float mn, float mx, float levels) {
-  mn = mn + 0.0f;   // -0 -> +0
-  mx = mx + 0.0f;
+  mn = mn == 0.f ? 0.f : mn;   // -0 -> +0
+  mx = mx == 0.f ? 0.f : mx;
   GroupParams r;
   __half z16 = __float2half_rn(mn);          // exact: mn is an fp16 value
   float s32 = (mx - mn) / levels;            // IEEE divide
@@ -229,14 +229,14 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
 // The same record, built for throughput (Gk a multiple of 16, Gv >= 16, 16-byte aligned rows):
 //   - both tiles are fetched with all loads in flight at once (the value tile waits in registers while the
 //     keys are encoded);
-//   - minima and maxima are taken on packed 16-bit keys that order like the fp16 values, two channels per
-//     instruction, first per chunk of 16 tokens (all threads), then per group / per block;
+//   - minima and maxima are taken with packed fp16 instructions, two channels at a time, first per chunk of
+//     16 tokens (all threads), then per group / per block;
 //   - positions inside the tiers come from wavefront ballots;
 //   - in the encode loops a thread keeps the scale and zero-point of its channels (keys) or tokens (values)
 //     in registers and only the element itself comes from LDS.
 // Every rounding step is the one of flush_block_kernel: results are bit-identical.
 // ---------------------------------------------------------------------------
-typedef short fs16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 fh2 __attribute__((ext_vector_type(2)));
 
 #ifdef MIXKVQ_PHASE_CLOCKS
 // Profiling aid, not part of the default build: 100 MHz timestamps of the phases of the first 1024 workgroups.
@@ -248,14 +248,10 @@ __device__ unsigned long long g_flush_clock[1024 * 16];
 #define MIXKVQ_FPHASE(K_)
 #endif
 
-__device__ __forceinline__ fs16x2 fkey(unsigned w) {   // fp16 pair -> keys ordered like the values (an involution)
-  const fs16x2 v = __builtin_bit_cast(fs16x2, w);
-  return v ^ ((v >> 15) & (short)0x7fff);
-}
-__device__ __forceinline__ float key_to_float(short key) {
-  const unsigned short bits = (unsigned short)(key ^ ((key >> 15) & (short)0x7fff));
-  return __half2float(__ushort_as_half(bits));
-}
+// Minima and maxima are taken with the packed fp16 instructions, two values at a time.  Which zero they return for
+// {-0, +0} does not matter: group_params() and the integer range both take -0 as +0.
+__device__ __forceinline__ fh2 as_h2(unsigned w) { return __builtin_bit_cast(fh2, w); }
+__device__ __forceinline__ unsigned short h_bits(_Float16 h) { return __builtin_bit_cast(unsigned short, h); }
 
 // Code of u = x - z with the reciprocal r of the scale (r = 0 for scale 0); TOP = 3 or 15.  q0 = u*r is within
 // (TOP + 1.3) * 2.4e-7 of the correctly rounded quotient (rcp and the product are good to 1.8e-7 relative, the
@@ -338,10 +334,10 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
     const int d2 = tid & 63;
     const unsigned* sT32 = reinterpret_cast<const unsigned*>(sT);
     for (int ch = tid >> 6; ch < n_ch; ch += 4) {
-      fs16x2 lo = fkey(sT32[(16 * ch) * (kRowStride / 2) + d2]), hi = lo;
+      fh2 lo = as_h2(sT32[(16 * ch) * (kRowStride / 2) + d2]), hi = lo;
 #pragma unroll
       for (int t = 1; t < 16; ++t) {
-        const fs16x2 key = fkey(sT32[(16 * ch + t) * (kRowStride / 2) + d2]);
+        const fh2 key = as_h2(sT32[(16 * ch + t) * (kRowStride / 2) + d2]);
         lo = __builtin_elementwise_min(lo, key);
         hi = __builtin_elementwise_max(hi, key);
       }
@@ -356,16 +352,15 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   if (sel_in == nullptr && ks > 0) {
     double A = 0.0;
     if (tid < kD) {
-      const short* cl = reinterpret_cast<const short*>(&sCLo[0][0]);
-      const short* chh = reinterpret_cast<const short*>(&sCHi[0][0]);
-      short lo = cl[tid], hi = chh[tid];
+      const _Float16* cl = reinterpret_cast<const _Float16*>(&sCLo[0][0]);
+      const _Float16* chh = reinterpret_cast<const _Float16*>(&sCHi[0][0]);
+      _Float16 lo = cl[tid], hi = chh[tid];
       for (int ch = 1; ch < n_ch; ++ch) {
-        const short a = cl[ch * kD + tid], b2 = chh[ch * kD + tid];
+        const _Float16 a = cl[ch * kD + tid], b2 = chh[ch * kD + tid];
         lo = a < lo ? a : lo;
         hi = b2 > hi ? b2 : hi;
       }
-      const long long rng = fix24((unsigned short)(hi ^ ((hi >> 15) & (short)0x7fff))) -
-                            fix24((unsigned short)(lo ^ ((lo >> 15) & (short)0x7fff)));
+      const long long rng = fix24(h_bits(hi)) - fix24(h_bits(lo));
       A = score_mode ? (double)rng : (double)cv.qacc[(size_t)p * kD + tid] * (double)rng;
       sA[tid] = A;
     }
@@ -411,20 +406,20 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   MIXKVQ_FPHASE(3)
   // ---- key group parameters from the chunk extrema ------------------------------------------
   {
-    const short* cl = reinterpret_cast<const short*>(&sCLo[0][0]);
-    const short* chh = reinterpret_cast<const short*>(&sCHi[0][0]);
+    const _Float16* cl = reinterpret_cast<const _Float16*>(&sCLo[0][0]);
+    const _Float16* chh = reinterpret_cast<const _Float16*>(&sCHi[0][0]);
     const int cpg = Gk / 16;     // chunks per group
     for (int it = tid; it < NG * kD; it += kFlushThreads) {
       const int grp = it / kD, d = it % kD;
       const unsigned char tier = sTier[d];
       if (tier == 2) continue;
-      short lo = cl[(grp * cpg) * kD + d], hi = chh[(grp * cpg) * kD + d];
+      _Float16 lo = cl[(grp * cpg) * kD + d], hi = chh[(grp * cpg) * kD + d];
       for (int c = 1; c < cpg; ++c) {
-        const short a = cl[(grp * cpg + c) * kD + d], b2 = chh[(grp * cpg + c) * kD + d];
+        const _Float16 a = cl[(grp * cpg + c) * kD + d], b2 = chh[(grp * cpg + c) * kD + d];
         lo = a < lo ? a : lo;
         hi = b2 > hi ? b2 : hi;
       }
-      const GroupParams gp = group_params(key_to_float(lo), key_to_float(hi), tier ? 15.f : 3.f);
+      const GroupParams gp = group_params((float)lo, (float)hi, tier ? 15.f : 3.f);
       sS[grp * kD + d] = gp.s;
       sZ[grp * kD + d] = gp.z;
       sR[grp * kD + d] = safe_rcp(gp.s);
@@ -527,21 +522,21 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   float* sVZ = sZ;
   {
     // per token and value group: 16 threads cover a row, a group is Gv/8 neighbouring threads.  The pair
-    // (min key, ~max key) is reduced with packed 16-bit minima over DPP lane exchanges inside the row of 16.
+    // (min, -max) is reduced with packed fp16 minima over DPP lane exchanges inside the row of 16.
     const int c = tid & 15, lpg = Gv / 8;
-    unsigned* sRow = &sChunk[0][0][0];     // [token][value group] packed (min key, ~max key); <= 128 * 8 entries
+    unsigned* sRow = &sChunk[0][0][0];     // [token][value group] packed (min, -max); <= 128 * 8 entries
     for (int row = tid >> 4; row < R; row += 16) {
       const uint4 v = *reinterpret_cast<const uint4*>(sT + row * kRowStride + c * 8);
-      const fs16x2 k0 = fkey(v.x), k1 = fkey(v.y), k2 = fkey(v.z), k3 = fkey(v.w);
-      const fs16x2 lo2 = __builtin_elementwise_min(__builtin_elementwise_min(k0, k1), __builtin_elementwise_min(k2, k3));
-      const fs16x2 hi2 = __builtin_elementwise_max(__builtin_elementwise_max(k0, k1), __builtin_elementwise_max(k2, k3));
-      fs16x2 m;
+      const fh2 k0 = as_h2(v.x), k1 = as_h2(v.y), k2 = as_h2(v.z), k3 = as_h2(v.w);
+      const fh2 lo2 = __builtin_elementwise_min(__builtin_elementwise_min(k0, k1), __builtin_elementwise_min(k2, k3));
+      const fh2 hi2 = __builtin_elementwise_max(__builtin_elementwise_max(k0, k1), __builtin_elementwise_max(k2, k3));
+      fh2 m;
       m[0] = lo2[0] < lo2[1] ? lo2[0] : lo2[1];
-      m[1] = (short)~(hi2[0] > hi2[1] ? hi2[0] : hi2[1]);
+      m[1] = -(hi2[0] > hi2[1] ? hi2[0] : hi2[1]);
       int mi = __builtin_bit_cast(int, m);
 #define MIXKVQ_DPP_MIN(CTRL)                                                                                   \
   mi = __builtin_bit_cast(int, __builtin_elementwise_min(                                                      \
-      __builtin_bit_cast(fs16x2, mi), __builtin_bit_cast(fs16x2, __builtin_amdgcn_update_dpp(mi, mi, CTRL, 0xf, 0xf, false))));
+      __builtin_bit_cast(fh2, mi), __builtin_bit_cast(fh2, __builtin_amdgcn_update_dpp(mi, mi, CTRL, 0xf, 0xf, false))));
       if (lpg >= 2) MIXKVQ_DPP_MIN(0xB1)     // quad_perm [1,0,3,2]
       if (lpg >= 4) MIXKVQ_DPP_MIN(0x4E)     // quad_perm [2,3,0,1]
       if (lpg >= 8) MIXKVQ_DPP_MIN(0x141)    // row_half_mirror
@@ -551,8 +546,8 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
     }
     __syncthreads();
     for (int it = tid; it < R * NVG; it += kFlushThreads) {
-      const unsigned mi = sRow[it];
-      const GroupParams gp = group_params(key_to_float((short)(mi & 0xffffu)), key_to_float((short)~(mi >> 16)), 3.f);
+      const fh2 mm = as_h2(sRow[it]);
+      const GroupParams gp = group_params((float)mm[0], -(float)mm[1], 3.f);
       sVS[it] = gp.s;
       sVZ[it] = gp.z;
       sR[it] = safe_rcp(gp.s);
