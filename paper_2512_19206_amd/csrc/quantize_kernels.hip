@@ -268,10 +268,13 @@ __device__ __forceinline__ unsigned code_fast(float x, float z, float r, bool& n
 }
 __device__ __forceinline__ float safe_rcp(float s) { return s > 0.f ? __builtin_amdgcn_rcpf(s) : 0.f; }
 
-__device__ __forceinline__ uint4 load_chunk(const __half* res, const __half* fresh, Strides3 st, int p, int Hkv, int R,
-                                            int r0, int pos0, int idx) {
-  const int t = idx >> 4, c = idx & 15;
-  return *reinterpret_cast<const uint4*>(token_row(res, fresh, st, p, Hkv, R, r0, pos0 + t) + c * 8);
+// 16-byte piece `idx` of the tile that starts at stream position pos0; `res_p` and `fresh_p` are the pair's
+// residual window and its slice of the caller's tensor (token 0 of this call).
+__device__ __forceinline__ uint4 load_chunk(const __half* res_p, const __half* fresh_p, int64_t stride_t, int r0, int pos0,
+                                            int idx) {
+  const int pos = pos0 + (idx >> 4), c = idx & 15;
+  const __half* row = pos < r0 ? res_p + (size_t)pos * kD : fresh_p + (int64_t)(pos - r0) * stride_t;
+  return *reinterpret_cast<const uint4*>(row + c * 8);
 }
 
 __global__ void __launch_bounds__(kFlushThreads, 3)   // three workgroups per CU (LDS) = three wavefronts per SIMD
@@ -306,17 +309,20 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   MIXKVQ_FPHASE(0)
   // ---- both tiles: every load in flight ------------------------------------------------------
   uint4 kreg[8], vreg[8];
+  const int64_t pair_off = (int64_t)(p / Hkv) * st.b + (int64_t)(p % Hkv) * st.h;
+  const __half* res_kp = cv.res_k + (size_t)p * R * kD;
+  const __half* res_vp = cv.res_v + (size_t)p * R * kD;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int idx = tid + kFlushThreads * i;
     kreg[i] = make_uint4(0u, 0u, 0u, 0u);
-    if (idx < n_chunks16) kreg[i] = load_chunk(cv.res_k, k_new, st, p, Hkv, R, r0, f * R, idx);
+    if (idx < n_chunks16) kreg[i] = load_chunk(res_kp, k_new + pair_off, st.t, r0, f * R, idx);
   }
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int idx = tid + kFlushThreads * i;
     vreg[i] = make_uint4(0u, 0u, 0u, 0u);
-    if (idx < n_chunks16) vreg[i] = load_chunk(cv.res_v, v_new, st, p, Hkv, R, r0, f * R, idx);
+    if (idx < n_chunks16) vreg[i] = load_chunk(res_vp, v_new + pair_off, st.t, r0, f * R, idx);
   }
   // zero the small planes of the record (index bytes, tails of the scale/zero planes)
   for (int i = tid; i < off_klo / 4; i += kFlushThreads) reinterpret_cast<unsigned*>(rec)[i] = 0u;
@@ -483,8 +489,11 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   }
   MIXKVQ_FPHASE(5)
   // ---- 4-bit key words: [token][k4/8] -------------------------------------
-  for (int it = tid; it < R * W4; it += kFlushThreads) {
-    const int t = it / W4, wd = it % W4, grp = t / Gk;
+  // (a thread keeps its token; the two halves of the workgroup alternate over the words: no divisions by run-time values)
+  for (int wd = tid >> 7; wd < W4; wd += 2) {
+    const int t = tid & 127;
+    if (t >= R) break;
+    const int grp = t / Gk, it = t * W4 + wd;
     unsigned w = 0;
     bool near = false;
 #pragma unroll
@@ -503,9 +512,9 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
     reinterpret_cast<unsigned*>(rec + off_k4)[it] = w;
   }
   // ---- fp16 tier: [token][k16] ------------------------------------------
-  for (int it = tid; it < R * k16; it += kFlushThreads) {
-    const int t = it / k16, i = it % k16;
-    reinterpret_cast<__half*>(rec + off_k16)[it] = sT[t * kRowStride + sHiList[i]];
+  for (int i = tid >> 7; i < k16; i += 2) {
+    const int t = tid & 127;
+    if (t < R) reinterpret_cast<__half*>(rec + off_k16)[t * k16 + i] = sT[t * kRowStride + sHiList[i]];
   }
   __syncthreads();
 
@@ -523,7 +532,8 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   {
     // per token and value group: 16 threads cover a row, a group is Gv/8 neighbouring threads.  The pair
     // (min, -max) is reduced with packed fp16 minima over DPP lane exchanges inside the row of 16.
-    const int c = tid & 15, lpg = Gv / 8;
+    const int c = tid & 15, lpg = Gv / 8;                 // lpg = 2, 4, 8 or 16 (Gv divides 128)
+    const int lpg_shift = 31 - __builtin_clz(lpg);
     unsigned* sRow = &sChunk[0][0][0];     // [token][value group] packed (min, -max); <= 128 * 8 entries
     for (int row = tid >> 4; row < R; row += 16) {
       const uint4 v = *reinterpret_cast<const uint4*>(sT + row * kRowStride + c * 8);
@@ -542,7 +552,7 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
       if (lpg >= 8) MIXKVQ_DPP_MIN(0x141)    // row_half_mirror
       if (lpg >= 16) MIXKVQ_DPP_MIN(0x140)   // row_mirror
 #undef MIXKVQ_DPP_MIN
-      if (c % lpg == 0) sRow[row * NVG + c / lpg] = (unsigned)mi;
+      if ((c & (lpg - 1)) == 0) sRow[row * NVG + (c >> lpg_shift)] = (unsigned)mi;
     }
     __syncthreads();
     for (int it = tid; it < R * NVG; it += kFlushThreads) {
