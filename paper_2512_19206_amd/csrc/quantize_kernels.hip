@@ -520,40 +520,40 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
 
   MIXKVQ_FPHASE(6)
   // ---- values ---------------------------------------------------------------------------------
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int idx = tid + kFlushThreads * i;
-    if (idx < n_chunks16) *reinterpret_cast<uint4*>(sT + (idx >> 4) * kRowStride + (idx & 15) * 8) = vreg[i];
-  }
-  __syncthreads();
-  MIXKVQ_FPHASE(7)
+  // The tile goes to LDS; on the way every thread reduces its 16-byte pieces (still in registers) to the minimum
+  // and maximum per token and value group: 16 threads cover a row, a group is Gv/8 neighbouring threads, and the
+  // pair (min, -max) is reduced with packed fp16 minima over DPP lane exchanges inside the row of 16.
   float* sVS = sS;   // [token][NVG]
   float* sVZ = sZ;
   {
-    // per token and value group: 16 threads cover a row, a group is Gv/8 neighbouring threads.  The pair
-    // (min, -max) is reduced with packed fp16 minima over DPP lane exchanges inside the row of 16.
     const int c = tid & 15, lpg = Gv / 8;                 // lpg = 2, 4, 8 or 16 (Gv divides 128)
     const int lpg_shift = 31 - __builtin_clz(lpg);
     unsigned* sRow = &sChunk[0][0][0];     // [token][value group] packed (min, -max); <= 128 * 8 entries
-    for (int row = tid >> 4; row < R; row += 16) {
-      const uint4 v = *reinterpret_cast<const uint4*>(sT + row * kRowStride + c * 8);
-      const fh2 k0 = as_h2(v.x), k1 = as_h2(v.y), k2 = as_h2(v.z), k3 = as_h2(v.w);
-      const fh2 lo2 = __builtin_elementwise_min(__builtin_elementwise_min(k0, k1), __builtin_elementwise_min(k2, k3));
-      const fh2 hi2 = __builtin_elementwise_max(__builtin_elementwise_max(k0, k1), __builtin_elementwise_max(k2, k3));
-      fh2 m;
-      m[0] = lo2[0] < lo2[1] ? lo2[0] : lo2[1];
-      m[1] = -(hi2[0] > hi2[1] ? hi2[0] : hi2[1]);
-      int mi = __builtin_bit_cast(int, m);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int row = (tid >> 4) + 16 * i;
+      if (row < R) {
+        const uint4 v = vreg[i];
+        *reinterpret_cast<uint4*>(sT + row * kRowStride + c * 8) = v;
+        const fh2 k0 = as_h2(v.x), k1 = as_h2(v.y), k2 = as_h2(v.z), k3 = as_h2(v.w);
+        const fh2 lo2 = __builtin_elementwise_min(__builtin_elementwise_min(k0, k1), __builtin_elementwise_min(k2, k3));
+        const fh2 hi2 = __builtin_elementwise_max(__builtin_elementwise_max(k0, k1), __builtin_elementwise_max(k2, k3));
+        fh2 m;
+        m[0] = lo2[0] < lo2[1] ? lo2[0] : lo2[1];
+        m[1] = -(hi2[0] > hi2[1] ? hi2[0] : hi2[1]);
+        int mi = __builtin_bit_cast(int, m);
 #define MIXKVQ_DPP_MIN(CTRL)                                                                                   \
   mi = __builtin_bit_cast(int, __builtin_elementwise_min(                                                      \
       __builtin_bit_cast(fh2, mi), __builtin_bit_cast(fh2, __builtin_amdgcn_update_dpp(mi, mi, CTRL, 0xf, 0xf, false))));
-      if (lpg >= 2) MIXKVQ_DPP_MIN(0xB1)     // quad_perm [1,0,3,2]
-      if (lpg >= 4) MIXKVQ_DPP_MIN(0x4E)     // quad_perm [2,3,0,1]
-      if (lpg >= 8) MIXKVQ_DPP_MIN(0x141)    // row_half_mirror
-      if (lpg >= 16) MIXKVQ_DPP_MIN(0x140)   // row_mirror
+        if (lpg >= 2) MIXKVQ_DPP_MIN(0xB1)     // quad_perm [1,0,3,2]
+        if (lpg >= 4) MIXKVQ_DPP_MIN(0x4E)     // quad_perm [2,3,0,1]
+        if (lpg >= 8) MIXKVQ_DPP_MIN(0x141)    // row_half_mirror
+        if (lpg >= 16) MIXKVQ_DPP_MIN(0x140)   // row_mirror
 #undef MIXKVQ_DPP_MIN
-      if ((c & (lpg - 1)) == 0) sRow[row * NVG + (c >> lpg_shift)] = (unsigned)mi;
+        if ((c & (lpg - 1)) == 0) sRow[row * NVG + (c >> lpg_shift)] = (unsigned)mi;
+      }
     }
+    MIXKVQ_FPHASE(7)
     __syncthreads();
     for (int it = tid; it < R * NVG; it += kFlushThreads) {
       const fh2 mm = as_h2(sRow[it]);
