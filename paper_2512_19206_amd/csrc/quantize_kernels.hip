@@ -258,13 +258,23 @@ __device__ __forceinline__ unsigned short h_bits(_Float16 h) { return __builtin_
 // quotient itself to 6e-8), i.e. within 1e-6 for two-bit and 4e-6 for four-bit codes; so whenever q0 is further
 // than EPS (2^-18, 2^-16) from every half-integer, rint(q0) IS the code Eq. 2 defines.  `near` collects the
 // other cases, which the caller redoes with the IEEE division.  (u >= 0, so no lower clamp is needed.)
+// The code is returned as a float: the callers build each half-word of a packed word as an exact fp32 sum
+// c_0 + c_1 2^w + c_2 2^2w + ... (< 2^16) with one fused multiply-add per code and convert once per half-word.
 template <int TOP>
-__device__ __forceinline__ unsigned code_fast(float x, float z, float r, bool& near) {
+__device__ __forceinline__ float code_fast(float x, float z, float r, bool& near) {
   constexpr float kEps = TOP == 3 ? 3.814697265625e-6f : 1.52587890625e-5f;
   const float q0 = (x - z) * r;
   const float c = rintf(q0);
   near |= fabsf(q0 - c) > 0.5f - kEps;
-  return (unsigned)fminf(c, (float)TOP);
+  return fminf(c, (float)TOP);
+}
+// code i of a word sits at bit 16 (i & 1) + W (i >> 1): even codes in the low half-word, odd codes in the high one
+template <int W>
+__device__ __forceinline__ void add_code(float (&half)[2], int i, float c) {
+  half[i & 1] = __builtin_fmaf(c, (float)(1u << (W * (i >> 1))), half[i & 1]);
+}
+__device__ __forceinline__ unsigned join_halves(const float (&half)[2]) {
+  return (unsigned)half[0] | ((unsigned)half[1] << 16);
 }
 __device__ __forceinline__ float safe_rcp(float s) { return s > 0.f ? __builtin_amdgcn_rcpf(s) : 0.f; }
 
@@ -466,13 +476,14 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
         for (int tt = tl; tt < Gk; tt += 32) {
           const int t = grp * Gk + tt;
           const __half* row = sT + t * kRowStride;
-          unsigned w = 0;
+          float hw[2] = {0.f, 0.f};
           bool near = false;
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
             const float x = __half2float(row[doff[i] < 0 ? 0 : doff[i]]);
-            w |= code_fast<3>(x, zp[i], rc[i], near) << (16 * (i & 1) + 2 * (i >> 1));
+            add_code<2>(hw, i, code_fast<3>(x, zp[i], rc[i], near));
           }
+          unsigned w = join_halves(hw);
           if (__any(near)) {     // rare: some quotient sits next to a rounding boundary
             w = 0;
 #pragma unroll
@@ -494,13 +505,14 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
     const int t = tid & 127;
     if (t >= R) break;
     const int grp = t / Gk, it = t * W4 + wd;
-    unsigned w = 0;
+    float hw[2] = {0.f, 0.f};
     bool near = false;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int d = sHiList[k16 + wd * 8 + i];
-      w |= code_fast<15>(__half2float(sT[t * kRowStride + d]), sZ[grp * kD + d], sR[grp * kD + d], near) << (16 * (i & 1) + 4 * (i >> 1));
+      add_code<4>(hw, i, code_fast<15>(__half2float(sT[t * kRowStride + d]), sZ[grp * kD + d], sR[grp * kD + d], near));
     }
+    unsigned w = join_halves(hw);
     if (__any(near)) {     // rare: some quotient sits next to a rounding boundary
       w = 0;
 #pragma unroll
@@ -587,12 +599,12 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
           zp[i] = sVZ[(tg * 16 + i) * NVG + vg];
         }
       }
-      unsigned w = 0;
+      float hw[2] = {0.f, 0.f};
       bool near = false;
 #pragma unroll
       for (int i = 0; i < 16; ++i)
-        w |= code_fast<3>(__half2float(sT[(tg * 16 + i) * kRowStride + d]), zp[i], rc[i], near)
-             << (16 * (i & 1) + 2 * (i >> 1));
+        add_code<2>(hw, i, code_fast<3>(__half2float(sT[(tg * 16 + i) * kRowStride + d]), zp[i], rc[i], near));
+      unsigned w = join_halves(hw);
       if (__any(near)) {     // rare: some quotient sits next to a rounding boundary
         w = 0;
 #pragma unroll
