@@ -322,17 +322,38 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   const int64_t pair_off = (int64_t)(p / Hkv) * st.b + (int64_t)(p % Hkv) * st.h;
   const __half* res_kp = cv.res_k + (size_t)p * R * kD;
   const __half* res_vp = cv.res_v + (size_t)p * R * kD;
+  const int pos0 = f * R;
+  if (pos0 >= r0 || pos0 + R <= r0) {
+    // the usual case: the whole tile comes from one place, rows a constant stride apart
+    const bool from_res = pos0 + R <= r0;
+    const int64_t row_stride = from_res ? (int64_t)kD : st.t;
+    const int64_t first = (int64_t)(from_res ? pos0 : pos0 - r0) + (tid >> 4);
+    const __half* kp = (from_res ? res_kp : k_new + pair_off) + first * row_stride + (tid & 15) * 8;
+    const __half* vp = (from_res ? res_vp : v_new + pair_off) + first * row_stride + (tid & 15) * 8;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int idx = tid + kFlushThreads * i;
-    kreg[i] = make_uint4(0u, 0u, 0u, 0u);
-    if (idx < n_chunks16) kreg[i] = load_chunk(res_kp, k_new + pair_off, st.t, r0, f * R, idx);
-  }
+    for (int i = 0; i < 8; ++i) {
+      kreg[i] = make_uint4(0u, 0u, 0u, 0u);
+      if (tid + kFlushThreads * i < n_chunks16) kreg[i] = *reinterpret_cast<const uint4*>(kp + 16 * i * row_stride);
+    }
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int idx = tid + kFlushThreads * i;
-    vreg[i] = make_uint4(0u, 0u, 0u, 0u);
-    if (idx < n_chunks16) vreg[i] = load_chunk(res_vp, v_new + pair_off, st.t, r0, f * R, idx);
+    for (int i = 0; i < 8; ++i) {
+      vreg[i] = make_uint4(0u, 0u, 0u, 0u);
+      if (tid + kFlushThreads * i < n_chunks16) vreg[i] = *reinterpret_cast<const uint4*>(vp + 16 * i * row_stride);
+    }
+  } else {
+    // the tile straddles the end of the residual window (first block of an append onto a partly filled window)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int idx = tid + kFlushThreads * i;
+      kreg[i] = make_uint4(0u, 0u, 0u, 0u);
+      if (idx < n_chunks16) kreg[i] = load_chunk(res_kp, k_new + pair_off, st.t, r0, pos0, idx);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int idx = tid + kFlushThreads * i;
+      vreg[i] = make_uint4(0u, 0u, 0u, 0u);
+      if (idx < n_chunks16) vreg[i] = load_chunk(res_vp, v_new + pair_off, st.t, r0, pos0, idx);
+    }
   }
   // zero the small planes of the record (index bytes, tails of the scale/zero planes)
   for (int i = tid; i < off_klo / 4; i += kFlushThreads) reinterpret_cast<unsigned*>(rec)[i] = 0u;
