@@ -2,8 +2,8 @@
 
 A plain, slow, numpy implementation of what the GPU library computes: the
 asymmetric min/max quantizer (Section 3.2, Eq. 2-3), the query-aware channel
-salience score (Section 4.2, Eq. 6-8) with a top-k channel budget, the lazy
-residual-buffer flush (Appendix D.1), the running |q| accumulator
+salience score (Section 4.2, Eq. 6-8) with a top-k channel budget or the
+three-tier threshold rule of Section 4.2, the lazy residual-buffer flush (Appendix D.1), the running |q| accumulator
 (Appendix D.2) and decode attention (Section 3.1, Eq. 1) over the resulting
 mixed-precision cache, in fp64.
 
@@ -22,7 +22,9 @@ Pins (tests/test_oracle_*.py): Eq. 2-3 error bound |x - x~| <= s/2, code
 monotonicity and end points, top-k against exact rational arithmetic, Eq. 6-8
 in float64, brute-force attention loops, exact attention when every channel is
 kept in fp16 / every token sits in the residual window, split invariance,
-closed-form state-machine counts and byte counts.  The paper's model-quality
+closed-form state-machine counts and byte counts; the threshold rule against
+the three inequalities of Section 4.2 in exact rational arithmetic and against
+the top-k rule where the two must coincide.  The paper's model-quality
 numbers (accuracy, perplexity) are parity unpinned here: they need weights and
 datasets that are not available.
 """
@@ -53,6 +55,9 @@ class OracleConfig:
     flush_mode: int = 0           # 0 deferred (newest <= R tokens stay fp16), 1 eager
     score_mode: int = 0           # 0: A = I*S (Eq. 8); 1: A = S (error-only ablation, Appendix E)
     qacc_reset_on_flush: int = 0  # 0: running since sequence start (Appendix D.2); 1: per window (Section 4.2)
+    policy: int = 0               # 0: the k16 + k4 best channels; 1: thresholds of Section 4.2, k16 / k4 are capacities
+    tau16: float = math.inf       # policy 1: A_d > tau16 -> fp16 tier
+    tau4: float = math.inf        # policy 1: tau4 < A_d <= tau16 -> 4-bit tier
 
     @property
     def g(self):
@@ -169,10 +174,55 @@ def select_channels(A: np.ndarray, k16: int, k4: int) -> np.ndarray:
     return np.array(hi16 + hi4, dtype=np.uint8)
 
 
+NO_CHANNEL = 255  # an unused entry of a channel list (threshold policy)
+
+
+def threshold_in_score_units(tau: float, qcnt: int, score_mode: int = 0) -> float:
+    """The threshold of Section 4.2 carried over to the units of `salience`.
+
+    In real units A_d = I_d * S_d with I_d = (sum|q|_d 2^-24) / count (Eq. 6) and
+    S_d = (range_d 2^-24) / (2^2 - 1) (Eq. 7 for the two-bit quantizer a channel
+    gets unless it is promoted), so  A_d > tau  <=>  sum|q|_d * range_d > tau * 3 * 2^48 * count.
+    The right-hand side is formed in binary64, left to right: (tau * 3) * 2^48
+    (exact) * count.  With the error-only score, S_d > tau <=> range_d > tau * 3 * 2^24."""
+    if score_mode == 1:
+        return (float(tau) * 3.0) * float(1 << FIX_SHIFT)
+    return ((float(tau) * 3.0) * float(1 << (2 * FIX_SHIFT))) * float(int(qcnt))
+
+
+def select_channels_threshold(A: np.ndarray, thr16: float, thr4: float, cap16: int, cap4: int) -> np.ndarray:
+    """The three-tier rule of Section 4.2 on the scores A (thresholds already in
+    the units of A): A_d > thr16 -> fp16, thr4 < A_d <= thr16 -> 4 bit, else 2 bit.
+    The record has room for cap16 fp16 channels and cap4 four-bit channels per
+    block: when more pass a threshold the best by (score, lower index) keep
+    the tier and the others fall to the next one down.  Returns uint8
+    [cap16 + cap4]: the fp16 tier ascending, filled up with NO_CHANNEL, then the
+    4-bit tier likewise."""
+    D = A.shape[0]
+    order = sorted(range(D), key=lambda d: (-float(A[d]), d))
+    hi16 = [d for d in order if float(A[d]) > thr16][:cap16]
+    # candidates of the 4-bit tier: channels between the thresholds, and channels above thr16 that found no fp16 place
+    cand4 = [d for d in order if d not in hi16 and (float(A[d]) > thr4 or float(A[d]) > thr16)]
+    hi4 = cand4[:cap4]
+    out = np.full(cap16 + cap4, NO_CHANNEL, dtype=np.uint8)
+    out[:len(hi16)] = sorted(hi16)
+    out[cap16:cap16 + len(hi4)] = sorted(hi4)
+    return out
+
+
+def tier_lists(sel: np.ndarray, k16: int):
+    """(fp16-tier channels, 4-bit-tier channels) of a stored selection, unused entries dropped."""
+    sel = np.asarray(sel, dtype=np.uint8)
+    hi16 = sel[:k16]
+    hi4 = sel[k16:]
+    return hi16[hi16 != NO_CHANNEL].astype(np.int64), hi4[hi4 != NO_CHANNEL].astype(np.int64)
+
+
 def lo_channels(sel: np.ndarray, D: int) -> np.ndarray:
     """The non-salient channels in ascending order."""
     mask = np.ones(D, dtype=bool)
-    mask[sel.astype(np.int64)] = False
+    sel = np.asarray(sel).astype(np.int64)
+    mask[sel[sel != NO_CHANNEL]] = False
     return np.nonzero(mask)[0]
 
 
@@ -209,7 +259,8 @@ class BlockLayout:
 def block_layout(cfg: OracleConfig) -> BlockLayout:
     """Byte offsets of the planes inside one block record.  Every plane starts
     on a 16-byte boundary; padding bytes are zero.
-      idx    u8  [ks]               fp16-tier channels ascending, then 4-bit tier ascending
+      idx    u8  [ks]               fp16-tier channels ascending, then 4-bit tier ascending (threshold policy:
+                                    each tier filled up to its capacity with NO_CHANNEL)
       kmax   f16 [NG]               largest stored scale of the group's 2-bit and 4-bit channels (derived
                                     metadata: lets a reader normalise the scales without scanning them)
       klo_s  f16 [NG][NLp]          scales of the 2-bit key channels (ascending non-salient channels)
@@ -225,7 +276,7 @@ def block_layout(cfg: OracleConfig) -> BlockLayout:
       v_z    f16 [R][D/Gv]
     """
     D, R = cfg.D, cfg.R
-    NL = D - cfg.ks
+    NL = D if cfg.policy == 1 else D - cfg.ks     # threshold policy: room for every channel (tier sizes vary per block)
     Wlo = (NL + 15) // 16
     NLp = 16 * Wlo
     NG = R // cfg.Gk
@@ -246,13 +297,13 @@ def block_layout(cfg: OracleConfig) -> BlockLayout:
 class QuantBlock:
     """One flushed block of R tokens of one (batch, KV head) pair."""
     sel: np.ndarray        # u8 [ks]
-    lo_codes: np.ndarray   # u8 [R, NL]
-    lo_s: np.ndarray       # f16 [NG, NL]
+    lo_codes: np.ndarray   # u8 [R, n_lo]   (n_lo = D - n16 - n4 channels at 2 bit)
+    lo_s: np.ndarray       # f16 [NG, n_lo]
     lo_z: np.ndarray
-    k4_codes: np.ndarray   # u8 [R, k4]
-    k4_s: np.ndarray       # f16 [NG, k4]
+    k4_codes: np.ndarray   # u8 [R, n4]     (n4 = k4, n16 = k16 under the top-k policy)
+    k4_s: np.ndarray       # f16 [NG, n4]
     k4_z: np.ndarray
-    k16: np.ndarray        # f16 [R, k16]
+    k16: np.ndarray        # f16 [R, n16]
     v_codes: np.ndarray    # u8 [R, D]
     v_s: np.ndarray        # f16 [R, NVG]
     v_z: np.ndarray
@@ -262,8 +313,7 @@ def quantize_block(cfg: OracleConfig, K16: np.ndarray, V16: np.ndarray, sel: np.
     """The KeyQuant step of Appendix D.1 on one R-token block: split channels by
     tier, group-quantize each tier, keep the fp16 tier raw; per-token 2-bit values."""
     sel = np.asarray(sel, dtype=np.uint8)
-    hi16 = sel[:cfg.k16].astype(np.int64)
-    hi4 = sel[cfg.k16:].astype(np.int64)
+    hi16, hi4 = tier_lists(sel, cfg.k16)
     lo = lo_channels(sel, cfg.D)
     lo_codes, lo_s, lo_z = quantize_keys(K16, lo, 2, cfg.Gk)
     k4_codes, k4_s, k4_z = quantize_keys(K16, hi4, 4, cfg.Gk)
@@ -293,21 +343,24 @@ def pack_block(cfg: OracleConfig, blk: QuantBlock) -> np.ndarray:
         b = np.ascontiguousarray(arr).view(np.uint8).reshape(-1)
         rec[off:off + b.size] = b
 
+    # Planes are sized for the capacity of each tier; entries past a tier's actual size are zero.
     put(lay.off_idx, blk.sel)
-    allscales = np.concatenate([blk.lo_s, blk.k4_s], axis=1)          # [NG, NL + k4] fp16, all >= 0
+    allscales = np.concatenate([blk.lo_s, blk.k4_s], axis=1)          # [NG, n_lo + n4] fp16, all >= 0
     put(lay.off_kmax, allscales.max(axis=1).astype(np.float16))
-    pad = lay.NLp - lay.NL
+    pad = lay.NLp - blk.lo_codes.shape[1]
+    pad4 = cfg.k4 - blk.k4_codes.shape[1]
+    pad16 = cfg.k16 - blk.k16.shape[1]
     s = np.pad(blk.lo_s, ((0, 0), (0, pad)))
     z = np.pad(blk.lo_z, ((0, 0), (0, pad)))
     put(lay.off_klo_s, s.astype(np.float16))
     put(lay.off_klo_z, z.astype(np.float16))
-    put(lay.off_k4_s, blk.k4_s)
-    put(lay.off_k4_z, blk.k4_z)
+    put(lay.off_k4_s, np.pad(blk.k4_s, ((0, 0), (0, pad4))))
+    put(lay.off_k4_z, np.pad(blk.k4_z, ((0, 0), (0, pad4))))
     put(lay.off_klo, _pack_along_last(np.pad(blk.lo_codes, ((0, 0), (0, pad))), 2))
     if cfg.k4:
-        put(lay.off_k4, _pack_along_last(blk.k4_codes, 4))
+        put(lay.off_k4, _pack_along_last(np.pad(blk.k4_codes, ((0, 0), (0, pad4))), 4))
     if cfg.k16:
-        put(lay.off_k16, blk.k16)
+        put(lay.off_k16, np.pad(blk.k16, ((0, 0), (0, pad16))))
     # values: 16 codes per word along tokens, one word per (token group, channel)
     vc = blk.v_codes.reshape(cfg.R // 16, 16, cfg.D).transpose(0, 2, 1)  # [tg, d, 16]
     put(lay.off_v, _pack_along_last(vc, 2))
@@ -320,14 +373,13 @@ def dequant_block_keys(cfg: OracleConfig, blk: QuantBlock) -> np.ndarray:
     """K^ of one block in binary64, [R, D]: fp16 tier raw, other tiers by Eq. 3."""
     R, D, Gk = cfg.R, cfg.D, cfg.Gk
     out = np.empty((R, D), dtype=np.float64)
-    hi16 = blk.sel[:cfg.k16].astype(np.int64)
-    hi4 = blk.sel[cfg.k16:].astype(np.int64)
+    hi16, hi4 = tier_lists(blk.sel, cfg.k16)
     lo = lo_channels(blk.sel, D)
     rep = lambda a: np.repeat(a, Gk, axis=0)
     out[:, lo] = decode(blk.lo_codes, rep(blk.lo_s), rep(blk.lo_z))
-    if cfg.k4:
+    if len(hi4):
         out[:, hi4] = decode(blk.k4_codes, rep(blk.k4_s), rep(blk.k4_z))
-    if cfg.k16:
+    if len(hi16):
         out[:, hi16] = blk.k16.astype(np.float64)
     return out
 
@@ -382,9 +434,19 @@ class OracleCache:
         for b in range(B):
             for j in range(Hkv):
                 p = b * Hkv + j
-                A = salience(self.qacc[p], key_range(K16[b, j]), cfg.score_mode)
-                sel[b, j] = select_channels(A, cfg.k16, cfg.k4)
+                sel[b, j] = self.score_and_select(p, K16[b, j])
         return sel
+
+    def score_and_select(self, p: int, Kb: np.ndarray) -> np.ndarray:
+        """Channel tiers of pair p for the keys Kb [L, D]: Eq. 6-8 with the current
+        accumulator, then the top-k budget or the thresholds of Section 4.2."""
+        cfg = self.cfg
+        A = salience(self.qacc[p], key_range(Kb), cfg.score_mode)
+        if cfg.policy == 1:
+            t16 = threshold_in_score_units(cfg.tau16, int(self.qcnt[p]), cfg.score_mode)
+            t4 = threshold_in_score_units(cfg.tau4, int(self.qcnt[p]), cfg.score_mode)
+            return select_channels_threshold(A, t16, t4, cfg.k16, cfg.k4)
+        return select_channels(A, cfg.k16, cfg.k4)
 
     def select_channels(self, Q16, K16):
         """The library's select call: add the queries (if any) to the
@@ -425,8 +487,7 @@ class OracleCache:
                     if sel is not None:
                         s = sel[b, j]
                     else:
-                        A = salience(self.qacc[p], key_range(Kb), cfg.score_mode)
-                        s = select_channels(A, cfg.k16, cfg.k4)
+                        s = self.score_and_select(p, Kb)
                     self.blocks[p].append(quantize_block(cfg, Kb, Vb, s))
                 rest_k, rest_v = ks[F * R:], vs[F * R:]
                 self.res_k[p, :len(rest_k)] = rest_k
