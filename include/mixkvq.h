@@ -49,7 +49,15 @@ typedef struct {
   int32_t flush_mode;   /* 0 deferred: the newest <= R tokens stay fp16; 1 eager: flush as soon as R are buffered */
   int32_t score_mode;   /* 0: A_d = I_d * S_d (Eq. 8); 1: A_d = S_d (error-only ablation) */
   int32_t qacc_reset_on_flush; /* 0: |q| accumulator runs since sequence start; 1: cleared by every call that flushes */
+  int32_t policy;       /* 0: the k16 + k4 channels with the highest score; 1: the thresholds of Section 4.2 (below) */
+  double tau16, tau4;   /* policy 1: A_d > tau16 -> fp16 tier; tau4 < A_d <= tau16 -> 4-bit tier; otherwise 2 bit.
+                         * A_d = I_d * S_d in real units: I_d the mean |q| (Eq. 6), S_d = range / 3 (Eq. 7 for the two-bit
+                         * quantizer), or S_d alone with score_mode 1.  Both >= 0 (infinity allowed), not NaN.  k16 and k4
+                         * are then the record's capacity per block: if more channels pass a threshold, the best by (score,
+                         * lower index) keep the tier and the others fall to the next tier down. */
 } mixkvq_config;
+
+#define MIXKVQ_NO_CHANNEL 255  /* unused entry of a channel list (policy 1) */
 
 /* Bytes of each caller-owned device buffer. */
 typedef struct {
@@ -66,7 +74,9 @@ typedef struct {
 
 /* Byte offsets of the planes inside one block record (R tokens of one
  * (batch, KV head) pair).  Every plane starts on a 16-byte boundary, padding is 0.
- *   idx    u8  [k16+k4]      fp16-tier channels ascending, then 4-bit-tier channels ascending
+ *   idx    u8  [k16+k4]      fp16-tier channels ascending, then 4-bit-tier channels ascending; under policy 1 each
+ *                            tier is filled up to its capacity with MIXKVQ_NO_CHANNEL and the unused entries of
+ *                            every plane of that tier are 0
  *   kmax   f16 [NG]          largest stored scale among the group's 2-bit and 4-bit channels (derived metadata)
  *   klo_s  f16 [NG][NLp]     scales of the 2-bit key channels (the non-salient channels, ascending)
  *   klo_z  f16 [NG][NLp]     zero-points (group minima, Eq. 2)
@@ -77,7 +87,8 @@ typedef struct {
  *   k16    f16 [R][k16]      raw values of the fp16 tier
  *   v      u32 [R/16][D]     16 two-bit codes per word along TOKENS for one channel, same bit order as klo
  *   v_s    f16 [R][D/Gv]     value scales per (token, channel group);  v_z likewise
- * NL = D-k4-k16, Wlo = ceil(NL/16), NLp = 16*Wlo, NG = R/Gk, NVG = D/Gv, W4 = k4/8. */
+ * NL = D-k4-k16 (policy 1: NL = D, room for every channel; the 2-bit channels of a block fill the first
+ * D-n16-n4 places), Wlo = ceil(NL/16), NLp = 16*Wlo, NG = R/Gk, NVG = D/Gv, W4 = k4/8. */
 typedef struct {
   int32_t NL, Wlo, NLp, NG, NVG, W4;
   int32_t off_idx, off_kmax, off_klo_s, off_klo_z, off_k4_s, off_k4_z, off_klo, off_k4, off_k16, off_v, off_v_s, off_v_z;
@@ -102,7 +113,7 @@ int mixkvq_cache_reset(mixkvq_cache* c, void* stream);
 /* Host-only: quantized and residual token counts.  Either out pointer may be NULL. */
 int mixkvq_cache_state(const mixkvq_cache* c, int64_t* n_quantized, int32_t* n_residual);
 
-/* Channel selection (Section 4.2, Eq. 6-8, with a top-k channel budget instead of thresholds).
+/* Channel selection (Section 4.2, Eq. 6-8; top-k channel budget or thresholds, see mixkvq_config.policy).
  *   q  DEVICE fp16 [B][Hq][Lq][D] after rotary embedding, element strides q_strides = {batch, head, token},
  *      channel stride 1; may be NULL with Lq = 0 (use the running accumulator only).
  *   k  DEVICE fp16 [B][Hkv][L][D] after rotary embedding, strides k_strides likewise; L >= 1.
@@ -110,7 +121,8 @@ int mixkvq_cache_state(const mixkvq_cache* c, int64_t* n_quantized, int32_t* n_r
  * (Eq. 6; Appendix D), takes max-min of every key channel over the L tokens (Eq. 7), scores
  * A_d = sum|q|_d * range_d (Eq. 8 up to constants shared by the head), and writes the k16+k4 best
  * channels per (b, KV head) to sel DEVICE u8 [B][Hkv][k16+k4]: first the k16 best, ascending, then the
- * next k4, ascending.  Ties go to the lower channel index.  The token counts are unchanged. */
+ * next k4, ascending.  Ties go to the lower channel index.  Under policy 1 the two lists hold the channels
+ * that pass the thresholds, each filled up with MIXKVQ_NO_CHANNEL.  The token counts are unchanged. */
 int mixkvq_select_channels(mixkvq_cache* c, const void* q, int32_t Lq, const int64_t q_strides[3],
                            const void* k, int32_t L, const int64_t k_strides[3],
                            uint8_t* sel, void* stream);

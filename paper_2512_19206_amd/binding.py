@@ -22,7 +22,8 @@ EXPORTS = ("mixkvq_block_layout", "mixkvq_cache_sizes", "mixkvq_cache_create", "
 
 class Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("B", "Hq", "Hkv", "D", "T_max", "Gk", "Gv", "R", "k4", "k16",
-                                         "flush_mode", "score_mode", "qacc_reset_on_flush")]
+                                         "flush_mode", "score_mode", "qacc_reset_on_flush", "policy")] + \
+               [("tau16", C.c_double), ("tau4", C.c_double)]
 
 
 class Sizes(C.Structure):
@@ -97,8 +98,9 @@ def _strides3(t: torch.Tensor):
 
 def make_config(**kw) -> Config:
     cfg = Config()
+    cfg.tau16 = cfg.tau4 = float("inf")
     for k, v in kw.items():
-        setattr(cfg, k, int(v))
+        setattr(cfg, k, float(v) if k in ("tau16", "tau4") else int(v))
     return cfg
 
 

@@ -33,10 +33,12 @@ int compute_layout(const mixkvq_config& c, Layout* out) {
   if (c.T_max < c.R || c.T_max % c.R != 0) return MIXKVQ_EINVAL;
   if (c.flush_mode < 0 || c.flush_mode > 1 || c.score_mode < 0 || c.score_mode > 1) return MIXKVQ_EINVAL;
   if ((int64_t)c.B * c.Hkv > (1 << 20)) return MIXKVQ_EINVAL;
+  if (c.policy < 0 || c.policy > 1) return MIXKVQ_EINVAL;
+  if (c.policy == 1 && !(c.tau16 >= 0.0 && c.tau4 >= 0.0)) return MIXKVQ_EINVAL;   // also rejects NaN
   Layout l;
   memset(&l, 0, sizeof(l));
   const int ks = c.k4 + c.k16;
-  l.NL = c.D - ks;
+  l.NL = c.policy == 1 ? c.D : c.D - ks;
   l.Wlo = (l.NL + 15) / 16;
   l.NLp = 16 * l.Wlo;
   l.NG = c.R / c.Gk;

@@ -31,6 +31,7 @@ decode_split_kernel(CacheView cv, const __half* __restrict__ q, float scale, int
   __shared__ float sM[kMaxG], sL[kMaxG], sAlpha[kMaxG];
   __shared__ unsigned char sLoList[kD];
   __shared__ unsigned char sIsHi[kD];
+  __shared__ int sNLo;                     // 2-bit channels of the staged block
 
   const mixkvq_config& cfg = cv.cfg;
   const Layout& lay = cv.lay;
@@ -61,12 +62,17 @@ decode_split_kernel(CacheView cv, const __half* __restrict__ q, float scale, int
         reinterpret_cast<uint4*>(sRec)[i] = reinterpret_cast<const uint4*>(rec)[i];
       if (tid < kD) sIsHi[tid] = 0;
       __syncthreads();
-      if (tid < ks) sIsHi[sRec[lay.off_idx + tid]] = 1;
+      if (tid < ks && sRec[lay.off_idx + tid] < kD) sIsHi[sRec[lay.off_idx + tid]] = 1;   // skips unused entries
       __syncthreads();
       if (tid < kD && !sIsHi[tid]) {
         int pos = 0;
         for (int e = 0; e < tid; ++e) pos += !sIsHi[e];
         sLoList[pos] = (unsigned char)tid;
+      }
+      if (tid == 0) {
+        int c = 0;
+        for (int e = 0; e < kD; ++e) c += !sIsHi[e];
+        sNLo = c;
       }
       __syncthreads();
     }
@@ -87,7 +93,7 @@ decode_split_kernel(CacheView cv, const __half* __restrict__ q, float scale, int
         const unsigned* klo = reinterpret_cast<const unsigned*>(sRec + lay.off_klo) + t * lay.Wlo;
         const __half* ls = reinterpret_cast<const __half*>(sRec + lay.off_klo_s) + grp * lay.NLp;
         const __half* lz = reinterpret_cast<const __half*>(sRec + lay.off_klo_z) + grp * lay.NLp;
-        for (int jj = 0; jj < lay.NL; ++jj) {
+        for (int jj = 0; jj < sNLo; ++jj) {
           const unsigned c = (klo[jj >> 4] >> (16 * (jj & 1) + 2 * ((jj & 15) >> 1))) & 3u;
           const float kv = (float)c * __half2float(ls[jj]) + __half2float(lz[jj]);
           const int d = sLoList[jj];
@@ -101,6 +107,7 @@ decode_split_kernel(CacheView cv, const __half* __restrict__ q, float scale, int
           const unsigned c = (k4w[jj >> 3] >> (16 * (jj & 1) + 4 * ((jj & 7) >> 1))) & 15u;
           const float kv = (float)c * __half2float(hs[jj]) + __half2float(hz[jj]);
           const int d = sRec[lay.off_idx + k16 + jj];
+          if (d >= kD) break;      // the tier ends at the first unused entry
 #pragma unroll
           for (int i = 0; i < 4; ++i) s[i] += sQ[(h0 + i) & 7][d] * kv;
         }
@@ -108,6 +115,7 @@ decode_split_kernel(CacheView cv, const __half* __restrict__ q, float scale, int
         for (int jj = 0; jj < k16; ++jj) {
           const float kv = __half2float(k16p[jj]);
           const int d = sRec[lay.off_idx + jj];
+          if (d >= kD) break;
 #pragma unroll
           for (int i = 0; i < 4; ++i) s[i] += sQ[(h0 + i) & 7][d] * kv;
         }

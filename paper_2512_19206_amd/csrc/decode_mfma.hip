@@ -126,9 +126,11 @@ __device__ __forceinline__ void wave_lds_handoff() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int K4, int K16>
+// THR = 1: threshold policy.  K4 and K16 are capacities, a block's channel lists may hold unused entries
+// (MIXKVQ_NO_CHANNEL) and the 2-bit planes have room for every channel.
+template <int K4, int K16, int THR>
 struct Tiers {
-  static constexpr int NL = kD - K4 - K16;
+  static constexpr int NL = THR ? kD : kD - K4 - K16;
   static constexpr int Wlo = (NL + 15) / 16;   // 2-bit words per token
   static constexpr int NLp = Wlo * 16;
   static constexpr int NU = (Wlo + 3) / 4;     // word rounds: lane group kg takes 2-bit word 4u + kg in round u
@@ -233,11 +235,11 @@ decode_merge_pair_kernel(CacheView cv, const float* __restrict__ part, int n_par
   }
 }
 
-template <int K4, int K16, int NVG, int NKL, int RG>
+template <int K4, int K16, int NVG, int NKL, int RG, int THR>
 __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __restrict__ q, float scale_log2e,
                                           int n_blocks, int n_res, int n_splits, float* __restrict__ part,
                                           int accumulate_q, const NewToken& nt, unsigned char* smem) {
-  using T = Tiers<K4, K16>;
+  using T = Tiers<K4, K16, THR>;
   constexpr int NU = T::NU;
   // scalars of the by-value view (kept in SGPRs; no references into the kernel argument)
   // RG = 1: R = Gk = 128 known at compile time (one straight-line body per block record)
@@ -373,16 +375,18 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 #define MIXKVQ_REBUILD_Q(SELW)                                                                                 \
   {                                                                                                            \
     unsigned char* sIdx = sLo + kD;                                                                            \
+    int n_lo_ = kD;                        /* 2-bit channels of the block (wave-uniform) */                    \
     if (K4 + K16 > 0) {                                                                                        \
       if (lane == 0) {                                                                                         \
         _Pragma("unroll") for (int i = 0; i < kSelWords; ++i) reinterpret_cast<unsigned*>(sIdx)[i] = SELW[i];  \
       }                                                                                                        \
       unsigned long long m0 = 0, m1 = 0; /* bitmap of salient channels (scalar arithmetic) */                  \
       _Pragma("unroll") for (int i = 0; i < K4 + K16; ++i) {                                                   \
-        const unsigned ch = (SELW[i >> 2] >> (8 * (i & 3))) & 0xffu;                                           \
+        const unsigned ch = (SELW[i >> 2] >> (8 * (i & 3))) & 0xffu;   /* >= 128: an unused entry */           \
         m0 |= ch < 64u ? 1ull << (ch & 63u) : 0ull;                                                            \
-        m1 |= ch < 64u ? 0ull : 1ull << (ch & 63u);                                                            \
+        m1 |= (ch >= 64u && ch < 128u) ? 1ull << (ch & 63u) : 0ull;                                            \
       }                                                                                                        \
+      n_lo_ = kD - __popcll(m0) - __popcll(m1);                                                                \
       /* lanes cover channels lane and lane + 64 */                                                            \
       if (!((m0 >> lane) & 1)) sLo[lane - __popcll(m0 & ((1ull << lane) - 1))] = (unsigned char)lane;          \
       if (!((m1 >> lane) & 1))                                                                                 \
@@ -395,7 +399,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
     _Pragma("unroll") for (int cch = 0; cch < 3; ++cch) {                                                      \
       const int slot = 64 * cch + lane;                                                                        \
       const unsigned ch = cch < 2 ? sLo[slot & 127] : sIdx[lane & 31];                                         \
-      const bool valid = cch < 2 ? slot < T::NL : lane < K4 + K16;                                             \
+      const bool valid = cch < 2 ? slot < n_lo_ : (lane < K4 + K16 && ch < (unsigned)kD);                      \
       u32x4 hv = *reinterpret_cast<const u32x4*>(sQt + (ch & 127u) * 8);                                       \
       if (!valid) hv = u32x4{0u, 0u, 0u, 0u};                                                                  \
       if (cch < 2 || lane < 32) {                                                                              \
@@ -907,20 +911,20 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 
 // One launch per decode step: the workgroups (pair, split) share the pair's block records and its
 // residual window.
-template <int K4, int K16, int NVG, int NKL, int RG>
+template <int K4, int K16, int NVG, int NKL, int RG, int THR>
 __global__ void __launch_bounds__(kMfmaThreads, 2)
 decode_fused_kernel(CacheView cv, const __half* __restrict__ q, float scale, int n_blocks, int n_res, int n_splits,
                     float* __restrict__ part, int accumulate_q, NewToken nt) {
   extern __shared__ __align__(16) unsigned char smem[];
-  mfma_part<K4, K16, NVG, NKL, RG>(cv, q, scale * 1.4426950408889634f, n_blocks, n_res, n_splits, part, accumulate_q, nt,
+  mfma_part<K4, K16, NVG, NKL, RG, THR>(cv, q, scale * 1.4426950408889634f, n_blocks, n_res, n_splits, part, accumulate_q, nt,
                                    smem);
 }
 
-template <int K4, int K16, int NVG, int NKL, int RG>
+template <int K4, int K16, int NVG, int NKL, int RG, int THR>
 static hipError_t launch_one(const CacheView& v, const __half* q, float scale, int n_blocks, int n_res, int n_splits,
                              float* part, __half* out, float* lse, int accumulate_q, NewToken nt,
                              hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
-  auto kern = decode_fused_kernel<K4, K16, NVG, NKL, RG>;
+  auto kern = decode_fused_kernel<K4, K16, NVG, NKL, RG, THR>;
   const size_t lds = kHdrLds + (size_t)kWaves * kWaveLds;
   static bool attr_set = false;
   if (!attr_set) {
@@ -946,24 +950,30 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
   const int nkl = (v.lay.off_v / 16 + 63) / 64;
   hipError_t e = hipErrorInvalidValue;
   bool ok = true;
-#define MIXKVQ_CASE(K4_, K16_, NVG_, NKL_, RG_)                                                                     \
-  if (c.k4 == K4_ && c.k16 == K16_ && nvg == NVG_ && nkl <= NKL_ && (RG_ == 0 || (c.R == 128 && c.Gk == 128)))     \
-    e = launch_one<K4_, K16_, NVG_, NKL_, RG_>(v, q, scale, n_blocks, n_res, n_splits, part, out, lse,   \
-                                               accumulate_q, nt, s, ev_start, ev_stop);                            \
+#define MIXKVQ_CASE(K4_, K16_, NVG_, NKL_, RG_, THR_)                                                               \
+  if (c.k4 == K4_ && c.k16 == K16_ && nvg == NVG_ && nkl <= NKL_ && c.policy == THR_ &&                             \
+      (RG_ == 0 || (c.R == 128 && c.Gk == 128)))                                                                    \
+    e = launch_one<K4_, K16_, NVG_, NKL_, RG_, THR_>(v, q, scale, n_blocks, n_res, n_splits, part, out, lse,        \
+                                                     accumulate_q, nt, s, ev_start, ev_stop);                       \
   else
-  MIXKVQ_CASE(16, 0, 1, 6, 1)
-  MIXKVQ_CASE(0, 12, 1, 8, 1)
-  MIXKVQ_CASE(8, 0, 1, 6, 1)
-  MIXKVQ_CASE(16, 0, 1, 6, 0)
-  MIXKVQ_CASE(0, 12, 1, 8, 0)
-  MIXKVQ_CASE(0, 0, 1, 6, 0)
-  MIXKVQ_CASE(8, 0, 1, 6, 0)
-  MIXKVQ_CASE(24, 0, 1, 6, 0)
-  MIXKVQ_CASE(32, 0, 1, 6, 0)
-  MIXKVQ_CASE(16, 0, 2, 6, 0)
-  MIXKVQ_CASE(0, 12, 2, 8, 0)
-  MIXKVQ_CASE(8, 4, 1, 8, 0)
-  MIXKVQ_CASE(0, 32, 1, 8, 0)
+  MIXKVQ_CASE(16, 0, 1, 6, 1, 0)
+  MIXKVQ_CASE(0, 12, 1, 8, 1, 0)
+  MIXKVQ_CASE(8, 0, 1, 6, 1, 0)
+  MIXKVQ_CASE(16, 0, 1, 6, 0, 0)
+  MIXKVQ_CASE(0, 12, 1, 8, 0, 0)
+  MIXKVQ_CASE(0, 0, 1, 6, 0, 0)
+  MIXKVQ_CASE(8, 0, 1, 6, 0, 0)
+  MIXKVQ_CASE(24, 0, 1, 6, 0, 0)
+  MIXKVQ_CASE(32, 0, 1, 6, 0, 0)
+  MIXKVQ_CASE(16, 0, 2, 6, 0, 0)
+  MIXKVQ_CASE(0, 12, 2, 8, 0, 0)
+  MIXKVQ_CASE(8, 4, 1, 8, 0, 0)
+  MIXKVQ_CASE(0, 32, 1, 8, 0, 0)
+  // threshold policy: the capacities of the two side tiers
+  MIXKVQ_CASE(16, 8, 1, 8, 0, 1)
+  MIXKVQ_CASE(16, 0, 1, 6, 0, 1)
+  MIXKVQ_CASE(0, 12, 1, 8, 0, 1)
+  MIXKVQ_CASE(8, 4, 1, 8, 0, 1)
   ok = false;
 #undef MIXKVQ_CASE
   if (!ok) return false;

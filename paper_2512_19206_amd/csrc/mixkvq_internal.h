@@ -69,4 +69,25 @@ __device__ __forceinline__ long long fix24(unsigned short h) {
   return (h & 0x8000u) ? -v : v;
 }
 
+// Threshold of Section 4.2 in the units of the integer score sum|q|_d * range_d (units 2^-48):
+// A_d = (sum|q|_d 2^-24 / count) * (range_d 2^-24 / 3) > tau  <=>  score_d > tau * 3 * 2^48 * count, the right-hand
+// side formed in binary64 from left to right; with the error-only score, range_d > tau * 3 * 2^24.
+__device__ __forceinline__ double score_threshold(double tau, unsigned long long count, int score_mode) {
+  if (score_mode) return (tau * 3.0) * 16777216.0;
+  return ((tau * 3.0) * 281474976710656.0) * (double)count;
+}
+
+// Sizes of the fp16 and the 4-bit tier of one block: the budgets themselves, or under the threshold policy the
+// number of channels that pass (c16 above tau16, c_any above the lower of the two thresholds) cut to the capacities.
+__device__ __forceinline__ void tier_sizes(const mixkvq_config& cfg, int c16, int c_any, int* n16, int* n4) {
+  if (cfg.policy == 1) {
+    *n16 = c16 < cfg.k16 ? c16 : cfg.k16;
+    const int rest = c_any - *n16;
+    *n4 = rest < cfg.k4 ? rest : cfg.k4;
+  } else {
+    *n16 = cfg.k16;
+    *n4 = cfg.k4;
+  }
+}
+
 }  // namespace mixkvq

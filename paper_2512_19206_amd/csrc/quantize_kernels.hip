@@ -72,6 +72,7 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
   __shared__ unsigned char sHiList[kD];    // fp16 tier then 4-bit tier
   __shared__ float sS[8 * kD], sZ[8 * kD]; // [group][channel] scale / zero-point of the channel's tier
   __shared__ unsigned sKmax[8];            // per group: largest stored scale (fp16 bits; scales are >= 0)
+  __shared__ int sN[3];                    // channels per tier
 
   const mixkvq_config& cfg = cv.cfg;
   const Layout& lay = cv.lay;
@@ -81,7 +82,9 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
 
   // zero the record's padding by clearing the small planes that may have holes
   // (index bytes and the tails of the scale/zero planes); full planes are overwritten below.
-  for (int i = tid; i < lay.off_klo / 4; i += kFlushThreads) reinterpret_cast<unsigned*>(rec)[i] = 0u;
+  // (under the threshold policy the channel lists start out as "no channel")
+  for (int i = tid; i < lay.off_klo / 4; i += kFlushThreads)
+    reinterpret_cast<unsigned*>(rec)[i] = (cfg.policy == 1 && i < ks / 4) ? 0xffffffffu : 0u;
 
   load_tile(sT, cv.res_k, k_new, st, p, cfg.Hkv, R, r0, f * R);
   if (tid < 8) sKmax[tid] = 0u;
@@ -103,19 +106,33 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
     }
     __syncthreads();
     if (tid < kD) {
-      int rank = 0;
+      const double thr16 = cfg.policy == 1 ? score_threshold(cfg.tau16, cv.qcnt[p], cfg.score_mode) : 0.0;
+      const double thr4 = cfg.policy == 1 ? score_threshold(cfg.tau4, cv.qcnt[p], cfg.score_mode) : 0.0;
+      int rank = 0, c16 = 0, c_any = 0;
       for (int e = 0; e < kD; ++e) {
         double o = sA[e];
         rank += (o > A) || (o == A && e < tid);
+        c16 += o > thr16;
+        c_any += (o > thr16) || (o > thr4);
       }
-      sTier[tid] = rank < k16 ? 2 : (rank < ks ? 1 : 0);
+      int n16, n4;
+      tier_sizes(cfg, c16, c_any, &n16, &n4);
+      sTier[tid] = rank < n16 ? 2 : (rank < n16 + n4 ? 1 : 0);
     }
   } else {
     if (tid < kD) sTier[tid] = 0;
     __syncthreads();
-    if (tid < ks) sTier[sel_in[(size_t)p * ks + tid]] = tid < k16 ? 2 : 1;
+    if (tid < ks) {
+      const unsigned ch = sel_in[(size_t)p * ks + tid];
+      if (ch < (unsigned)kD) sTier[ch] = tid < k16 ? 2 : 1;     // MIXKVQ_NO_CHANNEL: an unused entry
+    }
   }
   __syncthreads();
+  if (tid < 3) {
+    int c = 0;
+    for (int e = 0; e < kD; ++e) c += sTier[e] == tid;
+    sN[tid] = c;
+  }
   if (tid < kD) {
     const unsigned char tier = sTier[tid];
     int pos = 0;
@@ -165,7 +182,7 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int jj = wd * 16 + i;
-      if (jj < lay.NL) {
+      if (jj < sN[0]) {
         const int d = sLoList[jj];
         w |= encode(__half2float(sT[t * kRowStride + d]), sZ[grp * kD + d], sS[grp * kD + d], 3.f) << (16 * (i & 1) + 2 * (i >> 1));
       }
@@ -178,15 +195,17 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
     unsigned w = 0;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const int d = sHiList[k16 + wd * 8 + i];
-      w |= encode(__half2float(sT[t * kRowStride + d]), sZ[grp * kD + d], sS[grp * kD + d], 15.f) << (16 * (i & 1) + 4 * (i >> 1));
+      if (wd * 8 + i < sN[1]) {
+        const int d = sHiList[k16 + wd * 8 + i];
+        w |= encode(__half2float(sT[t * kRowStride + d]), sZ[grp * kD + d], sS[grp * kD + d], 15.f) << (16 * (i & 1) + 4 * (i >> 1));
+      }
     }
     reinterpret_cast<unsigned*>(rec + lay.off_k4)[it] = w;
   }
   // ---- fp16 tier: [token][k16] ------------------------------------------
   for (int it = tid; it < R * k16; it += kFlushThreads) {
     const int t = it / k16, i = it % k16;
-    reinterpret_cast<__half*>(rec + lay.off_k16)[it] = sT[t * kRowStride + sHiList[i]];
+    reinterpret_cast<__half*>(rec + lay.off_k16)[it] = i < sN[2] ? sT[t * kRowStride + sHiList[i]] : __ushort_as_half(0);
   }
   __syncthreads();
 
@@ -302,14 +321,14 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   __shared__ unsigned sChunk[2][kMaxR / 16][kD / 2];   // (min, max) keys per 16-token chunk and channel pair
   unsigned (*sCLo)[kD / 2] = sChunk[0];
   unsigned (*sCHi)[kD / 2] = sChunk[1];
-  __shared__ int sCnt[3];                  // channels per tier in wavefront 0
+  __shared__ int sCnt[6];                  // channels per tier in wavefront 0, then in wavefront 1
 
   const int R = cv.cfg.R, Gk = cv.cfg.Gk, Gv = cv.cfg.Gv, k4 = cv.cfg.k4, k16 = cv.cfg.k16, ks = k4 + k16;
-  const int Hkv = cv.cfg.Hkv, score_mode = cv.cfg.score_mode;
+  const int Hkv = cv.cfg.Hkv, score_mode = cv.cfg.score_mode, policy = cv.cfg.policy;
   const int rec_bytes = cv.lay.rec_bytes, off_idx = cv.lay.off_idx, off_kmax = cv.lay.off_kmax,
             off_klo_s = cv.lay.off_klo_s, off_klo_z = cv.lay.off_klo_z, off_k4_s = cv.lay.off_k4_s,
             off_k4_z = cv.lay.off_k4_z, off_klo = cv.lay.off_klo, off_k4 = cv.lay.off_k4, off_k16 = cv.lay.off_k16,
-            off_v = cv.lay.off_v, off_v_s = cv.lay.off_v_s, off_v_z = cv.lay.off_v_z, NL = cv.lay.NL, NLp = cv.lay.NLp,
+            off_v = cv.lay.off_v, off_v_s = cv.lay.off_v_s, off_v_z = cv.lay.off_v_z, NLp = cv.lay.NLp,
             Wlo = cv.lay.Wlo, W4 = cv.lay.W4, NG = cv.lay.NG, NVG = cv.lay.NVG;
   const int p = blockIdx.x, f = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   uint8_t* rec = cv.blocks + ((size_t)p * cv.NB + first_block + f) * rec_bytes;
@@ -356,7 +375,9 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
     }
   }
   // zero the small planes of the record (index bytes, tails of the scale/zero planes)
-  for (int i = tid; i < off_klo / 4; i += kFlushThreads) reinterpret_cast<unsigned*>(rec)[i] = 0u;
+  // (under the threshold policy the channel lists start out as "no channel")
+  for (int i = tid; i < off_klo / 4; i += kFlushThreads)
+    reinterpret_cast<unsigned*>(rec)[i] = (policy == 1 && i < ks / 4) ? 0xffffffffu : 0u;
   if (tid < 8) sKmax[tid] = 0u;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
@@ -404,26 +425,44 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
     __syncthreads();
     if (tid < kD) {
       int rank = 0;
-      for (int e = 0; e < kD; ++e) {
-        const double o = sA[e];
-        rank += (o > A) || (o == A && e < tid);
+      if (policy == 1) {
+        const double thr16 = score_threshold(cv.cfg.tau16, cv.qcnt[p], score_mode);
+        const double thr4 = score_threshold(cv.cfg.tau4, cv.qcnt[p], score_mode);
+        int c16 = 0, c_any = 0;
+        for (int e = 0; e < kD; ++e) {
+          const double o = sA[e];
+          rank += (o > A) || (o == A && e < tid);
+          c16 += o > thr16;
+          c_any += (o > thr16) || (o > thr4);
+        }
+        int n16, n4;
+        tier_sizes(cv.cfg, c16, c_any, &n16, &n4);
+        sTier[tid] = rank < n16 ? 2 : (rank < n16 + n4 ? 1 : 0);
+      } else {
+        for (int e = 0; e < kD; ++e) {
+          const double o = sA[e];
+          rank += (o > A) || (o == A && e < tid);
+        }
+        sTier[tid] = rank < k16 ? 2 : (rank < ks ? 1 : 0);
       }
-      sTier[tid] = rank < k16 ? 2 : (rank < ks ? 1 : 0);
     }
   } else {
     if (tid < kD) sTier[tid] = 0;
     __syncthreads();
-    if (tid < ks) sTier[sel_in[(size_t)p * ks + tid]] = tid < k16 ? 2 : 1;
+    if (tid < ks) {
+      const unsigned ch = sel_in[(size_t)p * ks + tid];
+      if (ch < (unsigned)kD) sTier[ch] = tid < k16 ? 2 : 1;     // MIXKVQ_NO_CHANNEL: an unused entry
+    }
   }
   __syncthreads();
   // position of every channel inside its tier: ballots over the two wavefronts that hold the channels
   {
     const int tier = tid < kD ? sTier[tid] : 3;
     const unsigned long long m0 = __ballot(tier == 0), m1 = __ballot(tier == 1), m2 = __ballot(tier == 2);
-    if (tid == 0) {
-      sCnt[0] = __popcll(m0);
-      sCnt[1] = __popcll(m1);
-      sCnt[2] = __popcll(m2);
+    if (lane == 0 && wave < 2) {
+      sCnt[3 * wave] = __popcll(m0);
+      sCnt[3 * wave + 1] = __popcll(m1);
+      sCnt[3 * wave + 2] = __popcll(m2);
     }
     __syncthreads();
     if (tid < kD) {
@@ -439,6 +478,9 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
     }
   }
   __syncthreads();
+
+  // sizes of the tiers of this block (the budgets, or what passed the thresholds)
+  const int n_lo = sCnt[0] + sCnt[3], n_4 = sCnt[1] + sCnt[4], n_16 = sCnt[2] + sCnt[5];
 
   MIXKVQ_FPHASE(3)
   // ---- key group parameters from the chunk extrema ------------------------------------------
@@ -484,7 +526,7 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int jj = 16 * wd + i;
-        doff[i] = jj < NL ? (int)sLoList[jj] : -1;
+        doff[i] = jj < n_lo ? (int)sLoList[jj] : -1;
       }
       for (int grp = 0; grp < NG; ++grp) {
         float rc[16], zp[16];
@@ -530,16 +572,20 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
     bool near = false;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const int d = sHiList[k16 + wd * 8 + i];
-      add_code<4>(hw, i, code_fast<15>(__half2float(sT[t * kRowStride + d]), sZ[grp * kD + d], sR[grp * kD + d], near));
+      const bool used = wd * 8 + i < n_4;                    // an unused entry gets reciprocal 0, i.e. code 0
+      const int d = used ? sHiList[k16 + wd * 8 + i] : 0;
+      add_code<4>(hw, i, code_fast<15>(__half2float(sT[t * kRowStride + d]), sZ[grp * kD + d],
+                                       used ? sR[grp * kD + d] : 0.f, near));
     }
     unsigned w = join_halves(hw);
     if (__any(near)) {     // rare: some quotient sits next to a rounding boundary
       w = 0;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const int d = sHiList[k16 + wd * 8 + i];
-        w |= encode(__half2float(sT[t * kRowStride + d]), sZ[grp * kD + d], sS[grp * kD + d], 15.f) << (16 * (i & 1) + 4 * (i >> 1));
+        const bool used = wd * 8 + i < n_4;
+        const int d = used ? sHiList[k16 + wd * 8 + i] : 0;
+        w |= encode(__half2float(sT[t * kRowStride + d]), sZ[grp * kD + d], used ? sS[grp * kD + d] : 0.f, 15.f)
+             << (16 * (i & 1) + 4 * (i >> 1));
       }
     }
     reinterpret_cast<unsigned*>(rec + off_k4)[it] = w;
@@ -547,7 +593,7 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   // ---- fp16 tier: [token][k16] ------------------------------------------
   for (int i = tid >> 7; i < k16; i += 2) {
     const int t = tid & 127;
-    if (t < R) reinterpret_cast<__half*>(rec + off_k16)[t * k16 + i] = sT[t * kRowStride + sHiList[i]];
+    if (t < R) reinterpret_cast<__half*>(rec + off_k16)[t * k16 + i] = i < n_16 ? sT[t * kRowStride + sHiList[i]] : __ushort_as_half(0);
   }
   __syncthreads();
 

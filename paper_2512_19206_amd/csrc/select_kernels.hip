@@ -206,16 +206,30 @@ __global__ void __launch_bounds__(kD) key_range_unaligned_kernel(const __half* _
 // Eq. 8 + top-k.  One workgroup per (batch, KV head) pair, one thread per channel.
 // rank_d = number of channels that beat d (higher score, or equal score and lower index).
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void rank_and_emit(double A, int d, int k16, int k4, double* sA, unsigned char* sTier,
-                                              uint8_t* out) {
+__global__ void __launch_bounds__(kD) select_topk_kernel(CacheView cv, const long long* __restrict__ mn,
+                                                        const long long* __restrict__ mx, uint8_t* __restrict__ sel) {
+  __shared__ double sA[kD];
+  __shared__ unsigned char sTier[kD];
+  const mixkvq_config& cfg = cv.cfg;
+  const int p = blockIdx.x, d = threadIdx.x, k16 = cfg.k16, ks = cfg.k16 + cfg.k4;
+  const long long rng = mx[(size_t)p * kD + d] - mn[(size_t)p * kD + d];
+  const double A = cfg.score_mode ? (double)rng : (double)cv.qacc[(size_t)p * kD + d] * (double)rng;
+  uint8_t* out = sel + (size_t)p * ks;
+  if (d < ks) out[d] = MIXKVQ_NO_CHANNEL;     // entries no channel claims (threshold policy)
   sA[d] = A;
   __syncthreads();
-  int rank = 0;
+  const double thr16 = cfg.policy == 1 ? score_threshold(cfg.tau16, cv.qcnt[p], cfg.score_mode) : 0.0;
+  const double thr4 = cfg.policy == 1 ? score_threshold(cfg.tau4, cv.qcnt[p], cfg.score_mode) : 0.0;
+  int rank = 0, c16 = 0, c_any = 0;
   for (int e = 0; e < kD; ++e) {
-    double o = sA[e];
+    const double o = sA[e];
     rank += (o > A) || (o == A && e < d);
+    c16 += o > thr16;
+    c_any += (o > thr16) || (o > thr4);
   }
-  unsigned char tier = rank < k16 ? 2 : (rank < k16 + k4 ? 1 : 0);
+  int n16, n4;
+  tier_sizes(cfg, c16, c_any, &n16, &n4);
+  const unsigned char tier = rank < n16 ? 2 : (rank < n16 + n4 ? 1 : 0);
   sTier[d] = tier;
   __syncthreads();
   if (tier) {
@@ -223,18 +237,6 @@ __device__ __forceinline__ void rank_and_emit(double A, int d, int k16, int k4, 
     for (int e = 0; e < d; ++e) pos += sTier[e] == tier;
     out[(tier == 2 ? 0 : k16) + pos] = (uint8_t)d;
   }
-}
-
-__global__ void __launch_bounds__(kD) select_topk_kernel(const unsigned long long* __restrict__ qacc,
-                                                        const long long* __restrict__ mn,
-                                                        const long long* __restrict__ mx, int k16, int k4,
-                                                        int score_mode, uint8_t* __restrict__ sel) {
-  __shared__ double sA[kD];
-  __shared__ unsigned char sTier[kD];
-  const int p = blockIdx.x, d = threadIdx.x;
-  const long long rng = mx[(size_t)p * kD + d] - mn[(size_t)p * kD + d];
-  const double A = score_mode ? (double)rng : (double)qacc[(size_t)p * kD + d] * (double)rng;
-  rank_and_emit(A, d, k16, k4, sA, sTier, sel + (size_t)p * (k16 + k4));
 }
 
 size_t select_workspace_bytes(const mixkvq_config& c) { return (size_t)c.B * c.Hkv * kD * 2 * sizeof(long long); }
@@ -249,7 +251,7 @@ hipError_t launch_select(const CacheView& v, const __half* k, int L, Strides3 ks
     key_range_kernel<<<grid, dim3(kStreamThreads), 0, s>>>(k, L, ks, v.cfg.Hkv, mn, mx);
   else
     key_range_unaligned_kernel<<<grid, dim3(kD), 0, s>>>(k, L, ks, v.cfg.Hkv, mn, mx);
-  select_topk_kernel<<<dim3(v.P), dim3(kD), 0, s>>>(v.qacc, mn, mx, v.cfg.k16, v.cfg.k4, v.cfg.score_mode, sel);
+  select_topk_kernel<<<dim3(v.P), dim3(kD), 0, s>>>(v, mn, mx, sel);
   return hipGetLastError();
 }
 

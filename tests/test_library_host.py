@@ -46,6 +46,8 @@ CONFIGS = [
     dict(B=64, Hq=40, Hkv=8, D=128, T_max=32768, Gk=128, Gv=128, R=128, k4=0, k16=12),
     dict(B=2, Hq=8, Hkv=2, D=128, T_max=256, Gk=16, Gv=16, R=64, k4=8, k16=4),
     dict(B=1, Hq=2, Hkv=2, D=128, T_max=128, Gk=64, Gv=64, R=128, k4=0, k16=0),
+    dict(B=2, Hq=14, Hkv=2, D=128, T_max=512, Gk=128, Gv=128, R=128, k4=16, k16=8, policy=1, tau16=1.44, tau4=0.79),
+    dict(B=1, Hq=5, Hkv=1, D=128, T_max=64, Gk=32, Gv=32, R=32, k4=8, k16=4, policy=1, tau16=0.0, tau4=float("inf")),
 ]
 
 
@@ -73,7 +75,8 @@ def test_buffer_sizes(M, kw):
 @pytest.mark.parametrize("bad", [
     dict(D=64), dict(Hq=3, Hkv=2), dict(Hq=18, Hkv=2), dict(R=24), dict(R=256, T_max=256), dict(Gk=48),
     dict(Gv=24), dict(k4=4), dict(k16=2), dict(k4=64, k16=64), dict(T_max=100), dict(flush_mode=2),
-    dict(score_mode=-1), dict(B=0),
+    dict(score_mode=-1), dict(B=0), dict(policy=2), dict(policy=1, tau16=-0.5, tau4=1.0),
+    dict(policy=1, tau16=1.0, tau4=float("nan")),
 ])
 def test_bad_configurations_are_rejected(M, bad):
     kw = dict(CONFIGS[1])
