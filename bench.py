@@ -33,6 +33,22 @@ LLC_BYTES = 256 << 20   # last-level (Infinity) cache
 MEASURED_TRAFFIC_BYTES = {("cfg1_gqa7b_b8_32k", 32768): 39502.9 * 1024 * 2.0 + 1867.9 * 1024 * 1.0}
 
 
+def algorithmic_bytes_thresholds(w, gc, r):
+    """The same count under the threshold policy, where every block has its own tier sizes: they are read from
+    the channel lists of the cache's block records (entries other than 255)."""
+    lay, k16, ks = gc.layout, w.k16, w.k4 + w.k16
+    nb = gc.state()[0] // w.R
+    idx = gc.block_records()[:, :nb, lay.off_idx:lay.off_idx + ks]
+    n16 = (idx[..., :k16] != 255).sum(dim=-1).double()
+    n4 = (idx[..., k16:] != 255).sum(dim=-1).double()
+    D, R, ng, g = w.D, w.R, w.R // w.Gk, w.Hq // w.Hkv
+    nlo = D - n16 - n4
+    per_block = R * nlo / 4 + ng * nlo * 4 + R * n4 / 2 + ng * n4 * 4 + R * n16 * 2 + (n16 + n4) \
+        + R * D // 4 + R * (D // w.Gv) * 4
+    total = float(per_block.sum()) + w.B * w.Hkv * (r * D * 4 + g * D * 4)
+    return int(total), float(n16.mean()), float(n4.mean())
+
+
 def algorithmic_bytes(w, n_q, r):
     """Bytes one decode step must move, all (batch, KV head) pairs."""
     D, ks, g = w.D, w.k4 + w.k16, w.Hq // w.Hkv
@@ -210,6 +226,12 @@ def main():
     ap.add_argument("--host-batch", type=int, default=2)
     ap.add_argument("--tokens", type=int, default=0, help="override the context length of the configuration")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--per-block-selection", action="store_true",
+                    help="fill the cache with every block scored on its own tokens (as blocks flushed during decoding "
+                         "are) instead of one selection for the whole prompt")
+    ap.add_argument("--thresholds", type=str, default="",
+                    help="'tau16,tau4': the three-tier threshold policy with room for 8 fp16 and 16 four-bit channels per "
+                         "block instead of the configuration's top-k budget (every block scored on its own tokens)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run 4 plain device copies of this many MiB (reference reading for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -230,22 +252,35 @@ def main():
         args.steps, args.warmup = min(args.steps, 8), min(args.warmup, 2)
         bench_prefill(args, w, args.config)
         return
+    policy_kw = {}
+    if args.thresholds:
+        import dataclasses
+        tau16, tau4 = (float(x) for x in args.thresholds.split(","))
+        w = dataclasses.replace(w, name=w.name + "_thresholds", k4=16, k16=8)
+        policy_kw = dict(policy=1, tau16=tau16, tau4=tau4)
+        args.no_cpu_baseline = True
     n_q0 = w.R * (-(-w.T // w.R) - 1)
-    step_bytes = algorithmic_bytes(w, n_q0, w.T - n_q0)
+    step_bytes = algorithmic_bytes(w, n_q0, w.T - n_q0)     # with thresholds: the capacity, refined below
     copies = args.copies or max(1, math.ceil(2 * LLC_BYTES / step_bytes))
     total_steps = args.steps * 3 + args.warmup
     per_copy = -(-total_steps // copies)
     T_max = (w.T + per_copy + 272 + 2 * w.R) // w.R * w.R     # + the single-copy pass on copy 0
 
     dk, dv, dqp, dq, host = build_inputs(args.config, w, args.host_batch)
-    kw = dict(B=w.B, Hq=w.Hq, Hkv=w.Hkv, D=w.D, T_max=T_max, Gk=w.Gk, Gv=w.Gv, R=w.R, k4=w.k4, k16=w.k16)
+    kw = dict(B=w.B, Hq=w.Hq, Hkv=w.Hkv, D=w.D, T_max=T_max, Gk=w.Gk, Gv=w.Gv, R=w.R, k4=w.k4, k16=w.k16, **policy_kw)
     caches = []
     for c in range(copies):
         gc = M.Cache(M.make_config(**kw))
         sel = M.mixkvq_select_channels(gc, dqp, dk)
-        M.mixkvq_quantize_append(gc, dk, dv, sel=sel)
+        M.mixkvq_quantize_append(gc, dk, dv, sel=None if (args.thresholds or args.per_block_selection) else sel)
         caches.append(gc)
     torch.cuda.synchronize()
+    tiers = None
+    if args.thresholds:
+        step_bytes, n16_mean, n4_mean = algorithmic_bytes_thresholds(w, caches[0], w.T - n_q0)
+        tiers = {"tau16": tau16, "tau4": tau4, "mean_fp16_channels_per_block": round(n16_mean, 2),
+                 "mean_4bit_channels_per_block": round(n4_mean, 2),
+                 "key_bits_per_channel": round((16 * n16_mean + 4 * n4_mean + 2 * (w.D - n16_mean - n4_mean)) / w.D, 3)}
     k1 = dk[:, :, :64]   # new tokens are drawn from the prompt tensors (same distribution)
     v1 = dv[:, :, :64]
     out = torch.empty((w.B, w.Hq, w.D), dtype=torch.float16, device="cuda")
@@ -351,6 +386,9 @@ def main():
         "amortised_with_flush_every_R": round((sum(ps_plain) / max(1, len(ps_plain)) * (w.R - 1)
                                                + (sum(ps_flush) / len(ps_flush) if ps_flush else 0.0)) / w.R, 2),
         "note": "each step between its own event pair (adds event overhead to every step)"}
+    if tiers:
+        result["config"]["threshold_policy"] = tiers
+    result["config"]["selection"] = "per block" if (args.thresholds or args.per_block_selection) else "one per prompt"
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args.config, w, host)
     print(json.dumps(result))
