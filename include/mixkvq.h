@@ -85,7 +85,10 @@ typedef struct {
  *                            codes the high one: code i in bits [16(i&1) + 2(i>>1), +2)
  *   k4     u32 [R][k4/8]     8 four-bit codes per word, code i in bits [16(i&1) + 4(i>>1), +4)
  *   k16    f16 [R][k16]      raw values of the fp16 tier
- *   v      u32 [R/16][D]     16 two-bit codes per word along TOKENS for one channel, same bit order as klo
+ *   v      u32 [R/16][D]     16 two-bit codes per word along TOKENS for one channel, same bit order as klo.  Code i of
+ *                            word tg belongs to token 16 tg + i; with v_interleave (set when Gk == 32 and R % 64 == 0)
+ *                            to token 64 (tg/4) + 8 (tg%4) + (i%8) + 32 (i/8): word j of a 64-token span holds the
+ *                            j-th 8 tokens of each of the span's two key groups
  *   v_s    f16 [R][D/Gv]     value scales per (token, channel group);  v_z likewise
  * NL = D-k4-k16 (policy 1: NL = D, room for every channel; the 2-bit channels of a block fill the first
  * D-n16-n4 places), Wlo = ceil(NL/16), NLp = 16*Wlo, NG = R/Gk, NVG = D/Gv, W4 = k4/8. */
@@ -93,6 +96,7 @@ typedef struct {
   int32_t NL, Wlo, NLp, NG, NVG, W4;
   int32_t off_idx, off_kmax, off_klo_s, off_klo_z, off_k4_s, off_k4_z, off_klo, off_k4, off_k16, off_v, off_v_s, off_v_z;
   int32_t rec_bytes;
+  int32_t v_interleave;
 } mixkvq_block_layout_t;
 
 /* Validates cfg and fills the record layout.  HOST pointers.  EINVAL on a bad configuration. */

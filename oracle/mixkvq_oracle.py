@@ -254,6 +254,7 @@ class BlockLayout:
     off_v_s: int
     off_v_z: int
     rec_bytes: int
+    v_interleave: int   # 1: value words take their 16 tokens from both 32-token halves of a 64-token span
 
 
 def block_layout(cfg: OracleConfig) -> BlockLayout:
@@ -271,7 +272,8 @@ def block_layout(cfg: OracleConfig) -> BlockLayout:
                                     odd codes the high one: code i in bits [16(i&1) + 2(i>>1), +2)
       k4     u32 [R][k4/8]          8 four-bit codes per word, code i in bits [16(i&1) + 4(i>>1), +4)
       k16    f16 [R][k16]           raw fp16 values of the fp16 tier
-      v      u32 [R/16][D]          16 two-bit codes per word along TOKENS for one channel, same bit order as klo
+      v      u32 [R/16][D]          16 two-bit codes per word along TOKENS for one channel, same bit order as klo;
+                                    code i of word tg belongs to token value_word_token(tg, i)
       v_s    f16 [R][D/Gv]          value scales per (token, channel group)
       v_z    f16 [R][D/Gv]
     """
@@ -290,7 +292,18 @@ def block_layout(cfg: OracleConfig) -> BlockLayout:
                        ("v", (R // 16) * D * 4), ("v_s", R * NVG * 2), ("v_z", R * NVG * 2)):
         offs["off_" + name] = off
         off += _al16(size)
-    return BlockLayout(NL=NL, Wlo=Wlo, NLp=NLp, NG=NG, NVG=NVG, W4=W4, rec_bytes=off, **offs)
+    return BlockLayout(NL=NL, Wlo=Wlo, NLp=NLp, NG=NG, NVG=NVG, W4=W4, rec_bytes=off,
+                       v_interleave=int(cfg.Gk == 32 and R % 64 == 0), **offs)
+
+
+def value_word_token(tg: int, i: int, interleave: int) -> int:
+    """Token (inside the block) of code i of value word tg.  Plain: the 16 consecutive tokens 16 tg + i.
+    Interleaved (key groups of 32 tokens, R a multiple of 64): word j of a 64-token span holds the j-th 8 tokens
+    of the span's first key group (codes 0..7) and the j-th 8 tokens of its second key group (codes 8..15), so
+    that a reader that walks key group by key group consumes half a word per group."""
+    if not interleave:
+        return 16 * tg + i
+    return 64 * (tg // 4) + 8 * (tg % 4) + (i % 8) + 32 * (i // 8)
 
 
 @dataclasses.dataclass
@@ -362,7 +375,8 @@ def pack_block(cfg: OracleConfig, blk: QuantBlock) -> np.ndarray:
     if cfg.k16:
         put(lay.off_k16, np.pad(blk.k16, ((0, 0), (0, pad16))))
     # values: 16 codes per word along tokens, one word per (token group, channel)
-    vc = blk.v_codes.reshape(cfg.R // 16, 16, cfg.D).transpose(0, 2, 1)  # [tg, d, 16]
+    tok = np.array([[value_word_token(tg, i, lay.v_interleave) for i in range(16)] for tg in range(cfg.R // 16)])
+    vc = blk.v_codes[tok].transpose(0, 2, 1)                              # [tg, d, 16]
     put(lay.off_v, _pack_along_last(vc, 2))
     put(lay.off_v_s, blk.v_s)
     put(lay.off_v_z, blk.v_z)

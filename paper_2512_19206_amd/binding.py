@@ -38,7 +38,7 @@ class BlockLayout(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("NL", "Wlo", "NLp", "NG", "NVG", "W4", "off_idx", "off_kmax", "off_klo_s",
                                          "off_klo_z",
                                          "off_k4_s", "off_k4_z", "off_klo", "off_k4", "off_k16", "off_v", "off_v_s",
-                                         "off_v_z", "rec_bytes")]
+                                         "off_v_z", "rec_bytes", "v_interleave")]
 
 
 class MixKVQError(RuntimeError):

@@ -59,6 +59,7 @@ int compute_layout(const mixkvq_config& c, Layout* out) {
   plane(&l.off_v_s, c.R * l.NVG * 2);
   plane(&l.off_v_z, c.R * l.NVG * 2);
   l.rec_bytes = off;
+  l.v_interleave = (c.Gk == 32 && c.R % 64 == 0) ? 1 : 0;
   if (l.rec_bytes > kMaxRec) return MIXKVQ_EINVAL;
   *out = l;
   return MIXKVQ_OK;

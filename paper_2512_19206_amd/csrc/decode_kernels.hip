@@ -172,7 +172,7 @@ decode_split_kernel(CacheView cv, const __half* __restrict__ q, float scale, int
           const unsigned w = vw[tg * kD + d];
 #pragma unroll
           for (int i16 = 0; i16 < 16; ++i16) {
-            const int t = tg * 16 + i16;
+            const int t = value_word_token(tg, i16, lay.v_interleave);
             const float vv = (float)((w >> (16 * (i16 & 1) + 2 * (i16 >> 1))) & 3u) * __half2float(vs[t * lay.NVG + vg]) +
                              __half2float(vz[t * lay.NVG + vg]);
 #pragma unroll

@@ -235,7 +235,7 @@ decode_merge_pair_kernel(CacheView cv, const float* __restrict__ part, int n_par
   }
 }
 
-template <int K4, int K16, int NVG, int NKL, int RG, int THR>
+template <int K4, int K16, int NVG, int NKL, int RG, int THR, int G32>
 __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __restrict__ q, float scale_log2e,
                                           int n_blocks, int n_res, int n_splits, float* __restrict__ part,
                                           int accumulate_q, const NewToken& nt, unsigned char* smem) {
@@ -243,7 +243,12 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   constexpr int NU = T::NU;
   // scalars of the by-value view (kept in SGPRs; no references into the kernel argument)
   // RG = 1: R = Gk = 128 known at compile time (one straight-line body per block record)
-  const int R = RG ? 128 : cv.cfg.R, Gk = RG ? 128 : cv.cfg.Gk;
+  // G32 = 1: key groups of 32 tokens.  A tile of 16 tokens must lie in ONE key group (its small operand carries
+  // that group's scales), so tiles 0, 1 take the first 32 tokens of a 64-token span and tiles 2, 3 the second 32,
+  // each lane group owning 8 tokens of either half; the value words of such a cache are interleaved to match
+  // (codes 0..7 from the first half, 8..15 from the second: see the record layout).
+  static_assert(!(G32 && RG), "RG fixes Gk = 128");
+  const int R = RG ? 128 : cv.cfg.R, Gk = RG ? 128 : (G32 ? 32 : cv.cfg.Gk);
   const int g = cv.g, Hq = cv.cfg.Hq, Hkv = cv.cfg.Hkv, NB = cv.NB;
   const int rec_bytes = cv.lay.rec_bytes, off_idx = cv.lay.off_idx, off_klo_s = cv.lay.off_klo_s,
             off_klo_z = cv.lay.off_klo_z, off_k4_s = cv.lay.off_k4_s, off_k4_z = cv.lay.off_k4_z,
@@ -285,7 +290,8 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   const bool bookkeeper = (n_blocks + n_sub) % n_gw == gw;
 
   // ---- per-lane constants -------------------------------------------------
-  const int tokbase = 16 * (n >> 2) + 2 * (n & 3);   // token of A-row n in tile (h, x): 64h + tokbase + {0,1,8,9}[x]
+  // token of A-row n in tile (h, x): 64h + tokbase + {0,1,8,9}[x]  (G32: 8 (n/4) + 2 (n%4) + {0,1,32,33}[x])
+  const int tokbase = (G32 ? 8 : 16) * (n >> 2) + 2 * (n & 3);
   const int rec_chunks = rec_bytes >> 4;
   const int nvm = (rec_bytes - off_v_s) >> 4;     // 16-byte chunks of the value scale/zero planes
   // LDS byte offsets of this lane's words in token `tokbase` (clamped to existing words)
@@ -595,6 +601,120 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
     wave_lds_handoff();     // the staging area is the record buffer of the block loop
   }
 
+  // The two pieces of a super-group's key work, written once and placed per key group (see the loop below).
+#define MIXKVQ_GROUP_OPERANDS(GRP)                                                                                     \
+  {                                                                                                                    \
+    /* ---- small key operand of this group: Qs = q * s (head and tail), bias = sum q z ---- */                        \
+    /* The bias runs on the matrix cores too: the zero-points of a step's 32 slots as every row of the */              \
+    /* large operand, q as the small one; all 16 rows of the result hold sum q z of the lane's head. */                \
+    unsigned sp[2 * NU][4], sp4[4];   /* scales of this lane's slots: adjacent pairs, as stored */                     \
+    f32x4 zd4 = {0.f, 0.f, 0.f, 0.f};                                                                                  \
+    _Pragma("unroll")                                                                                                  \
+    for (int u = 0; u < NU; ++u) {                                                                                     \
+      const int c = 4 * u + kg < T::Wlo ? 4 * u + kg : T::Wlo - 1;                                                     \
+      const uint4* ps = reinterpret_cast<const uint4*>(sK + off_klo_s + 2 * ((GRP) * T::NLp + 16 * c));                \
+      const uint4* pz = reinterpret_cast<const uint4*>(sK + off_klo_z + 2 * ((GRP) * T::NLp + 16 * c));                \
+    _Pragma("unroll")                                                                                                  \
+      for (int x = 0; x < 2; ++x) {                                                                                    \
+        const uint4 sv = ps[x], zv = pz[x];                                                                            \
+        const unsigned sw[4] = {sv.x, sv.y, sv.z, sv.w}, zw[4] = {zv.x, zv.y, zv.z, zv.w};                             \
+    _Pragma("unroll")                                                                                                  \
+        for (int e = 0; e < 4; ++e) sp[2 * u + x][e] = sw[e];                                                          \
+        zd4 = mfma(u32x4{zw[0], zw[1], zw[2], zw[3]},                                                                  \
+                   u32x4{qlo[2 * u + x][0], qlo[2 * u + x][1], qlo[2 * u + x][2], qlo[2 * u + x][3]}, zd4);            \
+      }                                                                                                                \
+    }                                                                                                                  \
+    if (K4 > 0) {                                                                                                      \
+      const int w = kg < T::W4 ? kg : 0;                                                                               \
+      const uint4 sv = *reinterpret_cast<const uint4*>(sK + off_k4_s + 2 * ((GRP) * K4 + 8 * w));                      \
+      const uint4 zv = *reinterpret_cast<const uint4*>(sK + off_k4_z + 2 * ((GRP) * K4 + 8 * w));                      \
+      const unsigned sw[4] = {sv.x, sv.y, sv.z, sv.w}, zw[4] = {zv.x, zv.y, zv.z, zv.w};                               \
+    _Pragma("unroll")                                                                                                  \
+      for (int e = 0; e < 4; ++e) sp4[e] = sw[e];                                                                      \
+      zd4 = mfma(u32x4{zw[0], zw[1], zw[2], zw[3]}, u32x4{qh4[0], qh4[1], qh4[2], qh4[3]}, zd4);                       \
+    }                                                                                                                  \
+    zdot = zd4[0];                                                                                                     \
+    /* block exponent: scales are multiplied by 2^e0 so that the largest lands in [2^14, 2^15) (e0 <= 15), */          \
+    /* and by 4^-sc, the position factor of the code they meet in the product */                                       \
+    int efs = (int)(*reinterpret_cast<const unsigned short*>(sK + off_kmax + 2 * (GRP)) >> 10);   /* exponent field */ \
+    if (efs < 1) efs = 1;                                                                                              \
+    efs = __builtin_amdgcn_readfirstlane(efs);                                                                         \
+    const int e0 = 29 - efs < 15 ? 29 - efs : 15;                                                                      \
+    /* every lane forms the head fp16(q s); the lanes of the tail columns then replace it by the exact */              \
+    /* remainder q s - head in ONE divergent region (cheaper than a select per register) */                            \
+    _Pragma("unroll")                                                                                                  \
+    for (int s = 0; s < 2 * NU; ++s)                                                                                   \
+    _Pragma("unroll")                                                                                                  \
+      for (int e = 0; e < 4; ++e) {                                                                                    \
+        const unsigned mult = ((unsigned)(15 + e0 - 2 * sc2(4 * (s & 1) + e)) << 10) * 0x00010001u;                    \
+        sp[s][e] = pk_mul(sp[s][e], mult);                 /* fp16 pair s * 2^(e0 - 2 sc) */                           \
+        Blo[s][e] = pk_mul(qlo[s][e], sp[s][e]);                                                                       \
+      }                                                                                                                \
+    if (K4 > 0) {                                                                                                      \
+    _Pragma("unroll")                                                                                                  \
+      for (int e = 0; e < 4; ++e) {                                                                                    \
+        const unsigned mult = ((unsigned)(15 + e0 - 2 * sc4(e)) << 10) * 0x00010001u;                                  \
+        sp4[e] = pk_mul(sp4[e], mult);                                                                                 \
+        Bh4[e] = pk_mul(qh4[e], sp4[e]);                                                                               \
+      }                                                                                                                \
+    }                                                                                                                  \
+    if (role) {                                                                                                        \
+    _Pragma("unroll")                                                                                                  \
+      for (int s = 0; s < 2 * NU; ++s)                                                                                 \
+    _Pragma("unroll")                                                                                                  \
+        for (int e = 0; e < 4; ++e) Blo[s][e] = pk_fma_neg(qlo[s][e], sp[s][e], Blo[s][e]);                            \
+      if (K4 > 0) {                                                                                                    \
+    _Pragma("unroll")                                                                                                  \
+        for (int e = 0; e < 4; ++e) Bh4[e] = pk_fma_neg(qh4[e], sp4[e], Bh4[e]);                                       \
+      }                                                                                                                \
+    }                                                                                                                  \
+    /* logits in the log2 domain: x2 = S * C + Z * Cz */                                                               \
+    Cz = ldexpf(scale_log2e, Eq);                                                                                      \
+    C = ldexpf(scale_log2e, 24 - e0 + Eq);                                                                             \
+    zc = zdot * Cz;                                                                                                    \
+  }
+#define MIXKVQ_KEY_TILES(X0, X1)                                                                         \
+  {                                                                                                      \
+    _Pragma("unroll")                                                                                    \
+    for (int x = (X0); x < (X1); ++x) {                                                                  \
+      const int tk = 64 * hsg + offx[x];                                                                 \
+    _Pragma("unroll")                                                                                    \
+      for (int u = 0; u < NU; ++u)                                                                       \
+        wlo[u][x] = *reinterpret_cast<const unsigned*>(sK + lo_word_off[u] + 4 * tk * T::Wlo);           \
+      if (K4 > 0) wh4[x] = *reinterpret_cast<const unsigned*>(sK + h4_word_off + 4 * tk * T::W4);        \
+    }                                                                                                    \
+    _Pragma("unroll")                                                                                    \
+    for (int u = 0; u < NU; ++u) {                                                                       \
+      u32x4 a0[4], a1[4];                                                                                \
+    _Pragma("unroll")                                                                                    \
+      for (int x = (X0); x < (X1); ++x) unpack2(wlo[u][x], a0[x], a1[x]);                                \
+    _Pragma("unroll")                                                                                    \
+      for (int x = (X0); x < (X1); ++x) S[x] = mfma(a0[x], Blo[2 * u], S[x]);                            \
+    _Pragma("unroll")                                                                                    \
+      for (int x = (X0); x < (X1); ++x) S[x] = mfma(a1[x], Blo[2 * u + 1], S[x]);                        \
+    }                                                                                                    \
+    if (K4 > 0) {                                                                                        \
+    _Pragma("unroll")                                                                                    \
+      for (int x = (X0); x < (X1); ++x) S[x] = mfma(unpack4(wh4[x]), Bh4, S[x]);                         \
+    }                                                                                                    \
+    if (K16 > 0) {                                                                                       \
+      const u32x4 bq = {q16[0], q16[1], q16[2], q16[3]};                                                 \
+    _Pragma("unroll")                                                                                    \
+      for (int x = (X0); x < (X1); ++x) {                                                                \
+        const unsigned char* src = sK + k16_off + 2 * (64 * hsg + offx[x]) * K16;                        \
+        const uint2 v0 = *reinterpret_cast<const uint2*>(src);                                           \
+        const uint2 v1 = *reinterpret_cast<const uint2*>(src + 8);                                       \
+        /* entries beyond the tier are cleared: they belong to the next token's row or the next plane */ \
+        u32x4 a;                                                                                         \
+        a[0] = 8 * kg < K16 ? v0.x : 0u;                                                                 \
+        a[1] = 8 * kg + 2 < K16 ? v0.y : 0u;                                                             \
+        a[2] = 8 * kg + 4 < K16 ? v1.x : 0u;                                                             \
+        a[3] = 8 * kg + 6 < K16 ? v1.y : 0u;                                                             \
+        S16[x] = mfma(a, bq, f32x4{zdot, zdot, zdot, zdot});                                             \
+      }                                                                                                  \
+    }                                                                                                    \
+  }
+
   MIXKVQ_PHASE(2)
   [[maybe_unused]] int phase_i = 3;
   for (; blk < blk_hi; blk += blk_step) {
@@ -624,122 +744,27 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 #pragma unroll
     for (int hsg = 0; hsg < 2; ++hsg) {       // super-groups of 64 tokens
       if (64 * hsg < R) {
-        if ((64 * hsg) % Gk == 0) {
-          const int grp = (64 * hsg) / Gk;
-          // ---- small key operand of this group: Qs = q * s (head and tail), bias = sum q z ----
-          // The bias runs on the matrix cores too: the zero-points of a step's 32 slots as every row of the
-          // large operand, q as the small one; all 16 rows of the result hold sum q z of the lane's head.
-          unsigned sp[2 * NU][4], sp4[4];   // scales of this lane's slots: adjacent pairs, as stored
-          f32x4 zd4 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int u = 0; u < NU; ++u) {
-            const int c = 4 * u + kg < T::Wlo ? 4 * u + kg : T::Wlo - 1;
-            const uint4* ps = reinterpret_cast<const uint4*>(sK + off_klo_s + 2 * (grp * T::NLp + 16 * c));
-            const uint4* pz = reinterpret_cast<const uint4*>(sK + off_klo_z + 2 * (grp * T::NLp + 16 * c));
-#pragma unroll
-            for (int x = 0; x < 2; ++x) {
-              const uint4 sv = ps[x], zv = pz[x];
-              const unsigned sw[4] = {sv.x, sv.y, sv.z, sv.w}, zw[4] = {zv.x, zv.y, zv.z, zv.w};
-#pragma unroll
-              for (int e = 0; e < 4; ++e) sp[2 * u + x][e] = sw[e];
-              zd4 = mfma(u32x4{zw[0], zw[1], zw[2], zw[3]},
-                         u32x4{qlo[2 * u + x][0], qlo[2 * u + x][1], qlo[2 * u + x][2], qlo[2 * u + x][3]}, zd4);
-            }
-          }
-          if (K4 > 0) {
-            const int w = kg < T::W4 ? kg : 0;
-            const uint4 sv = *reinterpret_cast<const uint4*>(sK + off_k4_s + 2 * (grp * K4 + 8 * w));
-            const uint4 zv = *reinterpret_cast<const uint4*>(sK + off_k4_z + 2 * (grp * K4 + 8 * w));
-            const unsigned sw[4] = {sv.x, sv.y, sv.z, sv.w}, zw[4] = {zv.x, zv.y, zv.z, zv.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) sp4[e] = sw[e];
-            zd4 = mfma(u32x4{zw[0], zw[1], zw[2], zw[3]}, u32x4{qh4[0], qh4[1], qh4[2], qh4[3]}, zd4);
-          }
-          zdot = zd4[0];
-          // block exponent: scales are multiplied by 2^e0 so that the largest lands in [2^14, 2^15) (e0 <= 15),
-          // and by 4^-sc, the position factor of the code they meet in the product
-          int efs = (int)(*reinterpret_cast<const unsigned short*>(sK + off_kmax + 2 * grp) >> 10);   // exponent field
-          if (efs < 1) efs = 1;
-          efs = __builtin_amdgcn_readfirstlane(efs);
-          const int e0 = 29 - efs < 15 ? 29 - efs : 15;
-          // every lane forms the head fp16(q s); the lanes of the tail columns then replace it by the exact
-          // remainder q s - head in ONE divergent region (cheaper than a select per register)
-#pragma unroll
-          for (int s = 0; s < 2 * NU; ++s)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const unsigned mult = ((unsigned)(15 + e0 - 2 * sc2(4 * (s & 1) + e)) << 10) * 0x00010001u;
-              sp[s][e] = pk_mul(sp[s][e], mult);                 // fp16 pair s * 2^(e0 - 2 sc)
-              Blo[s][e] = pk_mul(qlo[s][e], sp[s][e]);
-            }
-          if (K4 > 0) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const unsigned mult = ((unsigned)(15 + e0 - 2 * sc4(e)) << 10) * 0x00010001u;
-              sp4[e] = pk_mul(sp4[e], mult);
-              Bh4[e] = pk_mul(qh4[e], sp4[e]);
-            }
-          }
-          if (role) {
-#pragma unroll
-            for (int s = 0; s < 2 * NU; ++s)
-#pragma unroll
-              for (int e = 0; e < 4; ++e) Blo[s][e] = pk_fma_neg(qlo[s][e], sp[s][e], Blo[s][e]);
-            if (K4 > 0) {
-#pragma unroll
-              for (int e = 0; e < 4; ++e) Bh4[e] = pk_fma_neg(qh4[e], sp4[e], Bh4[e]);
-            }
-          }
-          // logits in the log2 domain: x2 = S * C + Z * Cz
-          Cz = ldexpf(scale_log2e, Eq);
-          C = ldexpf(scale_log2e, 24 - e0 + Eq);
-          zc = zdot * Cz;
-        }
-
-        // ---- S^T tiles: tile x holds tokens 64*hsg + 16*(row/4) + 2*(row%4) + {0,1,8,9}[x] ----
-        constexpr int offx[4] = {0, 1, 8, 9};
+        // ---- S^T tiles: tile x holds tokens 64*hsg + tokbase(row) + offx[x] ----
+        constexpr int offx[4] = {0, 1, G32 ? 32 : 8, G32 ? 33 : 9};
         unsigned wlo[NU][4], wh4[4];
-#pragma unroll
-        for (int x = 0; x < 4; ++x) {
-          const int tk = 64 * hsg + offx[x];
-#pragma unroll
-          for (int u = 0; u < NU; ++u)
-            wlo[u][x] = *reinterpret_cast<const unsigned*>(sK + lo_word_off[u] + 4 * tk * T::Wlo);
-          if (K4 > 0) wh4[x] = *reinterpret_cast<const unsigned*>(sK + h4_word_off + 4 * tk * T::W4);
-        }
-        f32x4 S[4];
+        f32x4 S[4], S16[4];
 #pragma unroll
         for (int x = 0; x < 4; ++x) S[x] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int u = 0; u < NU; ++u) {
-          u32x4 a0[4], a1[4];
-#pragma unroll
-          for (int x = 0; x < 4; ++x) unpack2(wlo[u][x], a0[x], a1[x]);
-#pragma unroll
-          for (int x = 0; x < 4; ++x) S[x] = mfma(a0[x], Blo[2 * u], S[x]);
-#pragma unroll
-          for (int x = 0; x < 4; ++x) S[x] = mfma(a1[x], Blo[2 * u + 1], S[x]);
-        }
-        if (K4 > 0) {
-#pragma unroll
-          for (int x = 0; x < 4; ++x) S[x] = mfma(unpack4(wh4[x]), Bh4, S[x]);
-        }
-        f32x4 S16[4];
-        if (K16 > 0) {
-          const u32x4 bq = {q16[0], q16[1], q16[2], q16[3]};
-#pragma unroll
-          for (int x = 0; x < 4; ++x) {
-            const unsigned char* src = sK + k16_off + 2 * (64 * hsg + offx[x]) * K16;
-            const uint2 v0 = *reinterpret_cast<const uint2*>(src);
-            const uint2 v1 = *reinterpret_cast<const uint2*>(src + 8);
-            // entries beyond the tier are cleared: they belong to the next token's row or the next plane
-            u32x4 a;
-            a[0] = 8 * kg < K16 ? v0.x : 0u;
-            a[1] = 8 * kg + 2 < K16 ? v0.y : 0u;
-            a[2] = 8 * kg + 4 < K16 ? v1.x : 0u;
-            a[3] = 8 * kg + 6 < K16 ? v1.y : 0u;
-            S16[x] = mfma(a, bq, f32x4{zdot, zdot, zdot, zdot});
-          }
+        float Cx = 0.f, zcx = 0.f;      // logit constants of this lane's tiles
+        if (G32) {
+          // two key groups per super-group: tiles 0, 1 with the first group's operands, tiles 2, 3 with the second's
+          MIXKVQ_GROUP_OPERANDS(2 * hsg)
+          MIXKVQ_KEY_TILES(0, 2)
+          const float C0 = C, zc0 = zc;
+          MIXKVQ_GROUP_OPERANDS(2 * hsg + 1)
+          MIXKVQ_KEY_TILES(2, 4)
+          Cx = role ? C : C0;            // lanes 0..7 of a row keep tiles 0, 1; lanes 8..15 tiles 2, 3
+          zcx = role ? zc : zc0;
+        } else {
+          if ((64 * hsg) % Gk == 0) MIXKVQ_GROUP_OPERANDS((64 * hsg) / Gk)
+          MIXKVQ_KEY_TILES(0, 4)
+          Cx = C;
+          zcx = zc;
         }
 
         // ---- logits.  Only columns 0..7 carry heads, so two tiles share one register: lanes 0..7 of a
@@ -752,11 +777,11 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
           const float c1 = S[1][i] + row_ror8(S[1][i]), c3 = S[3][i] + row_ror8(S[3][i]);
           const float sa = role ? c2 : c0, sb = role ? c3 : c1;
           if (K16 > 0) {
-            xa[i] = fmaf(sa, C, (role ? S16[2][i] : S16[0][i]) * Cz);
-            xb[i] = fmaf(sb, C, (role ? S16[3][i] : S16[1][i]) * Cz);
+            xa[i] = fmaf(sa, Cx, (role ? S16[2][i] : S16[0][i]) * Cz);
+            xb[i] = fmaf(sb, Cx, (role ? S16[3][i] : S16[1][i]) * Cz);
           } else {
-            xa[i] = fmaf(sa, C, zc);
-            xb[i] = fmaf(sb, C, zc);
+            xa[i] = fmaf(sa, Cx, zcx);
+            xb[i] = fmaf(sb, Cx, zcx);
           }
           mx = fmaxf(mx, fmaxf(xa[i], xb[i]));
         }
@@ -789,11 +814,11 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         // value scales / zero-points of the tokens this lane half pairs
         u32x4 Bp[NVG][2];
         {
-          const int t0 = 64 * hsg + 16 * kg;
+          // the 8 tokens this lane half pairs: 16 kg + 8 role .. (G32: 32 role + 8 kg ..), pair i = tokens 2i, 2i + 1
+          const int tv = 64 * hsg + (G32 ? 32 * role + 8 * kg : 16 * kg + 8 * role);
           if (NVG == 1) {
-            // pair i of this lane half = tokens (8*role + 2i, 8*role + 2i + 1): dword 4*role + i of the run
-            const uint4 sv = *reinterpret_cast<const uint4*>(sVm + 2 * t0 + 16 * role);
-            const uint4 zv = *reinterpret_cast<const uint4*>(sVm + 2 * R + 2 * t0 + 16 * role);
+            const uint4 sv = *reinterpret_cast<const uint4*>(sVm + 2 * tv);
+            const uint4 zv = *reinterpret_cast<const uint4*>(sVm + 2 * R + 2 * tv);
             const unsigned sw[4] = {sv.x, sv.y, sv.z, sv.w}, zw[4] = {zv.x, zv.y, zv.z, zv.w};
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -804,8 +829,8 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
             }
           } else {
             // [token][2] layout: one dword per token, value group a in half a; tokens 8*role .. 8*role+7
-            const uint4* ps = reinterpret_cast<const uint4*>(sVm + 4 * t0 + 32 * role);
-            const uint4* pz = reinterpret_cast<const uint4*>(sVm + 4 * R + 4 * t0 + 32 * role);
+            const uint4* ps = reinterpret_cast<const uint4*>(sVm + 4 * tv);
+            const uint4* pz = reinterpret_cast<const uint4*>(sVm + 4 * R + 4 * tv);
             const uint4 s0 = ps[0], s1 = ps[1], z0 = pz[0], z1 = pz[1];
             const unsigned sw[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
             const unsigned zw[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
@@ -846,6 +871,8 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 #undef MIXKVQ_ISSUE_V_LOADS
 #undef MIXKVQ_ISSUE_V_HALF
 #undef MIXKVQ_REBUILD_Q
+#undef MIXKVQ_GROUP_OPERANDS
+#undef MIXKVQ_KEY_TILES
 
   // ---- wave results -> workgroup partial ------------------------------------------
   l_run = xkg_sum(l_run);
@@ -911,20 +938,20 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 
 // One launch per decode step: the workgroups (pair, split) share the pair's block records and its
 // residual window.
-template <int K4, int K16, int NVG, int NKL, int RG, int THR>
+template <int K4, int K16, int NVG, int NKL, int RG, int THR, int G32>
 __global__ void __launch_bounds__(kMfmaThreads, 2)
 decode_fused_kernel(CacheView cv, const __half* __restrict__ q, float scale, int n_blocks, int n_res, int n_splits,
                     float* __restrict__ part, int accumulate_q, NewToken nt) {
   extern __shared__ __align__(16) unsigned char smem[];
-  mfma_part<K4, K16, NVG, NKL, RG, THR>(cv, q, scale * 1.4426950408889634f, n_blocks, n_res, n_splits, part, accumulate_q, nt,
+  mfma_part<K4, K16, NVG, NKL, RG, THR, G32>(cv, q, scale * 1.4426950408889634f, n_blocks, n_res, n_splits, part, accumulate_q, nt,
                                    smem);
 }
 
-template <int K4, int K16, int NVG, int NKL, int RG, int THR>
+template <int K4, int K16, int NVG, int NKL, int RG, int THR, int G32>
 static hipError_t launch_one(const CacheView& v, const __half* q, float scale, int n_blocks, int n_res, int n_splits,
                              float* part, __half* out, float* lse, int accumulate_q, NewToken nt,
                              hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
-  auto kern = decode_fused_kernel<K4, K16, NVG, NKL, RG, THR>;
+  auto kern = decode_fused_kernel<K4, K16, NVG, NKL, RG, THR, G32>;
   const size_t lds = kHdrLds + (size_t)kWaves * kWaveLds;
   static bool attr_set = false;
   if (!attr_set) {
@@ -944,36 +971,44 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
                             float* part, __half* out, float* lse, int accumulate_q, NewToken nt,
                             hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop, hipError_t* err) {
   const mixkvq_config& c = v.cfg;
-  if (c.R % 64 != 0 || c.Gk % 64 != 0 || c.Gv % 64 != 0 || n_blocks < 1) return false;
+  // key groups of 32 tokens take the G32 variants, multiples of 64 the others; value groups of 64 or 128 channels
+  if (c.R % 64 != 0 || (c.Gk % 64 != 0 && c.Gk != 32) || c.Gv % 64 != 0 || n_blocks < 1) return false;
   if (v.lay.off_v > kKPartMax || v.lay.rec_bytes - v.lay.off_v_s > kVMetaMax) return false;
   const int nvg = v.lay.NVG;
   const int nkl = (v.lay.off_v / 16 + 63) / 64;
+  const int g32 = c.Gk == 32;
   hipError_t e = hipErrorInvalidValue;
   bool ok = true;
-#define MIXKVQ_CASE(K4_, K16_, NVG_, NKL_, RG_, THR_)                                                               \
-  if (c.k4 == K4_ && c.k16 == K16_ && nvg == NVG_ && nkl <= NKL_ && c.policy == THR_ &&                             \
+#define MIXKVQ_CASE(K4_, K16_, NVG_, NKL_, RG_, THR_, G32_)                                                         \
+  if (c.k4 == K4_ && c.k16 == K16_ && nvg == NVG_ && nkl <= NKL_ && c.policy == THR_ && g32 == G32_ &&              \
       (RG_ == 0 || (c.R == 128 && c.Gk == 128)))                                                                    \
-    e = launch_one<K4_, K16_, NVG_, NKL_, RG_, THR_>(v, q, scale, n_blocks, n_res, n_splits, part, out, lse,        \
-                                                     accumulate_q, nt, s, ev_start, ev_stop);                       \
+    e = launch_one<K4_, K16_, NVG_, NKL_, RG_, THR_, G32_>(v, q, scale, n_blocks, n_res, n_splits, part, out, lse,  \
+                                                           accumulate_q, nt, s, ev_start, ev_stop);                 \
   else
-  MIXKVQ_CASE(16, 0, 1, 6, 1, 0)
-  MIXKVQ_CASE(0, 12, 1, 8, 1, 0)
-  MIXKVQ_CASE(8, 0, 1, 6, 1, 0)
-  MIXKVQ_CASE(16, 0, 1, 6, 0, 0)
-  MIXKVQ_CASE(0, 12, 1, 8, 0, 0)
-  MIXKVQ_CASE(0, 0, 1, 6, 0, 0)
-  MIXKVQ_CASE(8, 0, 1, 6, 0, 0)
-  MIXKVQ_CASE(24, 0, 1, 6, 0, 0)
-  MIXKVQ_CASE(32, 0, 1, 6, 0, 0)
-  MIXKVQ_CASE(16, 0, 2, 6, 0, 0)
-  MIXKVQ_CASE(0, 12, 2, 8, 0, 0)
-  MIXKVQ_CASE(8, 4, 1, 8, 0, 0)
-  MIXKVQ_CASE(0, 32, 1, 8, 0, 0)
+  MIXKVQ_CASE(16, 0, 1, 6, 1, 0, 0)
+  MIXKVQ_CASE(0, 12, 1, 8, 1, 0, 0)
+  MIXKVQ_CASE(8, 0, 1, 6, 1, 0, 0)
+  MIXKVQ_CASE(16, 0, 1, 6, 0, 0, 0)
+  MIXKVQ_CASE(0, 12, 1, 8, 0, 0, 0)
+  MIXKVQ_CASE(0, 0, 1, 6, 0, 0, 0)
+  MIXKVQ_CASE(8, 0, 1, 6, 0, 0, 0)
+  MIXKVQ_CASE(24, 0, 1, 6, 0, 0, 0)
+  MIXKVQ_CASE(32, 0, 1, 6, 0, 0, 0)
+  MIXKVQ_CASE(16, 0, 2, 6, 0, 0, 0)
+  MIXKVQ_CASE(0, 12, 2, 8, 0, 0, 0)
+  MIXKVQ_CASE(8, 4, 1, 8, 0, 0, 0)
+  MIXKVQ_CASE(0, 32, 1, 8, 0, 0, 0)
   // threshold policy: the capacities of the two side tiers
-  MIXKVQ_CASE(16, 8, 1, 8, 0, 1)
-  MIXKVQ_CASE(16, 0, 1, 6, 0, 1)
-  MIXKVQ_CASE(0, 12, 1, 8, 0, 1)
-  MIXKVQ_CASE(8, 4, 1, 8, 0, 1)
+  MIXKVQ_CASE(16, 8, 1, 8, 0, 1, 0)
+  MIXKVQ_CASE(16, 0, 1, 6, 0, 1, 0)
+  MIXKVQ_CASE(0, 12, 1, 8, 0, 1, 0)
+  MIXKVQ_CASE(8, 4, 1, 8, 0, 1, 0)
+  // key groups of 32 tokens
+  MIXKVQ_CASE(16, 0, 1, 8, 0, 0, 1)
+  MIXKVQ_CASE(8, 0, 1, 8, 0, 0, 1)
+  MIXKVQ_CASE(0, 0, 1, 8, 0, 0, 1)
+  MIXKVQ_CASE(16, 0, 2, 8, 0, 0, 1)
+  MIXKVQ_CASE(16, 0, 1, 8, 0, 1, 1)
   ok = false;
 #undef MIXKVQ_CASE
   if (!ok) return false;

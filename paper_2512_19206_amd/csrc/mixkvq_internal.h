@@ -69,6 +69,11 @@ __device__ __forceinline__ long long fix24(unsigned short h) {
   return (h & 0x8000u) ? -v : v;
 }
 
+// Token (inside the block) of code i of value word tg; see the record layout in mixkvq.h.
+__device__ __forceinline__ int value_word_token(int tg, int i, int interleave) {
+  return interleave ? 64 * (tg >> 2) + 8 * (tg & 3) + (i & 7) + 32 * (i >> 3) : 16 * tg + i;
+}
+
 // Threshold of Section 4.2 in the units of the integer score sum|q|_d * range_d (units 2^-48):
 // A_d = (sum|q|_d 2^-24 / count) * (range_d 2^-24 / 3) > tau  <=>  score_d > tau * 3 * 2^48 * count, the right-hand
 // side formed in binary64 from left to right; with the error-only score, range_d > tau * 3 * 2^24.

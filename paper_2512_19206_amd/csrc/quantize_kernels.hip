@@ -237,7 +237,7 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
     unsigned w = 0;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const int t = tg * 16 + i;
+      const int t = value_word_token(tg, i, lay.v_interleave);
       w |= encode(__half2float(sT[t * kRowStride + d]), sVZ[t * NVG + vg], sVS[t * NVG + vg], 3.f) << (16 * (i & 1) + 2 * (i >> 1));
     }
     reinterpret_cast<unsigned*>(rec + lay.off_v)[it] = w;
@@ -649,35 +649,41 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   // value words [token group][channel], 16 codes along tokens: the 16 tokens' parameters in registers
   {
     const int d = tid & (kD - 1), vg = d / Gv;
+    const int ilv = cv.lay.v_interleave;
     for (int tg = tid >> 7; tg < n_ch; tg += 2) {
+      // tokens of the word: two runs of 8 (tok0 .. tok0+7 and tok0 + hi_off ..), consecutive unless interleaved
+      const int tok0 = value_word_token(tg, 0, ilv), hi_off = ilv ? 32 : 8;
       float rc[16], zp[16];
       if (NVG == 1) {
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
-          const float4 a = *reinterpret_cast<const float4*>(sR + tg * 16 + 4 * i4);
-          const float4 b2 = *reinterpret_cast<const float4*>(sVZ + tg * 16 + 4 * i4);
+          const int t4 = tok0 + 4 * (i4 & 1) + (i4 >> 1) * hi_off;
+          const float4 a = *reinterpret_cast<const float4*>(sR + t4);
+          const float4 b2 = *reinterpret_cast<const float4*>(sVZ + t4);
           rc[4 * i4] = a.x; rc[4 * i4 + 1] = a.y; rc[4 * i4 + 2] = a.z; rc[4 * i4 + 3] = a.w;
           zp[4 * i4] = b2.x; zp[4 * i4 + 1] = b2.y; zp[4 * i4 + 2] = b2.z; zp[4 * i4 + 3] = b2.w;
         }
       } else {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          rc[i] = sR[(tg * 16 + i) * NVG + vg];
-          zp[i] = sVZ[(tg * 16 + i) * NVG + vg];
+          const int t = tok0 + (i & 7) + (i >> 3) * hi_off;
+          rc[i] = sR[t * NVG + vg];
+          zp[i] = sVZ[t * NVG + vg];
         }
       }
       float hw[2] = {0.f, 0.f};
       bool near = false;
 #pragma unroll
       for (int i = 0; i < 16; ++i)
-        add_code<2>(hw, i, code_fast<3>(__half2float(sT[(tg * 16 + i) * kRowStride + d]), zp[i], rc[i], near));
+        add_code<2>(hw, i, code_fast<3>(__half2float(sT[(tok0 + (i & 7) + (i >> 3) * hi_off) * kRowStride + d]), zp[i], rc[i], near));
       unsigned w = join_halves(hw);
       if (__any(near)) {     // rare: some quotient sits next to a rounding boundary
         w = 0;
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
-          w |= encode(__half2float(sT[(tg * 16 + i) * kRowStride + d]), zp[i], sVS[(tg * 16 + i) * NVG + vg], 3.f)
-               << (16 * (i & 1) + 2 * (i >> 1));
+        for (int i = 0; i < 16; ++i) {
+          const int t = tok0 + (i & 7) + (i >> 3) * hi_off;
+          w |= encode(__half2float(sT[t * kRowStride + d]), zp[i], sVS[t * NVG + vg], 3.f) << (16 * (i & 1) + 2 * (i >> 1));
+        }
       }
       reinterpret_cast<unsigned*>(rec + off_v)[tg * kD + d] = w;
     }

@@ -206,6 +206,46 @@ def test_fused_decode_step(H, R, Gk, k4, k16, flush_mode):
     assert oc.n_flush_calls >= 2
 
 
+@pytest.mark.parametrize("R,Gv,k4,k16,g,policy", [(128, 128, 16, 0, 7, 0), (64, 64, 16, 0, 5, 0), (128, 128, 8, 0, 8, 0),
+                                                  (128, 128, 0, 0, 3, 0), (128, 128, 16, 0, 4, 1), (128, 32, 16, 0, 7, 0),
+                                                  (128, 32, 0, 12, 2, 0)])
+def test_key_groups_of_32_tokens(H, R, Gv, k4, k16, g, policy):
+    """The paper's group size (Section 5, "Settings": G = 32) with a residual length of 64 or 128: four (two) key
+    groups per block, value words interleaved over the two key groups of a 64-token span."""
+    rng = np.random.default_rng(300 + R + Gv + k4 + g)
+    B, Hkv = 2, 2
+    kw = dict(B=B, Hq=Hkv * g, Hkv=Hkv, D=128, T_max=8 * R, Gk=32, Gv=Gv, R=R, k4=k4, k16=k16)
+    if policy:
+        kw.update(policy=1, tau16=np.inf, tau4=6.0)
+    oc, gc = H.make_pair(**kw)
+    assert gc.layout.v_interleave == 1
+    n0 = 3 * R + 21
+    # every 32-token group gets its own magnitude, so that a scale taken from the wrong group cannot pass
+    grp_mag = np.repeat(rng.uniform(0.2, 1.25, (n0 + 31) // 32), 32)[:n0, None]
+    K = (rng.standard_normal((B, Hkv, n0, 128)) * rng.uniform(0.3, 8, 128) * grp_mag).astype(np.float16)
+    V = (rng.standard_normal((B, Hkv, n0, 128)) * rng.uniform(0.5, 2, (n0, 1))).astype(np.float16)
+    Qp = (rng.standard_normal((B, Hkv * g, 16, 128)) * rng.uniform(0.2, 5, 128)).astype(np.float16)
+    if k4 + k16:        # feed the |q| accumulator (the selection itself is redone per block)
+        oc.accumulate_queries(Qp)
+        gc.select_channels(H.dev(Qp), H.dev(K))
+    oc.append(K, V)
+    gc.quantize_append(H.dev(K), H.dev(V))
+    H.check_state(oc, gc)
+    for step in range(R + 3):
+        k1 = (rng.standard_normal((B, Hkv, 1, 128)) * rng.uniform(0.3, 8, 128)).astype(np.float16)
+        v1 = rng.standard_normal((B, Hkv, 1, 128)).astype(np.float16)
+        q1 = (rng.standard_normal((B, Hkv * g, 128)) * rng.uniform(0.2, 5, 128)).astype(np.float16)
+        oc.append(k1, v1)
+        ro, rl = oc.decode_attention(q1, accumulate_q=True)
+        out, lse = gc.decode_step(H.dev(k1), H.dev(v1), H.dev(q1), accumulate_q=True)
+        torch.cuda.synchronize()
+        err = np.abs(out.float().cpu().numpy() - ro)
+        assert np.all(err <= H.ATOL + H.RTOL * np.abs(ro)), (step, float(err.max()))
+        assert np.all(np.abs(lse.cpu().numpy() - rl) <= H.LSE_ATOL + 1e-4 * np.abs(rl))
+    H.check_state(oc, gc)
+    assert oc.n_flush_calls >= 4
+
+
 def test_chunked_append_without_selection_matches_oracle(H):
     """sel = NULL on a multi-token append: every flushed block is scored on its own."""
     rng = np.random.default_rng(8)

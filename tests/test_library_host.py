@@ -47,6 +47,7 @@ CONFIGS = [
     dict(B=2, Hq=8, Hkv=2, D=128, T_max=256, Gk=16, Gv=16, R=64, k4=8, k16=4),
     dict(B=1, Hq=2, Hkv=2, D=128, T_max=128, Gk=64, Gv=64, R=128, k4=0, k16=0),
     dict(B=2, Hq=14, Hkv=2, D=128, T_max=512, Gk=128, Gv=128, R=128, k4=16, k16=8, policy=1, tau16=1.44, tau4=0.79),
+    dict(B=2, Hq=14, Hkv=2, D=128, T_max=512, Gk=32, Gv=32, R=128, k4=16, k16=0),
     dict(B=1, Hq=5, Hkv=1, D=128, T_max=64, Gk=32, Gv=32, R=32, k4=8, k16=4, policy=1, tau16=0.0, tau4=float("inf")),
 ]
 

@@ -169,3 +169,31 @@ def test_fp16_footprint_example_of_the_introduction():
     total = (g["kv_example_layers"] * g["kv_example_batch"] * g["kv_example_kv_heads"] * g["kv_example_tokens"]
              * g["kv_example_head_dim"] * 2 * 2)
     assert total / 2 ** 30 == g["kv_fp16_footprint_gb"]
+
+
+@pytest.mark.parametrize("Gk,R,interleave", [(32, 128, 1), (32, 64, 1), (32, 32, 0), (64, 128, 0), (16, 64, 0)])
+def test_value_words_hold_every_token_once(Gk, R, interleave):
+    """Value codes read back from the packed record with the bit positions of the layout comment (code i at bit
+    16 (i & 1) + 2 (i >> 1)) and the word's token list: every (token, channel) code is recovered, whether the
+    words take consecutive tokens or are interleaved over the two key groups of a 64-token span."""
+    rng = np.random.default_rng(21)
+    cfg = O.OracleConfig(B=1, Hq=1, Hkv=1, D=128, T_max=R, Gk=Gk, Gv=64, R=R, k4=8, k16=0)
+    lay = O.block_layout(cfg)
+    assert lay.v_interleave == interleave
+    K = rng.standard_normal((R, 128)).astype(np.float16)
+    V = rng.standard_normal((R, 128)).astype(np.float16)
+    blk = O.quantize_block(cfg, K, V, np.arange(8, dtype=np.uint8))
+    rec = O.pack_block(cfg, blk)
+    words = rec[lay.off_v:lay.off_v_s].view(np.uint32).reshape(R // 16, 128)
+    seen = np.zeros(R, dtype=int)
+    for tg in range(R // 16):
+        toks = [O.value_word_token(tg, i, interleave) for i in range(16)]
+        for i, t in enumerate(toks):
+            seen[t] += 1
+            got = (words[tg] >> np.uint32(16 * (i & 1) + 2 * (i >> 1))) & np.uint32(3)
+            assert np.array_equal(got.astype(np.uint8), blk.v_codes[t])
+        if interleave:   # codes 0..7 from the first key group of the span, codes 8..15 from the second
+            assert {t // 32 for t in toks[:8]} == {2 * (tg // 4)} and {t // 32 for t in toks[8:]} == {2 * (tg // 4) + 1}
+        else:
+            assert toks == list(range(16 * tg, 16 * tg + 16))
+    assert np.all(seen == 1)
