@@ -226,6 +226,8 @@ def main():
     ap.add_argument("--host-batch", type=int, default=2)
     ap.add_argument("--tokens", type=int, default=0, help="override the context length of the configuration")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--group-size", type=int, default=0,
+                    help="override the key and value group size of the configuration (32: the paper's accuracy setting)")
     ap.add_argument("--per-block-selection", action="store_true",
                     help="fill the cache with every block scored on its own tokens (as blocks flushed during decoding "
                          "are) instead of one selection for the whole prompt")
@@ -253,6 +255,10 @@ def main():
         bench_prefill(args, w, args.config)
         return
     policy_kw = {}
+    if args.group_size:
+        import dataclasses
+        w = dataclasses.replace(w, name=w.name + "_g%d" % args.group_size, Gk=args.group_size, Gv=args.group_size)
+        args.no_cpu_baseline = True
     if args.thresholds:
         import dataclasses
         tau16, tau4 = (float(x) for x in args.thresholds.split(","))

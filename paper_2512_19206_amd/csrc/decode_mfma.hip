@@ -32,7 +32,7 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kMfmaThreads = 256;
 constexpr int kWaves = kMfmaThreads / 64;
 constexpr int kKPartMax = 8192;                 // bytes of a record before the value plane (staged in LDS)
-constexpr int kVMetaMax = 1024;                 // value scales + zero-points of one block
+constexpr int kVMetaMax = 2048;                 // value scales + zero-points of one block
 constexpr int kQsStride = 168;                  // halfs per head row of the slot-ordered q table (160 slots + padding)
 constexpr int kQsBytes = 8 * kQsStride * 2;
 constexpr int kWaveLds = kKPartMax + kVMetaMax + 256 + kQsBytes;   // + channel lists + slot-ordered q
@@ -124,6 +124,19 @@ __device__ __forceinline__ void wave_lds_handoff() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Channel of A-row `row` of the value product (xp, qq), i.e. which value code word a lane holds in element qq of
+// vreg[.][xp].  All 16 rows of one product must share a value group (the small operand carries the group's
+// scales): with groups of 64 or 128 channels row r of (xp, qq) is channel 64 xp + 4 r + qq; with groups of 32
+// channels (NVG = 4) it is channel 32 (2 xp + qq/2) + 2 r + qq%2, and (xp, qq) belongs to value group 2 xp + qq/2.
+template <int NVG>
+__device__ __forceinline__ constexpr int value_channel(int xp, int qq, int row) {
+  return NVG == 4 ? 32 * (2 * xp + (qq >> 1)) + 2 * row + (qq & 1) : 64 * xp + 4 * row + qq;
+}
+template <int NVG>
+__device__ __forceinline__ constexpr int value_group(int xp, int qq) {
+  return NVG == 4 ? 2 * xp + (qq >> 1) : (NVG == 2 ? xp : 0);
 }
 
 // THR = 1: threshold policy.  K4 and K16 are capacities, a block's channel lists may hold unused entries
@@ -342,7 +355,8 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 
   // prefetch registers
   u32x4 kreg[NKL];
-  u32x4 vmreg;
+  constexpr int NVM = NVG == 4 ? 2 : 1;   // 1 KiB pieces of the value scale / zero-point planes
+  u32x4 vmreg[NVM];
   u32x4 vreg[2][2];   // [h][x]
 
   // Loads of one block.  Chunk indices are clamped to the record so that every lane loads and
@@ -354,14 +368,28 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
       const int idx_ = c * 64 + lane;                                                                        \
       kreg[c] = reinterpret_cast<const u32x4*>(rec_)[idx_ < rec_chunks ? idx_ : rec_chunks - 1];            \
     }                                                                                                        \
-    vmreg = reinterpret_cast<const u32x4*>(rec_ + off_v_s)[lane < nvm ? lane : nvm - 1];                    \
+    _Pragma("unroll") for (int c = 0; c < NVM; ++c) {                                                       \
+      const int idx_ = c * 64 + lane;                                                                        \
+      vmreg[c] = reinterpret_cast<const u32x4*>(rec_ + off_v_s)[idx_ < nvm ? idx_ : nvm - 1];               \
+    }                                                                                                        \
+  }
+  /* the four value words of vreg[.][X]: channels value_channel(X, 0..3, n) of one token group's row ROW_ */
+#define MIXKVQ_LOAD_VWORDS(DST, ROW_, X)                                                                     \
+  {                                                                                                          \
+    if (NVG == 4) {                                                                                          \
+      const uint2 lo_ = *reinterpret_cast<const uint2*>((ROW_) + 64 * (X) + 2 * n);                          \
+      const uint2 hi_ = *reinterpret_cast<const uint2*>((ROW_) + 64 * (X) + 32 + 2 * n);                     \
+      DST = u32x4{lo_.x, lo_.y, hi_.x, hi_.y};                                                               \
+    } else {                                                                                                 \
+      DST = *reinterpret_cast<const u32x4*>((ROW_) + 64 * (X) + 4 * n);                                      \
+    }                                                                                                        \
   }
 #define MIXKVQ_ISSUE_V_LOADS(BLK)                                                                           \
   {                                                                                                          \
     const unsigned char* rec_ = blocks + ((size_t)p * NB + (BLK)) * rec_bytes;                              \
     const unsigned* vw_ = reinterpret_cast<const unsigned*>(rec_ + off_v);                                  \
     _Pragma("unroll") for (int h = 0; h < 2; ++h) _Pragma("unroll") for (int x = 0; x < 2; ++x)             \
-        vreg[h][x] = *reinterpret_cast<const u32x4*>(vw_ + (4 * (h * 64 < R ? h : 0) + kg) * kD + 64 * x + 4 * n); \
+        MIXKVQ_LOAD_VWORDS(vreg[h][x], vw_ + (4 * (h * 64 < R ? h : 0) + kg) * kD, x)                       \
   }
 
   // The value words of one half (64 tokens) of a record: asked for as soon as the previous record's matrix
@@ -371,7 +399,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
     const unsigned char* rec_ = blocks + ((size_t)p * NB + (BLK)) * rec_bytes;                              \
     const unsigned* vw_ = reinterpret_cast<const unsigned*>(rec_ + off_v);                                  \
     _Pragma("unroll") for (int x = 0; x < 2; ++x)                                                           \
-        vreg[H][x] = *reinterpret_cast<const u32x4*>(vw_ + (4 * (H) + kg) * kD + 64 * x + 4 * n);           \
+        MIXKVQ_LOAD_VWORDS(vreg[H][x], vw_ + (4 * (H) + kg) * kD, x)                                        \
   }
 
   // q in slot order from the selection words SELW (wave-uniform).  The list of 2-bit channels and the salient
@@ -591,7 +619,8 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         u32x4 a;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const unsigned short* cp = reinterpret_cast<const unsigned short*>(sK + (8 * kg + 2 * e) * kVStride) + 64 * xp + 4 * n + qq;
+          const unsigned short* cp = reinterpret_cast<const unsigned short*>(sK + (8 * kg + 2 * e) * kVStride) +
+                                     value_channel<NVG>(xp, qq, n);
           a[e] = (unsigned)cp[0] | ((unsigned)cp[kVStride / 2] << 16);
         }
         // the block loop accumulates sum p' c 4^sc 2^-24 and is scaled by 2^24 at the end
@@ -721,7 +750,8 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
     // ---- stage the key part and value metadata in LDS (wave-private: no barrier needed) ----
 #pragma unroll
     for (int c = 0; c < NKL; ++c) reinterpret_cast<u32x4*>(sK)[c * 64 + lane] = kreg[c];
-    reinterpret_cast<u32x4*>(sVm)[lane < nvm ? lane : nvm - 1] = vmreg;
+#pragma unroll
+    for (int c = 0; c < NVM; ++c) reinterpret_cast<u32x4*>(sVm)[c * 64 + lane < nvm ? c * 64 + lane : nvm - 1] = vmreg[c];
     wave_lds_handoff();
     if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_K_LOADS(blk + blk_step)
 
@@ -812,7 +842,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
           l_run = dot2(pk[i], w4sc[i], l_run);
         }
         // value scales / zero-points of the tokens this lane half pairs
-        u32x4 Bp[NVG][2];
+        u32x4 Bp[NVG == 4 ? 2 : NVG][2];   // NVG = 4: the two value groups of one xp at a time
         {
           // the 8 tokens this lane half pairs: 16 kg + 8 role .. (G32: 32 role + 8 kg ..), pair i = tokens 2i, 2i + 1
           const int tv = 64 * hsg + (G32 ? 32 * role + 8 * kg : 16 * kg + 8 * role);
@@ -827,7 +857,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
               Bp[0][1][i] = row_shl8u(pm);
               zacc[0][i] = dot2(pk[i], zw[i], zacc[0][i]);
             }
-          } else {
+          } else if (NVG == 2) {
             // [token][2] layout: one dword per token, value group a in half a; tokens 8*role .. 8*role+7
             const uint4* ps = reinterpret_cast<const uint4*>(sVm + 4 * tv);
             const uint4* pz = reinterpret_cast<const uint4*>(sVm + 4 * R + 4 * tv);
@@ -847,13 +877,40 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
           }
         }
 
+        // NVG = 4, [token][4] layout: 8 bytes per token, value groups (0, 1) in the first dword, (2, 3) in the second;
+        // element i of s4 / z4 holds tokens 2i and 2i + 1 of this lane half
+        uint4 s4[NVG == 4 ? 4 : 1], z4[NVG == 4 ? 4 : 1];
+        if (NVG == 4) {
+          const int tv = 64 * hsg + (G32 ? 32 * role + 8 * kg : 16 * kg + 8 * role);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            s4[i] = reinterpret_cast<const uint4*>(sVm + 8 * tv)[i];
+            z4[i] = reinterpret_cast<const uint4*>(sVm + 8 * R + 8 * tv)[i];
+          }
+        }
+
         // ---- O^T += V_codes^T . Ps^T ----
 #pragma unroll
         for (int xp = 0; xp < 2; ++xp) {
           const u32x4 vw = vreg[hsg][xp];
-          const int a = NVG == 1 ? 0 : xp;
+          if (NVG == 4) {      // small operands of value groups 2 xp and 2 xp + 1
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const unsigned s_a = xp ? s4[i].y : s4[i].x, s_b = xp ? s4[i].w : s4[i].z;   // tokens 2i, 2i + 1
+              const unsigned z_a = xp ? z4[i].y : z4[i].x, z_b = xp ? z4[i].w : z4[i].z;
+#pragma unroll
+              for (int cc = 0; cc < 2; ++cc) {
+                const unsigned selb = cc ? 0x07060302u : 0x05040100u;
+                const unsigned pm = pk_mul(pk[i], __builtin_amdgcn_perm(s_b, s_a, selb));
+                Bp[cc][0][i] = pm;
+                Bp[cc][1][i] = row_shl8u(pm);
+                zacc[2 * xp + cc][i] = dot2(pk[i], __builtin_amdgcn_perm(z_b, z_a, selb), zacc[2 * xp + cc][i]);
+              }
+            }
+          }
 #pragma unroll
           for (int qq = 0; qq < 4; ++qq) {
+            const int a = NVG == 4 ? (qq >> 1) : value_group<NVG>(xp, qq);
             u32x4 a0, a1;
             unpack2(vw[qq], a0, a1);
             O[xp][qq] = mfma(a0, Bp[a][0], O[xp][qq]);
@@ -870,6 +927,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 #undef MIXKVQ_ISSUE_K_LOADS
 #undef MIXKVQ_ISSUE_V_LOADS
 #undef MIXKVQ_ISSUE_V_HALF
+#undef MIXKVQ_LOAD_VWORDS
 #undef MIXKVQ_REBUILD_Q
 #undef MIXKVQ_GROUP_OPERANDS
 #undef MIXKVQ_KEY_TILES
@@ -897,8 +955,8 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
       for (int qq = 0; qq < 4; ++qq)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const int ch = 64 * xp + 16 * kg + 4 * i + qq;
-          const int a = NVG == 1 ? 0 : xp;
+          const int ch = value_channel<NVG>(xp, qq, 4 * kg + i);
+          const int a = value_group<NVG>(xp, qq);
           wO[head * kD + ch] = fmaf(O[xp][qq][i], 16777216.f, zsum[a]);
         }
     if (kg == 0) {
@@ -971,8 +1029,8 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
                             float* part, __half* out, float* lse, int accumulate_q, NewToken nt,
                             hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop, hipError_t* err) {
   const mixkvq_config& c = v.cfg;
-  // key groups of 32 tokens take the G32 variants, multiples of 64 the others; value groups of 64 or 128 channels
-  if (c.R % 64 != 0 || (c.Gk % 64 != 0 && c.Gk != 32) || c.Gv % 64 != 0 || n_blocks < 1) return false;
+  // key groups of 32 tokens take the G32 variants, multiples of 64 the others; value groups of 32, 64 or 128 channels
+  if (c.R % 64 != 0 || (c.Gk % 64 != 0 && c.Gk != 32) || (c.Gv % 64 != 0 && c.Gv != 32) || n_blocks < 1) return false;
   if (v.lay.off_v > kKPartMax || v.lay.rec_bytes - v.lay.off_v_s > kVMetaMax) return false;
   const int nvg = v.lay.NVG;
   const int nkl = (v.lay.off_v / 16 + 63) / 64;
@@ -1004,11 +1062,16 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
   MIXKVQ_CASE(0, 12, 1, 8, 0, 1, 0)
   MIXKVQ_CASE(8, 4, 1, 8, 0, 1, 0)
   // key groups of 32 tokens
-  MIXKVQ_CASE(16, 0, 1, 8, 0, 0, 1)
-  MIXKVQ_CASE(8, 0, 1, 8, 0, 0, 1)
-  MIXKVQ_CASE(0, 0, 1, 8, 0, 0, 1)
-  MIXKVQ_CASE(16, 0, 2, 8, 0, 0, 1)
+  MIXKVQ_CASE(16, 0, 1, 7, 0, 0, 1)
+  MIXKVQ_CASE(8, 0, 1, 7, 0, 0, 1)
+  MIXKVQ_CASE(0, 0, 1, 7, 0, 0, 1)
+  MIXKVQ_CASE(16, 0, 2, 7, 0, 0, 1)
   MIXKVQ_CASE(16, 0, 1, 8, 0, 1, 1)
+  // value groups of 32 channels (with key groups of 32 tokens: the group size of the paper's experiments)
+  MIXKVQ_CASE(16, 0, 4, 7, 0, 0, 1)
+  MIXKVQ_CASE(8, 0, 4, 7, 0, 0, 1)
+  MIXKVQ_CASE(16, 0, 4, 8, 0, 1, 1)
+  MIXKVQ_CASE(16, 0, 4, 6, 0, 0, 0)
   ok = false;
 #undef MIXKVQ_CASE
   if (!ok) return false;

@@ -63,7 +63,8 @@ def test_prefill_slice(H, cfg_id, B, T):
 
 
 @pytest.mark.parametrize("g,k4,k16,Gk,Gv,R", [(1, 0, 0, 16, 16, 16), (5, 8, 4, 32, 64, 64), (8, 0, 32, 128, 128, 128),
-                                              (7, 24, 0, 64, 32, 128), (2, 8, 0, 16, 128, 48)])
+                                              (7, 24, 0, 64, 32, 128), (2, 8, 0, 16, 128, 48), (6, 16, 0, 128, 32, 128),
+                                              (8, 8, 0, 32, 32, 64)])
 def test_shapes_and_tiers(H, g, k4, k16, Gk, Gv, R):
     rng = np.random.default_rng(100 + g)
     B, Hkv, T = 2, 2, 5 * R + 7
@@ -207,7 +208,7 @@ def test_fused_decode_step(H, R, Gk, k4, k16, flush_mode):
 
 
 @pytest.mark.parametrize("R,Gv,k4,k16,g,policy", [(128, 128, 16, 0, 7, 0), (64, 64, 16, 0, 5, 0), (128, 128, 8, 0, 8, 0),
-                                                  (128, 128, 0, 0, 3, 0), (128, 128, 16, 0, 4, 1), (128, 32, 16, 0, 7, 0),
+                                                  (128, 128, 0, 0, 3, 0), (128, 128, 16, 0, 4, 1), (128, 32, 16, 0, 7, 0), (128, 32, 16, 0, 5, 1),
                                                   (128, 32, 0, 12, 2, 0)])
 def test_key_groups_of_32_tokens(H, R, Gv, k4, k16, g, policy):
     """The paper's group size (Section 5, "Settings": G = 32) with a residual length of 64 or 128: four (two) key
