@@ -31,12 +31,16 @@ def _host_pair(host, w, b, j, hb):
     return K, V, Qp, qs
 
 
-@pytest.mark.parametrize("cfg_id,host_batch,samples,n_steps", [
-    (1, 2, [(0, 0), (1, 3), (5, 2), (7, 1)], 3),
-    (3, 1, [(0, 0), (3, 5)], 2),
-    (2, 1, [(0, 7), (37, 2)], 2),
+@pytest.mark.parametrize("cfg_id,host_batch,samples,n_steps,over", [
+    (1, 2, [(0, 0), (1, 3), (5, 2), (7, 1)], 3, {}),
+    (3, 1, [(0, 0), (3, 5)], 2, {}),
+    (2, 1, [(0, 7), (37, 2)], 2, {}),
+    # the shape of configuration 1 with the paper's group size, every block scored on its own tokens
+    (1, 2, [(2, 1), (7, 3)], 2, dict(Gk=32, Gv=32, per_block=True)),
+    # ... and with the three-tier threshold policy (room for 8 fp16 and 16 four-bit channels per block)
+    (1, 2, [(3, 0), (6, 2)], 2, dict(k4=16, k16=8, policy=1, tau16=20.0, tau4=4.0, per_block=True)),
 ])
-def test_full_size_sampled_pairs(H, cfg_id, host_batch, samples, n_steps):
+def test_full_size_sampled_pairs(H, cfg_id, host_batch, samples, n_steps, over):
     import bench
     import paper_2512_19206_amd as M
     import synth_inputs as S
@@ -47,9 +51,12 @@ def test_full_size_sampled_pairs(H, cfg_id, host_batch, samples, n_steps):
     dk, dv, dqp, dq, host = bench.build_inputs(cfg_id, w, host_batch)
     hb = min(host_batch, w.B)
     kw = dict(D=w.D, T_max=w.T + 2 * w.R, Gk=w.Gk, Gv=w.Gv, R=w.R, k4=w.k4, k16=w.k16)
+    over = dict(over)
+    per_block = over.pop("per_block", False)
+    kw.update(over)
     gc = M.Cache(M.make_config(B=w.B, Hq=w.Hq, Hkv=w.Hkv, **kw))
     sel = M.mixkvq_select_channels(gc, dqp, dk)
-    M.mixkvq_quantize_append(gc, dk, dv, sel=sel)
+    M.mixkvq_quantize_append(gc, dk, dv, sel=None if per_block else sel)
     outs = []
     for t in range(n_steps):
         out, lse = M.mixkvq_decode_step(gc, dk[:, :, t:t + 1], dv[:, :, t:t + 1], dq[t], accumulate_q=True)
@@ -68,7 +75,7 @@ def test_full_size_sampled_pairs(H, cfg_id, host_batch, samples, n_steps):
         oc = O.OracleCache(O.OracleConfig(B=1, Hq=g, Hkv=1, **kw))
         sel_ref = oc.select_channels(Qp, K)
         assert np.array_equal(sel_h[b, j], sel_ref[0, 0]), f"selection differs for pair ({b}, {j})"
-        oc.append(K, V, sel_ref)
+        oc.append(K, V, None if per_block else sel_ref)
         for t in range(n_steps):
             oc.append(K[:, :, t:t + 1], V[:, :, t:t + 1])
             ro, rl = oc.decode_attention(np.ascontiguousarray(qs[:, :, t]), accumulate_q=True)
