@@ -35,7 +35,7 @@ constexpr int kKPartMax = 8192;                 // bytes of a record before the 
 constexpr int kVMetaMax = 2048;                 // value scales + zero-points of one block
 constexpr int kQsStride = 168;                  // halfs per head row of the slot-ordered q table (160 slots + padding)
 constexpr int kQsBytes = 8 * kQsStride * 2;
-constexpr int kWaveLds = kKPartMax + kVMetaMax + 256 + kQsBytes;   // + channel lists + slot-ordered q
+constexpr int kWaveLds = kKPartMax + kVMetaMax + 256 + kQsBytes;   // + a spare 256 bytes + slot-ordered q
 constexpr int kHdrLds = 2048 + 256 + 2048 + 2048;   // normalised q [8][128], exponents and wave maxima, q transposed [128][8], raw q [8][128]
 constexpr int kPartStrideM = kD + 2;
 
@@ -281,7 +281,6 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   unsigned char* wbase = smem + kHdrLds + wave * kWaveLds;           // this wave's private region
   unsigned char* sK = wbase;                                        // record bytes [0, NKL KiB)
   unsigned char* sVm = wbase + kKPartMax;                           // v_s, v_z planes
-  unsigned char* sLo = wbase + kKPartMax + kVMetaMax;               // 2-bit channel list [128], then salient idx [<=64]
   unsigned short* sQs = reinterpret_cast<unsigned short*>(wbase + kKPartMax + kVMetaMax + 256);   // [8][kQsStride]
 
   // Work units of the pair: its block records, then the residual window in sub-units of 32 tokens, dealt
@@ -402,45 +401,52 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         MIXKVQ_LOAD_VWORDS(vreg[H][x], vw_ + (4 * (H) + kg) * kD, x)                                        \
   }
 
-  // q in slot order from the selection words SELW (wave-uniform).  The list of 2-bit channels and the salient
-  // list go to LDS; a table [head][slot] of q is filled from the transposed q (one 16-byte read per slot brings
-  // all heads of the slot's channel): slots 0..127 follow the 2-bit list (zero past its end), slots 128.. the
-  // salient list.  Every lane then reads the 8 entries of each of its contraction steps with one 16-byte read.
-#define MIXKVQ_REBUILD_Q(SELW)                                                                                 \
+  // q in slot order from the selection words SELW (wave-uniform): a table [head][slot] in LDS, slots 0..127 for the
+  // block's 2-bit channels in ascending order (zero past the last one), slots 128.. for the fp16 tier and then the
+  // 4-bit tier.  Bitmaps of the two tiers are built with scalar arithmetic; every lane then knows the slots of its
+  // two channels (lane, lane + 64) from population counts, reads their 8 heads from the transposed q (one 16-byte
+  // read each) and scatters them into the table: no list of channels goes through memory.  Places no channel
+  // claims are zeroed (FIRST_: the ones that never change; threshold policy: also the ones that depend on the block).
+  // Every lane finally reads the 8 entries of each of its contraction steps with one 16-byte read.
+#define MIXKVQ_BELOW(MASK_) \
+  ((int)__builtin_amdgcn_mbcnt_hi((unsigned)((MASK_) >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)(MASK_), 0u)))
+#define MIXKVQ_REBUILD_Q(SELW, FIRST_)                                                                         \
   {                                                                                                            \
-    unsigned char* sIdx = sLo + kD;                                                                            \
-    int n_lo_ = kD;                        /* 2-bit channels of the block (wave-uniform) */                    \
-    if (K4 + K16 > 0) {                                                                                        \
-      if (lane == 0) {                                                                                         \
-        _Pragma("unroll") for (int i = 0; i < kSelWords; ++i) reinterpret_cast<unsigned*>(sIdx)[i] = SELW[i];  \
-      }                                                                                                        \
-      unsigned long long m0 = 0, m1 = 0; /* bitmap of salient channels (scalar arithmetic) */                  \
-      _Pragma("unroll") for (int i = 0; i < K4 + K16; ++i) {                                                   \
-        const unsigned ch = (SELW[i >> 2] >> (8 * (i & 3))) & 0xffu;   /* >= 128: an unused entry */           \
-        m0 |= ch < 64u ? 1ull << (ch & 63u) : 0ull;                                                            \
-        m1 |= (ch >= 64u && ch < 128u) ? 1ull << (ch & 63u) : 0ull;                                            \
-      }                                                                                                        \
-      n_lo_ = kD - __popcll(m0) - __popcll(m1);                                                                \
-      /* lanes cover channels lane and lane + 64 */                                                            \
-      if (!((m0 >> lane) & 1)) sLo[lane - __popcll(m0 & ((1ull << lane) - 1))] = (unsigned char)lane;          \
-      if (!((m1 >> lane) & 1))                                                                                 \
-        sLo[lane + 64 - __popcll(m0) - __popcll(m1 & ((1ull << lane) - 1))] = (unsigned char)(lane + 64);      \
-    } else {                                                                                                   \
-      sLo[lane] = (unsigned char)lane;                                                                         \
-      sLo[lane + 64] = (unsigned char)(lane + 64);                                                             \
+    unsigned long long a0_ = 0, a1_ = 0, b0_ = 0, b1_ = 0;   /* fp16 tier / 4-bit tier, channels 0..63 / 64..127 */ \
+    _Pragma("unroll") for (int i = 0; i < K4 + K16; ++i) {                                                     \
+      const unsigned ch = (SELW[i >> 2] >> (8 * (i & 3))) & 0xffu;   /* >= 128: an unused entry */             \
+      const unsigned long long lo_ = ch < 64u ? 1ull << (ch & 63u) : 0ull;                                     \
+      const unsigned long long hi_ = (ch >= 64u && ch < 128u) ? 1ull << (ch & 63u) : 0ull;                     \
+      if (i < K16) { a0_ |= lo_; a1_ |= hi_; } else { b0_ |= lo_; b1_ |= hi_; }                                \
     }                                                                                                          \
-    wave_lds_handoff();                                                                                        \
-    _Pragma("unroll") for (int cch = 0; cch < 3; ++cch) {                                                      \
-      const int slot = 64 * cch + lane;                                                                        \
-      const unsigned ch = cch < 2 ? sLo[slot & 127] : sIdx[lane & 31];                                         \
-      const bool valid = cch < 2 ? slot < n_lo_ : (lane < K4 + K16 && ch < (unsigned)kD);                      \
-      u32x4 hv = *reinterpret_cast<const u32x4*>(sQt + (ch & 127u) * 8);                                       \
-      if (!valid) hv = u32x4{0u, 0u, 0u, 0u};                                                                  \
-      if (cch < 2 || lane < 32) {                                                                              \
-        _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                                        \
-          sQs[(2 * e) * kQsStride + slot] = (unsigned short)(hv[e] & 0xffffu);                                 \
-          sQs[(2 * e + 1) * kQsStride + slot] = (unsigned short)(hv[e] >> 16);                                 \
-        }                                                                                                      \
+    const unsigned long long m0_ = a0_ | b0_, m1_ = a1_ | b1_;                                                 \
+    const int n16_ = __popcll(a0_) + __popcll(a1_), n4_ = __popcll(b0_) + __popcll(b1_);                       \
+    const int n_lo_ = kD - n16_ - n4_;                                                                         \
+    int slot0_ = lane - MIXKVQ_BELOW(m0_), slot1_ = 64 + lane - __popcll(m0_) - MIXKVQ_BELOW(m1_);             \
+    if (K16 > 0) {                                                                                             \
+      if ((a0_ >> lane) & 1) slot0_ = 128 + MIXKVQ_BELOW(a0_);                                                 \
+      if ((a1_ >> lane) & 1) slot1_ = 128 + __popcll(a0_) + MIXKVQ_BELOW(a1_);                                 \
+    }                                                                                                          \
+    if (K4 > 0) {                                                                                              \
+      if ((b0_ >> lane) & 1) slot0_ = 128 + K16 + MIXKVQ_BELOW(b0_);                                           \
+      if ((b1_ >> lane) & 1) slot1_ = 128 + K16 + __popcll(b0_) + MIXKVQ_BELOW(b1_);                           \
+    }                                                                                                          \
+    {                                                                                                          \
+      const u32x4 h0_ = *reinterpret_cast<const u32x4*>(sQt + lane * 8);                                       \
+      const u32x4 h1_ = *reinterpret_cast<const u32x4*>(sQt + (lane + 64) * 8);                                \
+      _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                                          \
+        sQs[(2 * e) * kQsStride + slot0_] = (unsigned short)(h0_[e] & 0xffffu);                                \
+        sQs[(2 * e + 1) * kQsStride + slot0_] = (unsigned short)(h0_[e] >> 16);                                \
+        sQs[(2 * e) * kQsStride + slot1_] = (unsigned short)(h1_[e] & 0xffffu);                                \
+        sQs[(2 * e + 1) * kQsStride + slot1_] = (unsigned short)(h1_[e] >> 16);                                \
+      }                                                                                                        \
+    }                                                                                                          \
+    if (THR || (FIRST_)) {                                                                                     \
+      /* 2-bit places past the block's last 2-bit channel; side places that are unused or beyond both tiers */ \
+      const bool side_ = lane < 32 && (lane >= K16 + K4 || (lane < K16 ? lane >= n16_ : lane - K16 >= n4_));   \
+      _Pragma("unroll") for (int h = 0; h < 8; ++h) {                                                          \
+        if (lane < kD - n_lo_) sQs[h * kQsStride + n_lo_ + lane] = 0;                                          \
+        if (side_) sQs[h * kQsStride + 128 + lane] = 0;                                                        \
       }                                                                                                        \
     }                                                                                                          \
     wave_lds_handoff();                                                                                        \
@@ -564,7 +570,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
     MIXKVQ_ISSUE_V_LOADS(blk)
 #pragma unroll
     for (int i = 0; i < kSelWords; ++i) sel_prev[i] = __builtin_amdgcn_readfirstlane(sel_first[i]);
-    MIXKVQ_REBUILD_Q(sel_prev)
+    MIXKVQ_REBUILD_Q(sel_prev, true)
   }
 
   // ---- residual window (fp16 keys/values): 32 tokens per wavefront, before its block records ----
@@ -765,7 +771,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         rebuild |= selw[i] != sel_prev[i];
         sel_prev[i] = selw[i];
       }
-      if (rebuild) MIXKVQ_REBUILD_Q(selw)
+      if (rebuild) MIXKVQ_REBUILD_Q(selw, false)
     }
 
     // operands that live across the super-groups of one key group
@@ -929,6 +935,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 #undef MIXKVQ_ISSUE_V_HALF
 #undef MIXKVQ_LOAD_VWORDS
 #undef MIXKVQ_REBUILD_Q
+#undef MIXKVQ_BELOW
 #undef MIXKVQ_GROUP_OPERANDS
 #undef MIXKVQ_KEY_TILES
 
