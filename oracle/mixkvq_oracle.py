@@ -58,6 +58,7 @@ class OracleConfig:
     policy: int = 0               # 0: the k16 + k4 best channels; 1: thresholds of Section 4.2, k16 / k4 are capacities
     tau16: float = math.inf       # policy 1: A_d > tau16 -> fp16 tier
     tau4: float = math.inf        # policy 1: tau4 < A_d <= tau16 -> 4-bit tier
+    sink: int = 0                 # the first `sink` tokens of a sequence stay in full precision for good (Appendix E)
 
     @property
     def g(self):
@@ -418,6 +419,9 @@ class OracleCache:
         self.blocks = [[] for _ in range(P)]                       # QuantBlock lists
         self.res_k = np.zeros((P, cfg.R, cfg.D), dtype=np.float16)
         self.res_v = np.zeros((P, cfg.R, cfg.D), dtype=np.float16)
+        self.sink_k = np.zeros((P, cfg.sink, cfg.D), dtype=np.float16)
+        self.sink_v = np.zeros((P, cfg.sink, cfg.D), dtype=np.float16)
+        self.n_sink = 0
         self.n_res = 0
         self.n_quant = 0
         self.qacc = np.zeros((P, cfg.D), dtype=np.uint64)
@@ -487,9 +491,19 @@ class OracleCache:
         cfg = self.cfg
         B, Hkv, n, D = k_new.shape
         R = cfg.R
-        F = self.flush_count(n)
+        # the first cfg.sink tokens of the sequence go to the sink and never leave it
+        take = min(n, cfg.sink - self.n_sink)
+        F = self.flush_count(n - take)
         if self.n_quant + F * R > cfg.T_max:
             raise OverflowError("cache capacity exceeded")
+        if take:
+            for p in range(B * Hkv):
+                self.sink_k[p, self.n_sink:self.n_sink + take] = k_new[p // Hkv, p % Hkv, :take]
+                self.sink_v[p, self.n_sink:self.n_sink + take] = v_new[p // Hkv, p % Hkv, :take]
+            self.n_sink += take
+            k_new, v_new, n = k_new[:, :, take:], v_new[:, :, take:], n - take
+            if n == 0:
+                return
         for b in range(B):
             for j in range(Hkv):
                 p = b * Hkv + j
@@ -527,11 +541,11 @@ class OracleCache:
 
     # -- Eq. 1 over the mixed-precision cache ----------------------------------
     def dequantized(self, p: int):
-        """(K^, V^) in binary64 for pair p, [T, D] each: quantized tokens by Eq. 3,
-        residual tokens as stored."""
+        """(K^, V^) in binary64 for pair p, [T, D] each: sink tokens as stored,
+        quantized tokens by Eq. 3, residual tokens as stored."""
         cfg = self.cfg
-        Ks = [dequant_block_keys(cfg, blk) for blk in self.blocks[p]]
-        Vs = [dequant_block_values(cfg, blk) for blk in self.blocks[p]]
+        Ks = [self.sink_k[p, :self.n_sink].astype(np.float64)] + [dequant_block_keys(cfg, blk) for blk in self.blocks[p]]
+        Vs = [self.sink_v[p, :self.n_sink].astype(np.float64)] + [dequant_block_values(cfg, blk) for blk in self.blocks[p]]
         Ks.append(self.res_k[p, :self.n_res].astype(np.float64))
         Vs.append(self.res_v[p, :self.n_res].astype(np.float64))
         return np.concatenate(Ks, axis=0), np.concatenate(Vs, axis=0)

@@ -197,3 +197,45 @@ def test_value_words_hold_every_token_once(Gk, R, interleave):
         else:
             assert toks == list(range(16 * tg, 16 * tg + 16))
     assert np.all(seen == 1)
+
+
+@pytest.mark.parametrize("n", [1, 31, 32, 33, 48, 49, 100])
+@pytest.mark.parametrize("flush_mode", [0, 1])
+def test_sink_tokens_counts_and_contents(n, flush_mode):
+    """The first `sink` tokens never leave full precision (Appendix E fixes a sink length of 32); everything after
+    them follows the window / flush rules as if the sequence started there."""
+    rng = np.random.default_rng(40)
+    K, V = _kv(rng, n)
+    c = O.OracleCache(_cfg(sink=32, flush_mode=flush_mode))
+    for lo, hi in ((0, min(n, 5)), (min(n, 5), min(n, 40)), (min(n, 40), n)):     # chunks that straddle the sink's end
+        if hi > lo:
+            c.append(K[:, :, lo:hi], V[:, :, lo:hi])
+    assert c.n_sink == min(n, 32)
+    assert np.array_equal(c.sink_k[0, :c.n_sink], K[0, 0, :c.n_sink]) and np.array_equal(c.sink_v[0, :c.n_sink], V[0, 0, :c.n_sink])
+    rest = n - c.n_sink
+    plain = O.OracleCache(_cfg(flush_mode=flush_mode))
+    if rest:
+        plain.append(K[:, :, 32:], V[:, :, 32:])
+    assert (c.n_quant, c.n_res) == (plain.n_quant, plain.n_res)
+    assert c.n_sink + c.n_quant + c.n_res == n
+    assert np.array_equal(c.res_k[0, :c.n_res], plain.res_k[0, :plain.n_res])
+    if c.n_quant:
+        assert np.array_equal(c.packed_blocks(), plain.packed_blocks())
+    Kh, Vh = c.dequantized(0)
+    assert Kh.shape == (n, 32) and np.array_equal(Kh[:c.n_sink], K[0, 0, :c.n_sink].astype(np.float64))
+
+
+def test_attention_is_exact_when_all_tokens_sit_in_sink_and_window():
+    rng = np.random.default_rng(41)
+    K, V = _kv(rng, 44)
+    c = O.OracleCache(_cfg(sink=32))
+    c.append(K, V)
+    assert (c.n_sink, c.n_quant, c.n_res) == (32, 0, 12)
+    q = rng.standard_normal((1, 2, 32)).astype(np.float16)
+    out, lse = c.decode_attention(q)
+    K64, V64 = K[0, 0].astype(np.float64), V[0, 0].astype(np.float64)
+    for h in range(2):
+        logits = K64 @ q[0, h].astype(np.float64) / np.sqrt(32.0)
+        w = np.exp(logits - logits.max())
+        assert np.allclose(out[0, h], (w / w.sum()) @ V64, rtol=1e-13, atol=1e-15)
+        assert np.isclose(lse[0, h], logits.max() + np.log(w.sum()), rtol=1e-13)
