@@ -55,6 +55,8 @@ typedef struct {
                          * quantizer), or S_d alone with score_mode 1.  Both >= 0 (infinity allowed), not NaN.  k16 and k4
                          * are then the record's capacity per block: if more channels pass a threshold, the best by (score,
                          * lower index) keep the tier and the others fall to the next tier down. */
+  int32_t sink;         /* the first `sink` tokens of every sequence stay in fp16 for good (the sink length of Appendix E);
+                         * 0, 32, 64, 96 or 128.  They are attended like the residual window and never quantized. */
 } mixkvq_config;
 
 #define MIXKVQ_NO_CHANNEL 255  /* unused entry of a channel list (policy 1) */
@@ -62,8 +64,8 @@ typedef struct {
 /* Bytes of each caller-owned device buffer. */
 typedef struct {
   uint64_t blocks;     /* [B*Hkv][T_max/R] block records, see mixkvq_block_layout */
-  uint64_t res_k;      /* [B*Hkv][R][D] fp16 residual keys   */
-  uint64_t res_v;      /* [B*Hkv][R][D] fp16 residual values */
+  uint64_t res_k;      /* [B*Hkv][sink + R][D] fp16 keys: per pair the sink rows, then the residual window */
+  uint64_t res_v;      /* [B*Hkv][sink + R][D] fp16 values likewise */
   uint64_t qacc;       /* [B*Hkv][D] u64 sums of |q| in units of 2^-24, then [B*Hkv] u64 counts */
   uint64_t workspace;  /* split-K partials and selection scratch */
 } mixkvq_sizes;
@@ -114,8 +116,8 @@ void mixkvq_cache_destroy(mixkvq_cache* c);
 /* Empties the cache (token counts to 0) and zeroes the |q| accumulator on `stream`. */
 int mixkvq_cache_reset(mixkvq_cache* c, void* stream);
 
-/* Host-only: quantized and residual token counts.  Either out pointer may be NULL. */
-int mixkvq_cache_state(const mixkvq_cache* c, int64_t* n_quantized, int32_t* n_residual);
+/* Host-only: quantized, residual-window and sink token counts.  Any out pointer may be NULL. */
+int mixkvq_cache_state(const mixkvq_cache* c, int64_t* n_quantized, int32_t* n_residual, int32_t* n_sink);
 
 /* Channel selection (Section 4.2, Eq. 6-8; top-k channel budget or thresholds, see mixkvq_config.policy).
  *   q  DEVICE fp16 [B][Hq][Lq][D] after rotary embedding, element strides q_strides = {batch, head, token},
@@ -134,7 +136,8 @@ int mixkvq_select_channels(mixkvq_cache* c, const void* q, int32_t Lq, const int
 /* Prefill (n_new = prompt length) and per-step (n_new = 1) append (Appendix D.1).
  *   k_new, v_new  DEVICE fp16 [B][Hkv][n_new][D], element strides kv_strides = {batch, head, token}.
  *   sel           DEVICE u8 [B][Hkv][k16+k4] or NULL.
- * Tokens enter the fp16 residual window; whole R-token blocks leave it per flush_mode and are quantized
+ * The first cfg.sink tokens of a sequence go to the sink and stay there.  Later tokens enter the fp16 residual window;
+ * whole R-token blocks leave it per flush_mode and are quantized
  * (Eq. 2: keys per channel in groups of Gk tokens, 2 bit, the selected channels at 4 bit or fp16; values per
  * token in groups of Gv channels, 2 bit) into block records.  With sel != NULL every block flushed by this
  * call uses that selection; with sel == NULL each block is scored from the accumulator and its own R tokens.

@@ -23,7 +23,7 @@ EXPORTS = ("mixkvq_block_layout", "mixkvq_cache_sizes", "mixkvq_cache_create", "
 class Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("B", "Hq", "Hkv", "D", "T_max", "Gk", "Gv", "R", "k4", "k16",
                                          "flush_mode", "score_mode", "qacc_reset_on_flush", "policy")] + \
-               [("tau16", C.c_double), ("tau4", C.c_double)]
+               [("tau16", C.c_double), ("tau4", C.c_double), ("sink", C.c_int32)]
 
 
 class Sizes(C.Structure):
@@ -66,7 +66,7 @@ def load_library() -> C.CDLL:
     lib.mixkvq_cache_destroy.argtypes = [vp]
     lib.mixkvq_cache_destroy.restype = None
     lib.mixkvq_cache_reset.argtypes = [vp, vp]
-    lib.mixkvq_cache_state.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
+    lib.mixkvq_cache_state.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.mixkvq_select_channels.argtypes = [vp, vp, i32, i64p, vp, i32, i64p, vp, vp]
     lib.mixkvq_quantize_append.argtypes = [vp, vp, vp, i32, i64p, vp, vp]
     lib.mixkvq_decode_attention.argtypes = [vp, vp, vp, vp, C.c_float, i32, vp]
@@ -150,9 +150,15 @@ class Cache:
         _check(self.lib.mixkvq_cache_reset(self.handle, _stream_ptr(stream)))
 
     def state(self):
+        """(quantized tokens, tokens in the residual window)."""
         nq, r = C.c_int64(), C.c_int32()
-        _check(self.lib.mixkvq_cache_state(self.handle, C.byref(nq), C.byref(r)))
+        _check(self.lib.mixkvq_cache_state(self.handle, C.byref(nq), C.byref(r), None))
         return nq.value, r.value
+
+    def sink_count(self) -> int:
+        n = C.c_int32()
+        _check(self.lib.mixkvq_cache_state(self.handle, None, None, C.byref(n)))
+        return n.value
 
     def select_channels(self, q, k, sel=None, stream=None):
         """q: fp16 [B, Hq, Lq, D] or None; k: fp16 [B, Hkv, L, D].  Returns u8 [B, Hkv, ks] on the device."""
@@ -205,11 +211,21 @@ class Cache:
         n = P * NB * self.layout.rec_bytes
         return self.blocks[:n].view(P, NB, self.layout.rec_bytes)
 
-    def residual(self):
+    def fp16_rows(self):
+        """fp16 views [P, sink + R, D] of the key and value rows kept in full precision (sink rows first)."""
         P = self.cfg.B * self.cfg.Hkv
-        n = P * self.cfg.R * self.cfg.D * 2
-        shape = (P, self.cfg.R, self.cfg.D)
+        rows = self.cfg.sink + self.cfg.R
+        n = P * rows * self.cfg.D * 2
+        shape = (P, rows, self.cfg.D)
         return self.res_k[:n].view(torch.float16).view(shape), self.res_v[:n].view(torch.float16).view(shape)
+
+    def residual(self):
+        k, v = self.fp16_rows()
+        return k[:, self.cfg.sink:], v[:, self.cfg.sink:]
+
+    def sink(self):
+        k, v = self.fp16_rows()
+        return k[:, :self.cfg.sink], v[:, :self.cfg.sink]
 
     def query_accumulator(self):
         P = self.cfg.B * self.cfg.Hkv

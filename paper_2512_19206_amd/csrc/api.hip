@@ -35,6 +35,7 @@ int compute_layout(const mixkvq_config& c, Layout* out) {
   if ((int64_t)c.B * c.Hkv > (1 << 20)) return MIXKVQ_EINVAL;
   if (c.policy < 0 || c.policy > 1) return MIXKVQ_EINVAL;
   if (c.policy == 1 && !(c.tau16 >= 0.0 && c.tau4 >= 0.0)) return MIXKVQ_EINVAL;   // also rejects NaN
+  if (c.sink < 0 || c.sink > 128 || c.sink % 32 != 0) return MIXKVQ_EINVAL;
   Layout l;
   memset(&l, 0, sizeof(l));
   const int ks = c.k4 + c.k16;
@@ -82,6 +83,7 @@ struct mixkvq_cache {
   CacheView v;
   int64_t n_quant;
   int32_t n_res;
+  int32_t n_sink;
   hipEvent_t ev_start = nullptr, ev_stop = nullptr;   // optional timing of the split kernel
 };
 
@@ -103,7 +105,7 @@ int mixkvq_cache_sizes(const mixkvq_config* cfg, mixkvq_sizes* out) {
   if (rc != MIXKVQ_OK) return rc;
   const uint64_t P = (uint64_t)cfg->B * cfg->Hkv;
   out->blocks = al256(P * (uint64_t)(cfg->T_max / cfg->R) * (uint64_t)l.rec_bytes);
-  out->res_k = al256(P * (uint64_t)cfg->R * cfg->D * 2);
+  out->res_k = al256(P * (uint64_t)(cfg->R + cfg->sink) * cfg->D * 2);
   out->res_v = out->res_k;
   out->qacc = al256(P * (uint64_t)(cfg->D + 1) * 8);
   uint64_t a = decode_workspace_bytes(*cfg), b = select_workspace_bytes(*cfg);
@@ -126,6 +128,8 @@ int mixkvq_cache_create(const mixkvq_config* cfg, const mixkvq_buffers* bufs, mi
   c->v.P = cfg->B * cfg->Hkv;
   c->v.g = cfg->Hq / cfg->Hkv;
   c->v.NB = cfg->T_max / cfg->R;
+  c->v.S = cfg->sink;
+  c->v.RW = cfg->sink + cfg->R;
   c->v.blocks = (uint8_t*)bufs->blocks;
   c->v.res_k = (__half*)bufs->res_k;
   c->v.res_v = (__half*)bufs->res_v;
@@ -134,6 +138,7 @@ int mixkvq_cache_create(const mixkvq_config* cfg, const mixkvq_buffers* bufs, mi
   c->v.ws = (uint8_t*)bufs->workspace;
   c->n_quant = 0;
   c->n_res = 0;
+  c->n_sink = 0;
   *out = c;
   return MIXKVQ_OK;
 }
@@ -145,13 +150,15 @@ int mixkvq_cache_reset(mixkvq_cache* c, void* stream) {
   MIXKVQ_TRY_HIP(launch_zero_qacc(c->v, (hipStream_t)stream));
   c->n_quant = 0;
   c->n_res = 0;
+  c->n_sink = 0;
   return MIXKVQ_OK;
 }
 
-int mixkvq_cache_state(const mixkvq_cache* c, int64_t* n_quantized, int32_t* n_residual) {
+int mixkvq_cache_state(const mixkvq_cache* c, int64_t* n_quantized, int32_t* n_residual, int32_t* n_sink) {
   if (!c) return MIXKVQ_EINVAL;
   if (n_quantized) *n_quantized = c->n_quant;
   if (n_residual) *n_residual = c->n_res;
+  if (n_sink) *n_sink = c->n_sink;
   return MIXKVQ_OK;
 }
 
@@ -180,8 +187,11 @@ int mixkvq_quantize_append(mixkvq_cache* c, const void* k_new, const void* v_new
   for (int i = 0; i < 3; ++i)
     if (kv_strides[i] % 8 != 0) return MIXKVQ_EINVAL;
   const mixkvq_config& cfg = c->v.cfg;
-  const int R = cfg.R;
-  const int64_t total = (int64_t)c->n_res + n_new;
+  const int R = cfg.R, S = cfg.sink;
+  // the first S tokens of the sequence go to the sink; the others take the window / flush path below
+  const int take = c->n_sink < S ? (n_new < S - c->n_sink ? n_new : S - c->n_sink) : 0;
+  const int n_win = n_new - take;
+  const int64_t total = (int64_t)c->n_res + n_win;
   // Deferred: a full window is flushed just before the next token enters, so 1..R tokens remain.
   // Eager: a window is flushed as soon as it is full, so 0..R-1 tokens remain.
   int64_t F = cfg.flush_mode == 0 ? (total + R - 1) / R - 1 : total / R;
@@ -190,20 +200,27 @@ int mixkvq_quantize_append(mixkvq_cache* c, const void* k_new, const void* v_new
   if (F > (1 << 24)) return MIXKVQ_EINVAL;
   hipStream_t s = (hipStream_t)stream;
   Strides3 kvs{kv_strides[0], kv_strides[1], kv_strides[2]};
+  if (take > 0) {
+    MIXKVQ_TRY_HIP(launch_residual_copy(c->v, (const __half*)k_new, (const __half*)v_new, kvs, 0, c->n_sink, take, s));
+    c->n_sink += take;
+    if (n_win == 0) return MIXKVQ_OK;
+  }
+  // from here on "new tokens" are the n_win tokens after the sink's share (strides are multiples of 8 elements,
+  // so the shifted pointers keep their 16-byte alignment)
+  const __half* kw = (const __half*)k_new + (int64_t)take * kvs.t;
+  const __half* vw = (const __half*)v_new + (int64_t)take * kvs.t;
   const int r0 = c->n_res;
   if (F > 0) {
-    MIXKVQ_TRY_HIP(launch_flush(c->v, (const __half*)k_new, (const __half*)v_new, kvs, r0,
-                                (int)(c->n_quant / R), (int)F, sel, s));
+    MIXKVQ_TRY_HIP(launch_flush(c->v, kw, vw, kvs, r0, (int)(c->n_quant / R), (int)F, sel, s));
   }
   // Tokens that stay in the window.  Stream position x of (old residual ++ new tokens) maps to
   // new-token index x - r0; after F flushes positions [F*R, total) remain.
   const int64_t rest_first = F * R;
   const int n_rest = (int)(total - rest_first);
   if (F == 0) {
-    MIXKVQ_TRY_HIP(launch_residual_copy(c->v, (const __half*)k_new, (const __half*)v_new, kvs, 0, r0, n_new, s));
+    MIXKVQ_TRY_HIP(launch_residual_copy(c->v, kw, vw, kvs, 0, S + r0, n_win, s));
   } else if (n_rest > 0) {
-    MIXKVQ_TRY_HIP(launch_residual_copy(c->v, (const __half*)k_new, (const __half*)v_new, kvs,
-                                        (int)(rest_first - r0), 0, n_rest, s));
+    MIXKVQ_TRY_HIP(launch_residual_copy(c->v, kw, vw, kvs, (int)(rest_first - r0), S, n_rest, s));
   }
   if (F > 0 && cfg.qacc_reset_on_flush) MIXKVQ_TRY_HIP(launch_zero_qacc(c->v, s));
   c->n_quant += F * R;
@@ -214,12 +231,12 @@ int mixkvq_quantize_append(mixkvq_cache* c, const void* k_new, const void* v_new
 int mixkvq_decode_attention(mixkvq_cache* c, const void* q, void* out, float* lse, float scale,
                             int32_t accumulate_q, void* stream) {
   if (!c || !q || !out) return MIXKVQ_EINVAL;
-  if (c->n_quant == 0 && c->n_res == 0) return MIXKVQ_EEMPTY;
+  if (c->n_quant == 0 && c->n_res == 0 && c->n_sink == 0) return MIXKVQ_EEMPTY;
   const mixkvq_config& cfg = c->v.cfg;
   hipStream_t s = (hipStream_t)stream;
   if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)cfg.D);
   MIXKVQ_TRY_HIP(launch_decode(c->v, (const __half*)q, (__half*)out, lse, scale, (int)(c->n_quant / cfg.R),
-                               c->n_res, accumulate_q, NewToken{nullptr, nullptr, {0, 0, 0}, 0}, s, c->ev_start,
+                               c->n_sink + c->n_res, accumulate_q, NewToken{nullptr, nullptr, {0, 0, 0}, 0}, s, c->ev_start,
                                c->ev_stop));
   return MIXKVQ_OK;
 }
@@ -234,7 +251,7 @@ int mixkvq_decode_step(mixkvq_cache* c, const void* k_new, const void* v_new, co
   const int R = cfg.R;
   const int total = c->n_res + 1;
   const bool flushes = cfg.flush_mode == 0 ? total > R : total >= R;
-  if (flushes) {   // the append flushes a block: take the general path for it
+  if (flushes || c->n_sink < cfg.sink) {   // the append flushes a block or feeds the sink: take the general path for it
     int rc = mixkvq_quantize_append(c, k_new, v_new, 1, kv_strides, nullptr, stream);
     if (rc != MIXKVQ_OK) return rc;
     return mixkvq_decode_attention(c, q, out, lse, scale, accumulate_q, stream);
@@ -242,8 +259,9 @@ int mixkvq_decode_step(mixkvq_cache* c, const void* k_new, const void* v_new, co
   hipStream_t s = (hipStream_t)stream;
   if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)cfg.D);
   NewToken nt{(const __half*)k_new, (const __half*)v_new, Strides3{kv_strides[0], kv_strides[1], kv_strides[2]},
-              c->n_res};
-  MIXKVQ_TRY_HIP(launch_decode(c->v, (const __half*)q, (__half*)out, lse, scale, (int)(c->n_quant / R), total,
+              cfg.sink + c->n_res};
+  MIXKVQ_TRY_HIP(launch_decode(c->v, (const __half*)q, (__half*)out, lse, scale, (int)(c->n_quant / R),
+                               cfg.sink + total,
                                accumulate_q, nt, s, c->ev_start, c->ev_stop));
   c->n_res = total;
   return MIXKVQ_OK;

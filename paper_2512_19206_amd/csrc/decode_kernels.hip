@@ -23,7 +23,7 @@ size_t decode_workspace_bytes(const mixkvq_config& c) { return decode_partials_b
 // softmax update, (channel, head-half) for P.V.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(kDecThreads)
-decode_split_kernel(CacheView cv, const __half* __restrict__ q, float scale, int n_blocks, int n_res, int n_splits,
+decode_split_kernel(CacheView cv, const __half* __restrict__ q, float scale, int n_blocks, int n_fp16, int n_splits,
                     float* __restrict__ part) {
   __shared__ __align__(16) unsigned char sRec[kMaxRec];
   __shared__ float sQ[kMaxG][kD];
@@ -49,12 +49,16 @@ decode_split_kernel(CacheView cv, const __half* __restrict__ q, float scale, int
 
   const int blk0 = (int)((long long)n_blocks * split / n_splits);
   const int blk1 = (int)((long long)n_blocks * (split + 1) / n_splits);
-  const bool owns_res = (split == n_splits - 1) && n_res > 0;
-  const int n_iter = (blk1 - blk0) + (owns_res ? 1 : 0);
+  // the last split also takes the fp16 rows (sink, then residual window) in chunks of up to kMaxR tokens
+  const int n_chunks = (split == n_splits - 1) ? (n_fp16 + kMaxR - 1) / kMaxR : 0;
+  const int n_iter = (blk1 - blk0) + n_chunks;
+  const __half* fk = cv.res_k + (size_t)p * cv.RW * kD;
+  const __half* fv = cv.res_v + (size_t)p * cv.RW * kD;
 
   for (int it = 0; it < n_iter; ++it) {
-    const bool is_res = it == blk1 - blk0;
-    const int nt = is_res ? n_res : R;
+    const bool is_res = it >= blk1 - blk0;
+    const int row0 = is_res ? (it - (blk1 - blk0)) * kMaxR : 0;       // first fp16 row of this chunk
+    const int nt = is_res ? (n_fp16 - row0 < kMaxR ? n_fp16 - row0 : kMaxR) : R;
     __syncthreads();
     const uint8_t* rec = cv.blocks + ((size_t)p * cv.NB + blk0 + it) * lay.rec_bytes;
     if (!is_res) {
@@ -82,7 +86,7 @@ decode_split_kernel(CacheView cv, const __half* __restrict__ q, float scale, int
       const int t = lane_lo;
       float s[4] = {0.f, 0.f, 0.f, 0.f};
       if (is_res) {
-        const __half* row = cv.res_k + ((size_t)p * R + t) * kD;
+        const __half* row = fk + (size_t)(row0 + t) * kD;
         for (int d = 0; d < kD; ++d) {
           const float kv = __half2float(row[d]);
 #pragma unroll
@@ -159,7 +163,7 @@ decode_split_kernel(CacheView cv, const __half* __restrict__ q, float scale, int
       for (int i = 0; i < 4; ++i) acc[i] *= sAlpha[(h0 + i) & 7];
       if (is_res) {
         for (int t = 0; t < nt; ++t) {
-          const float vv = __half2float(cv.res_v[((size_t)p * R + t) * kD + d]);
+          const float vv = __half2float(fv[(size_t)(row0 + t) * kD + d]);
 #pragma unroll
           for (int i = 0; i < 4; ++i) acc[i] += sP[(h0 + i) & 7][t] * vv;
         }
@@ -225,7 +229,7 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
                             hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop, hipError_t* err);
 
 hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float* lse, float scale, int n_blocks,
-                         int n_res, int accumulate_q, NewToken nt, hipStream_t s, hipEvent_t ev_start,
+                         int n_fp16, int accumulate_q, NewToken nt, hipStream_t s, hipEvent_t ev_start,
                          hipEvent_t ev_stop) {
   // split count: enough workgroups to fill the chip (tunable through MIXKVQ_DECODE_WGS for experiments),
   // never above the ceiling the workspace was sized for
@@ -240,9 +244,13 @@ hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float
   if (n_splits < 1) n_splits = 1;
   float* part = reinterpret_cast<float*>(v.ws);
   hipError_t e = hipSuccess;
-  // matrix-core path: one launch (n_splits partials from the quantized blocks, one from the residual
-  // window, merged by the last workgroup of each pair)
-  if (try_launch_decode_mfma(v, q, scale, n_blocks, n_res, n_splits, part, out, lse, accumulate_q, nt, s,
+  // matrix-core path: the fp16 rows are cut into sub-units of 32 tokens and a wavefront takes at most one of them,
+  // so a pair needs at least as many wavefronts (4 per workgroup) as it has sub-units
+  int n_splits_mc = n_splits;
+  const int min_splits = ((n_fp16 + 31) / 32 + 3) / 4;
+  if (n_splits_mc < min_splits) n_splits_mc = min_splits;
+  if (n_splits_mc <= max_splits_for(v.P) &&
+      try_launch_decode_mfma(v, q, scale, n_blocks, n_fp16, n_splits_mc, part, out, lse, accumulate_q, nt, s,
                              ev_start, ev_stop, &e))
     return e;
   if (nt.k) {   // this path does not move the new token itself
@@ -255,7 +263,7 @@ hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float
     if (e != hipSuccess) return e;
   }
   if (ev_start) (void)hipEventRecord(ev_start, s);
-  decode_split_kernel<<<dim3(v.P, n_splits), dim3(kDecThreads), 0, s>>>(v, q, scale, n_blocks, n_res, n_splits, part);
+  decode_split_kernel<<<dim3(v.P, n_splits), dim3(kDecThreads), 0, s>>>(v, q, scale, n_blocks, n_fp16, n_splits, part);
   if (ev_stop) (void)hipEventRecord(ev_stop, s);
   decode_merge_kernel<<<dim3(v.cfg.B * v.cfg.Hq), dim3(kD), 0, s>>>(part, n_splits, v.g, v.cfg.Hq, out, lse);
   return hipGetLastError();

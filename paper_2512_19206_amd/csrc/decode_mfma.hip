@@ -291,11 +291,12 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   const int blk_lo = gw;
   const int blk_hi = n_blocks;
   const int blk_step = n_gw;
-  // residual window: sub-units of 32 tokens follow the records in the same round-robin deal
-  const int n_sub = (n_res + 31) >> 5;
+  // fp16 rows (sink tokens, then the residual window; n_res counts both): sub-units of 32 tokens follow the
+  // records in the same round-robin deal
+  const int n_sub = (n_res + 31) >> 5;     // <= 8 (sink + window <= 256 rows) and <= n_gw (the launcher sees to it)
   int my_sub = -1;
 #pragma unroll
-  for (int j = 0; j < 4; ++j)
+  for (int j = 0; j < 8; ++j)
     if (j < n_sub && (n_blocks + j) % n_gw == gw) my_sub = j;
   // one wavefront per pair (the next in the deal, never one with a sub-unit unless the pair has a single
   // workgroup) stores this step's new token and adds |q| to the accumulator
@@ -504,8 +505,8 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   const int tokb = 8 * (n >> 2) + 2 * (n & 3);      // A-row n of tile x: token sub_t0 + tokb + x
   u32x4 kr[2][4], vr[8];
   if (my_sub >= 0) {
-    const __half* rk = cv.res_k + (size_t)p * R * kD;
-    const __half* rv = cv.res_v + (size_t)p * R * kD;
+    const __half* rk = cv.res_k + (size_t)p * cv.RW * kD;     // the pair's fp16 rows: sink, then residual window
+    const __half* rv = cv.res_v + (size_t)p * cv.RW * kD;
     const int64_t nt_off = (int64_t)b * nt.st.b + (int64_t)jkv * nt.st.h;
 #pragma unroll
     for (int x = 0; x < 2; ++x) {
@@ -550,7 +551,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   MIXKVQ_PHASE(1)
   if (bookkeeper) {   // the new token enters the window; |q| of this step joins the accumulator (one writer per pair)
     if (nt.k && lane < 32) {
-      const size_t dst = ((size_t)p * R + nt.row) * kD + (lane & 15) * 8;
+      const size_t dst = ((size_t)p * cv.RW + nt.row) * kD + (lane & 15) * 8;
       *reinterpret_cast<uint4*>((lane < 16 ? cv.res_k : cv.res_v) + dst) = nt_row;
     }
     if (accumulate_q) {

@@ -18,7 +18,7 @@ struct Layout : mixkvq_block_layout_t {};
 
 struct Strides3 { int64_t b, h, t; };
 
-// One new token per sequence that the decode launch itself moves into residual-window row `row`
+// One new token per sequence that the decode launch itself moves into fp16 row `row` of every pair
 // (k == nullptr: none).
 struct NewToken { const __half* k; const __half* v; Strides3 st; int row; };
 
@@ -29,8 +29,10 @@ struct CacheView {
   int32_t P;             // B * Hkv
   int32_t g;             // Hq / Hkv
   int32_t NB;            // block capacity per pair = T_max / R
+  int32_t S;             // sink rows per pair (cfg.sink)
+  int32_t RW;            // fp16 rows per pair = S + R: the sink rows, then the residual window
   uint8_t* blocks;       // [P][NB][rec_bytes]
-  __half* res_k;         // [P][R][D]
+  __half* res_k;         // [P][RW][D]
   __half* res_v;
   unsigned long long* qacc;  // [P][D]
   unsigned long long* qcnt;  // [P]
@@ -46,10 +48,14 @@ hipError_t launch_qabs_accumulate(const CacheView& v, const __half* q, int Lq, S
 hipError_t launch_select(const CacheView& v, const __half* k, int L, Strides3 ks, uint8_t* sel, hipStream_t s);
 hipError_t launch_flush(const CacheView& v, const __half* k_new, const __half* v_new, Strides3 kvs,
                         int r0, int first_block, int n_flush, const uint8_t* sel, hipStream_t s);
+// n tokens starting at new-token index src_first go to fp16 rows dst_row.. of every pair (row 0 = first sink row,
+// row S = first row of the residual window)
 hipError_t launch_residual_copy(const CacheView& v, const __half* k_new, const __half* v_new, Strides3 kvs,
-                                int src_first, int dst_first, int n, hipStream_t s);
+                                int src_first, int dst_row, int n, hipStream_t s);
+// n_fp16: fp16 tokens of every pair = rows [0, n_fp16) of its fp16 rows (the sink, then the window; the window only
+// holds tokens once the sink is full, so the rows in use are contiguous)
 hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float* lse, float scale,
-                         int n_blocks, int n_res, int accumulate_q, NewToken nt, hipStream_t s, hipEvent_t ev_start,
+                         int n_blocks, int n_fp16, int accumulate_q, NewToken nt, hipStream_t s, hipEvent_t ev_start,
                          hipEvent_t ev_stop);
 
 size_t decode_workspace_bytes(const mixkvq_config& c);

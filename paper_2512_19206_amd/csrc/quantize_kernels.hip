@@ -41,21 +41,26 @@ __device__ __forceinline__ unsigned encode(float x, float z, float s, float top)
   return (unsigned)c;
 }
 
+// First row of pair p's residual window inside the pair's fp16 rows (the sink rows come first).
+__device__ __forceinline__ const __half* window_rows(const CacheView& cv, const __half* res, int p) {
+  return res + ((size_t)p * cv.RW + cv.S) * kD;
+}
+
 // Token `i` of the block being flushed: stream position pos = f*R + i of
-// (old residual ++ new tokens); positions < r0 live in the residual window.
-__device__ __forceinline__ const __half* token_row(const __half* res, const __half* fresh, Strides3 st, int p, int Hkv,
-                                                  int R, int r0, int pos) {
-  if (pos < r0) return res + ((size_t)p * R + pos) * kD;
+// (old residual ++ new tokens); positions < r0 live in the residual window `win` of the pair.
+__device__ __forceinline__ const __half* token_row(const __half* win, const __half* fresh, Strides3 st, int p, int Hkv,
+                                                  int r0, int pos) {
+  if (pos < r0) return win + (size_t)pos * kD;
   const int b = p / Hkv, j = p % Hkv;
   return fresh + (int64_t)b * st.b + (int64_t)j * st.h + (int64_t)(pos - r0) * st.t;
 }
 
-__device__ __forceinline__ void load_tile(__half* sT, const __half* res, const __half* fresh, Strides3 st, int p, int Hkv,
+__device__ __forceinline__ void load_tile(__half* sT, const __half* win, const __half* fresh, Strides3 st, int p, int Hkv,
                                           int R, int r0, int pos0) {
   // R rows of 256 bytes; 16 threads per row, 16 bytes each
   for (int idx = threadIdx.x; idx < R * 16; idx += kFlushThreads) {
     const int t = idx >> 4, c = idx & 15;
-    const __half* row = token_row(res, fresh, st, p, Hkv, R, r0, pos0 + t);
+    const __half* row = token_row(win, fresh, st, p, Hkv, r0, pos0 + t);
     uint4 v = *reinterpret_cast<const uint4*>(row + c * 8);
     *reinterpret_cast<uint4*>(sT + t * kRowStride + c * 8) = v;
   }
@@ -86,7 +91,7 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
   for (int i = tid; i < lay.off_klo / 4; i += kFlushThreads)
     reinterpret_cast<unsigned*>(rec)[i] = (cfg.policy == 1 && i < ks / 4) ? 0xffffffffu : 0u;
 
-  load_tile(sT, cv.res_k, k_new, st, p, cfg.Hkv, R, r0, f * R);
+  load_tile(sT, window_rows(cv, cv.res_k, p), k_new, st, p, cfg.Hkv, R, r0, f * R);
   if (tid < 8) sKmax[tid] = 0u;
   __syncthreads();
 
@@ -210,7 +215,7 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
   __syncthreads();
 
   // ---- values -----------------------------------------------------------------
-  load_tile(sT, cv.res_v, v_new, st, p, cfg.Hkv, R, r0, f * R);
+  load_tile(sT, window_rows(cv, cv.res_v, p), v_new, st, p, cfg.Hkv, R, r0, f * R);
   __syncthreads();
   const int NVG = lay.NVG;
   float* sVS = sS;   // [token][NVG] (R * NVG <= 128 * 8)
@@ -339,8 +344,8 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   // ---- both tiles: every load in flight ------------------------------------------------------
   uint4 kreg[8], vreg[8];
   const int64_t pair_off = (int64_t)(p / Hkv) * st.b + (int64_t)(p % Hkv) * st.h;
-  const __half* res_kp = cv.res_k + (size_t)p * R * kD;
-  const __half* res_vp = cv.res_v + (size_t)p * R * kD;
+  const __half* res_kp = window_rows(cv, cv.res_k, p);
+  const __half* res_vp = window_rows(cv, cv.res_v, p);
   const int pos0 = f * R;
   if (pos0 >= r0 || pos0 + R <= r0) {
     // the usual case: the whole tile comes from one place, rows a constant stride apart
@@ -714,27 +719,27 @@ hipError_t launch_flush(const CacheView& v, const __half* k_new, const __half* v
 }
 
 // ---------------------------------------------------------------------------
-// residual-window copy: n tokens starting at new-token index src_first go to
-// window rows dst_first.. of every pair.
+// copy into the fp16 rows: n tokens starting at new-token index src_first go to rows dst_row.. of every pair
+// (row 0 = first sink row, row S = first row of the residual window).
 // ---------------------------------------------------------------------------
 __global__ void residual_copy_kernel(CacheView cv, const __half* __restrict__ k_new, const __half* __restrict__ v_new,
-                                     Strides3 st, int src_first, int dst_first, int n) {
+                                     Strides3 st, int src_first, int dst_row, int n) {
   const int p = blockIdx.x, b = p / cv.cfg.Hkv, j = p % cv.cfg.Hkv;
   for (int idx = blockIdx.y * blockDim.x + threadIdx.x; idx < n * 16; idx += gridDim.y * blockDim.x) {
     const int t = idx >> 4, c = idx & 15;
     const int64_t src = (int64_t)b * st.b + (int64_t)j * st.h + (int64_t)(src_first + t) * st.t + c * 8;
-    const size_t dst = ((size_t)p * cv.cfg.R + dst_first + t) * kD + c * 8;
+    const size_t dst = ((size_t)p * cv.RW + dst_row + t) * kD + c * 8;
     *reinterpret_cast<uint4*>(cv.res_k + dst) = *reinterpret_cast<const uint4*>(k_new + src);
     *reinterpret_cast<uint4*>(cv.res_v + dst) = *reinterpret_cast<const uint4*>(v_new + src);
   }
 }
 
 hipError_t launch_residual_copy(const CacheView& v, const __half* k_new, const __half* v_new, Strides3 kvs,
-                                int src_first, int dst_first, int n, hipStream_t s) {
+                                int src_first, int dst_row, int n, hipStream_t s) {
   const int threads = n * 16 < 256 ? 64 : 256;
   int gy = (n * 16 + threads - 1) / threads;
   if (gy > 8) gy = 8;
-  residual_copy_kernel<<<dim3(v.P, gy), dim3(threads), 0, s>>>(v, k_new, v_new, kvs, src_first, dst_first, n);
+  residual_copy_kernel<<<dim3(v.P, gy), dim3(threads), 0, s>>>(v, k_new, v_new, kvs, src_first, dst_row, n);
   return hipGetLastError();
 }
 

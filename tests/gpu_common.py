@@ -36,6 +36,12 @@ def check_state(oc: O.OracleCache, gc: M.Cache, check_qacc=True):
             plane = max((o, n) for n, o in planes if o <= off)[1]
             raise AssertionError(f"{len(bad)} record bytes differ; first at pair {p} block {b} byte {off} ({plane}): "
                                  f"gpu {got[p, b, off]} oracle {ref[p, b, off]}")
+    ns = gc.sink_count()
+    assert ns == oc.n_sink
+    if ns:
+        sk, sv = gc.sink()
+        assert np.array_equal(sk[:, :ns].cpu().numpy().view(np.uint16), oc.sink_k[:, :ns].view(np.uint16))
+        assert np.array_equal(sv[:, :ns].cpu().numpy().view(np.uint16), oc.sink_v[:, :ns].view(np.uint16))
     if r:
         rk, rv = gc.residual()
         assert np.array_equal(rk[:, :r].cpu().numpy().view(np.uint16), oc.res_k[:, :r].view(np.uint16))

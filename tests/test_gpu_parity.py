@@ -247,6 +247,46 @@ def test_key_groups_of_32_tokens(H, R, Gv, k4, k16, g, policy):
     assert oc.n_flush_calls >= 4
 
 
+@pytest.mark.parametrize("R,Gk,sink,k4,g,flush_mode", [(128, 128, 32, 16, 7, 0), (64, 64, 128, 16, 5, 0), (128, 32, 64, 8, 8, 1),
+                                                      (32, 32, 32, 8, 3, 0), (128, 128, 128, 0, 2, 0)])
+def test_sink_tokens(H, R, Gk, sink, k4, g, flush_mode):
+    """The first `sink` tokens stay in fp16 (Appendix E): token by token while the sink fills, a prefill chunk that
+    straddles its end, then decode steps across flushes."""
+    rng = np.random.default_rng(500 + R + sink)
+    B, Hkv = 2, 2
+    kw = dict(B=B, Hq=Hkv * g, Hkv=Hkv, D=128, T_max=6 * R, Gk=Gk, Gv=128, R=R, k4=k4, k16=0, sink=sink,
+              flush_mode=flush_mode)
+    oc, gc = H.make_pair(**kw)
+    n0 = sink + 2 * R + 9
+    K = (rng.standard_normal((B, Hkv, n0, 128)) * rng.uniform(0.3, 8, 128)).astype(np.float16)
+    V = rng.standard_normal((B, Hkv, n0, 128)).astype(np.float16)
+
+    def step(k1, v1):
+        q1 = (rng.standard_normal((B, Hkv * g, 128)) * rng.uniform(0.2, 5, 128)).astype(np.float16)
+        oc.append(k1, v1)
+        ro, rl = oc.decode_attention(q1, accumulate_q=True)
+        out, lse = gc.decode_step(H.dev(k1), H.dev(v1), H.dev(q1), accumulate_q=True)
+        torch.cuda.synchronize()
+        err = np.abs(out.float().cpu().numpy() - ro)
+        assert np.all(err <= H.ATOL + H.RTOL * np.abs(ro)), float(err.max())
+        assert np.all(np.abs(lse.cpu().numpy() - rl) <= H.LSE_ATOL + 1e-4 * np.abs(rl))
+
+    for t in range(5):                       # the sink fills token by token
+        step(K[:, :, t:t + 1], V[:, :, t:t + 1])
+    H.check_state(oc, gc)
+    assert gc.sink_count() == 5 and gc.state() == (0, 0)
+    oc.append(K[:, :, 5:], V[:, :, 5:])      # the rest of the sink, whole blocks and a window in one call
+    gc.quantize_append(H.dev(K)[:, :, 5:], H.dev(V)[:, :, 5:])
+    H.check_state(oc, gc)
+    assert gc.sink_count() == sink
+    for t in range(R + 3):
+        k1 = (rng.standard_normal((B, Hkv, 1, 128)) * rng.uniform(0.3, 8, 128)).astype(np.float16)
+        v1 = rng.standard_normal((B, Hkv, 1, 128)).astype(np.float16)
+        step(k1, v1)
+    H.check_state(oc, gc)
+    assert oc.n_sink + oc.n_quant + oc.n_res == n0 + R + 3
+
+
 def test_chunked_append_without_selection_matches_oracle(H):
     """sel = NULL on a multi-token append: every flushed block is scored on its own."""
     rng = np.random.default_rng(8)

@@ -48,6 +48,7 @@ CONFIGS = [
     dict(B=1, Hq=2, Hkv=2, D=128, T_max=128, Gk=64, Gv=64, R=128, k4=0, k16=0),
     dict(B=2, Hq=14, Hkv=2, D=128, T_max=512, Gk=128, Gv=128, R=128, k4=16, k16=8, policy=1, tau16=1.44, tau4=0.79),
     dict(B=2, Hq=14, Hkv=2, D=128, T_max=512, Gk=32, Gv=32, R=128, k4=16, k16=0),
+    dict(B=2, Hq=14, Hkv=2, D=128, T_max=512, Gk=32, Gv=32, R=128, k4=16, k16=0, sink=32),
     dict(B=1, Hq=5, Hkv=1, D=128, T_max=64, Gk=32, Gv=32, R=32, k4=8, k16=4, policy=1, tau16=0.0, tau4=float("inf")),
 ]
 
@@ -66,7 +67,7 @@ def test_buffer_sizes(M, kw):
     sz, lay = M.cache_sizes(cfg), M.block_layout(cfg)
     P = kw["B"] * kw["Hkv"]
     assert sz.blocks >= P * (kw["T_max"] // kw["R"]) * lay.rec_bytes
-    assert sz.res_k >= P * kw["R"] * 128 * 2 and sz.res_v == sz.res_k
+    assert sz.res_k >= P * (kw["R"] + kw.get("sink", 0)) * 128 * 2 and sz.res_v == sz.res_k
     assert sz.qacc >= P * 129 * 8
     assert sz.workspace >= P * 128 * 16
     for f in ("blocks", "res_k", "res_v", "qacc", "workspace"):
@@ -77,7 +78,7 @@ def test_buffer_sizes(M, kw):
     dict(D=64), dict(Hq=3, Hkv=2), dict(Hq=18, Hkv=2), dict(R=24), dict(R=256, T_max=256), dict(Gk=48),
     dict(Gv=24), dict(k4=4), dict(k16=2), dict(k4=64, k16=64), dict(T_max=100), dict(flush_mode=2),
     dict(score_mode=-1), dict(B=0), dict(policy=2), dict(policy=1, tau16=-0.5, tau4=1.0),
-    dict(policy=1, tau16=1.0, tau4=float("nan")),
+    dict(policy=1, tau16=1.0, tau4=float("nan")), dict(sink=16), dict(sink=160), dict(sink=-32),
 ])
 def test_bad_configurations_are_rejected(M, bad):
     kw = dict(CONFIGS[1])
@@ -92,7 +93,7 @@ def test_bad_configurations_are_rejected(M, bad):
 def test_null_arguments_and_error_strings(M):
     lib = M.load_library()
     assert lib.mixkvq_block_layout(None, None) == -1
-    assert lib.mixkvq_cache_state(None, None, None) == -1
+    assert lib.mixkvq_cache_state(None, None, None, None) == -1
     assert lib.mixkvq_decode_attention(None, None, None, None, 0.0, 0, None) == -1
     assert lib.mixkvq_quantize_append(None, None, None, 1, None, None, None) == -1
     for code in (0, -1, -2, -3, -4, -5, -99):
