@@ -294,13 +294,14 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   // fp16 rows (sink tokens, then the residual window; n_res counts both): sub-units of 32 tokens follow the
   // records in the same round-robin deal
   const int n_sub = (n_res + 31) >> 5;     // <= 8 (sink + window <= 256 rows) and <= n_gw (the launcher sees to it)
-  int my_sub = -1;
-#pragma unroll
-  for (int j = 0; j < 8; ++j)
-    if (j < n_sub && (n_blocks + j) % n_gw == gw) my_sub = j;
+  // unit n_blocks + j belongs to wavefront (n_blocks + j) % n_gw; n_sub <= n_gw, so one division serves them all
+  const int first_sub_gw = n_blocks % n_gw;
+  int my_sub = gw - first_sub_gw;
+  if (my_sub < 0) my_sub += n_gw;
+  if (my_sub >= n_sub) my_sub = -1;
   // one wavefront per pair (the next in the deal, never one with a sub-unit unless the pair has a single
   // workgroup) stores this step's new token and adds |q| to the accumulator
-  const bool bookkeeper = (n_blocks + n_sub) % n_gw == gw;
+  const bool bookkeeper = (first_sub_gw + n_sub >= n_gw ? first_sub_gw + n_sub - n_gw : first_sub_gw + n_sub) == gw;
 
   // ---- per-lane constants -------------------------------------------------
   // token of A-row n in tile (h, x): 64h + tokbase + {0,1,8,9}[x]  (G32: 8 (n/4) + 2 (n%4) + {0,1,32,33}[x])
