@@ -105,3 +105,24 @@ def test_null_arguments_and_error_strings(M):
     assert lib.mixkvq_cache_create(C.byref(cfg), C.byref(bufs), C.byref(h)) == -1
     bufs = M.binding.Buffers(256, 256, 256, 256, 260)
     assert lib.mixkvq_cache_create(C.byref(cfg), C.byref(bufs), C.byref(h)) == -1
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the public header must compile as C99 on its own, and a C program that fills the
+    structs sees the sizes the Python binding assumes."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "abi.c"
+    src.write_text('#include "mixkvq.h"\n#include <stdio.h>\n'
+                   'int main(void) { mixkvq_config c = {0}; mixkvq_block_layout_t l; (void)c; (void)l;\n'
+                   '  printf("%zu %zu %zu %zu\\n", sizeof(mixkvq_config), sizeof(mixkvq_block_layout_t),\n'
+                   '         sizeof(mixkvq_sizes), sizeof(mixkvq_buffers)); return 0; }\n')
+    exe = tmp_path / "abi"
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", inc, str(src), "-o", str(exe)], check=True)
+    sizes = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    import paper_2512_19206_amd.binding as Bd
+    assert sizes == [C.sizeof(Bd.Config), C.sizeof(Bd.BlockLayout), C.sizeof(Bd.Sizes), C.sizeof(Bd.Buffers)]
