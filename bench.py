@@ -179,10 +179,10 @@ def bench_prefill(args, w, cfg_id):
     gc = M.Cache(M.make_config(**kw))
     sel = torch.empty((w.B, w.Hkv, w.k4 + w.k16), dtype=torch.uint8, device="cuda")
 
-    def step(with_q=True):
+    def step(with_q=True, per_block=False):
         gc.reset()
         M.mixkvq_select_channels(gc, dq if with_q else None, dk, sel=sel)
-        M.mixkvq_quantize_append(gc, dk, dv, sel=sel)
+        M.mixkvq_quantize_append(gc, dk, dv, sel=None if per_block else sel)
 
     def timed(n, **kws):
         torch.cuda.synchronize()
@@ -196,6 +196,7 @@ def bench_prefill(args, w, cfg_id):
         step()
     el = timed(args.steps)
     el_noq = timed(args.steps, with_q=False)
+    el_pb = timed(args.steps, per_block=True)
     in_b, out_b = prefill_bytes(w, Lq)
     in_noq = in_b - w.B * w.Hq * Lq * w.D * 2
     value = in_b / el / 1e9
@@ -209,6 +210,9 @@ def bench_prefill(args, w, cfg_id):
                    "step": "cache_reset + select_channels(Q, K) + quantize_append(K, V, sel)"},
         "without_prompt_queries": {"ms_per_step": round(el_noq * 1e3, 4), "value": round(in_noq / el_noq / 1e9, 2),
                                    "unit": "GB/s", "input_bytes": in_noq},
+        "per_block_selection": {"ms_per_step": round(el_pb * 1e3, 4), "value": round(in_b / el_pb / 1e9, 2), "unit": "GB/s",
+                                "note": "same calls, but every block is scored on its own tokens inside the pack kernel "
+                                        "(sel = NULL) instead of using the selection made over the whole prompt"},
         "roofline": {"bound": "hbm", "kernel": "whole step (qabs_accumulate, key_range, flush_block: streaming kernels)",
                      "achieved": round((in_b + out_b) / el / 1e9, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round((in_b + out_b) / el / 1e9 / HBM_PEAK_GBS, 4), "traffic": None},
