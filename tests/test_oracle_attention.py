@@ -38,7 +38,7 @@ def brute_force_from_bytes(cfg, recs, res_k, res_v, n_res, q16, scale):
         for blk in range(nb):
             raw = recs[p, blk]
             sel = [int(raw[lay.off_idx + i]) for i in range(cfg.ks)]
-            hi16, hi4 = sel[:cfg.k16], sel[cfg.k16:]
+            hi16, hi4 = sel[:cfg.k16], sel[cfg.k16:]      # 255 marks an unused entry (threshold policy)
             lo = [d for d in range(cfg.D) if d not in sel]
             for t in range(cfg.R):
                 grp = t // cfg.Gk
@@ -50,17 +50,27 @@ def brute_force_from_bytes(cfg, recs, res_k, res_v, n_res, q16, scale):
                     z = _f16(raw, lay.off_klo_z + 2 * (grp * lay.NLp + i))
                     krow[d] = c * s + z
                 for i, d in enumerate(hi4):
+                    if d == 255:
+                        continue
                     w = _u32(raw, lay.off_k4 + 4 * (t * lay.W4 + i // 8))
                     c = (w >> _bit4(i % 8)) & 15
                     s = _f16(raw, lay.off_k4_s + 2 * (grp * cfg.k4 + i))
                     z = _f16(raw, lay.off_k4_z + 2 * (grp * cfg.k4 + i))
                     krow[d] = c * s + z
                 for i, d in enumerate(hi16):
+                    if d == 255:
+                        continue
                     krow[d] = _f16(raw, lay.off_k16 + 2 * (t * cfg.k16 + i))
                 vrow = [0.0] * cfg.D
+                if lay.v_interleave:
+                    # word j of a 64-token span: codes 0..7 = tokens 8j.. of its first 32 tokens, 8..15 = 8j.. of its second 32
+                    span, r = divmod(t, 64)
+                    word, code = 4 * span + (r % 32) // 8, r % 8 + 8 * (r // 32)
+                else:
+                    word, code = t // 16, t % 16
                 for d in range(cfg.D):
-                    w = _u32(raw, lay.off_v + 4 * ((t // 16) * cfg.D + d))
-                    c = (w >> _bit2(t % 16)) & 3
+                    w = _u32(raw, lay.off_v + 4 * (word * cfg.D + d))
+                    c = (w >> _bit2(code)) & 3
                     vg = d // cfg.Gv
                     s = _f16(raw, lay.off_v_s + 2 * (t * lay.NVG + vg))
                     z = _f16(raw, lay.off_v_z + 2 * (t * lay.NVG + vg))
@@ -84,10 +94,10 @@ def brute_force_from_bytes(cfg, recs, res_k, res_v, n_res, q16, scale):
     return out, lse
 
 
-def _tiny_cache(k4, k16, Gk=16, Gv=16, D=32, R=16, T=56, Hq=4, Hkv=2, B=2, seed=20, flush_mode=0):
+def _tiny_cache(k4, k16, Gk=16, Gv=16, D=32, R=16, T=56, Hq=4, Hkv=2, B=2, seed=20, flush_mode=0, **more):
     rng = np.random.default_rng(seed)
     cfg = O.OracleConfig(B=B, Hq=Hq, Hkv=Hkv, D=D, T_max=128, Gk=Gk, Gv=Gv, R=R, k4=k4, k16=k16,
-                         flush_mode=flush_mode)
+                         flush_mode=flush_mode, **more)
     K = (rng.standard_normal((B, Hkv, T, D)) * rng.uniform(0.5, 6, D)).astype(np.float16)
     V = rng.standard_normal((B, Hkv, T, D)).astype(np.float16)
     Qp = rng.standard_normal((B, Hq, 9, D)).astype(np.float16)
@@ -102,6 +112,20 @@ def _tiny_cache(k4, k16, Gk=16, Gv=16, D=32, R=16, T=56, Hq=4, Hkv=2, B=2, seed=
 def test_attention_equals_brute_force_over_packed_bytes(k4, k16, Gk, Gv):
     cfg, cache, K, V, q = _tiny_cache(k4, k16, Gk, Gv)
     assert cache.n_quant == 48 and cache.n_res == 8
+    out, lse = cache.decode_attention(q)
+    ref_out, ref_lse = brute_force_from_bytes(cfg, cache.packed_blocks(), cache.res_k, cache.res_v,
+                                              cache.n_res, q, 1.0 / math.sqrt(cfg.D))
+    assert np.allclose(out, ref_out, rtol=1e-11, atol=1e-12)
+    assert np.allclose(lse, ref_lse, rtol=1e-12, atol=1e-12)
+
+
+def test_brute_force_over_packed_bytes_with_interleaved_value_words_and_thresholds():
+    """Key groups of 32 tokens in blocks of 64 (value words interleaved over the two key groups) and the threshold
+    policy with partly used channel lists: the bytes still decode to what the oracle attends over."""
+    cfg, cache, K, V, q = _tiny_cache(8, 4, Gk=32, Gv=16, R=64, T=100, B=1, policy=1, tau16=8.0, tau4=6.0)
+    assert cache.n_quant == 64 and cache.n_res == 36 and O.block_layout(cfg).v_interleave == 1
+    used = [int((b.sel != O.NO_CHANNEL).sum()) for blocks in cache.blocks for b in blocks]
+    assert all(0 < u < 12 for u in used), used
     out, lse = cache.decode_attention(q)
     ref_out, ref_lse = brute_force_from_bytes(cfg, cache.packed_blocks(), cache.res_k, cache.res_v,
                                               cache.n_res, q, 1.0 / math.sqrt(cfg.D))
