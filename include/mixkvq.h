@@ -14,7 +14,8 @@
  *     values, so the host-side state is exact without a read-back.
  *   - All sequences of a batch advance in lock-step (same token count).
  *   - Grouped-query mapping: query heads [j*g, (j+1)*g) use KV head j, g = Hq/Hkv.
- *   - fp16 tensors are IEEE binary16; Inf/NaN inputs are outside the contract.
+ *   - "fp16" tensors below are IEEE binary16, or bfloat16 when cfg.in_dtype == 1 (same shapes and strides, in
+ *     elements); Inf/NaN inputs are outside the contract.
  *   - Calls on one cache must be issued from one host thread at a time.
  */
 #ifndef MIXKVQ_H
@@ -57,6 +58,9 @@ typedef struct {
                          * lower index) keep the tier and the others fall to the next tier down. */
   int32_t sink;         /* the first `sink` tokens of every sequence stay in fp16 for good (the sink length of Appendix E);
                          * 0, 32, 64, 96 or 128.  They are attended like the residual window and never quantized. */
+  int32_t in_dtype;     /* element type of every q, k, v tensor the caller passes and of `out`: 0 binary16, 1 bfloat16.
+                         * bfloat16 inputs enter the cache as the nearest binary16 (ties to even, saturated at +-65504:
+                         * exact wherever binary16 has the range); everything stored and computed is as for binary16. */
 } mixkvq_config;
 
 #define MIXKVQ_NO_CHANNEL 255  /* unused entry of a channel list (policy 1) */

@@ -59,6 +59,8 @@ class OracleConfig:
     tau16: float = math.inf       # policy 1: A_d > tau16 -> fp16 tier
     tau4: float = math.inf        # policy 1: tau4 < A_d <= tau16 -> 4-bit tier
     sink: int = 0                 # the first `sink` tokens of a sequence stay in full precision for good (Appendix E)
+    in_dtype: int = 0             # mirrors the library's field; the oracle itself always takes binary16 arrays (a
+                                  # bfloat16 input is converted with bf16_bits_to_f16 before it is handed over)
 
     @property
     def g(self):
@@ -67,6 +69,18 @@ class OracleConfig:
     @property
     def ks(self):
         return self.k4 + self.k16
+
+
+# --------------------------------------------------------------------------
+# input precision
+# --------------------------------------------------------------------------
+def bf16_bits_to_f16(bits: np.ndarray) -> np.ndarray:
+    """The cache works on binary16 values.  A bfloat16 input (the precision of the paper's models, Section 5)
+    enters it as the nearest binary16 (ties to even), saturated at +-65504: exact wherever binary16 has the range
+    (bfloat16 carries 8 significant bits, binary16 11), rounded only inside the binary16 subnormals.
+    `bits`: uint16 bfloat16 patterns (finite)."""
+    x32 = (np.asarray(bits).astype(np.uint32) << np.uint32(16)).view(np.float32)
+    return np.clip(x32, np.float32(-65504.0), np.float32(65504.0)).astype(np.float16)
 
 
 # --------------------------------------------------------------------------

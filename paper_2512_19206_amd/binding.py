@@ -23,7 +23,7 @@ EXPORTS = ("mixkvq_block_layout", "mixkvq_cache_sizes", "mixkvq_cache_create", "
 class Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("B", "Hq", "Hkv", "D", "T_max", "Gk", "Gv", "R", "k4", "k16",
                                          "flush_mode", "score_mode", "qacc_reset_on_flush", "policy")] + \
-               [("tau16", C.c_double), ("tau4", C.c_double), ("sink", C.c_int32)]
+               [("tau16", C.c_double), ("tau4", C.c_double), ("sink", C.c_int32), ("in_dtype", C.c_int32)]
 
 
 class Sizes(C.Structure):

@@ -36,6 +36,7 @@ int compute_layout(const mixkvq_config& c, Layout* out) {
   if (c.policy < 0 || c.policy > 1) return MIXKVQ_EINVAL;
   if (c.policy == 1 && !(c.tau16 >= 0.0 && c.tau4 >= 0.0)) return MIXKVQ_EINVAL;   // also rejects NaN
   if (c.sink < 0 || c.sink > 128 || c.sink % 32 != 0) return MIXKVQ_EINVAL;
+  if (c.in_dtype < 0 || c.in_dtype > 1) return MIXKVQ_EINVAL;
   Layout l;
   memset(&l, 0, sizeof(l));
   const int ks = c.k4 + c.k16;

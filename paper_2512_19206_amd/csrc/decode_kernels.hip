@@ -42,7 +42,8 @@ decode_split_kernel(CacheView cv, const __half* __restrict__ q, float scale, int
   const int h0 = half * 4;                               // heads h0 .. h0+3 (< g)
 
   for (int i = tid; i < g * kD; i += kDecThreads)
-    sQ[i / kD][i % kD] = __half2float(q[((size_t)b * cfg.Hq + (size_t)j * g) * kD + i]);
+    sQ[i / kD][i % kD] = __half2float(__ushort_as_half(in_bits(q + ((size_t)b * cfg.Hq + (size_t)j * g) * kD + i,
+                                                               cfg.in_dtype != 0)));
   if (tid < kMaxG) { sM[tid] = -INFINITY; sL[tid] = 0.f; }
 
   float acc[4] = {0.f, 0.f, 0.f, 0.f};   // O[h0+i][channel lane_lo]
@@ -203,7 +204,7 @@ decode_split_kernel(CacheView cv, const __half* __restrict__ q, float scale, int
 // One workgroup per (batch, query head), one thread per channel.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(kD) decode_merge_kernel(const float* __restrict__ part, int n_splits, int g, int Hq,
-                                                         __half* __restrict__ out, float* __restrict__ lse) {
+                                                         int out_bf16, __half* __restrict__ out, float* __restrict__ lse) {
   const int bh = blockIdx.x, b = bh / Hq, h = bh % Hq, d = threadIdx.x;
   const int Hkv = Hq / g, j = h / g, hh = h % g;
   const int p = b * Hkv + j;
@@ -220,7 +221,8 @@ __global__ void __launch_bounds__(kD) decode_merge_kernel(const float* __restric
     l += base[s * stride + kD + 1] * w;
     o += base[s * stride + d] * w;
   }
-  out[(size_t)bh * kD + d] = __float2half_rn(o / l);
+  reinterpret_cast<unsigned short*>(out)[(size_t)bh * kD + d] =
+      out_bf16 ? f32_to_bf16_bits(o / l) : __half_as_ushort(__float2half_rn(o / l));
   if (lse && d == 0) lse[bh] = m + __logf(l);
 }
 
@@ -265,7 +267,7 @@ hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float
   if (ev_start) (void)hipEventRecord(ev_start, s);
   decode_split_kernel<<<dim3(v.P, n_splits), dim3(kDecThreads), 0, s>>>(v, q, scale, n_blocks, n_fp16, n_splits, part);
   if (ev_stop) (void)hipEventRecord(ev_stop, s);
-  decode_merge_kernel<<<dim3(v.cfg.B * v.cfg.Hq), dim3(kD), 0, s>>>(part, n_splits, v.g, v.cfg.Hq, out, lse);
+  decode_merge_kernel<<<dim3(v.cfg.B * v.cfg.Hq), dim3(kD), 0, s>>>(part, n_splits, v.g, v.cfg.Hq, v.cfg.in_dtype, out, lse);
   return hipGetLastError();
 }
 

@@ -38,6 +38,8 @@ constexpr int kQsBytes = 8 * kQsStride * 2;
 constexpr int kWaveLds = kKPartMax + kVMetaMax + 256 + kQsBytes;   // + a spare 256 bytes + slot-ordered q
 constexpr int kHdrLds = 2048 + 256 + 2048 + 2048;   // normalised q [8][128], exponents and wave maxima, q transposed [128][8], raw q [8][128]
 constexpr int kPartStrideM = kD + 2;
+constexpr int kPBoost = 8;                      // softmax weights go to the matrix cores as p * 2^kPBoost (see mfma_part)
+constexpr unsigned kBigScale = 0x5BF8u;         // fp16 255: the largest value scale for which p' * s cannot overflow
 
 #ifdef MIXKVQ_PHASE_CLOCKS
 // Profiling aid, not part of the default build: 100 MHz timestamps of each wavefront's phases.
@@ -243,7 +245,9 @@ decode_merge_pair_kernel(CacheView cv, const float* __restrict__ part, int n_par
       for (int i = 0; i < 16; ++i) o = fmaf(v[i], s0 + i < n_parts ? sW[(s0 + i) * g + h] : 0.f, o);
     }
     const size_t bh = (size_t)b * cv.cfg.Hq + (size_t)j * g + h;
-    out[bh * kD + d] = __float2half_rn(o / sML[8 + h]);
+    const float r = o / sML[8 + h];
+    reinterpret_cast<unsigned short*>(out)[bh * kD + d] =
+        cv.cfg.in_dtype ? f32_to_bf16_bits(r) : __half_as_ushort(__float2half_rn(r));
     if (lse && d == 0) lse[bh] = sML[h] + __logf(sML[8 + h]);
   }
 }
@@ -322,13 +326,16 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   float m_run = -INFINITY, l_run = 0.f;
   float zacc[NVG][4];   // sum p' z per register index; its position factor is a per-lane constant
   // position exponent of pair i in this lane half: step 0 (lanes 0..7 of a row) or step 1 (lanes 8..15)
-  float sc2f[4];
-  unsigned w4sc[4];     // fp16 pair (4^sc, 4^sc)
+  // p is rounded to fp16 once, as p' = p * 4^-sc * 2^kPBoost (p <= 1, so p' <= 2^kPBoost).  The boost keeps small
+  // weights out of the fp16 subnormals: with it the weight of a token that meets a code at position 4 is resolved
+  // down to 2^-25 of the wavefront's largest weight (2^-17 without).
+  float sc2f[4];        // 2 sc - kPBoost: exponent offset of p' for pair i
+  unsigned w4sc[4];     // fp16 pair (4^sc 2^-kPBoost, same): turns p' back into p for the sum l
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int sc = role ? sc2(4 + i) : i;
-    sc2f[i] = 2.f * sc;
-    w4sc[i] = ((unsigned)(15 + 2 * sc) << 10) * 0x00010001u;
+    sc2f[i] = 2.f * sc - (float)kPBoost;
+    w4sc[i] = ((unsigned)(15 + 2 * sc - kPBoost) << 10) * 0x00010001u;
   }
   f32x4 O[2][4];   // [x'][q]: channels 64x' + 16kg + 4i + q
 #pragma unroll
@@ -528,6 +535,10 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   // ---- normalise q per head: qn = q * 2^-Eq with max|qn| in [1/2, 1) ----
   {
     const int h = tid >> 5, l32 = tid & 31;
+    if (cv.cfg.in_dtype) {      // bfloat16 queries enter as binary16
+      qraw.x = bf16x2_to_f16x2(qraw.x);
+      qraw.y = bf16x2_to_f16x2(qraw.y);
+    }
     const h2 q01 = __builtin_bit_cast(h2, qraw.x), q23 = __builtin_bit_cast(h2, qraw.y);
     const float v[4] = {(float)q01[0], (float)q01[1], (float)q23[0], (float)q23[1]};
     float mx = fmaxf(fmaxf(fabsf(v[0]), fabsf(v[1])), fmaxf(fabsf(v[2]), fabsf(v[3])));
@@ -553,7 +564,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   if (bookkeeper) {   // the new token enters the window; |q| of this step joins the accumulator (one writer per pair)
     if (nt.k && lane < 32) {
       const size_t dst = ((size_t)p * cv.RW + nt.row) * kD + (lane & 15) * 8;
-      *reinterpret_cast<uint4*>((lane < 16 ? cv.res_k : cv.res_v) + dst) = nt_row;
+      *reinterpret_cast<uint4*>((lane < 16 ? cv.res_k : cv.res_v) + dst) = as_f16x8(nt_row, cv.cfg.in_dtype != 0);
     }
     if (accumulate_q) {
 #pragma unroll
@@ -578,6 +589,22 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   // ---- residual window (fp16 keys/values): 32 tokens per wavefront, before its block records ----
   if (my_sub >= 0) {
     const int t0 = sub_t0;
+    if (cv.cfg.in_dtype && nt.k) {     // the new token's rows came from the caller's bfloat16 tensors
+#pragma unroll
+      for (int x = 0; x < 2; ++x)
+        if (sub_t0 + tokb + x == nt.row) {
+#pragma unroll
+          for (int st = 0; st < 4; ++st)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) kr[x][st][e] = bf16x2_to_f16x2(kr[x][st][e]);
+        }
+#pragma unroll
+      for (int it = 0; it < 8; ++it)
+        if (sub_t0 + ((it * 64 + lane) >> 4) == nt.row) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) vr[it][e] = bf16x2_to_f16x2(vr[it][e]);
+        }
+    }
     constexpr int kVStride = 264;     // bytes per staged value row (+8 against bank conflicts)
     const float Cres = ldexpf(scale_log2e, Eq);
     f32x4 S0 = {0.f, 0.f, 0.f, 0.f}, S1 = {0.f, 0.f, 0.f, 0.f};
@@ -631,9 +658,9 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
                                      value_channel<NVG>(xp, qq, n);
           a[e] = (unsigned)cp[0] | ((unsigned)cp[kVStride / 2] << 16);
         }
-        // the block loop accumulates sum p' c 4^sc 2^-24 and is scaled by 2^24 at the end
+        // the block loop accumulates sum p' c 4^sc 2^-24 = 2^(kPBoost-24) sum p c and is scaled back at the end
         const f32x4 t = mfma(a, Bp, f32x4{0.f, 0.f, 0.f, 0.f});
-        O[xp][qq] = t * 5.9604644775390625e-8f;
+        O[xp][qq] = t * (5.9604644775390625e-8f * (float)(1 << kPBoost));
       }
     wave_lds_handoff();     // the staging area is the record buffer of the block loop
   }
@@ -758,8 +785,16 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
     // ---- stage the key part and value metadata in LDS (wave-private: no barrier needed) ----
 #pragma unroll
     for (int c = 0; c < NKL; ++c) reinterpret_cast<u32x4*>(sK)[c * 64 + lane] = kreg[c];
+    // Value scales above 255 (a group of values that spans more than 765) would overflow p' * s in fp16: such a
+    // record takes the guarded form of the value product below (wave-uniform, rare).
+    bool big_lane = false;
 #pragma unroll
-    for (int c = 0; c < NVM; ++c) reinterpret_cast<u32x4*>(sVm)[c * 64 + lane < nvm ? c * 64 + lane : nvm - 1] = vmreg[c];
+    for (int c = 0; c < NVM; ++c) {
+      reinterpret_cast<u32x4*>(sVm)[c * 64 + lane < nvm ? c * 64 + lane : nvm - 1] = vmreg[c];
+      const unsigned mx_ = pk_max(pk_max(vmreg[c][0], vmreg[c][1]), pk_max(vmreg[c][2], vmreg[c][3]));
+      big_lane |= c * 64 + lane < (nvm >> 1) && ((mx_ & 0xffffu) > kBigScale || (mx_ >> 16) > kBigScale);   // scales come first
+    }
+    const bool big_s = __builtin_amdgcn_readfirstlane((int)__any(big_lane)) != 0;
     wave_lds_handoff();
     if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_K_LOADS(blk + blk_step)
 
@@ -851,13 +886,20 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         }
         // value scales / zero-points of the tokens this lane half pairs
         u32x4 Bp[NVG == 4 ? 2 : NVG][2];   // NVG = 4: the two value groups of one xp at a time
+        // In a guarded record (some value scale above 255) the scales are taken down by 2^-kPBoost before they meet p'.
+        constexpr unsigned kVsDown = ((unsigned)(15 - kPBoost) << 10) * 0x00010001u;   // fp16 pair (2^-kPBoost, same)
         {
           // the 8 tokens this lane half pairs: 16 kg + 8 role .. (G32: 32 role + 8 kg ..), pair i = tokens 2i, 2i + 1
           const int tv = 64 * hsg + (G32 ? 32 * role + 8 * kg : 16 * kg + 8 * role);
           if (NVG == 1) {
             const uint4 sv = *reinterpret_cast<const uint4*>(sVm + 2 * tv);
             const uint4 zv = *reinterpret_cast<const uint4*>(sVm + 2 * R + 2 * tv);
-            const unsigned sw[4] = {sv.x, sv.y, sv.z, sv.w}, zw[4] = {zv.x, zv.y, zv.z, zv.w};
+            unsigned sw[4] = {sv.x, sv.y, sv.z, sv.w};
+            const unsigned zw[4] = {zv.x, zv.y, zv.z, zv.w};
+            if (big_s) {
+#pragma unroll
+              for (int i = 0; i < 4; ++i) sw[i] = pk_mul(sw[i], kVsDown);
+            }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
               const unsigned pm = pk_mul(pk[i], sw[i]);
@@ -870,8 +912,12 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
             const uint4* ps = reinterpret_cast<const uint4*>(sVm + 4 * tv);
             const uint4* pz = reinterpret_cast<const uint4*>(sVm + 4 * R + 4 * tv);
             const uint4 s0 = ps[0], s1 = ps[1], z0 = pz[0], z1 = pz[1];
-            const unsigned sw[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+            unsigned sw[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
             const unsigned zw[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
+            if (big_s) {
+#pragma unroll
+              for (int i = 0; i < 8; ++i) sw[i] = pk_mul(sw[i], kVsDown);
+            }
 #pragma unroll
             for (int a = 0; a < NVG; ++a)
 #pragma unroll
@@ -895,9 +941,26 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
             s4[i] = reinterpret_cast<const uint4*>(sVm + 8 * tv)[i];
             z4[i] = reinterpret_cast<const uint4*>(sVm + 8 * R + 8 * tv)[i];
           }
+          if (big_s) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              s4[i].x = pk_mul(s4[i].x, kVsDown);
+              s4[i].y = pk_mul(s4[i].y, kVsDown);
+              s4[i].z = pk_mul(s4[i].z, kVsDown);
+              s4[i].w = pk_mul(s4[i].w, kVsDown);
+            }
+          }
         }
 
         // ---- O^T += V_codes^T . Ps^T ----
+        // (guarded record: the products come out 2^-kPBoost too small, so the sums they join are taken down by the
+        //  same exact factor first and brought back afterwards)
+        if (big_s) {
+#pragma unroll
+          for (int xp = 0; xp < 2; ++xp)
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) O[xp][qq] *= 1.f / (float)(1 << kPBoost);
+        }
 #pragma unroll
         for (int xp = 0; xp < 2; ++xp) {
           const u32x4 vw = vreg[hsg][xp];
@@ -924,6 +987,12 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
             O[xp][qq] = mfma(a0, Bp[a][0], O[xp][qq]);
             O[xp][qq] = mfma(a1, Bp[a][1], O[xp][qq]);
           }
+        }
+        if (big_s) {
+#pragma unroll
+          for (int xp = 0; xp < 2; ++xp)
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) O[xp][qq] *= (float)(1 << kPBoost);
         }
         if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_V_HALF(blk + blk_step, hsg)
       }
@@ -966,7 +1035,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         for (int i = 0; i < 4; ++i) {
           const int ch = value_channel<NVG>(xp, qq, 4 * kg + i);
           const int a = value_group<NVG>(xp, qq);
-          wO[head * kD + ch] = fmaf(O[xp][qq][i], 16777216.f, zsum[a]);
+          wO[head * kD + ch] = fmaf(O[xp][qq][i], 16777216.f / (float)(1 << kPBoost), zsum[a]);
         }
     if (kg == 0) {
       wO[8 * kD + head] = l_run;

@@ -7,6 +7,8 @@
 
 namespace mixkvq {
 
+__device__ __forceinline__ unsigned short h2bits(__half h) { return __half_as_ushort(h); }
+
 constexpr int kD = 128;             // head dimension of the hot path
 constexpr int kMaxR = 128;          // largest residual window / flush unit
 constexpr int kMaxSplits = 64;      // split-K ceiling per (batch, KV head) pair
@@ -63,7 +65,6 @@ size_t decode_partials_bytes(const mixkvq_config& c);
 size_t select_workspace_bytes(const mixkvq_config& c);
 
 // ---- small device helpers used by several kernels ----
-__device__ __forceinline__ unsigned short h2bits(__half h) { return __half_as_ushort(h); }
 
 // |x| * 2^24 of an fp16 as an exact integer (< 2^40).
 __device__ __forceinline__ unsigned long long fix24_abs(unsigned short h) {
@@ -73,6 +74,37 @@ __device__ __forceinline__ unsigned long long fix24_abs(unsigned short h) {
 __device__ __forceinline__ long long fix24(unsigned short h) {
   long long v = (long long)fix24_abs(h);
   return (h & 0x8000u) ? -v : v;
+}
+
+// ---- input precision: bfloat16 tensors enter as the nearest binary16 (ties to even), saturated at +-65504 ----
+__device__ __forceinline__ unsigned bf16x2_to_f16x2(unsigned w) {
+  const float lo = __builtin_amdgcn_fmed3f(__uint_as_float(w << 16), -65504.f, 65504.f);
+  const float hi = __builtin_amdgcn_fmed3f(__uint_as_float(w & 0xffff0000u), -65504.f, 65504.f);
+  const __half2 r = __float22half2_rn(make_float2(lo, hi));
+  return __builtin_bit_cast(unsigned, r);
+}
+__device__ __forceinline__ unsigned short bf16_to_f16_bits(unsigned short b) {
+  return (unsigned short)(bf16x2_to_f16x2((unsigned)b) & 0xffffu);
+}
+// eight input elements (16 bytes) as eight binary16
+__device__ __forceinline__ uint4 as_f16x8(uint4 v, bool bf16) {
+  if (bf16) {
+    v.x = bf16x2_to_f16x2(v.x);
+    v.y = bf16x2_to_f16x2(v.y);
+    v.z = bf16x2_to_f16x2(v.z);
+    v.w = bf16x2_to_f16x2(v.w);
+  }
+  return v;
+}
+// one input element's binary16 bit pattern
+__device__ __forceinline__ unsigned short in_bits(const __half* p, bool bf16) {
+  const unsigned short b = h2bits(*p);
+  return bf16 ? bf16_to_f16_bits(b) : b;
+}
+// fp32 -> bfloat16 bits, round to nearest even (finite values)
+__device__ __forceinline__ unsigned short f32_to_bf16_bits(float x) {
+  const unsigned u = __float_as_uint(x);
+  return (unsigned short)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
 }
 
 // Token (inside the block) of code i of value word tg; see the record layout in mixkvq.h.

@@ -56,12 +56,13 @@ __device__ __forceinline__ const __half* token_row(const __half* win, const __ha
 }
 
 __device__ __forceinline__ void load_tile(__half* sT, const __half* win, const __half* fresh, Strides3 st, int p, int Hkv,
-                                          int R, int r0, int pos0) {
-  // R rows of 256 bytes; 16 threads per row, 16 bytes each
+                                          int R, int r0, int pos0, bool bf16) {
+  // R rows of 256 bytes; 16 threads per row, 16 bytes each.  Window rows are binary16 already; rows of the
+  // caller's tensor may be bfloat16.
   for (int idx = threadIdx.x; idx < R * 16; idx += kFlushThreads) {
     const int t = idx >> 4, c = idx & 15;
     const __half* row = token_row(win, fresh, st, p, Hkv, r0, pos0 + t);
-    uint4 v = *reinterpret_cast<const uint4*>(row + c * 8);
+    uint4 v = as_f16x8(*reinterpret_cast<const uint4*>(row + c * 8), bf16 && pos0 + t >= r0);
     *reinterpret_cast<uint4*>(sT + t * kRowStride + c * 8) = v;
   }
 }
@@ -91,7 +92,7 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
   for (int i = tid; i < lay.off_klo / 4; i += kFlushThreads)
     reinterpret_cast<unsigned*>(rec)[i] = (cfg.policy == 1 && i < ks / 4) ? 0xffffffffu : 0u;
 
-  load_tile(sT, window_rows(cv, cv.res_k, p), k_new, st, p, cfg.Hkv, R, r0, f * R);
+  load_tile(sT, window_rows(cv, cv.res_k, p), k_new, st, p, cfg.Hkv, R, r0, f * R, cfg.in_dtype != 0);
   if (tid < 8) sKmax[tid] = 0u;
   __syncthreads();
 
@@ -215,7 +216,7 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
   __syncthreads();
 
   // ---- values -----------------------------------------------------------------
-  load_tile(sT, window_rows(cv, cv.res_v, p), v_new, st, p, cfg.Hkv, R, r0, f * R);
+  load_tile(sT, window_rows(cv, cv.res_v, p), v_new, st, p, cfg.Hkv, R, r0, f * R, cfg.in_dtype != 0);
   __syncthreads();
   const int NVG = lay.NVG;
   float* sVS = sS;   // [token][NVG] (R * NVG <= 128 * 8)
@@ -305,10 +306,10 @@ __device__ __forceinline__ float safe_rcp(float s) { return s > 0.f ? __builtin_
 // 16-byte piece `idx` of the tile that starts at stream position pos0; `res_p` and `fresh_p` are the pair's
 // residual window and its slice of the caller's tensor (token 0 of this call).
 __device__ __forceinline__ uint4 load_chunk(const __half* res_p, const __half* fresh_p, int64_t stride_t, int r0, int pos0,
-                                            int idx) {
+                                            int idx, bool bf16) {
   const int pos = pos0 + (idx >> 4), c = idx & 15;
   const __half* row = pos < r0 ? res_p + (size_t)pos * kD : fresh_p + (int64_t)(pos - r0) * stride_t;
-  return *reinterpret_cast<const uint4*>(row + c * 8);
+  return as_f16x8(*reinterpret_cast<const uint4*>(row + c * 8), bf16 && pos >= r0);   // window rows are binary16 already
 }
 
 __global__ void __launch_bounds__(kFlushThreads, 3)   // three workgroups per CU (LDS) = three wavefronts per SIMD
@@ -330,6 +331,7 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
 
   const int R = cv.cfg.R, Gk = cv.cfg.Gk, Gv = cv.cfg.Gv, k4 = cv.cfg.k4, k16 = cv.cfg.k16, ks = k4 + k16;
   const int Hkv = cv.cfg.Hkv, score_mode = cv.cfg.score_mode, policy = cv.cfg.policy;
+  const bool bf16 = cv.cfg.in_dtype != 0;
   const int rec_bytes = cv.lay.rec_bytes, off_idx = cv.lay.off_idx, off_kmax = cv.lay.off_kmax,
             off_klo_s = cv.lay.off_klo_s, off_klo_z = cv.lay.off_klo_z, off_k4_s = cv.lay.off_k4_s,
             off_k4_z = cv.lay.off_k4_z, off_klo = cv.lay.off_klo, off_k4 = cv.lay.off_k4, off_k16 = cv.lay.off_k16,
@@ -347,6 +349,7 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   const __half* res_kp = window_rows(cv, cv.res_k, p);
   const __half* res_vp = window_rows(cv, cv.res_v, p);
   const int pos0 = f * R;
+  bool v_pending = false;     // the value tile in registers still holds bfloat16
   if (pos0 >= r0 || pos0 + R <= r0) {
     // the usual case: the whole tile comes from one place, rows a constant stride apart
     const bool from_res = pos0 + R <= r0;
@@ -364,19 +367,24 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
       vreg[i] = make_uint4(0u, 0u, 0u, 0u);
       if (tid + kFlushThreads * i < n_chunks16) vreg[i] = *reinterpret_cast<const uint4*>(vp + 16 * i * row_stride);
     }
+    if (bf16 && !from_res) {     // rows of the caller's bfloat16 tensors enter as binary16 (the values when they are staged)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) kreg[i] = as_f16x8(kreg[i], true);
+      v_pending = true;
+    }
   } else {
     // the tile straddles the end of the residual window (first block of an append onto a partly filled window)
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int idx = tid + kFlushThreads * i;
       kreg[i] = make_uint4(0u, 0u, 0u, 0u);
-      if (idx < n_chunks16) kreg[i] = load_chunk(res_kp, k_new + pair_off, st.t, r0, pos0, idx);
+      if (idx < n_chunks16) kreg[i] = load_chunk(res_kp, k_new + pair_off, st.t, r0, pos0, idx, bf16);
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int idx = tid + kFlushThreads * i;
       vreg[i] = make_uint4(0u, 0u, 0u, 0u);
-      if (idx < n_chunks16) vreg[i] = load_chunk(res_vp, v_new + pair_off, st.t, r0, pos0, idx);
+      if (idx < n_chunks16) vreg[i] = load_chunk(res_vp, v_new + pair_off, st.t, r0, pos0, idx, bf16);
     }
   }
   // zero the small planes of the record (index bytes, tails of the scale/zero planes)
@@ -617,7 +625,7 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
     for (int i = 0; i < 8; ++i) {
       const int row = (tid >> 4) + 16 * i;
       if (row < R) {
-        const uint4 v = vreg[i];
+        const uint4 v = as_f16x8(vreg[i], v_pending);
         *reinterpret_cast<uint4*>(sT + row * kRowStride + c * 8) = v;
         const fh2 k0 = as_h2(v.x), k1 = as_h2(v.y), k2 = as_h2(v.z), k3 = as_h2(v.w);
         const fh2 lo2 = __builtin_elementwise_min(__builtin_elementwise_min(k0, k1), __builtin_elementwise_min(k2, k3));
@@ -729,8 +737,9 @@ __global__ void residual_copy_kernel(CacheView cv, const __half* __restrict__ k_
     const int t = idx >> 4, c = idx & 15;
     const int64_t src = (int64_t)b * st.b + (int64_t)j * st.h + (int64_t)(src_first + t) * st.t + c * 8;
     const size_t dst = ((size_t)p * cv.RW + dst_row + t) * kD + c * 8;
-    *reinterpret_cast<uint4*>(cv.res_k + dst) = *reinterpret_cast<const uint4*>(k_new + src);
-    *reinterpret_cast<uint4*>(cv.res_v + dst) = *reinterpret_cast<const uint4*>(v_new + src);
+    const bool bf16 = cv.cfg.in_dtype != 0;
+    *reinterpret_cast<uint4*>(cv.res_k + dst) = as_f16x8(*reinterpret_cast<const uint4*>(k_new + src), bf16);
+    *reinterpret_cast<uint4*>(cv.res_v + dst) = as_f16x8(*reinterpret_cast<const uint4*>(v_new + src), bf16);
   }
 }
 

@@ -45,6 +45,7 @@ __device__ __forceinline__ void add8(double (&acc)[8], uint4 v) {
   }
 }
 
+template <bool BF>      // BF: the tensor holds bfloat16 (converted to binary16 on entry)
 __global__ void __launch_bounds__(kStreamThreads)
 qabs_accumulate_kernel(const __half* __restrict__ q, int Lq, Strides3 qs, int Hkv, int g,
                        unsigned long long* __restrict__ qacc, unsigned long long* __restrict__ qcnt) {
@@ -64,9 +65,9 @@ qabs_accumulate_kernel(const __half* __restrict__ q, int Lq, Strides3 qs, int Hk
 #pragma unroll
     for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const uint4*>(base + (int64_t)(t + 16 * u) * qs.t);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) add8(acc, v[u]);
+    for (int u = 0; u < 4; ++u) add8(acc, as_f16x8(v[u], BF));
   }
-  for (; t < t1; t += 16) add8(acc, *reinterpret_cast<const uint4*>(base + (int64_t)t * qs.t));
+  for (; t < t1; t += 16) add8(acc, as_f16x8(*reinterpret_cast<const uint4*>(base + (int64_t)t * qs.t), BF));
 #pragma unroll
   for (int i = 0; i < 8; ++i) sAcc[r][8 * c + i] = (unsigned long long)(acc[i] * 16777216.0);
   __syncthreads();
@@ -81,7 +82,7 @@ qabs_accumulate_kernel(const __half* __restrict__ q, int Lq, Strides3 qs, int Hk
 
 // Fallback for tensors whose rows are not 16-byte aligned: one thread per channel.
 __global__ void __launch_bounds__(kD) qabs_accumulate_unaligned_kernel(const __half* __restrict__ q, int Lq, Strides3 qs,
-                                                                      int Hkv, int g,
+                                                                      int Hkv, int g, int bf16,
                                                                       unsigned long long* __restrict__ qacc,
                                                                       unsigned long long* __restrict__ qcnt) {
   const int p = blockIdx.x, b = p / Hkv, j = p % Hkv, d = threadIdx.x;
@@ -89,7 +90,7 @@ __global__ void __launch_bounds__(kD) qabs_accumulate_unaligned_kernel(const __h
   const int t0 = chunk * kRowsPerWG, t1 = min(Lq, t0 + kRowsPerWG);
   const __half* base = q + (int64_t)b * qs.b + (int64_t)(j * g + hh) * qs.h + d;
   unsigned long long acc = 0;
-  for (int t = t0; t < t1; ++t) acc += fix24_abs(h2bits(base[(int64_t)t * qs.t]));
+  for (int t = t0; t < t1; ++t) acc += fix24_abs(in_bits(base + (int64_t)t * qs.t, bf16));
   atomicAdd(&qacc[(size_t)p * kD + d], acc);
   if (d == 0) atomicAdd(&qcnt[p], (unsigned long long)(t1 - t0));
 }
@@ -100,10 +101,12 @@ static bool rows_aligned16(const void* ptr, Strides3 st) {
 
 hipError_t launch_qabs_accumulate(const CacheView& v, const __half* q, int Lq, Strides3 qs, hipStream_t s) {
   dim3 grid(v.P, v.g * ((Lq + kRowsPerWG - 1) / kRowsPerWG));
-  if (rows_aligned16(q, qs))
-    qabs_accumulate_kernel<<<grid, dim3(kStreamThreads), 0, s>>>(q, Lq, qs, v.cfg.Hkv, v.g, v.qacc, v.qcnt);
+  if (!rows_aligned16(q, qs))
+    qabs_accumulate_unaligned_kernel<<<grid, dim3(kD), 0, s>>>(q, Lq, qs, v.cfg.Hkv, v.g, v.cfg.in_dtype, v.qacc, v.qcnt);
+  else if (v.cfg.in_dtype)
+    qabs_accumulate_kernel<true><<<grid, dim3(kStreamThreads), 0, s>>>(q, Lq, qs, v.cfg.Hkv, v.g, v.qacc, v.qcnt);
   else
-    qabs_accumulate_unaligned_kernel<<<grid, dim3(kD), 0, s>>>(q, Lq, qs, v.cfg.Hkv, v.g, v.qacc, v.qcnt);
+    qabs_accumulate_kernel<false><<<grid, dim3(kStreamThreads), 0, s>>>(q, Lq, qs, v.cfg.Hkv, v.g, v.qacc, v.qcnt);
   return hipGetLastError();
 }
 
@@ -128,6 +131,7 @@ __global__ void range_init_kernel(long long* mn, long long* mx, int n) {
   }
 }
 
+template <bool BF>
 __global__ void __launch_bounds__(kStreamThreads)
 key_range_kernel(const __half* __restrict__ k, int L, Strides3 ks, int Hkv, long long* __restrict__ mn,
                  long long* __restrict__ mx) {
@@ -157,9 +161,9 @@ key_range_kernel(const __half* __restrict__ k, int L, Strides3 ks, int Hkv, long
 #pragma unroll
     for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const uint4*>(base + (int64_t)(t + 16 * u) * ks.t);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) upd(v[u]);
+    for (int u = 0; u < 4; ++u) upd(as_f16x8(v[u], BF));
   }
-  for (; t < t1; t += 16) upd(*reinterpret_cast<const uint4*>(base + (int64_t)t * ks.t));
+  for (; t < t1; t += 16) upd(as_f16x8(*reinterpret_cast<const uint4*>(base + (int64_t)t * ks.t), BF));
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     sLo[r][4 * c + i] = __builtin_bit_cast(unsigned, lo[i]);
@@ -186,7 +190,7 @@ key_range_kernel(const __half* __restrict__ k, int L, Strides3 ks, int Hkv, long
 }
 
 __global__ void __launch_bounds__(kD) key_range_unaligned_kernel(const __half* __restrict__ k, int L, Strides3 ks,
-                                                                int Hkv, long long* __restrict__ mn,
+                                                                int Hkv, int bf16, long long* __restrict__ mn,
                                                                 long long* __restrict__ mx) {
   const int p = blockIdx.x, b = p / Hkv, j = p % Hkv, d = threadIdx.x;
   const int t0 = blockIdx.y * kRowsPerWG;
@@ -194,7 +198,7 @@ __global__ void __launch_bounds__(kD) key_range_unaligned_kernel(const __half* _
   const __half* base = k + (int64_t)b * ks.b + (int64_t)j * ks.h + d;
   long long lo = 0x7fffffffffffffffll, hi = -0x7fffffffffffffffll - 1;
   for (int t = t0; t < t1; ++t) {
-    long long x = fix24(h2bits(base[(int64_t)t * ks.t]));
+    long long x = fix24(in_bits(base + (int64_t)t * ks.t, bf16));
     lo = x < lo ? x : lo;
     hi = x > hi ? x : hi;
   }
@@ -247,10 +251,12 @@ hipError_t launch_select(const CacheView& v, const __half* k, int L, Strides3 ks
   const int n = v.P * kD;
   range_init_kernel<<<dim3((n + 255) / 256), dim3(256), 0, s>>>(mn, mx, n);
   dim3 grid(v.P, (L + kRowsPerWG - 1) / kRowsPerWG);
-  if (rows_aligned16(k, ks))
-    key_range_kernel<<<grid, dim3(kStreamThreads), 0, s>>>(k, L, ks, v.cfg.Hkv, mn, mx);
+  if (!rows_aligned16(k, ks))
+    key_range_unaligned_kernel<<<grid, dim3(kD), 0, s>>>(k, L, ks, v.cfg.Hkv, v.cfg.in_dtype, mn, mx);
+  else if (v.cfg.in_dtype)
+    key_range_kernel<true><<<grid, dim3(kStreamThreads), 0, s>>>(k, L, ks, v.cfg.Hkv, mn, mx);
   else
-    key_range_unaligned_kernel<<<grid, dim3(kD), 0, s>>>(k, L, ks, v.cfg.Hkv, mn, mx);
+    key_range_kernel<false><<<grid, dim3(kStreamThreads), 0, s>>>(k, L, ks, v.cfg.Hkv, mn, mx);
   select_topk_kernel<<<dim3(v.P), dim3(kD), 0, s>>>(v, mn, mx, sel);
   return hipGetLastError();
 }

@@ -135,3 +135,29 @@ def test_key_groups_restart_every_gk_tokens():
         c2, s2, z2 = O.quantize_keys(sub, np.arange(8), 2, 32)
         assert np.array_equal(c2, codes[32 * gidx:32 * (gidx + 1)])
         assert np.array_equal(s2[0], s[gidx])
+
+
+def test_bfloat16_inputs_enter_as_nearest_binary16():
+    """bfloat16 -> binary16: exact wherever binary16 has the range (8 significant bits fit into 11), the nearest
+    value with ties to even inside the binary16 subnormals, saturated at +-65504.  Checked for every finite
+    bfloat16 pattern against exact rational arithmetic."""
+    from fractions import Fraction
+    bits = np.arange(1 << 16, dtype=np.uint32)
+    exp = (bits >> 7) & 0xFF
+    bits = bits[exp != 0xFF].astype(np.uint16)                     # finite patterns
+    got = O.bf16_bits_to_f16(bits)
+    assert got.dtype == np.float16 and np.all(np.isfinite(got))
+    x32 = (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    normal_range = (np.abs(x32) >= 2.0 ** -14) & (np.abs(x32) <= 65504.0)
+    assert np.array_equal(got[normal_range].astype(np.float64), x32[normal_range])          # exact
+    big = np.abs(x32) > 65504.0
+    assert np.array_equal(got[big].astype(np.float64), np.sign(x32[big]) * 65504.0)         # saturated
+    # below the normal range: a multiple of 2^-24, nearest to x, ties to the even multiple
+    small = np.nonzero((np.abs(x32) < 2.0 ** -14) & (x32 != 0))[0]
+    for i in small[:: max(1, len(small) // 400)]:
+        x = Fraction(float(x32[i]))
+        n = Fraction(float(got[i])) * (1 << 24)
+        assert n.denominator == 1
+        d = abs(x * (1 << 24) - n)
+        assert d <= Fraction(1, 2) and (d < Fraction(1, 2) or n.numerator % 2 == 0)
+    assert O.bf16_bits_to_f16(np.array([0x0000, 0x8000], dtype=np.uint16)).view(np.uint16).tolist() == [0x0000, 0x8000]
