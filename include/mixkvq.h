@@ -83,7 +83,8 @@ typedef struct {
  *   idx    u8  [k16+k4]      fp16-tier channels ascending, then 4-bit-tier channels ascending; under policy 1 each
  *                            tier is filled up to its capacity with MIXKVQ_NO_CHANNEL and the unused entries of
  *                            every plane of that tier are 0
- *   kmax   f16 [NG]          largest stored scale among the group's 2-bit and 4-bit channels (derived metadata)
+ *   kmax   f16 [NG + 1]      [g < NG]: largest stored scale among group g's 2-bit and 4-bit key channels; [NG]: largest
+ *                            stored value scale of the block (derived metadata: lets a reader pick exponents without a scan)
  *   klo_s  f16 [NG][NLp]     scales of the 2-bit key channels (the non-salient channels, ascending)
  *   klo_z  f16 [NG][NLp]     zero-points (group minima, Eq. 2)
  *   k4_s   f16 [NG][k4]      4-bit tier scales, tier order;  k4_z likewise

@@ -277,7 +277,8 @@ def block_layout(cfg: OracleConfig) -> BlockLayout:
     on a 16-byte boundary; padding bytes are zero.
       idx    u8  [ks]               fp16-tier channels ascending, then 4-bit tier ascending (threshold policy:
                                     each tier filled up to its capacity with NO_CHANNEL)
-      kmax   f16 [NG]               largest stored scale of the group's 2-bit and 4-bit channels (derived
+      kmax   f16 [NG + 1]           [NG]: largest stored value scale of the block; [g < NG]:
+                                    largest stored scale of the group's 2-bit and 4-bit channels (derived
                                     metadata: lets a reader normalise the scales without scanning them)
       klo_s  f16 [NG][NLp]          scales of the 2-bit key channels (ascending non-salient channels)
       klo_z  f16 [NG][NLp]          zero-points
@@ -301,7 +302,7 @@ def block_layout(cfg: OracleConfig) -> BlockLayout:
     W4 = cfg.k4 // 8
     off = 0
     offs = {}
-    for name, size in (("idx", cfg.ks), ("kmax", NG * 2), ("klo_s", NG * NLp * 2), ("klo_z", NG * NLp * 2),
+    for name, size in (("idx", cfg.ks), ("kmax", (NG + 1) * 2), ("klo_s", NG * NLp * 2), ("klo_z", NG * NLp * 2),
                        ("k4_s", NG * cfg.k4 * 2), ("k4_z", NG * cfg.k4 * 2),
                        ("klo", R * Wlo * 4), ("k4", R * W4 * 4), ("k16", R * cfg.k16 * 2),
                        ("v", (R // 16) * D * 4), ("v_s", R * NVG * 2), ("v_z", R * NVG * 2)):
@@ -374,7 +375,7 @@ def pack_block(cfg: OracleConfig, blk: QuantBlock) -> np.ndarray:
     # Planes are sized for the capacity of each tier; entries past a tier's actual size are zero.
     put(lay.off_idx, blk.sel)
     allscales = np.concatenate([blk.lo_s, blk.k4_s], axis=1)          # [NG, n_lo + n4] fp16, all >= 0
-    put(lay.off_kmax, allscales.max(axis=1).astype(np.float16))
+    put(lay.off_kmax, np.concatenate([allscales.max(axis=1), [blk.v_s.max()]]).astype(np.float16))
     pad = lay.NLp - blk.lo_codes.shape[1]
     pad4 = cfg.k4 - blk.k4_codes.shape[1]
     pad16 = cfg.k16 - blk.k16.shape[1]

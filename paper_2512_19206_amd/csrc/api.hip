@@ -49,7 +49,7 @@ int compute_layout(const mixkvq_config& c, Layout* out) {
   int off = 0;
   auto plane = [&](int32_t* dst, int bytes) { *dst = off; off += al16(bytes); };
   plane(&l.off_idx, ks);
-  plane(&l.off_kmax, l.NG * 2);
+  plane(&l.off_kmax, (l.NG + 1) * 2);
   plane(&l.off_klo_s, l.NG * l.NLp * 2);
   plane(&l.off_klo_z, l.NG * l.NLp * 2);
   plane(&l.off_k4_s, l.NG * c.k4 * 2);

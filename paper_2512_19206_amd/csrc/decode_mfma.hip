@@ -785,18 +785,32 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
     // ---- stage the key part and value metadata in LDS (wave-private: no barrier needed) ----
 #pragma unroll
     for (int c = 0; c < NKL; ++c) reinterpret_cast<u32x4*>(sK)[c * 64 + lane] = kreg[c];
-    // Value scales above 255 (a group of values that spans more than 765) would overflow p' * s in fp16: such a
-    // record takes the guarded form of the value product below (wave-uniform, rare).
-    bool big_lane = false;
 #pragma unroll
-    for (int c = 0; c < NVM; ++c) {
-      reinterpret_cast<u32x4*>(sVm)[c * 64 + lane < nvm ? c * 64 + lane : nvm - 1] = vmreg[c];
-      const unsigned mx_ = pk_max(pk_max(vmreg[c][0], vmreg[c][1]), pk_max(vmreg[c][2], vmreg[c][3]));
-      big_lane |= c * 64 + lane < (nvm >> 1) && ((mx_ & 0xffffu) > kBigScale || (mx_ >> 16) > kBigScale);   // scales come first
-    }
-    const bool big_s = __builtin_amdgcn_readfirstlane((int)__any(big_lane)) != 0;
+    for (int c = 0; c < NVM; ++c) reinterpret_cast<u32x4*>(sVm)[c * 64 + lane < nvm ? c * 64 + lane : nvm - 1] = vmreg[c];
     wave_lds_handoff();
     if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_K_LOADS(blk + blk_step)
+    // Value scales above 255 (a group of values that spans more than 765) would overflow p' * s in fp16.  Such a
+    // record (the record carries its largest value scale; wave-uniform, rare) is guarded: its scales are staged
+    // 2^-kPBoost smaller, so its value products come out too small by that factor; the sums they join are taken
+    // down by the same exact factor before the record and brought back after it.
+    const bool big_s = (unsigned)__builtin_amdgcn_readfirstlane(
+                           (int)reinterpret_cast<const unsigned short*>(sK + off_kmax)[cv.lay.NG]) > kBigScale;
+    if (big_s) {
+      constexpr unsigned kVsDown = ((unsigned)(15 - kPBoost) << 10) * 0x00010001u;   // fp16 pair (2^-kPBoost, same)
+#pragma unroll
+      for (int c = 0; c < NVM; ++c)
+        if (c * 64 + lane < (nvm >> 1)) {     // the scales come first, then the zero-points
+          u32x4 v = reinterpret_cast<const u32x4*>(sVm)[c * 64 + lane];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = pk_mul(v[e], kVsDown);
+          reinterpret_cast<u32x4*>(sVm)[c * 64 + lane] = v;
+        }
+#pragma unroll
+      for (int xp = 0; xp < 2; ++xp)
+#pragma unroll
+        for (int qq = 0; qq < 4; ++qq) O[xp][qq] *= 1.f / (float)(1 << kPBoost);
+      wave_lds_handoff();
+    }
 
     // ---- channel selection of this block: rebuild q in slot order if it changed ----
     {
@@ -886,20 +900,13 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         }
         // value scales / zero-points of the tokens this lane half pairs
         u32x4 Bp[NVG == 4 ? 2 : NVG][2];   // NVG = 4: the two value groups of one xp at a time
-        // In a guarded record (some value scale above 255) the scales are taken down by 2^-kPBoost before they meet p'.
-        constexpr unsigned kVsDown = ((unsigned)(15 - kPBoost) << 10) * 0x00010001u;   // fp16 pair (2^-kPBoost, same)
         {
           // the 8 tokens this lane half pairs: 16 kg + 8 role .. (G32: 32 role + 8 kg ..), pair i = tokens 2i, 2i + 1
           const int tv = 64 * hsg + (G32 ? 32 * role + 8 * kg : 16 * kg + 8 * role);
           if (NVG == 1) {
             const uint4 sv = *reinterpret_cast<const uint4*>(sVm + 2 * tv);
             const uint4 zv = *reinterpret_cast<const uint4*>(sVm + 2 * R + 2 * tv);
-            unsigned sw[4] = {sv.x, sv.y, sv.z, sv.w};
-            const unsigned zw[4] = {zv.x, zv.y, zv.z, zv.w};
-            if (big_s) {
-#pragma unroll
-              for (int i = 0; i < 4; ++i) sw[i] = pk_mul(sw[i], kVsDown);
-            }
+            const unsigned sw[4] = {sv.x, sv.y, sv.z, sv.w}, zw[4] = {zv.x, zv.y, zv.z, zv.w};
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
               const unsigned pm = pk_mul(pk[i], sw[i]);
@@ -912,12 +919,8 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
             const uint4* ps = reinterpret_cast<const uint4*>(sVm + 4 * tv);
             const uint4* pz = reinterpret_cast<const uint4*>(sVm + 4 * R + 4 * tv);
             const uint4 s0 = ps[0], s1 = ps[1], z0 = pz[0], z1 = pz[1];
-            unsigned sw[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+            const unsigned sw[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
             const unsigned zw[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
-            if (big_s) {
-#pragma unroll
-              for (int i = 0; i < 8; ++i) sw[i] = pk_mul(sw[i], kVsDown);
-            }
 #pragma unroll
             for (int a = 0; a < NVG; ++a)
 #pragma unroll
@@ -941,26 +944,9 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
             s4[i] = reinterpret_cast<const uint4*>(sVm + 8 * tv)[i];
             z4[i] = reinterpret_cast<const uint4*>(sVm + 8 * R + 8 * tv)[i];
           }
-          if (big_s) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              s4[i].x = pk_mul(s4[i].x, kVsDown);
-              s4[i].y = pk_mul(s4[i].y, kVsDown);
-              s4[i].z = pk_mul(s4[i].z, kVsDown);
-              s4[i].w = pk_mul(s4[i].w, kVsDown);
-            }
-          }
         }
 
         // ---- O^T += V_codes^T . Ps^T ----
-        // (guarded record: the products come out 2^-kPBoost too small, so the sums they join are taken down by the
-        //  same exact factor first and brought back afterwards)
-        if (big_s) {
-#pragma unroll
-          for (int xp = 0; xp < 2; ++xp)
-#pragma unroll
-            for (int qq = 0; qq < 4; ++qq) O[xp][qq] *= 1.f / (float)(1 << kPBoost);
-        }
 #pragma unroll
         for (int xp = 0; xp < 2; ++xp) {
           const u32x4 vw = vreg[hsg][xp];
@@ -988,14 +974,14 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
             O[xp][qq] = mfma(a1, Bp[a][1], O[xp][qq]);
           }
         }
-        if (big_s) {
-#pragma unroll
-          for (int xp = 0; xp < 2; ++xp)
-#pragma unroll
-            for (int qq = 0; qq < 4; ++qq) O[xp][qq] *= (float)(1 << kPBoost);
-        }
         if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_V_HALF(blk + blk_step, hsg)
       }
+    }
+    if (big_s) {
+#pragma unroll
+      for (int xp = 0; xp < 2; ++xp)
+#pragma unroll
+        for (int qq = 0; qq < 4; ++qq) O[xp][qq] *= (float)(1 << kPBoost);
     }
     MIXKVQ_PHASE(phase_i < 11 ? phase_i : 11)
     ++phase_i;

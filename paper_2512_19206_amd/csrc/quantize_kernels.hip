@@ -77,7 +77,7 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
   __shared__ unsigned char sLoList[kD];    // 2-bit channels, ascending
   __shared__ unsigned char sHiList[kD];    // fp16 tier then 4-bit tier
   __shared__ float sS[8 * kD], sZ[8 * kD]; // [group][channel] scale / zero-point of the channel's tier
-  __shared__ unsigned sKmax[8];            // per group: largest stored scale (fp16 bits; scales are >= 0)
+  __shared__ unsigned sKmax[9];            // per key group: largest stored scale (fp16 bits; scales are >= 0); [8]: values
   __shared__ int sN[3];                    // channels per tier
 
   const mixkvq_config& cfg = cv.cfg;
@@ -93,7 +93,7 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
     reinterpret_cast<unsigned*>(rec)[i] = (cfg.policy == 1 && i < ks / 4) ? 0xffffffffu : 0u;
 
   load_tile(sT, window_rows(cv, cv.res_k, p), k_new, st, p, cfg.Hkv, R, r0, f * R, cfg.in_dtype != 0);
-  if (tid < 8) sKmax[tid] = 0u;
+  if (tid < 9) sKmax[tid] = 0u;
   __syncthreads();
 
   // ---- channel tiers --------------------------------------------------
@@ -233,10 +233,12 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
     GroupParams gp = group_params(mn, mx, 3.f);
     sVS[it] = gp.s;
     sVZ[it] = gp.z;
+    atomicMax(&sKmax[8], (unsigned)gp.s16);
     reinterpret_cast<unsigned short*>(rec + lay.off_v_s)[it] = gp.s16;
     reinterpret_cast<unsigned short*>(rec + lay.off_v_z)[it] = gp.z16;
   }
   __syncthreads();
+  if (tid == 0) reinterpret_cast<unsigned short*>(rec + lay.off_kmax)[NG] = (unsigned short)sKmax[8];
   // value words: [token group][channel], 16 codes along tokens
   for (int it = tid; it < (R / 16) * kD; it += kFlushThreads) {
     const int tg = it / kD, d = it % kD, vg = d / Gv;
@@ -323,7 +325,7 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   __shared__ unsigned char sHiList[kD];    // fp16 tier then 4-bit tier
   __shared__ __align__(16) float sS[8 * kD], sZ[8 * kD];   // keys: [group][channel]; values: [token][value group]
   __shared__ __align__(16) float sR[8 * kD];   // reciprocals of the scales in sS (0 for scale 0)
-  __shared__ unsigned sKmax[8];
+  __shared__ unsigned sKmax[9];            // [8]: largest value scale
   __shared__ unsigned sChunk[2][kMaxR / 16][kD / 2];   // (min, max) keys per 16-token chunk and channel pair
   unsigned (*sCLo)[kD / 2] = sChunk[0];
   unsigned (*sCHi)[kD / 2] = sChunk[1];
@@ -391,7 +393,7 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   // (under the threshold policy the channel lists start out as "no channel")
   for (int i = tid; i < off_klo / 4; i += kFlushThreads)
     reinterpret_cast<unsigned*>(rec)[i] = (policy == 1 && i < ks / 4) ? 0xffffffffu : 0u;
-  if (tid < 8) sKmax[tid] = 0u;
+  if (tid < 9) sKmax[tid] = 0u;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int idx = tid + kFlushThreads * i;
@@ -653,11 +655,13 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
       sVS[it] = gp.s;
       sVZ[it] = gp.z;
       sR[it] = safe_rcp(gp.s);
+      atomicMax(&sKmax[8], (unsigned)gp.s16);
       reinterpret_cast<unsigned short*>(rec + off_v_s)[it] = gp.s16;
       reinterpret_cast<unsigned short*>(rec + off_v_z)[it] = gp.z16;
     }
   }
   __syncthreads();
+  if (tid == 0) reinterpret_cast<unsigned short*>(rec + off_kmax)[NG] = (unsigned short)sKmax[8];
   MIXKVQ_FPHASE(8)
   // value words [token group][channel], 16 codes along tokens: the 16 tokens' parameters in registers
   {
