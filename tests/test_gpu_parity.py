@@ -287,6 +287,49 @@ def test_sink_tokens(H, R, Gk, sink, k4, g, flush_mode):
     assert oc.n_sink + oc.n_quant + oc.n_res == n0 + R + 3
 
 
+def test_dominant_token_with_flat_tail(H):
+    """The attention-sink shape at a batch so large that a pair gets ONE workgroup (512 pairs): one token carries
+    weight 1 and thousands of tokens 2^-17 of it, together an eighth of the mass.  A quarter of them share the
+    dominant token's wavefront, whose running maximum they are measured against; their weights must survive the
+    fp16 rounding on the way to the matrix cores."""
+    import math
+    import paper_2512_19206_amd as M
+    from oracle import mixkvq_oracle as O
+    rng = np.random.default_rng(900)
+    B, Hkv, g, R, T = 64, 8, 2, 128, 8192 + 64
+    kw = dict(Hq=g, Hkv=1, D=128, T_max=(T + 2 * R) // R * R, Gk=128, Gv=128, R=R, k4=16, k16=0)
+    gc = M.Cache(M.make_config(B=B, Hq=Hkv * g, Hkv=Hkv, D=128, **{k: v for k, v in kw.items() if k not in ("Hq", "Hkv", "D")}))
+    Kd = torch.zeros((B, Hkv, T, 128), dtype=torch.float16, device="cuda")
+    Vd = torch.zeros_like(Kd)
+    qd = torch.zeros((B, Hkv * g, 128), dtype=torch.float16, device="cuda")
+    scale = 1.0 / math.sqrt(128)
+    cases = []
+    for (b, j, spike) in ((3, 5, 17), (40, 0, 5000)):        # spike in the first record of its wavefront / mid-way
+        K = (rng.standard_normal((1, 1, T, 128)) * 0.5).astype(np.float16)
+        K[..., 0] = 0
+        K[0, 0, spike, 0] = 8.0
+        V = (1.0 + 0.3 * rng.standard_normal((1, 1, T, 128))).astype(np.float16)
+        V[0, 0, spike] = -5.0
+        q = np.zeros((1, g, 128), dtype=np.float16)
+        q[:, :, 0] = (17 * math.log(2)) / (8.0 * scale)       # the crowd sits at 2^-17 of the spike
+        Kd[b, j], Vd[b, j], qd[b, j * g:(j + 1) * g] = H.dev(K)[0, 0], H.dev(V)[0, 0], H.dev(q)[0]
+        cases.append((b, j, K, V, q))
+    gc.quantize_append(Kd, Vd)
+    out, lse = gc.decode_attention(qd)
+    torch.cuda.synchronize()
+    for b, j, K, V, q in cases:
+        oc = O.OracleCache(O.OracleConfig(B=1, **kw))
+        oc.append(K, V)
+        ro, rl = oc.decode_attention(q)
+        go = out[b, j * g:(j + 1) * g].float().cpu().numpy()
+        gl = lse[b, j * g:(j + 1) * g].cpu().numpy()
+        assert abs(float(ro[0, 0, 5]) + 5.0) > 0.3            # the crowd really carries weight
+        err = np.abs(go - ro[0])
+        assert np.all(err <= H.ATOL + H.RTOL * np.abs(ro[0])), (b, j, float(err.max()))
+        assert np.all(np.abs(gl - rl[0]) <= H.LSE_ATOL + 1e-4 * np.abs(rl[0])), (b, j, float(np.abs(gl - rl[0]).max()))
+        assert float(err.max()) < 5e-3, (b, j, float(err.max()))   # far inside the tolerance: no weight is dropped
+
+
 def test_chunked_append_without_selection_matches_oracle(H):
     """sel = NULL on a multi-token append: every flushed block is scored on its own."""
     rng = np.random.default_rng(8)
