@@ -12,7 +12,9 @@
  *     device work is enqueued asynchronously on it; no call synchronises or reads
  *     device memory back.  Token counts depend only on the sequence of n_new
  *     values, so the host-side state is exact without a read-back.
- *   - All sequences of a batch advance in lock-step (same token count).
+ *   - The batch calls advance all sequences together.  Sequences may still differ in length: the *_seq calls
+ *     work on one sequence of the batch (prefill of a new request into a free slot, reset of a finished one); after
+ *     them every batch call appends to / attends over each sequence from its own state.
  *   - Grouped-query mapping: query heads [j*g, (j+1)*g) use KV head j, g = Hq/Hkv.
  *   - "fp16" tensors below are IEEE binary16, or bfloat16 when cfg.in_dtype == 1 (same shapes and strides, in
  *     elements); Inf/NaN inputs are outside the contract.
@@ -34,6 +36,7 @@ extern "C" {
 #define MIXKVQ_EHIP      (-3)  /* a HIP call failed; mixkvq_strerror gives the HIP message */
 #define MIXKVQ_ENOMEM    (-4)  /* host allocation of the handle failed */
 #define MIXKVQ_EEMPTY    (-5)  /* decode attention on a cache that holds no token */
+#define MIXKVQ_ERAGGED   (-6)  /* mixkvq_cache_state on a batch whose sequences differ: use mixkvq_cache_state_seq */
 
 typedef struct mixkvq_cache mixkvq_cache; /* opaque HOST handle: counts + the caller's device pointers */
 
@@ -121,8 +124,13 @@ void mixkvq_cache_destroy(mixkvq_cache* c);
 /* Empties the cache (token counts to 0) and zeroes the |q| accumulator on `stream`. */
 int mixkvq_cache_reset(mixkvq_cache* c, void* stream);
 
-/* Host-only: quantized, residual-window and sink token counts.  Any out pointer may be NULL. */
+/* Host-only: quantized, residual-window and sink token counts.  Any out pointer may be NULL.
+ * ERAGGED if the sequences differ (then ask per sequence). */
 int mixkvq_cache_state(const mixkvq_cache* c, int64_t* n_quantized, int32_t* n_residual, int32_t* n_sink);
+int mixkvq_cache_state_seq(const mixkvq_cache* c, int32_t b, int64_t* n_quantized, int32_t* n_residual, int32_t* n_sink);
+
+/* Empties sequence b only (its token counts and its rows of the |q| accumulator). */
+int mixkvq_cache_reset_seq(mixkvq_cache* c, int32_t b, void* stream);
 
 /* Channel selection (Section 4.2, Eq. 6-8; top-k channel budget or thresholds, see mixkvq_config.policy).
  *   q  DEVICE fp16 [B][Hq][Lq][D] after rotary embedding, element strides q_strides = {batch, head, token},
@@ -138,6 +146,11 @@ int mixkvq_select_channels(mixkvq_cache* c, const void* q, int32_t Lq, const int
                            const void* k, int32_t L, const int64_t k_strides[3],
                            uint8_t* sel, void* stream);
 
+/* mixkvq_select_channels for sequence b alone: q DEVICE [Hq][Lq][D] with element strides {head, token}, k DEVICE
+ * [Hkv][L][D] likewise, sel DEVICE u8 [Hkv][k16+k4].  Same rules otherwise. */
+int mixkvq_select_channels_seq(mixkvq_cache* c, int32_t b, const void* q, int32_t Lq, const int64_t q_strides[2],
+                               const void* k, int32_t L, const int64_t k_strides[2], uint8_t* sel, void* stream);
+
 /* Prefill (n_new = prompt length) and per-step (n_new = 1) append (Appendix D.1).
  *   k_new, v_new  DEVICE fp16 [B][Hkv][n_new][D], element strides kv_strides = {batch, head, token}.
  *   sel           DEVICE u8 [B][Hkv][k16+k4] or NULL.
@@ -150,11 +163,17 @@ int mixkvq_select_channels(mixkvq_cache* c, const void* q, int32_t Lq, const int
 int mixkvq_quantize_append(mixkvq_cache* c, const void* k_new, const void* v_new, int32_t n_new,
                            const int64_t kv_strides[3], const uint8_t* sel, void* stream);
 
+/* mixkvq_quantize_append for sequence b alone: k_new, v_new DEVICE [Hkv][n_new][D] with element strides
+ * {head, token}, sel DEVICE u8 [Hkv][k16+k4] or NULL.  The other sequences are untouched. */
+int mixkvq_quantize_append_seq(mixkvq_cache* c, int32_t b, const void* k_new, const void* v_new, int32_t n_new,
+                               const int64_t kv_strides[2], const uint8_t* sel, void* stream);
+
 /* One query token per sequence (Section 3.1, Eq. 1, over keys/values dequantized by Eq. 3).
  *   q    DEVICE fp16 [B][Hq][D] contiguous;  out DEVICE fp16 [B][Hq][D];  lse DEVICE fp32 [B][Hq] or NULL
  *        (natural-log sum of exp of the scaled logits).
  *   scale <= 0 means 1/sqrt(D).  accumulate_q != 0 also adds |q| to the accumulator (Appendix D.2).
- * EEMPTY if the cache holds no token. */
+ * EEMPTY if the cache holds no token.  When the sequences differ in length each attends over its own tokens (at most
+ * 256 sequences then, else EINVAL); a sequence without tokens gets out = 0 and lse = -inf and its |q| is not accumulated. */
 int mixkvq_decode_attention(mixkvq_cache* c, const void* q, void* out, float* lse,
                             float scale, int32_t accumulate_q, void* stream);
 

@@ -16,7 +16,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmixkvq.so")
 
 EXPORTS = ("mixkvq_block_layout", "mixkvq_cache_sizes", "mixkvq_cache_create", "mixkvq_cache_destroy",
-           "mixkvq_cache_reset", "mixkvq_cache_state", "mixkvq_select_channels", "mixkvq_quantize_append",
+           "mixkvq_cache_reset", "mixkvq_cache_reset_seq", "mixkvq_cache_state", "mixkvq_cache_state_seq",
+           "mixkvq_select_channels", "mixkvq_select_channels_seq", "mixkvq_quantize_append", "mixkvq_quantize_append_seq",
            "mixkvq_decode_attention", "mixkvq_decode_step", "mixkvq_set_timing_events", "mixkvq_strerror")
 
 
@@ -67,6 +68,10 @@ def load_library() -> C.CDLL:
     lib.mixkvq_cache_destroy.restype = None
     lib.mixkvq_cache_reset.argtypes = [vp, vp]
     lib.mixkvq_cache_state.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    lib.mixkvq_cache_reset_seq.argtypes = [vp, i32, vp]
+    lib.mixkvq_cache_state_seq.argtypes = [vp, i32, C.POINTER(C.c_int64), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    lib.mixkvq_select_channels_seq.argtypes = [vp, i32, vp, i32, i64p, vp, i32, i64p, vp, vp]
+    lib.mixkvq_quantize_append_seq.argtypes = [vp, i32, vp, vp, i32, i64p, vp, vp]
     lib.mixkvq_select_channels.argtypes = [vp, vp, i32, i64p, vp, i32, i64p, vp, vp]
     lib.mixkvq_quantize_append.argtypes = [vp, vp, vp, i32, i64p, vp, vp]
     lib.mixkvq_decode_attention.argtypes = [vp, vp, vp, vp, C.c_float, i32, vp]
@@ -159,6 +164,34 @@ class Cache:
         n = C.c_int32()
         _check(self.lib.mixkvq_cache_state(self.handle, None, None, C.byref(n)))
         return n.value
+
+    # ---- one sequence of the batch (sequences may differ in length) ----
+    def reset_seq(self, b: int, stream=None):
+        _check(self.lib.mixkvq_cache_reset_seq(self.handle, int(b), _stream_ptr(stream)))
+
+    def state_seq(self, b: int):
+        """(quantized tokens, tokens in the residual window, tokens in the sink) of sequence b."""
+        nq, r, ns = C.c_int64(), C.c_int32(), C.c_int32()
+        _check(self.lib.mixkvq_cache_state_seq(self.handle, int(b), C.byref(nq), C.byref(r), C.byref(ns)))
+        return nq.value, r.value, ns.value
+
+    def select_channels_seq(self, b: int, q, k, sel=None, stream=None):
+        """q: fp16 [Hq, Lq, D] or None; k: fp16 [Hkv, L, D].  Returns u8 [Hkv, ks] on the device."""
+        if sel is None:
+            sel = torch.empty((self.cfg.Hkv, self.ks), dtype=torch.uint8, device=self.device)
+        s2 = lambda t: (C.c_int64 * 2)(t.stride(0), t.stride(1))
+        qp, Lq, qs = (None, 0, None) if q is None else (q.data_ptr(), q.shape[1], s2(q))
+        _check(self.lib.mixkvq_select_channels_seq(self.handle, int(b), qp, Lq, qs, k.data_ptr(), k.shape[1], s2(k),
+                                                   sel.data_ptr(), _stream_ptr(stream)))
+        return sel
+
+    def quantize_append_seq(self, b: int, k_new, v_new, sel=None, stream=None):
+        """k_new, v_new: fp16 [Hkv, n, D] with equal strides."""
+        assert k_new.dim() == 3 and k_new.stride(2) == 1 and k_new.stride() == v_new.stride()
+        st = (C.c_int64 * 2)(k_new.stride(0), k_new.stride(1))
+        _check(self.lib.mixkvq_quantize_append_seq(self.handle, int(b), k_new.data_ptr(), v_new.data_ptr(),
+                                                   k_new.shape[1], st, None if sel is None else sel.data_ptr(),
+                                                   _stream_ptr(stream)))
 
     def select_channels(self, q, k, sel=None, stream=None):
         """q: fp16 [B, Hq, Lq, D] or None; k: fp16 [B, Hkv, L, D].  Returns u8 [B, Hkv, ks] on the device."""

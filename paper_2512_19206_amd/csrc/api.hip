@@ -80,13 +80,121 @@ static inline uint64_t al256(uint64_t n) { return (n + 255) / 256 * 256; }
 
 using namespace mixkvq;
 
+struct SeqState {
+  int64_t n_quant;   // quantized tokens
+  int32_t n_res;     // tokens in the residual window
+  int32_t n_sink;    // tokens in the sink
+  bool operator==(const SeqState& o) const { return n_quant == o.n_quant && n_res == o.n_res && n_sink == o.n_sink; }
+};
+
 struct mixkvq_cache {
   CacheView v;
-  int64_t n_quant;
-  int32_t n_res;
-  int32_t n_sink;
+  SeqState* seq;     // [B]: every sequence has its own counts (they are equal while the batch runs in lock-step)
   hipEvent_t ev_start = nullptr, ev_stop = nullptr;   // optional timing of the split kernel
 };
+
+namespace mixkvq {
+
+// View of sequences [b0, b0 + nb) of the cache: the same kernels run on it as on the whole batch.
+static CacheView sub_view(const mixkvq_cache* c, int b0, int nb) {
+  CacheView v = c->v;
+  const size_t p0 = (size_t)b0 * v.cfg.Hkv;
+  v.cfg.B = nb;
+  v.P = nb * v.cfg.Hkv;
+  v.blocks += p0 * v.NB * v.lay.rec_bytes;
+  v.res_k += p0 * v.RW * kD;
+  v.res_v += p0 * v.RW * kD;
+  v.qacc += p0 * kD;
+  v.qcnt += p0;
+  return v;
+}
+
+// What an append of n_new tokens does to a sequence in state st: tokens for the sink, blocks flushed, what remains.
+struct AppendPlan { int take; int64_t F; int n_rest; int n_win; };
+static AppendPlan plan_append(const mixkvq_config& cfg, const SeqState& st, int n_new) {
+  const int R = cfg.R, S = cfg.sink;
+  AppendPlan pl;
+  // the first S tokens of the sequence go to the sink; the others take the window / flush path
+  pl.take = st.n_sink < S ? (n_new < S - st.n_sink ? n_new : S - st.n_sink) : 0;
+  pl.n_win = n_new - pl.take;
+  const int64_t total = (int64_t)st.n_res + pl.n_win;
+  // Deferred: a full window is flushed just before the next token enters, so 1..R tokens remain.
+  // Eager: a window is flushed as soon as it is full, so 0..R-1 tokens remain.
+  pl.F = cfg.flush_mode == 0 ? (total + R - 1) / R - 1 : total / R;
+  if (pl.F < 0) pl.F = 0;
+  pl.n_rest = (int)(total - pl.F * R);
+  return pl;
+}
+
+// Appends n_new tokens to sequences [b0, b0 + nb), which share one state.  k_new, v_new point at batch entry b0.
+static int append_range(mixkvq_cache* c, int b0, int nb, const __half* k_new, const __half* v_new, int n_new,
+                        Strides3 kvs, const uint8_t* sel, hipStream_t s) {
+  const mixkvq_config& cfg = c->v.cfg;
+  const int R = cfg.R, S = cfg.sink;
+  const SeqState st = c->seq[b0];
+  const AppendPlan pl = plan_append(cfg, st, n_new);
+  const CacheView v = sub_view(c, b0, nb);
+  SeqState nx = st;
+  if (pl.take > 0) {
+    MIXKVQ_TRY_HIP(launch_residual_copy(v, k_new, v_new, kvs, 0, st.n_sink, pl.take, s));
+    nx.n_sink += pl.take;
+  }
+  if (pl.n_win > 0) {
+    // from here on "new tokens" are the n_win tokens after the sink's share (strides are multiples of 8 elements,
+    // so the shifted pointers keep their 16-byte alignment)
+    const __half* kw = k_new + (int64_t)pl.take * kvs.t;
+    const __half* vw = v_new + (int64_t)pl.take * kvs.t;
+    const int r0 = st.n_res;
+    if (pl.F > 0) MIXKVQ_TRY_HIP(launch_flush(v, kw, vw, kvs, r0, (int)(st.n_quant / R), (int)pl.F, sel, s));
+    // Tokens that stay in the window.  Stream position x of (old residual ++ new tokens) maps to
+    // new-token index x - r0; after F flushes positions [F*R, total) remain.
+    const int64_t rest_first = pl.F * R;
+    if (pl.F == 0) {
+      MIXKVQ_TRY_HIP(launch_residual_copy(v, kw, vw, kvs, 0, S + r0, pl.n_win, s));
+    } else if (pl.n_rest > 0) {
+      MIXKVQ_TRY_HIP(launch_residual_copy(v, kw, vw, kvs, (int)(rest_first - r0), S, pl.n_rest, s));
+    }
+    if (pl.F > 0 && cfg.qacc_reset_on_flush) MIXKVQ_TRY_HIP(launch_zero_qacc(v, s));
+    nx.n_quant += pl.F * R;
+    nx.n_res = pl.n_rest;
+  }
+  for (int b = b0; b < b0 + nb; ++b) c->seq[b] = nx;
+  return MIXKVQ_OK;
+}
+
+static bool lock_step(const mixkvq_cache* c) {
+  for (int b = 1; b < c->v.cfg.B; ++b)
+    if (!(c->seq[b] == c->seq[0])) return false;
+  return true;
+}
+
+// Counts for a decode launch: the scalar maxima, and per sequence when they differ (sc->enabled).
+// Returns false when the batch is ragged and too large for the by-value table.
+static bool decode_counts(const mixkvq_cache* c, int extra_fp16, int* n_blocks, int* n_fp16, SeqCounts* sc) {
+  const mixkvq_config& cfg = c->v.cfg;
+  int mb = 0, mf = 0;
+  for (int b = 0; b < cfg.B; ++b) {
+    const SeqState& st = c->seq[b];
+    const int nb = (int)(st.n_quant / cfg.R), nf = st.n_sink + st.n_res + extra_fp16;
+    mb = nb > mb ? nb : mb;
+    mf = nf > mf ? nf : mf;
+  }
+  *n_blocks = mb;
+  *n_fp16 = mf;
+  sc->enabled = lock_step(c) ? 0 : 1;
+  if (sc->enabled) {
+    if (cfg.B > kMaxRaggedB) return false;
+    for (int b = 0; b < cfg.B; ++b) {
+      const SeqState& st = c->seq[b];
+      const int nf = st.n_sink + st.n_res;
+      sc->n_blocks[b] = (int)(st.n_quant / cfg.R);
+      sc->n_fp16[b] = (uint16_t)(nf + extra_fp16);
+    }
+  }
+  return true;
+}
+
+}  // namespace mixkvq
 
 extern "C" {
 
@@ -124,6 +232,11 @@ int mixkvq_cache_create(const mixkvq_config* cfg, const mixkvq_buffers* bufs, mi
     if (!p || ((uintptr_t)p & 255u)) return MIXKVQ_EINVAL;
   mixkvq_cache* c = new (std::nothrow) mixkvq_cache;
   if (!c) return MIXKVQ_ENOMEM;
+  c->seq = new (std::nothrow) SeqState[cfg->B];
+  if (!c->seq) {
+    delete c;
+    return MIXKVQ_ENOMEM;
+  }
   c->v.cfg = *cfg;
   c->v.lay = l;
   c->v.P = cfg->B * cfg->Hkv;
@@ -137,29 +250,45 @@ int mixkvq_cache_create(const mixkvq_config* cfg, const mixkvq_buffers* bufs, mi
   c->v.qacc = (unsigned long long*)bufs->qacc;
   c->v.qcnt = c->v.qacc + (size_t)c->v.P * cfg->D;
   c->v.ws = (uint8_t*)bufs->workspace;
-  c->n_quant = 0;
-  c->n_res = 0;
-  c->n_sink = 0;
+  for (int b = 0; b < cfg->B; ++b) c->seq[b] = SeqState{0, 0, 0};
   *out = c;
   return MIXKVQ_OK;
 }
 
-void mixkvq_cache_destroy(mixkvq_cache* c) { delete c; }
+void mixkvq_cache_destroy(mixkvq_cache* c) {
+  if (!c) return;
+  delete[] c->seq;
+  delete c;
+}
 
 int mixkvq_cache_reset(mixkvq_cache* c, void* stream) {
   if (!c) return MIXKVQ_EINVAL;
   MIXKVQ_TRY_HIP(launch_zero_qacc(c->v, (hipStream_t)stream));
-  c->n_quant = 0;
-  c->n_res = 0;
-  c->n_sink = 0;
+  for (int b = 0; b < c->v.cfg.B; ++b) c->seq[b] = SeqState{0, 0, 0};
+  return MIXKVQ_OK;
+}
+
+int mixkvq_cache_reset_seq(mixkvq_cache* c, int32_t b, void* stream) {
+  if (!c || b < 0 || b >= c->v.cfg.B) return MIXKVQ_EINVAL;
+  MIXKVQ_TRY_HIP(launch_zero_qacc(sub_view(c, b, 1), (hipStream_t)stream));
+  c->seq[b] = SeqState{0, 0, 0};
   return MIXKVQ_OK;
 }
 
 int mixkvq_cache_state(const mixkvq_cache* c, int64_t* n_quantized, int32_t* n_residual, int32_t* n_sink) {
   if (!c) return MIXKVQ_EINVAL;
-  if (n_quantized) *n_quantized = c->n_quant;
-  if (n_residual) *n_residual = c->n_res;
-  if (n_sink) *n_sink = c->n_sink;
+  if (!lock_step(c)) return MIXKVQ_ERAGGED;
+  if (n_quantized) *n_quantized = c->seq[0].n_quant;
+  if (n_residual) *n_residual = c->seq[0].n_res;
+  if (n_sink) *n_sink = c->seq[0].n_sink;
+  return MIXKVQ_OK;
+}
+
+int mixkvq_cache_state_seq(const mixkvq_cache* c, int32_t b, int64_t* n_quantized, int32_t* n_residual, int32_t* n_sink) {
+  if (!c || b < 0 || b >= c->v.cfg.B) return MIXKVQ_EINVAL;
+  if (n_quantized) *n_quantized = c->seq[b].n_quant;
+  if (n_residual) *n_residual = c->seq[b].n_res;
+  if (n_sink) *n_sink = c->seq[b].n_sink;
   return MIXKVQ_OK;
 }
 
@@ -178,93 +307,117 @@ int mixkvq_select_channels(mixkvq_cache* c, const void* q, int32_t Lq, const int
   return MIXKVQ_OK;
 }
 
+int mixkvq_select_channels_seq(mixkvq_cache* c, int32_t b, const void* q, int32_t Lq, const int64_t q_strides[2],
+                               const void* k, int32_t L, const int64_t k_strides[2], uint8_t* sel, void* stream) {
+  if (!c || b < 0 || b >= c->v.cfg.B || !k || !k_strides || !sel || L < 1 || Lq < 0) return MIXKVQ_EINVAL;
+  if (Lq > 0 && (!q || !q_strides)) return MIXKVQ_EINVAL;
+  if (c->v.cfg.k4 + c->v.cfg.k16 == 0) return MIXKVQ_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  const CacheView v = sub_view(c, b, 1);
+  if (Lq > 0) {
+    Strides3 qs{0, q_strides[0], q_strides[1]};
+    MIXKVQ_TRY_HIP(launch_qabs_accumulate(v, (const __half*)q, Lq, qs, s));
+  }
+  Strides3 ks{0, k_strides[0], k_strides[1]};
+  MIXKVQ_TRY_HIP(launch_select(v, (const __half*)k, L, ks, sel, s));
+  return MIXKVQ_OK;
+}
+
+static int check_kv_args(const void* k_new, const void* v_new, const int64_t* strides, int n_strides) {
+  if (!k_new || !v_new || !strides) return MIXKVQ_EINVAL;
+  // rows are moved with 16-byte accesses
+  if (((uintptr_t)k_new & 15u) || ((uintptr_t)v_new & 15u)) return MIXKVQ_EINVAL;
+  for (int i = 0; i < n_strides; ++i)
+    if (strides[i] % 8 != 0) return MIXKVQ_EINVAL;
+  return MIXKVQ_OK;
+}
+
 int mixkvq_quantize_append(mixkvq_cache* c, const void* k_new, const void* v_new, int32_t n_new,
                            const int64_t kv_strides[3], const uint8_t* sel, void* stream) {
   if (!c || n_new < 0) return MIXKVQ_EINVAL;
   if (n_new == 0) return MIXKVQ_OK;
-  if (!k_new || !v_new || !kv_strides) return MIXKVQ_EINVAL;
-  // rows are moved with 16-byte accesses
-  if (((uintptr_t)k_new & 15u) || ((uintptr_t)v_new & 15u)) return MIXKVQ_EINVAL;
-  for (int i = 0; i < 3; ++i)
-    if (kv_strides[i] % 8 != 0) return MIXKVQ_EINVAL;
+  int rc = check_kv_args(k_new, v_new, kv_strides, 3);
+  if (rc != MIXKVQ_OK) return rc;
   const mixkvq_config& cfg = c->v.cfg;
-  const int R = cfg.R, S = cfg.sink;
-  // the first S tokens of the sequence go to the sink; the others take the window / flush path below
-  const int take = c->n_sink < S ? (n_new < S - c->n_sink ? n_new : S - c->n_sink) : 0;
-  const int n_win = n_new - take;
-  const int64_t total = (int64_t)c->n_res + n_win;
-  // Deferred: a full window is flushed just before the next token enters, so 1..R tokens remain.
-  // Eager: a window is flushed as soon as it is full, so 0..R-1 tokens remain.
-  int64_t F = cfg.flush_mode == 0 ? (total + R - 1) / R - 1 : total / R;
-  if (F < 0) F = 0;
-  if (c->n_quant + F * R > cfg.T_max) return MIXKVQ_ECAPACITY;
-  if (F > (1 << 24)) return MIXKVQ_EINVAL;
-  hipStream_t s = (hipStream_t)stream;
+  for (int b = 0; b < cfg.B; ++b) {     // nothing is touched unless every sequence has room
+    const AppendPlan pl = plan_append(cfg, c->seq[b], n_new);
+    if (c->seq[b].n_quant + pl.F * cfg.R > cfg.T_max) return MIXKVQ_ECAPACITY;
+    if (pl.F > (1 << 24)) return MIXKVQ_EINVAL;
+  }
   Strides3 kvs{kv_strides[0], kv_strides[1], kv_strides[2]};
-  if (take > 0) {
-    MIXKVQ_TRY_HIP(launch_residual_copy(c->v, (const __half*)k_new, (const __half*)v_new, kvs, 0, c->n_sink, take, s));
-    c->n_sink += take;
-    if (n_win == 0) return MIXKVQ_OK;
+  const int ks = cfg.k4 + cfg.k16;
+  // runs of neighbouring sequences in the same state are appended to together (one run while the batch is in lock-step)
+  for (int b0 = 0; b0 < cfg.B;) {
+    int b1 = b0 + 1;
+    while (b1 < cfg.B && c->seq[b1] == c->seq[b0]) ++b1;
+    rc = append_range(c, b0, b1 - b0, (const __half*)k_new + (int64_t)b0 * kvs.b, (const __half*)v_new + (int64_t)b0 * kvs.b,
+                      n_new, kvs, sel ? sel + (size_t)b0 * cfg.Hkv * ks : nullptr, (hipStream_t)stream);
+    if (rc != MIXKVQ_OK) return rc;
+    b0 = b1;
   }
-  // from here on "new tokens" are the n_win tokens after the sink's share (strides are multiples of 8 elements,
-  // so the shifted pointers keep their 16-byte alignment)
-  const __half* kw = (const __half*)k_new + (int64_t)take * kvs.t;
-  const __half* vw = (const __half*)v_new + (int64_t)take * kvs.t;
-  const int r0 = c->n_res;
-  if (F > 0) {
-    MIXKVQ_TRY_HIP(launch_flush(c->v, kw, vw, kvs, r0, (int)(c->n_quant / R), (int)F, sel, s));
-  }
-  // Tokens that stay in the window.  Stream position x of (old residual ++ new tokens) maps to
-  // new-token index x - r0; after F flushes positions [F*R, total) remain.
-  const int64_t rest_first = F * R;
-  const int n_rest = (int)(total - rest_first);
-  if (F == 0) {
-    MIXKVQ_TRY_HIP(launch_residual_copy(c->v, kw, vw, kvs, 0, S + r0, n_win, s));
-  } else if (n_rest > 0) {
-    MIXKVQ_TRY_HIP(launch_residual_copy(c->v, kw, vw, kvs, (int)(rest_first - r0), S, n_rest, s));
-  }
-  if (F > 0 && cfg.qacc_reset_on_flush) MIXKVQ_TRY_HIP(launch_zero_qacc(c->v, s));
-  c->n_quant += F * R;
-  c->n_res = n_rest;
   return MIXKVQ_OK;
+}
+
+int mixkvq_quantize_append_seq(mixkvq_cache* c, int32_t b, const void* k_new, const void* v_new, int32_t n_new,
+                               const int64_t kv_strides[2], const uint8_t* sel, void* stream) {
+  if (!c || b < 0 || b >= c->v.cfg.B || n_new < 0) return MIXKVQ_EINVAL;
+  if (n_new == 0) return MIXKVQ_OK;
+  int rc = check_kv_args(k_new, v_new, kv_strides, 2);
+  if (rc != MIXKVQ_OK) return rc;
+  const mixkvq_config& cfg = c->v.cfg;
+  const AppendPlan pl = plan_append(cfg, c->seq[b], n_new);
+  if (c->seq[b].n_quant + pl.F * cfg.R > cfg.T_max) return MIXKVQ_ECAPACITY;
+  if (pl.F > (1 << 24)) return MIXKVQ_EINVAL;
+  Strides3 kvs{0, kv_strides[0], kv_strides[1]};
+  return append_range(c, b, 1, (const __half*)k_new, (const __half*)v_new, n_new, kvs, sel, (hipStream_t)stream);
 }
 
 int mixkvq_decode_attention(mixkvq_cache* c, const void* q, void* out, float* lse, float scale,
                             int32_t accumulate_q, void* stream) {
   if (!c || !q || !out) return MIXKVQ_EINVAL;
-  if (c->n_quant == 0 && c->n_res == 0 && c->n_sink == 0) return MIXKVQ_EEMPTY;
   const mixkvq_config& cfg = c->v.cfg;
+  int n_blocks, n_fp16;
+  SeqCounts sc;
+  if (!decode_counts(c, 0, &n_blocks, &n_fp16, &sc)) return MIXKVQ_EINVAL;
+  if (n_blocks == 0 && n_fp16 == 0) return MIXKVQ_EEMPTY;
   hipStream_t s = (hipStream_t)stream;
   if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)cfg.D);
-  MIXKVQ_TRY_HIP(launch_decode(c->v, (const __half*)q, (__half*)out, lse, scale, (int)(c->n_quant / cfg.R),
-                               c->n_sink + c->n_res, accumulate_q, NewToken{nullptr, nullptr, {0, 0, 0}, 0}, s, c->ev_start,
+  MIXKVQ_TRY_HIP(launch_decode(c->v, (const __half*)q, (__half*)out, lse, scale, n_blocks, n_fp16, accumulate_q,
+                               NewToken{nullptr, nullptr, {0, 0, 0}, 0}, sc.enabled ? &sc : nullptr, s, c->ev_start,
                                c->ev_stop));
   return MIXKVQ_OK;
 }
 
 int mixkvq_decode_step(mixkvq_cache* c, const void* k_new, const void* v_new, const int64_t kv_strides[3],
                        const void* q, void* out, float* lse, float scale, int32_t accumulate_q, void* stream) {
-  if (!c || !k_new || !v_new || !kv_strides || !q || !out) return MIXKVQ_EINVAL;
-  if (((uintptr_t)k_new & 15u) || ((uintptr_t)v_new & 15u)) return MIXKVQ_EINVAL;
-  for (int i = 0; i < 3; ++i)
-    if (kv_strides[i] % 8 != 0) return MIXKVQ_EINVAL;
+  if (!c || !q || !out) return MIXKVQ_EINVAL;
+  int rc = check_kv_args(k_new, v_new, kv_strides, 3);
+  if (rc != MIXKVQ_OK) return rc;
   const mixkvq_config& cfg = c->v.cfg;
   const int R = cfg.R;
-  const int total = c->n_res + 1;
-  const bool flushes = cfg.flush_mode == 0 ? total > R : total >= R;
-  if (flushes || c->n_sink < cfg.sink) {   // the append flushes a block or feeds the sink: take the general path for it
-    int rc = mixkvq_quantize_append(c, k_new, v_new, 1, kv_strides, nullptr, stream);
+  // some sequence flushes a block or still feeds its sink, or the sequences differ in length: take the general path
+  bool general = !lock_step(c);
+  for (int b = 0; b < cfg.B; ++b) {
+    const SeqState& st = c->seq[b];
+    const int total = st.n_res + 1;
+    general |= (cfg.flush_mode == 0 ? total > R : total >= R) || st.n_sink < cfg.sink;
+  }
+  if (general) {
+    rc = mixkvq_quantize_append(c, k_new, v_new, 1, kv_strides, nullptr, stream);
     if (rc != MIXKVQ_OK) return rc;
     return mixkvq_decode_attention(c, q, out, lse, scale, accumulate_q, stream);
   }
+  int n_blocks, n_fp16;
+  SeqCounts sc;
+  if (!decode_counts(c, 1, &n_blocks, &n_fp16, &sc)) return MIXKVQ_EINVAL;
   hipStream_t s = (hipStream_t)stream;
   if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)cfg.D);
+  // the attention launch moves the new rows into the window itself (row = the last fp16 row then in use)
   NewToken nt{(const __half*)k_new, (const __half*)v_new, Strides3{kv_strides[0], kv_strides[1], kv_strides[2]},
-              cfg.sink + c->n_res};
-  MIXKVQ_TRY_HIP(launch_decode(c->v, (const __half*)q, (__half*)out, lse, scale, (int)(c->n_quant / R),
-                               cfg.sink + total,
-                               accumulate_q, nt, s, c->ev_start, c->ev_stop));
-  c->n_res = total;
+              n_fp16 - 1};
+  MIXKVQ_TRY_HIP(launch_decode(c->v, (const __half*)q, (__half*)out, lse, scale, n_blocks, n_fp16, accumulate_q, nt,
+                               sc.enabled ? &sc : nullptr, s, c->ev_start, c->ev_stop));
+  for (int b = 0; b < cfg.B; ++b) c->seq[b].n_res += 1;
   return MIXKVQ_OK;
 }
 
@@ -283,6 +436,7 @@ const char* mixkvq_strerror(int code) {
     case MIXKVQ_EHIP: return mixkvq::g_hip_msg;
     case MIXKVQ_ENOMEM: return "host allocation failed";
     case MIXKVQ_EEMPTY: return "the cache holds no token";
+    case MIXKVQ_ERAGGED: return "the sequences of the batch hold different numbers of tokens: ask per sequence";
     default: return "unknown mixkvq error code";
   }
 }

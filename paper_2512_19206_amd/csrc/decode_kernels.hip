@@ -2,6 +2,7 @@
 // keys and values dequantized on the fly by Eq. 3) and the log-sum-exp merge of the
 // splits.
 #include <stdlib.h>
+#include <string.h>
 #include "mixkvq_internal.h"
 
 namespace mixkvq {
@@ -24,7 +25,7 @@ size_t decode_workspace_bytes(const mixkvq_config& c) { return decode_partials_b
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(kDecThreads)
 decode_split_kernel(CacheView cv, const __half* __restrict__ q, float scale, int n_blocks, int n_fp16, int n_splits,
-                    float* __restrict__ part) {
+                    float* __restrict__ part, SeqCounts sc) {
   __shared__ __align__(16) unsigned char sRec[kMaxRec];
   __shared__ float sQ[kMaxG][kD];
   __shared__ float sP[kMaxG][kMaxR];
@@ -38,6 +39,10 @@ decode_split_kernel(CacheView cv, const __half* __restrict__ q, float scale, int
   const int R = cfg.R, Gk = cfg.Gk, Gv = cfg.Gv, k4 = cfg.k4, k16 = cfg.k16, ks = k4 + k16, g = cv.g;
   const int p = blockIdx.x, split = blockIdx.y, tid = threadIdx.x;
   const int b = p / cfg.Hkv, j = p % cfg.Hkv;
+  if (sc.enabled) {      // sequences of different lengths: this pair's own counts
+    n_blocks = sc.n_blocks[b];
+    n_fp16 = sc.n_fp16[b];
+  }
   const int lane_lo = tid & (kD - 1), half = tid >> 7;   // role index and head half
   const int h0 = half * 4;                               // heads h0 .. h0+3 (< g)
 
@@ -221,18 +226,21 @@ __global__ void __launch_bounds__(kD) decode_merge_kernel(const float* __restric
     l += base[s * stride + kD + 1] * w;
     o += base[s * stride + d] * w;
   }
+  const float r = l > 0.f ? o / l : 0.f;       // l == 0: a sequence without tokens
   reinterpret_cast<unsigned short*>(out)[(size_t)bh * kD + d] =
-      out_bf16 ? f32_to_bf16_bits(o / l) : __half_as_ushort(__float2half_rn(o / l));
-  if (lse && d == 0) lse[bh] = m + __logf(l);
+      out_bf16 ? f32_to_bf16_bits(r) : __half_as_ushort(__float2half_rn(r));
+  if (lse && d == 0) lse[bh] = l > 0.f ? m + __logf(l) : -INFINITY;
 }
 
 bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, int n_blocks, int n_res, int n_splits,
-                            float* part, __half* out, float* lse, int accumulate_q, NewToken nt,
+                            float* part, __half* out, float* lse, int accumulate_q, NewToken nt, const SeqCounts& sc,
                             hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop, hipError_t* err);
 
 hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float* lse, float scale, int n_blocks,
-                         int n_fp16, int accumulate_q, NewToken nt, hipStream_t s, hipEvent_t ev_start,
-                         hipEvent_t ev_stop) {
+                         int n_fp16, int accumulate_q, NewToken nt, const SeqCounts* sc_in, hipStream_t s,
+                         hipEvent_t ev_start, hipEvent_t ev_stop) {
+  static const SeqCounts kLockStep = [] { SeqCounts z; memset(&z, 0, sizeof(z)); return z; }();
+  const SeqCounts& sc = sc_in ? *sc_in : kLockStep;
   // split count: enough workgroups to fill the chip (tunable through MIXKVQ_DECODE_WGS for experiments),
   // never above the ceiling the workspace was sized for
   static const int target_wgs = [] {
@@ -252,7 +260,7 @@ hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float
   const int min_splits = ((n_fp16 + 31) / 32 + 3) / 4;
   if (n_splits_mc < min_splits) n_splits_mc = min_splits;
   if (n_splits_mc <= max_splits_for(v.P) &&
-      try_launch_decode_mfma(v, q, scale, n_blocks, n_fp16, n_splits_mc, part, out, lse, accumulate_q, nt, s,
+      try_launch_decode_mfma(v, q, scale, n_blocks, n_fp16, n_splits_mc, part, out, lse, accumulate_q, nt, sc, s,
                              ev_start, ev_stop, &e))
     return e;
   if (nt.k) {   // this path does not move the new token itself
@@ -261,11 +269,24 @@ hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float
   }
   if (accumulate_q) {
     Strides3 qs{(int64_t)v.cfg.Hq * kD, (int64_t)kD, (int64_t)kD};
-    e = launch_qabs_accumulate(v, q, 1, qs, s);
-    if (e != hipSuccess) return e;
+    if (!sc.enabled) {
+      e = launch_qabs_accumulate(v, q, 1, qs, s);
+      if (e != hipSuccess) return e;
+    } else {      // sequences without tokens are skipped
+      for (int b = 0; b < v.cfg.B; ++b) {
+        if (sc.n_blocks[b] == 0 && sc.n_fp16[b] == 0) continue;
+        CacheView vb = v;
+        vb.cfg.B = 1;
+        vb.P = v.cfg.Hkv;
+        vb.qacc += (size_t)b * v.cfg.Hkv * kD;
+        vb.qcnt += (size_t)b * v.cfg.Hkv;
+        e = launch_qabs_accumulate(vb, q + (size_t)b * v.cfg.Hq * kD, 1, qs, s);
+        if (e != hipSuccess) return e;
+      }
+    }
   }
   if (ev_start) (void)hipEventRecord(ev_start, s);
-  decode_split_kernel<<<dim3(v.P, n_splits), dim3(kDecThreads), 0, s>>>(v, q, scale, n_blocks, n_fp16, n_splits, part);
+  decode_split_kernel<<<dim3(v.P, n_splits), dim3(kDecThreads), 0, s>>>(v, q, scale, n_blocks, n_fp16, n_splits, part, sc);
   if (ev_stop) (void)hipEventRecord(ev_stop, s);
   decode_merge_kernel<<<dim3(v.cfg.B * v.cfg.Hq), dim3(kD), 0, s>>>(part, n_splits, v.g, v.cfg.Hq, v.cfg.in_dtype, out, lse);
   return hipGetLastError();

@@ -245,17 +245,18 @@ decode_merge_pair_kernel(CacheView cv, const float* __restrict__ part, int n_par
       for (int i = 0; i < 16; ++i) o = fmaf(v[i], s0 + i < n_parts ? sW[(s0 + i) * g + h] : 0.f, o);
     }
     const size_t bh = (size_t)b * cv.cfg.Hq + (size_t)j * g + h;
-    const float r = o / sML[8 + h];
+    const float lsum = sML[8 + h];
+    const float r = lsum > 0.f ? o / lsum : 0.f;      // l == 0: a sequence without tokens
     reinterpret_cast<unsigned short*>(out)[bh * kD + d] =
         cv.cfg.in_dtype ? f32_to_bf16_bits(r) : __half_as_ushort(__float2half_rn(r));
-    if (lse && d == 0) lse[bh] = sML[h] + __logf(sML[8 + h]);
+    if (lse && d == 0) lse[bh] = lsum > 0.f ? sML[h] + __logf(lsum) : -INFINITY;
   }
 }
 
 template <int K4, int K16, int NVG, int NKL, int RG, int THR, int G32>
 __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __restrict__ q, float scale_log2e,
                                           int n_blocks, int n_res, int n_splits, float* __restrict__ part,
-                                          int accumulate_q, const NewToken& nt, unsigned char* smem) {
+                                          int accumulate_q, const NewToken& nt, const SeqCounts& sc, unsigned char* smem) {
   using T = Tiers<K4, K16, THR>;
   constexpr int NU = T::NU;
   // scalars of the by-value view (kept in SGPRs; no references into the kernel argument)
@@ -274,6 +275,12 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   const unsigned char* const blocks = cv.blocks;
   const int p = blockIdx.x, split = blockIdx.y, tid = threadIdx.x;
   const int b = p / Hkv, jkv = p % Hkv;
+  bool skip_pair = false;
+  if (sc.enabled) {      // sequences of different lengths: this pair's own counts; a sequence without tokens is skipped
+    n_blocks = sc.n_blocks[b];
+    n_res = sc.n_fp16[b];
+    skip_pair = n_blocks == 0 && n_res == 0;
+  }
   const int wave = tid >> 6, lane = tid & 63, n = lane & 15, kg = lane >> 4;
   const int head = n & 7, role = n >> 3;     // role 0: head of q*s, role 1: tail
   const bool live = head < g;
@@ -305,7 +312,8 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   if (my_sub >= n_sub) my_sub = -1;
   // one wavefront per pair (the next in the deal, never one with a sub-unit unless the pair has a single
   // workgroup) stores this step's new token and adds |q| to the accumulator
-  const bool bookkeeper = (first_sub_gw + n_sub >= n_gw ? first_sub_gw + n_sub - n_gw : first_sub_gw + n_sub) == gw;
+  const bool bookkeeper =
+      (first_sub_gw + n_sub >= n_gw ? first_sub_gw + n_sub - n_gw : first_sub_gw + n_sub) == gw && !skip_pair;
 
   // ---- per-lane constants -------------------------------------------------
   // token of A-row n in tile (h, x): 64h + tokbase + {0,1,8,9}[x]  (G32: 8 (n/4) + 2 (n%4) + {0,1,32,33}[x])
@@ -1063,15 +1071,15 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 template <int K4, int K16, int NVG, int NKL, int RG, int THR, int G32>
 __global__ void __launch_bounds__(kMfmaThreads, 2)
 decode_fused_kernel(CacheView cv, const __half* __restrict__ q, float scale, int n_blocks, int n_res, int n_splits,
-                    float* __restrict__ part, int accumulate_q, NewToken nt) {
+                    float* __restrict__ part, int accumulate_q, NewToken nt, SeqCounts sc) {
   extern __shared__ __align__(16) unsigned char smem[];
-  mfma_part<K4, K16, NVG, NKL, RG, THR, G32>(cv, q, scale * 1.4426950408889634f, n_blocks, n_res, n_splits, part, accumulate_q, nt,
-                                   smem);
+  mfma_part<K4, K16, NVG, NKL, RG, THR, G32>(cv, q, scale * 1.4426950408889634f, n_blocks, n_res, n_splits, part,
+                                             accumulate_q, nt, sc, smem);
 }
 
 template <int K4, int K16, int NVG, int NKL, int RG, int THR, int G32>
 static hipError_t launch_one(const CacheView& v, const __half* q, float scale, int n_blocks, int n_res, int n_splits,
-                             float* part, __half* out, float* lse, int accumulate_q, NewToken nt,
+                             float* part, __half* out, float* lse, int accumulate_q, NewToken nt, const SeqCounts& sc,
                              hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
   auto kern = decode_fused_kernel<K4, K16, NVG, NKL, RG, THR, G32>;
   const size_t lds = kHdrLds + (size_t)kWaves * kWaveLds;
@@ -1082,7 +1090,7 @@ static hipError_t launch_one(const CacheView& v, const __half* q, float scale, i
     attr_set = true;
   }
   if (ev_start) (void)hipEventRecord(ev_start, s);
-  kern<<<dim3(v.P, n_splits), dim3(kMfmaThreads), lds, s>>>(v, q, scale, n_blocks, n_res, n_splits, part, accumulate_q, nt);
+  kern<<<dim3(v.P, n_splits), dim3(kMfmaThreads), lds, s>>>(v, q, scale, n_blocks, n_res, n_splits, part, accumulate_q, nt, sc);
   if (ev_stop) (void)hipEventRecord(ev_stop, s);
   decode_merge_pair_kernel<<<dim3(v.P), dim3(256), 0, s>>>(v, part, n_splits, out, lse);
   return hipGetLastError();
@@ -1090,7 +1098,7 @@ static hipError_t launch_one(const CacheView& v, const __half* q, float scale, i
 
 // Returns true and launches when the configuration is one the matrix-core kernel covers.
 bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, int n_blocks, int n_res, int n_splits,
-                            float* part, __half* out, float* lse, int accumulate_q, NewToken nt,
+                            float* part, __half* out, float* lse, int accumulate_q, NewToken nt, const SeqCounts& sc,
                             hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop, hipError_t* err) {
   const mixkvq_config& c = v.cfg;
   // key groups of 32 tokens take the G32 variants, multiples of 64 the others; value groups of 32, 64 or 128 channels
@@ -1105,7 +1113,7 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
   if (c.k4 == K4_ && c.k16 == K16_ && nvg == NVG_ && nkl <= NKL_ && c.policy == THR_ && g32 == G32_ &&              \
       (RG_ == 0 || (c.R == 128 && c.Gk == 128)))                                                                    \
     e = launch_one<K4_, K16_, NVG_, NKL_, RG_, THR_, G32_>(v, q, scale, n_blocks, n_res, n_splits, part, out, lse,  \
-                                                           accumulate_q, nt, s, ev_start, ev_stop);                 \
+                                                           accumulate_q, nt, sc, s, ev_start, ev_stop);             \
   else
   MIXKVQ_CASE(16, 0, 1, 6, 1, 0, 0)
   MIXKVQ_CASE(0, 12, 1, 8, 1, 0, 0)

@@ -24,6 +24,15 @@ struct Strides3 { int64_t b, h, t; };
 // (k == nullptr: none).
 struct NewToken { const __half* k; const __half* v; Strides3 st; int row; };
 
+// Token counts per sequence for batches whose sequences differ in length, passed by value to the decode kernels
+// (enabled == 0: every sequence has the counts given as scalar arguments).
+constexpr int kMaxRaggedB = 256;
+struct SeqCounts {
+  int32_t enabled;
+  int32_t n_blocks[kMaxRaggedB];      // quantized blocks of sequence b
+  uint16_t n_fp16[kMaxRaggedB];       // its fp16 rows in use (sink + residual window)
+};
+
 // Device-visible view of a cache: plain data passed by value to kernels.
 struct CacheView {
   mixkvq_config cfg;
@@ -56,9 +65,11 @@ hipError_t launch_residual_copy(const CacheView& v, const __half* k_new, const _
                                 int src_first, int dst_row, int n, hipStream_t s);
 // n_fp16: fp16 tokens of every pair = rows [0, n_fp16) of its fp16 rows (the sink, then the window; the window only
 // holds tokens once the sink is full, so the rows in use are contiguous)
+// With sc != nullptr (sequences of different lengths) n_blocks and n_fp16 are the largest counts of the batch, a
+// sequence without tokens is skipped (output 0, lse -inf), and a new token (nt) goes to the last fp16 row in use.
 hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float* lse, float scale,
-                         int n_blocks, int n_fp16, int accumulate_q, NewToken nt, hipStream_t s, hipEvent_t ev_start,
-                         hipEvent_t ev_stop);
+                         int n_blocks, int n_fp16, int accumulate_q, NewToken nt, const SeqCounts* sc, hipStream_t s,
+                         hipEvent_t ev_start, hipEvent_t ev_stop);
 
 size_t decode_workspace_bytes(const mixkvq_config& c);
 size_t decode_partials_bytes(const mixkvq_config& c);

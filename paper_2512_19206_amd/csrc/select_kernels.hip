@@ -10,14 +10,16 @@ namespace mixkvq {
 // ---------------------------------------------------------------------------
 // accumulator clear
 // ---------------------------------------------------------------------------
-__global__ void zero_u64_kernel(unsigned long long* p, size_t n) {
+__global__ void zero_u64_kernel(unsigned long long* sums, size_t n_sums, unsigned long long* counts, size_t n_counts) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0ull;
+  if (i < n_sums) sums[i] = 0ull;
+  else if (i < n_sums + n_counts) counts[i - n_sums] = 0ull;
 }
 
+// the sums and the counts of the view's pairs (two ranges: a view of some sequences of the batch is not contiguous)
 hipError_t launch_zero_qacc(const CacheView& v, hipStream_t s) {
-  size_t n = (size_t)v.P * (kD + 1);
-  zero_u64_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(v.qacc, n);
+  const size_t n_sums = (size_t)v.P * kD, n = n_sums + (size_t)v.P;
+  zero_u64_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(v.qacc, n_sums, v.qcnt, (size_t)v.P);
   return hipGetLastError();
 }
 
