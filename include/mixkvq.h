@@ -121,6 +121,14 @@ int mixkvq_cache_sizes(const mixkvq_config* cfg, mixkvq_sizes* out);
 int mixkvq_cache_create(const mixkvq_config* cfg, const mixkvq_buffers* bufs, mixkvq_cache** out);
 void mixkvq_cache_destroy(mixkvq_cache* c);
 
+/* Paged storage of the block records.  table: DEVICE int32 [B][T_max/R], owned by the caller; block i of sequence b
+ * (its Hkv records, one after the other) then lives in slot table[b][i] of a pool, and bufs->blocks is that pool:
+ * slots * Hkv * rec_bytes bytes for as many slots as the caller's allocator hands out, instead of the size
+ * mixkvq_cache_sizes reports.  The kernels read the table when a call runs: an entry must be set before the call that
+ * flushes or reads its block, and must not change while the block is in use.  NULL returns to the contiguous layout.
+ * EINVAL while any sequence holds quantized blocks. */
+int mixkvq_cache_set_block_table(mixkvq_cache* c, const int32_t* table);
+
 /* Empties the cache (token counts to 0) and zeroes the |q| accumulator on `stream`. */
 int mixkvq_cache_reset(mixkvq_cache* c, void* stream);
 

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmixkvq.so")
 
 EXPORTS = ("mixkvq_block_layout", "mixkvq_cache_sizes", "mixkvq_cache_create", "mixkvq_cache_destroy",
-           "mixkvq_cache_reset", "mixkvq_cache_reset_seq", "mixkvq_cache_state", "mixkvq_cache_state_seq",
+           "mixkvq_cache_set_block_table", "mixkvq_cache_reset", "mixkvq_cache_reset_seq", "mixkvq_cache_state", "mixkvq_cache_state_seq",
            "mixkvq_select_channels", "mixkvq_select_channels_seq", "mixkvq_quantize_append", "mixkvq_quantize_append_seq",
            "mixkvq_decode_attention", "mixkvq_decode_step", "mixkvq_set_timing_events", "mixkvq_strerror")
 
@@ -68,6 +68,7 @@ def load_library() -> C.CDLL:
     lib.mixkvq_cache_destroy.restype = None
     lib.mixkvq_cache_reset.argtypes = [vp, vp]
     lib.mixkvq_cache_state.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    lib.mixkvq_cache_set_block_table.argtypes = [vp, vp]
     lib.mixkvq_cache_reset_seq.argtypes = [vp, i32, vp]
     lib.mixkvq_cache_state_seq.argtypes = [vp, i32, C.POINTER(C.c_int64), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.mixkvq_select_channels_seq.argtypes = [vp, i32, vp, i32, i64p, vp, i32, i64p, vp, vp]
@@ -164,6 +165,22 @@ class Cache:
         n = C.c_int32()
         _check(self.lib.mixkvq_cache_state(self.handle, None, None, C.byref(n)))
         return n.value
+
+    def set_block_table(self, table):
+        """table: int32 device tensor [B, T_max/R] (kept alive here) or None.  The block buffer becomes the pool:
+        B * T_max/R slots of Hkv records each."""
+        if table is None:
+            _check(self.lib.mixkvq_cache_set_block_table(self.handle, None))
+        else:
+            assert table.dtype == torch.int32 and table.is_contiguous() and table.is_cuda
+            _check(self.lib.mixkvq_cache_set_block_table(self.handle, table.data_ptr()))
+        self._table = table
+
+    def pool_records(self) -> torch.Tensor:
+        """uint8 [slots, Hkv, rec_bytes] view of the block buffer as a pool (paged layout)."""
+        slots = self.cfg.B * (self.cfg.T_max // self.cfg.R)
+        n = slots * self.cfg.Hkv * self.layout.rec_bytes
+        return self.blocks[:n].view(slots, self.cfg.Hkv, self.layout.rec_bytes)
 
     # ---- one sequence of the batch (sequences may differ in length) ----
     def reset_seq(self, b: int, stream=None):

@@ -33,6 +33,7 @@ int compute_layout(const mixkvq_config& c, Layout* out) {
   if (c.T_max < c.R || c.T_max % c.R != 0) return MIXKVQ_EINVAL;
   if (c.flush_mode < 0 || c.flush_mode > 1 || c.score_mode < 0 || c.score_mode > 1) return MIXKVQ_EINVAL;
   if ((int64_t)c.B * c.Hkv > (1 << 20)) return MIXKVQ_EINVAL;
+  if ((int64_t)c.B * c.Hkv * (c.T_max / c.R) >= (1ll << 31)) return MIXKVQ_EINVAL;   // record indices are 32-bit
   if (c.policy < 0 || c.policy > 1) return MIXKVQ_EINVAL;
   if (c.policy == 1 && !(c.tau16 >= 0.0 && c.tau4 >= 0.0)) return MIXKVQ_EINVAL;   // also rejects NaN
   if (c.sink < 0 || c.sink > 128 || c.sink % 32 != 0) return MIXKVQ_EINVAL;
@@ -101,7 +102,8 @@ static CacheView sub_view(const mixkvq_cache* c, int b0, int nb) {
   const size_t p0 = (size_t)b0 * v.cfg.Hkv;
   v.cfg.B = nb;
   v.P = nb * v.cfg.Hkv;
-  v.blocks += p0 * v.NB * v.lay.rec_bytes;
+  if (v.table) v.table += (size_t)b0 * v.NB;      // the pool itself is shared by all sequences
+  else v.blocks += p0 * v.NB * v.lay.rec_bytes;
   v.res_k += p0 * v.RW * kD;
   v.res_v += p0 * v.RW * kD;
   v.qacc += p0 * kD;
@@ -245,6 +247,7 @@ int mixkvq_cache_create(const mixkvq_config* cfg, const mixkvq_buffers* bufs, mi
   c->v.S = cfg->sink;
   c->v.RW = cfg->sink + cfg->R;
   c->v.blocks = (uint8_t*)bufs->blocks;
+  c->v.table = nullptr;
   c->v.res_k = (__half*)bufs->res_k;
   c->v.res_v = (__half*)bufs->res_v;
   c->v.qacc = (unsigned long long*)bufs->qacc;
@@ -418,6 +421,14 @@ int mixkvq_decode_step(mixkvq_cache* c, const void* k_new, const void* v_new, co
   MIXKVQ_TRY_HIP(launch_decode(c->v, (const __half*)q, (__half*)out, lse, scale, n_blocks, n_fp16, accumulate_q, nt,
                                sc.enabled ? &sc : nullptr, s, c->ev_start, c->ev_stop));
   for (int b = 0; b < cfg.B; ++b) c->seq[b].n_res += 1;
+  return MIXKVQ_OK;
+}
+
+int mixkvq_cache_set_block_table(mixkvq_cache* c, const int32_t* table) {
+  if (!c) return MIXKVQ_EINVAL;
+  for (int b = 0; b < c->v.cfg.B; ++b)      // the layout may only change while no block is stored
+    if (c->seq[b].n_quant != 0) return MIXKVQ_EINVAL;
+  c->v.table = table;
   return MIXKVQ_OK;
 }
 

@@ -66,7 +66,7 @@ decode_split_kernel(CacheView cv, const __half* __restrict__ q, float scale, int
     const int row0 = is_res ? (it - (blk1 - blk0)) * kMaxR : 0;       // first fp16 row of this chunk
     const int nt = is_res ? (n_fp16 - row0 < kMaxR ? n_fp16 - row0 : kMaxR) : R;
     __syncthreads();
-    const uint8_t* rec = cv.blocks + ((size_t)p * cv.NB + blk0 + it) * lay.rec_bytes;
+    const uint8_t* rec = cv.blocks + (is_res ? 0 : record_index(cv, p, blk0 + it)) * lay.rec_bytes;
     if (!is_res) {
       for (int i = tid; i < lay.rec_bytes / 16; i += kDecThreads)
         reinterpret_cast<uint4*>(sRec)[i] = reinterpret_cast<const uint4*>(rec)[i];

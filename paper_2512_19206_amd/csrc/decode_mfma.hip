@@ -253,7 +253,7 @@ decode_merge_pair_kernel(CacheView cv, const float* __restrict__ part, int n_par
   }
 }
 
-template <int K4, int K16, int NVG, int NKL, int RG, int THR, int G32>
+template <int K4, int K16, int NVG, int NKL, int RG, int THR, int G32, int PG>
 __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __restrict__ q, float scale_log2e,
                                           int n_blocks, int n_res, int n_splits, float* __restrict__ part,
                                           int accumulate_q, const NewToken& nt, const SeqCounts& sc, unsigned char* smem) {
@@ -375,11 +375,21 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   u32x4 vmreg[NVM];
   u32x4 vreg[2][2];   // [h][x]
 
+  // Where a record lives: block BLK of the pair in the contiguous layout, or with a block table the pair's record
+  // in pool slot SLOT.  The slots of this wavefront's next two records are looked up ahead of time, so that no
+  // record load ever waits for a table entry.
+  // (PG = 0: instantiations for the contiguous layout, where all of this folds away)
+  const int32_t* const tab = PG ? cv.table + (size_t)b * NB : nullptr;
+#define MIXKVQ_REC_INDEX(BLK, SLOT) \
+  (tab ? (unsigned)(SLOT) * (unsigned)Hkv + (unsigned)jkv : (unsigned)p * (unsigned)NB + (unsigned)(BLK))
+#define MIXKVQ_REC(IDX) (blocks + (size_t)(IDX) * rec_bytes)     // (fewer than 2^31 records: the host checks)
+  int slot_cur = 0, slot_nx = 0;
+
   // Loads of one block.  Chunk indices are clamped to the record so that every lane loads and
   // stores unconditionally (a clamped lane repeats the record's last chunk).
-#define MIXKVQ_ISSUE_K_LOADS(BLK)                                                                           \
+#define MIXKVQ_ISSUE_K_LOADS(REC)                                                                           \
   {                                                                                                          \
-    const unsigned char* rec_ = blocks + ((size_t)p * NB + (BLK)) * rec_bytes;                              \
+    const unsigned char* rec_ = MIXKVQ_REC(REC);                                                             \
     _Pragma("unroll") for (int c = 0; c < NKL; ++c) {                                                       \
       const int idx_ = c * 64 + lane;                                                                        \
       kreg[c] = reinterpret_cast<const u32x4*>(rec_)[idx_ < rec_chunks ? idx_ : rec_chunks - 1];            \
@@ -400,9 +410,9 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
       DST = *reinterpret_cast<const u32x4*>((ROW_) + 64 * (X) + 4 * n);                                      \
     }                                                                                                        \
   }
-#define MIXKVQ_ISSUE_V_LOADS(BLK)                                                                           \
+#define MIXKVQ_ISSUE_V_LOADS(REC)                                                                           \
   {                                                                                                          \
-    const unsigned char* rec_ = blocks + ((size_t)p * NB + (BLK)) * rec_bytes;                              \
+    const unsigned char* rec_ = MIXKVQ_REC(REC);                                                             \
     const unsigned* vw_ = reinterpret_cast<const unsigned*>(rec_ + off_v);                                  \
     _Pragma("unroll") for (int h = 0; h < 2; ++h) _Pragma("unroll") for (int x = 0; x < 2; ++x)             \
         MIXKVQ_LOAD_VWORDS(vreg[h][x], vw_ + (4 * (h * 64 < R ? h : 0) + kg) * kD, x)                       \
@@ -410,9 +420,9 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 
   // The value words of one half (64 tokens) of a record: asked for as soon as the previous record's matrix
   // products have consumed the registers they land in, so that each half has most of a record's time to arrive.
-#define MIXKVQ_ISSUE_V_HALF(BLK, H)                                                                          \
+#define MIXKVQ_ISSUE_V_HALF(REC, H)                                                                          \
   {                                                                                                          \
-    const unsigned char* rec_ = blocks + ((size_t)p * NB + (BLK)) * rec_bytes;                              \
+    const unsigned char* rec_ = MIXKVQ_REC(REC);                                                             \
     const unsigned* vw_ = reinterpret_cast<const unsigned*>(rec_ + off_v);                                  \
     _Pragma("unroll") for (int x = 0; x < 2; ++x)                                                           \
         MIXKVQ_LOAD_VWORDS(vreg[H][x], vw_ + (4 * (H) + kg) * kD, x)                                        \
@@ -510,8 +520,13 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   unsigned sel_first[kSelWords];
 #pragma unroll
   for (int i = 0; i < kSelWords; ++i) sel_first[i] = 0u;
+  if (tab) {
+    if (blk < blk_hi) slot_cur = tab[blk];
+    if (blk + blk_step < blk_hi) slot_nx = tab[blk + blk_step];
+  }
+  const unsigned rec_first = MIXKVQ_REC_INDEX(blk, slot_cur);
   if (K4 + K16 > 0 && blk < blk_hi) {
-    const unsigned* recw = reinterpret_cast<const unsigned*>(blocks + ((size_t)p * NB + blk) * rec_bytes + off_idx);
+    const unsigned* recw = reinterpret_cast<const unsigned*>(MIXKVQ_REC(rec_first) + off_idx);
 #pragma unroll
     for (int i = 0; i < kSelWords; ++i) sel_first[i] = recw[i];
   }
@@ -538,7 +553,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
       vr[it] = *reinterpret_cast<const u32x4*>(src + 8 * (ci & 15));
     }
   }
-  if (blk < blk_hi) MIXKVQ_ISSUE_K_LOADS(blk)
+  if (blk < blk_hi) MIXKVQ_ISSUE_K_LOADS(rec_first)
 
   // ---- normalise q per head: qn = q * 2^-Eq with max|qn| in [1/2, 1) ----
   {
@@ -588,7 +603,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   // q in the slot order of the first record, while that record is still on its way (its value words are
   // asked for only now: the first answers come the sooner the less every wavefront asks for at once)
   if (blk < blk_hi) {
-    MIXKVQ_ISSUE_V_LOADS(blk)
+    MIXKVQ_ISSUE_V_LOADS(rec_first)
 #pragma unroll
     for (int i = 0; i < kSelWords; ++i) sel_prev[i] = __builtin_amdgcn_readfirstlane(sel_first[i]);
     MIXKVQ_REBUILD_Q(sel_prev, true)
@@ -796,7 +811,10 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 #pragma unroll
     for (int c = 0; c < NVM; ++c) reinterpret_cast<u32x4*>(sVm)[c * 64 + lane < nvm ? c * 64 + lane : nvm - 1] = vmreg[c];
     wave_lds_handoff();
-    if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_K_LOADS(blk + blk_step)
+    const unsigned rec_nx = MIXKVQ_REC_INDEX(blk + blk_step, slot_nx);     // the next record of this wavefront
+    if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_K_LOADS(rec_nx)
+    int slot_nn = 0;      // requested behind the record loads; needed only after they have arrived
+    if (tab && blk + 2 * blk_step < blk_hi) slot_nn = tab[blk + 2 * blk_step];
     // Value scales above 255 (a group of values that spans more than 765) would overflow p' * s in fp16.  Such a
     // record (the record carries its largest value scale; wave-uniform, rare) is guarded: its scales are staged
     // 2^-kPBoost smaller, so its value products come out too small by that factor; the sums they join are taken
@@ -982,7 +1000,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
             O[xp][qq] = mfma(a1, Bp[a][1], O[xp][qq]);
           }
         }
-        if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_V_HALF(blk + blk_step, hsg)
+        if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_V_HALF(rec_nx, hsg)
       }
     }
     if (big_s) {
@@ -991,11 +1009,14 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 #pragma unroll
         for (int qq = 0; qq < 4; ++qq) O[xp][qq] *= (float)(1 << kPBoost);
     }
+    slot_nx = slot_nn;
     MIXKVQ_PHASE(phase_i < 11 ? phase_i : 11)
     ++phase_i;
   }
   MIXKVQ_PHASE(14)
 #undef MIXKVQ_ISSUE_K_LOADS
+#undef MIXKVQ_REC
+#undef MIXKVQ_REC_INDEX
 #undef MIXKVQ_ISSUE_V_LOADS
 #undef MIXKVQ_ISSUE_V_HALF
 #undef MIXKVQ_LOAD_VWORDS
@@ -1068,20 +1089,20 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 
 // One launch per decode step: the workgroups (pair, split) share the pair's block records and its
 // residual window.
-template <int K4, int K16, int NVG, int NKL, int RG, int THR, int G32>
+template <int K4, int K16, int NVG, int NKL, int RG, int THR, int G32, int PG>
 __global__ void __launch_bounds__(kMfmaThreads, 2)
 decode_fused_kernel(CacheView cv, const __half* __restrict__ q, float scale, int n_blocks, int n_res, int n_splits,
                     float* __restrict__ part, int accumulate_q, NewToken nt, SeqCounts sc) {
   extern __shared__ __align__(16) unsigned char smem[];
-  mfma_part<K4, K16, NVG, NKL, RG, THR, G32>(cv, q, scale * 1.4426950408889634f, n_blocks, n_res, n_splits, part,
+  mfma_part<K4, K16, NVG, NKL, RG, THR, G32, PG>(cv, q, scale * 1.4426950408889634f, n_blocks, n_res, n_splits, part,
                                              accumulate_q, nt, sc, smem);
 }
 
-template <int K4, int K16, int NVG, int NKL, int RG, int THR, int G32>
+template <int K4, int K16, int NVG, int NKL, int RG, int THR, int G32, int PG>
 static hipError_t launch_one(const CacheView& v, const __half* q, float scale, int n_blocks, int n_res, int n_splits,
                              float* part, __half* out, float* lse, int accumulate_q, NewToken nt, const SeqCounts& sc,
                              hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
-  auto kern = decode_fused_kernel<K4, K16, NVG, NKL, RG, THR, G32>;
+  auto kern = decode_fused_kernel<K4, K16, NVG, NKL, RG, THR, G32, PG>;
   const size_t lds = kHdrLds + (size_t)kWaves * kWaveLds;
   static bool attr_set = false;
   if (!attr_set) {
@@ -1107,43 +1128,50 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
   const int nvg = v.lay.NVG;
   const int nkl = (v.lay.off_v / 16 + 63) / 64;
   const int g32 = c.Gk == 32;
+  const int paged = v.table != nullptr;
   hipError_t e = hipErrorInvalidValue;
   bool ok = true;
-#define MIXKVQ_CASE(K4_, K16_, NVG_, NKL_, RG_, THR_, G32_)                                                         \
-  if (c.k4 == K4_ && c.k16 == K16_ && nvg == NVG_ && nkl <= NKL_ && c.policy == THR_ && g32 == G32_ &&              \
+#define MIXKVQ_CASE(K4_, K16_, NVG_, NKL_, RG_, THR_, G32_, PG_)                                                    \
+  if (c.k4 == K4_ && c.k16 == K16_ && nvg == NVG_ && nkl <= NKL_ && c.policy == THR_ && g32 == G32_ && paged == PG_ && \
       (RG_ == 0 || (c.R == 128 && c.Gk == 128)))                                                                    \
-    e = launch_one<K4_, K16_, NVG_, NKL_, RG_, THR_, G32_>(v, q, scale, n_blocks, n_res, n_splits, part, out, lse,  \
+    e = launch_one<K4_, K16_, NVG_, NKL_, RG_, THR_, G32_, PG_>(v, q, scale, n_blocks, n_res, n_splits, part, out, lse,  \
                                                            accumulate_q, nt, sc, s, ev_start, ev_stop);             \
   else
-  MIXKVQ_CASE(16, 0, 1, 6, 1, 0, 0)
-  MIXKVQ_CASE(0, 12, 1, 8, 1, 0, 0)
-  MIXKVQ_CASE(8, 0, 1, 6, 1, 0, 0)
-  MIXKVQ_CASE(16, 0, 1, 6, 0, 0, 0)
-  MIXKVQ_CASE(0, 12, 1, 8, 0, 0, 0)
-  MIXKVQ_CASE(0, 0, 1, 6, 0, 0, 0)
-  MIXKVQ_CASE(8, 0, 1, 6, 0, 0, 0)
-  MIXKVQ_CASE(24, 0, 1, 6, 0, 0, 0)
-  MIXKVQ_CASE(32, 0, 1, 6, 0, 0, 0)
-  MIXKVQ_CASE(16, 0, 2, 6, 0, 0, 0)
-  MIXKVQ_CASE(0, 12, 2, 8, 0, 0, 0)
-  MIXKVQ_CASE(8, 4, 1, 8, 0, 0, 0)
-  MIXKVQ_CASE(0, 32, 1, 8, 0, 0, 0)
+  MIXKVQ_CASE(16, 0, 1, 6, 1, 0, 0, 0)
+  MIXKVQ_CASE(0, 12, 1, 8, 1, 0, 0, 0)
+  MIXKVQ_CASE(8, 0, 1, 6, 1, 0, 0, 0)
+  MIXKVQ_CASE(16, 0, 1, 6, 0, 0, 0, 0)
+  MIXKVQ_CASE(0, 12, 1, 8, 0, 0, 0, 0)
+  MIXKVQ_CASE(0, 0, 1, 6, 0, 0, 0, 0)
+  MIXKVQ_CASE(8, 0, 1, 6, 0, 0, 0, 0)
+  MIXKVQ_CASE(24, 0, 1, 6, 0, 0, 0, 0)
+  MIXKVQ_CASE(32, 0, 1, 6, 0, 0, 0, 0)
+  MIXKVQ_CASE(16, 0, 2, 6, 0, 0, 0, 0)
+  MIXKVQ_CASE(0, 12, 2, 8, 0, 0, 0, 0)
+  MIXKVQ_CASE(8, 4, 1, 8, 0, 0, 0, 0)
+  MIXKVQ_CASE(0, 32, 1, 8, 0, 0, 0, 0)
   // threshold policy: the capacities of the two side tiers
-  MIXKVQ_CASE(16, 8, 1, 8, 0, 1, 0)
-  MIXKVQ_CASE(16, 0, 1, 6, 0, 1, 0)
-  MIXKVQ_CASE(0, 12, 1, 8, 0, 1, 0)
-  MIXKVQ_CASE(8, 4, 1, 8, 0, 1, 0)
+  MIXKVQ_CASE(16, 8, 1, 8, 0, 1, 0, 0)
+  MIXKVQ_CASE(16, 0, 1, 6, 0, 1, 0, 0)
+  MIXKVQ_CASE(0, 12, 1, 8, 0, 1, 0, 0)
+  MIXKVQ_CASE(8, 4, 1, 8, 0, 1, 0, 0)
   // key groups of 32 tokens
-  MIXKVQ_CASE(16, 0, 1, 7, 0, 0, 1)
-  MIXKVQ_CASE(8, 0, 1, 7, 0, 0, 1)
-  MIXKVQ_CASE(0, 0, 1, 7, 0, 0, 1)
-  MIXKVQ_CASE(16, 0, 2, 7, 0, 0, 1)
-  MIXKVQ_CASE(16, 0, 1, 8, 0, 1, 1)
+  MIXKVQ_CASE(16, 0, 1, 7, 0, 0, 1, 0)
+  MIXKVQ_CASE(8, 0, 1, 7, 0, 0, 1, 0)
+  MIXKVQ_CASE(0, 0, 1, 7, 0, 0, 1, 0)
+  MIXKVQ_CASE(16, 0, 2, 7, 0, 0, 1, 0)
+  MIXKVQ_CASE(16, 0, 1, 8, 0, 1, 1, 0)
   // value groups of 32 channels (with key groups of 32 tokens: the group size of the paper's experiments)
-  MIXKVQ_CASE(16, 0, 4, 7, 0, 0, 1)
-  MIXKVQ_CASE(8, 0, 4, 7, 0, 0, 1)
-  MIXKVQ_CASE(16, 0, 4, 8, 0, 1, 1)
-  MIXKVQ_CASE(16, 0, 4, 6, 0, 0, 0)
+  MIXKVQ_CASE(16, 0, 4, 7, 0, 0, 1, 0)
+  MIXKVQ_CASE(8, 0, 4, 7, 0, 0, 1, 0)
+  MIXKVQ_CASE(16, 0, 4, 8, 0, 1, 1, 0)
+  MIXKVQ_CASE(16, 0, 4, 6, 0, 0, 0, 0)
+  // paged layout (block table): the main tiers
+  MIXKVQ_CASE(16, 0, 1, 6, 0, 0, 0, 1)
+  MIXKVQ_CASE(0, 12, 1, 8, 0, 0, 0, 1)
+  MIXKVQ_CASE(8, 0, 1, 6, 0, 0, 0, 1)
+  MIXKVQ_CASE(16, 8, 1, 8, 0, 1, 0, 1)
+  MIXKVQ_CASE(16, 0, 4, 7, 0, 0, 1, 1)
   ok = false;
 #undef MIXKVQ_CASE
   if (!ok) return false;

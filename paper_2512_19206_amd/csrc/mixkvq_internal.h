@@ -42,13 +42,23 @@ struct CacheView {
   int32_t NB;            // block capacity per pair = T_max / R
   int32_t S;             // sink rows per pair (cfg.sink)
   int32_t RW;            // fp16 rows per pair = S + R: the sink rows, then the residual window
-  uint8_t* blocks;       // [P][NB][rec_bytes]
+  uint8_t* blocks;       // [P][NB][rec_bytes], or with a block table a pool [slots][Hkv][rec_bytes]
+  const int32_t* table;  // nullptr, or [B][NB]: pool slot of block i of sequence b
   __half* res_k;         // [P][RW][D]
   __half* res_v;
   unsigned long long* qacc;  // [P][D]
   unsigned long long* qcnt;  // [P]
   uint8_t* ws;
 };
+
+// Index (in records) of block `blk` of pair p inside cv.blocks.
+__device__ __forceinline__ size_t record_index(const CacheView& cv, int p, int blk) {
+  if (cv.table) {
+    const int Hkv = cv.cfg.Hkv, b = p / Hkv, j = p % Hkv;
+    return (size_t)cv.table[(size_t)b * cv.NB + blk] * Hkv + j;
+  }
+  return (size_t)p * cv.NB + blk;
+}
 
 int compute_layout(const mixkvq_config& c, Layout* out);   // MIXKVQ_OK or MIXKVQ_EINVAL
 int max_splits_for(int P);                                 // split-K ceiling used to size the workspace

@@ -84,7 +84,7 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
   const Layout& lay = cv.lay;
   const int R = cfg.R, Gk = cfg.Gk, Gv = cfg.Gv, k4 = cfg.k4, k16 = cfg.k16, ks = k4 + k16;
   const int p = blockIdx.x, f = blockIdx.y, tid = threadIdx.x;
-  uint8_t* rec = cv.blocks + ((size_t)p * cv.NB + first_block + f) * lay.rec_bytes;
+  uint8_t* rec = cv.blocks + record_index(cv, p, first_block + f) * lay.rec_bytes;
 
   // zero the record's padding by clearing the small planes that may have holes
   // (index bytes and the tails of the scale/zero planes); full planes are overwritten below.
@@ -340,7 +340,7 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
             off_v = cv.lay.off_v, off_v_s = cv.lay.off_v_s, off_v_z = cv.lay.off_v_z, NLp = cv.lay.NLp,
             Wlo = cv.lay.Wlo, W4 = cv.lay.W4, NG = cv.lay.NG, NVG = cv.lay.NVG;
   const int p = blockIdx.x, f = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  uint8_t* rec = cv.blocks + ((size_t)p * cv.NB + first_block + f) * rec_bytes;
+  uint8_t* rec = cv.blocks + record_index(cv, p, first_block + f) * rec_bytes;
   const int n_chunks16 = R * 16;           // 16-byte pieces of a tile
   const int n_ch = R / 16;                 // chunks of 16 tokens
 
