@@ -30,7 +30,7 @@ LLC_BYTES = 256 << 20   # last-level (Infinity) cache
 # HBM bytes per launch of the decode kernel from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), each scaled by what
 # the same counter read for a 512 MiB device copy in the same run (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0);
 # the readings and commands are in profiles/decode_fused_kernel_cfg1.txt.  Only for the default workload.
-MEASURED_TRAFFIC_BYTES = {("cfg1_gqa7b_b8_32k", 32768): 39546.8 * 1024 * 2.0 + 1868.3 * 1024 * 1.0}
+MEASURED_TRAFFIC_BYTES = {("cfg1_gqa7b_b8_32k", 32768): 39552.3 * 1024 * 2.0 + 1868.3 * 1024 * 1.0}
 
 
 def algorithmic_bytes_thresholds(w, gc, r):
