@@ -305,6 +305,16 @@ __device__ __forceinline__ unsigned join_halves(const float (&half)[2]) {
 }
 __device__ __forceinline__ float safe_rcp(float s) { return s > 0.f ? __builtin_amdgcn_rcpf(s) : 0.f; }
 
+// largest value over the wavefront (every lane must take part)
+__device__ __forceinline__ unsigned wave_max_u32(unsigned v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const unsigned other = (unsigned)__shfl_xor((int)v, o);
+    v = other > v ? other : v;
+  }
+  return v;
+}
+
 // 16-byte piece `idx` of the tile that starts at stream position pos0; `res_p` and `fresh_p` are the pair's
 // residual window and its slice of the caller's tensor (token 0 of this call).
 __device__ __forceinline__ uint4 load_chunk(const __half* res_p, const __half* fresh_p, int64_t stride_t, int r0, int pos0,
@@ -503,29 +513,35 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
     const _Float16* cl = reinterpret_cast<const _Float16*>(&sCLo[0][0]);
     const _Float16* chh = reinterpret_cast<const _Float16*>(&sCHi[0][0]);
     const int cpg = Gk / 16;     // chunks per group
+    // (a wavefront's 64 items of one pass belong to one group: its largest scale is reduced over the wavefront first,
+    //  one LDS atomic per wavefront and pass)
     for (int it = tid; it < NG * kD; it += kFlushThreads) {
       const int grp = it / kD, d = it % kD;
       const unsigned char tier = sTier[d];
-      if (tier == 2) continue;
-      _Float16 lo = cl[(grp * cpg) * kD + d], hi = chh[(grp * cpg) * kD + d];
-      for (int c = 1; c < cpg; ++c) {
-        const _Float16 a = cl[(grp * cpg + c) * kD + d], b2 = chh[(grp * cpg + c) * kD + d];
-        lo = a < lo ? a : lo;
-        hi = b2 > hi ? b2 : hi;
+      unsigned s16v = 0u;
+      if (tier != 2) {
+        _Float16 lo = cl[(grp * cpg) * kD + d], hi = chh[(grp * cpg) * kD + d];
+        for (int c = 1; c < cpg; ++c) {
+          const _Float16 a = cl[(grp * cpg + c) * kD + d], b2 = chh[(grp * cpg + c) * kD + d];
+          lo = a < lo ? a : lo;
+          hi = b2 > hi ? b2 : hi;
+        }
+        const GroupParams gp = group_params((float)lo, (float)hi, tier ? 15.f : 3.f);
+        sS[grp * kD + d] = gp.s;
+        sZ[grp * kD + d] = gp.z;
+        sR[grp * kD + d] = safe_rcp(gp.s);
+        const int pos = sPos[d];
+        s16v = gp.s16;
+        if (tier == 0) {
+          reinterpret_cast<unsigned short*>(rec + off_klo_s)[grp * NLp + pos] = gp.s16;
+          reinterpret_cast<unsigned short*>(rec + off_klo_z)[grp * NLp + pos] = gp.z16;
+        } else {
+          reinterpret_cast<unsigned short*>(rec + off_k4_s)[grp * k4 + pos] = gp.s16;
+          reinterpret_cast<unsigned short*>(rec + off_k4_z)[grp * k4 + pos] = gp.z16;
+        }
       }
-      const GroupParams gp = group_params((float)lo, (float)hi, tier ? 15.f : 3.f);
-      sS[grp * kD + d] = gp.s;
-      sZ[grp * kD + d] = gp.z;
-      sR[grp * kD + d] = safe_rcp(gp.s);
-      const int pos = sPos[d];
-      atomicMax(&sKmax[grp], (unsigned)gp.s16);
-      if (tier == 0) {
-        reinterpret_cast<unsigned short*>(rec + off_klo_s)[grp * NLp + pos] = gp.s16;
-        reinterpret_cast<unsigned short*>(rec + off_klo_z)[grp * NLp + pos] = gp.z16;
-      } else {
-        reinterpret_cast<unsigned short*>(rec + off_k4_s)[grp * k4 + pos] = gp.s16;
-        reinterpret_cast<unsigned short*>(rec + off_k4_z)[grp * k4 + pos] = gp.z16;
-      }
+      const unsigned wmax = wave_max_u32(s16v);
+      if (lane == 0) atomicMax(&sKmax[grp], wmax);
     }
   }
   __syncthreads();
@@ -649,16 +665,19 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
     }
     MIXKVQ_FPHASE(7)
     __syncthreads();
+    unsigned vmax_t = 0u;
     for (int it = tid; it < R * NVG; it += kFlushThreads) {
       const fh2 mm = as_h2(sRow[it]);
       const GroupParams gp = group_params((float)mm[0], -(float)mm[1], 3.f);
       sVS[it] = gp.s;
       sVZ[it] = gp.z;
       sR[it] = safe_rcp(gp.s);
-      atomicMax(&sKmax[8], (unsigned)gp.s16);
+      vmax_t = gp.s16 > vmax_t ? gp.s16 : vmax_t;
       reinterpret_cast<unsigned short*>(rec + off_v_s)[it] = gp.s16;
       reinterpret_cast<unsigned short*>(rec + off_v_z)[it] = gp.z16;
     }
+    const unsigned wmax = wave_max_u32(vmax_t);       // every lane is here: the loop above has ended for all
+    if (lane == 0) atomicMax(&sKmax[8], wmax);
   }
   __syncthreads();
   if (tid == 0) reinterpret_cast<unsigned short*>(rec + off_kmax)[NG] = (unsigned short)sKmax[8];
@@ -668,37 +687,41 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
     const int d = tid & (kD - 1), vg = d / Gv;
     const int ilv = cv.lay.v_interleave;
     for (int tg = tid >> 7; tg < n_ch; tg += 2) {
-      // tokens of the word: two runs of 8 (tok0 .. tok0+7 and tok0 + hi_off ..), consecutive unless interleaved
-      const int tok0 = value_word_token(tg, 0, ilv), hi_off = ilv ? 32 : 8;
+      // tokens of the word: two runs of 8 (tok0 .. tok0+7 and tok1 .. tok1+7), consecutive unless interleaved; each run
+      // gets one base address, so that the elements sit at compile-time offsets from it
+      const int tok0 = value_word_token(tg, 0, ilv), tok1 = tok0 + (ilv ? 32 : 8);
+      const __half* const col0 = sT + tok0 * kRowStride + d;
+      const __half* const col1 = sT + tok1 * kRowStride + d;
       float rc[16], zp[16];
       if (NVG == 1) {
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
-          const int t4 = tok0 + 4 * (i4 & 1) + (i4 >> 1) * hi_off;
+          const int t4 = (i4 >> 1 ? tok1 : tok0) + 4 * (i4 & 1);
           const float4 a = *reinterpret_cast<const float4*>(sR + t4);
           const float4 b2 = *reinterpret_cast<const float4*>(sVZ + t4);
           rc[4 * i4] = a.x; rc[4 * i4 + 1] = a.y; rc[4 * i4 + 2] = a.z; rc[4 * i4 + 3] = a.w;
           zp[4 * i4] = b2.x; zp[4 * i4 + 1] = b2.y; zp[4 * i4 + 2] = b2.z; zp[4 * i4 + 3] = b2.w;
         }
       } else {
+        const float* const r0 = sR + tok0 * NVG + vg, * const r1 = sR + tok1 * NVG + vg;
+        const float* const z0 = sVZ + tok0 * NVG + vg, * const z1 = sVZ + tok1 * NVG + vg;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const int t = tok0 + (i & 7) + (i >> 3) * hi_off;
-          rc[i] = sR[t * NVG + vg];
-          zp[i] = sVZ[t * NVG + vg];
+          rc[i] = (i < 8 ? r0 : r1)[(i & 7) * NVG];
+          zp[i] = (i < 8 ? z0 : z1)[(i & 7) * NVG];
         }
       }
       float hw[2] = {0.f, 0.f};
       bool near = false;
 #pragma unroll
       for (int i = 0; i < 16; ++i)
-        add_code<2>(hw, i, code_fast<3>(__half2float(sT[(tok0 + (i & 7) + (i >> 3) * hi_off) * kRowStride + d]), zp[i], rc[i], near));
+        add_code<2>(hw, i, code_fast<3>(__half2float((i < 8 ? col0 : col1)[(i & 7) * kRowStride]), zp[i], rc[i], near));
       unsigned w = join_halves(hw);
       if (__any(near)) {     // rare: some quotient sits next to a rounding boundary
         w = 0;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const int t = tok0 + (i & 7) + (i >> 3) * hi_off;
+          const int t = (i < 8 ? tok0 : tok1) + (i & 7);
           w |= encode(__half2float(sT[t * kRowStride + d]), zp[i], sVS[t * NVG + vg], 3.f) << (16 * (i & 1) + 2 * (i >> 1));
         }
       }
