@@ -502,3 +502,40 @@ def test_results_are_deterministic(H):
         recs.append(gc.block_records()[:, :gc.state()[0] // w.R].cpu().numpy())
     assert all(np.array_equal(outs[0], o) for o in outs[1:])
     assert all(np.array_equal(recs[0], r) for r in recs[1:])
+
+
+def test_decode_attention_replayed_from_a_hip_graph(H):
+    """The attention call enqueues kernels only (no allocation, no host read-back, no memset), so a caller can capture
+    it into a HIP graph.  Every replay, with new queries copied in and eager work in between, must equal the eager call."""
+    rng = np.random.default_rng(2000)
+    B, Hkv, g, R = 2, 2, 7, 128
+    kw = dict(B=B, Hq=Hkv * g, Hkv=Hkv, D=128, T_max=8 * R, Gk=128, Gv=128, R=R, k4=16, k16=0)
+    oc, gc = H.make_pair(**kw)
+    n0 = 5 * R + 40
+    K = (rng.standard_normal((B, Hkv, n0, 128)) * rng.uniform(0.3, 8, 128)).astype(np.float16)
+    V = rng.standard_normal((B, Hkv, n0, 128)).astype(np.float16)
+    oc.append(K, V)
+    gc.quantize_append(H.dev(K), H.dev(V))
+    q_static = torch.zeros((B, Hkv * g, 128), dtype=torch.float16, device="cuda")
+    out_static, lse_static = torch.empty_like(q_static), torch.empty((B, Hkv * g), dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        gc.decode_attention(q_static, out=out_static, lse=lse_static)        # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        gc.decode_attention(q_static, out=out_static, lse=lse_static)
+    for rep in range(4):
+        q = (rng.standard_normal((B, Hkv * g, 128)) * rng.uniform(0.2, 5, 128)).astype(np.float16)
+        q_static.copy_(H.dev(q))
+        graph.replay()
+        torch.cuda.synchronize()
+        got, got_lse = out_static.clone(), lse_static.clone()
+        eager, eager_lse = gc.decode_attention(H.dev(q))                      # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(got, eager) and torch.equal(got_lse, eager_lse), rep
+        ro, rl = oc.decode_attention(q)
+        err = np.abs(got.float().cpu().numpy() - ro)
+        assert np.all(err <= H.ATOL + H.RTOL * np.abs(ro)), (rep, float(err.max()))
