@@ -448,27 +448,38 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
       sA[tid] = A;
     }
     __syncthreads();
-    if (tid < kD) {
-      int rank = 0;
+    // rank of every channel (number of channels that beat it) and, under the threshold policy, how many channels
+    // pass each threshold: the two halves of the workgroup each compare against 64 of the channels
+    {
+      const int d = tid & (kD - 1), e0 = (tid >> 7) * (kD / 2);
+      const double Ad = sA[d];
+      int rank = 0, c16 = 0, c_any = 0;
       if (policy == 1) {
         const double thr16 = score_threshold(cv.cfg.tau16, cv.qcnt[p], score_mode);
         const double thr4 = score_threshold(cv.cfg.tau4, cv.qcnt[p], score_mode);
-        int c16 = 0, c_any = 0;
-        for (int e = 0; e < kD; ++e) {
+        for (int e = e0; e < e0 + kD / 2; ++e) {
           const double o = sA[e];
-          rank += (o > A) || (o == A && e < tid);
+          rank += (o > Ad) || (o == Ad && e < d);
           c16 += o > thr16;
           c_any += (o > thr16) || (o > thr4);
         }
+      } else {
+        for (int e = e0; e < e0 + kD / 2; ++e) {
+          const double o = sA[e];
+          rank += (o > Ad) || (o == Ad && e < d);
+        }
+      }
+      unsigned* sPart = reinterpret_cast<unsigned*>(sR);      // not yet in use: [2][kD] packed partial counts
+      sPart[tid] = (unsigned)rank | ((unsigned)c16 << 8) | ((unsigned)c_any << 16);     // each count <= 64
+      __syncthreads();
+      if (tid < kD) {
+        const unsigned both = sPart[tid] + sPart[tid + kD];                              // each count <= 128: no carry
+        rank = (int)(both & 0xffu);
+        c16 = (int)((both >> 8) & 0xffu);
+        c_any = (int)((both >> 16) & 0xffu);
         int n16, n4;
         tier_sizes(cv.cfg, c16, c_any, &n16, &n4);
         sTier[tid] = rank < n16 ? 2 : (rank < n16 + n4 ? 1 : 0);
-      } else {
-        for (int e = 0; e < kD; ++e) {
-          const double o = sA[e];
-          rank += (o > A) || (o == A && e < tid);
-        }
-        sTier[tid] = rank < k16 ? 2 : (rank < ks ? 1 : 0);
       }
     }
   } else {
