@@ -194,8 +194,10 @@ int mixkvq_decode_step(mixkvq_cache* c, const void* k_new, const void* v_new, co
                        const void* q, void* out, float* lse, float scale, int32_t accumulate_q, void* stream);
 
 /* Profiling aid.  With a pair of hipEvent_t handles (HOST, created by the caller with timing enabled), every
- * following mixkvq_decode_attention on this cache records start_event just before and stop_event just after
- * its split-K attention kernel, on the call's stream.  Pass NULL, NULL to switch it off. */
+ * following mixkvq_decode_attention / mixkvq_decode_step on this cache makes start_event and stop_event take the start
+ * and the end time of its split-K attention kernel (the kernel's own time stamps, as a profiler reports them; with the
+ * vector-ALU fallback kernel the events are recorded in the stream just before and after it).  Pass NULL, NULL to
+ * switch it off. */
 int mixkvq_set_timing_events(mixkvq_cache* c, void* start_event, void* stop_event);
 
 /* Message for a return code (for EHIP: the last HIP error string seen by this thread). */

@@ -21,6 +21,7 @@
 // columns 8..15 its exact fp16 tail (q*s - head, one fused multiply-add), so the
 // product keeps ~22 bits of q*s at no extra matrix instruction; the two halves are
 // added after the product with one DPP add.
+#include <hip/hip_ext.h>
 #include "mixkvq_internal.h"
 
 namespace mixkvq {
@@ -1110,9 +1111,13 @@ static hipError_t launch_one(const CacheView& v, const __half* q, float scale, i
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  if (ev_start) (void)hipEventRecord(ev_start, s);
-  kern<<<dim3(v.P, n_splits), dim3(kMfmaThreads), lds, s>>>(v, q, scale, n_blocks, n_res, n_splits, part, accumulate_q, nt, sc);
-  if (ev_stop) (void)hipEventRecord(ev_stop, s);
+  if (ev_start && ev_stop) {
+    // profiling aid: the two events take the start and the end time of this kernel itself (not of the launch call)
+    hipExtLaunchKernelGGL(kern, dim3(v.P, n_splits), dim3(kMfmaThreads), (uint32_t)lds, s, ev_start, ev_stop, 0u, v, q,
+                          scale, n_blocks, n_res, n_splits, part, accumulate_q, nt, sc);
+  } else {
+    kern<<<dim3(v.P, n_splits), dim3(kMfmaThreads), lds, s>>>(v, q, scale, n_blocks, n_res, n_splits, part, accumulate_q, nt, sc);
+  }
   decode_merge_pair_kernel<<<dim3(v.P), dim3(256), 0, s>>>(v, part, n_splits, out, lse);
   return hipGetLastError();
 }
