@@ -280,20 +280,40 @@ __device__ unsigned long long g_flush_clock[1024 * 16];
 __device__ __forceinline__ fh2 as_h2(unsigned w) { return __builtin_bit_cast(fh2, w); }
 __device__ __forceinline__ unsigned short h_bits(_Float16 h) { return __builtin_bit_cast(unsigned short, h); }
 
-// Code of u = x - z with the reciprocal r of the scale (r = 0 for scale 0); TOP = 3 or 15.  q0 = u*r is within
-// (TOP + 1.3) * 2.4e-7 of the correctly rounded quotient (rcp and the product are good to 1.8e-7 relative, the
-// quotient itself to 6e-8), i.e. within 1e-6 for two-bit and 4e-6 for four-bit codes; so whenever q0 is further
-// than EPS (2^-18, 2^-16) from every half-integer, rint(q0) IS the code Eq. 2 defines.  `near` collects the
-// other cases, which the caller redoes with the IEEE division.  (u >= 0, so no lower clamp is needed.)
+// Fast form of Eq. 2's code: q0 = x*r + nz in one fused multiply-add, with r the reciprocal of the scale and
+// nz = -z*r, both per group.  Against the quotient q that Eq. 2 defines (fp32 subtract, correctly rounded divide):
+//   |q0 - q| <= |q| (2^-23 [rcp] + 2^-24 [fma] + 2^-23 [the two roundings of q]) + |z r| 2^-24,
+// i.e. below 2.9e-6 for two-bit codes (q <= 3.002) and below 6.5e-6 for four-bit codes (q <= 15.008) as long as
+// |z r| <= 32 and the scale is a normal binary16 (its rounding is then fine enough that no quotient passes the top
+// code by more than 0.008).  So whenever q0 is further than EPS (2^-18, 2^-16) from every half-integer, rint(q0) IS
+// the code Eq. 2 defines, with no clamp needed; `dev` collects the largest distance from the nearest integer over a
+// word, and the caller redoes a word with dev > 1/2 - EPS with the IEEE division.  Groups outside those conditions
+// get (r, nz) = (0, 1/2): every q0 is 1/2, so all their words are redone.  Scale 0 gets (0, 0): code 0.
 // The code is returned as a float: the callers build each half-word of a packed word as an exact fp32 sum
 // c_0 + c_1 2^w + c_2 2^2w + ... (< 2^16) with one fused multiply-add per code and convert once per half-word.
-template <int TOP>
-__device__ __forceinline__ float code_fast(float x, float z, float r, bool& near) {
-  constexpr float kEps = TOP == 3 ? 3.814697265625e-6f : 1.52587890625e-5f;
-  const float q0 = (x - z) * r;
+constexpr float kEps2 = 3.814697265625e-6f, kEps4 = 1.52587890625e-5f;
+__device__ __forceinline__ void fast_params(float s, float z, float* r, float* nz) {
+  float rr = s > 0.f ? __builtin_amdgcn_rcpf(s) : 0.f;
+  float nn = -z * rr;
+  if (s > 0.f && (s < 6.103515625e-05f || !(fabsf(nn) <= 32.f))) {
+    rr = 0.f;
+    nn = 0.5f;
+  }
+  *r = rr;
+  *nz = nn;
+}
+__device__ __forceinline__ float code_fast(__half x, float r, float nz, float& dev) {
+  const float q0 = __builtin_fmaf(__half2float(x), r, nz);
   const float c = rintf(q0);
-  near |= fabsf(q0 - c) > 0.5f - kEps;
-  return fminf(c, (float)TOP);
+  dev = fmaxf(dev, fabsf(q0 - c));
+  return c;
+}
+// Eq. 2's code itself (IEEE division) as a float, from the group's packed parameters (scale | zero-point << 16, binary16 bits).
+__device__ __forceinline__ float code_exact(__half x, unsigned sz, float top) {
+  const float s = __half2float(__ushort_as_half((unsigned short)(sz & 0xffffu)));
+  const float z = __half2float(__ushort_as_half((unsigned short)(sz >> 16)));
+  if (!(s > 0.f)) return 0.f;
+  return fminf(fmaxf(rintf((__half2float(x) - z) / s), 0.f), top);
 }
 // code i of a word sits at bit 16 (i & 1) + W (i >> 1): even codes in the low half-word, odd codes in the high one
 template <int W>
@@ -303,7 +323,6 @@ __device__ __forceinline__ void add_code(float (&half)[2], int i, float c) {
 __device__ __forceinline__ unsigned join_halves(const float (&half)[2]) {
   return (unsigned)half[0] | ((unsigned)half[1] << 16);
 }
-__device__ __forceinline__ float safe_rcp(float s) { return s > 0.f ? __builtin_amdgcn_rcpf(s) : 0.f; }
 
 // largest value over the wavefront (every lane must take part)
 __device__ __forceinline__ unsigned wave_max_u32(unsigned v) {
@@ -333,8 +352,12 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   __shared__ unsigned char sPos[kD];       // position of the channel inside its tier
   __shared__ unsigned char sLoList[kD];    // 2-bit channels, ascending
   __shared__ unsigned char sHiList[kD];    // fp16 tier then 4-bit tier
-  __shared__ __align__(16) float sS[8 * kD], sZ[8 * kD];   // keys: [group][channel]; values: [token][value group]
-  __shared__ __align__(16) float sR[8 * kD];   // reciprocals of the scales in sS (0 for scale 0)
+  // parameters of the groups, keys: [group][channel], values: [token][value group]: the pair (r, nz) of the fast
+  // codes, and scale | zero-point << 16 (binary16 bits) for the codes that are redone with the division
+  __shared__ __align__(16) float sRN[2 * 8 * kD];
+  float* const sR = sRN;               // r
+  float* const sNZ = sRN + 8 * kD;     // nz
+  __shared__ unsigned sSZ[8 * kD];
   __shared__ unsigned sKmax[9];            // [8]: largest value scale
   __shared__ unsigned sChunk[2][kMaxR / 16][kD / 2];   // (min, max) keys per 16-token chunk and channel pair
   unsigned (*sCLo)[kD / 2] = sChunk[0];
@@ -516,7 +539,9 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   __syncthreads();
 
   // sizes of the tiers of this block (the budgets, or what passed the thresholds)
-  const int n_lo = sCnt[0] + sCnt[3], n_4 = sCnt[1] + sCnt[4], n_16 = sCnt[2] + sCnt[5];
+  // (the same for every thread: kept in scalar registers)
+  const int n_lo = __builtin_amdgcn_readfirstlane(sCnt[0] + sCnt[3]), n_4 = __builtin_amdgcn_readfirstlane(sCnt[1] + sCnt[4]),
+            n_16 = __builtin_amdgcn_readfirstlane(sCnt[2] + sCnt[5]);
 
   MIXKVQ_FPHASE(3)
   // ---- key group parameters from the chunk extrema ------------------------------------------
@@ -538,9 +563,8 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
           hi = b2 > hi ? b2 : hi;
         }
         const GroupParams gp = group_params((float)lo, (float)hi, tier ? 15.f : 3.f);
-        sS[grp * kD + d] = gp.s;
-        sZ[grp * kD + d] = gp.z;
-        sR[grp * kD + d] = safe_rcp(gp.s);
+        sSZ[grp * kD + d] = (unsigned)gp.s16 | ((unsigned)gp.z16 << 16);
+        fast_params(gp.s, gp.z, &sR[grp * kD + d], &sNZ[grp * kD + d]);
         const int pos = sPos[d];
         s16v = gp.s16;
         if (tier == 0) {
@@ -571,33 +595,32 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
         doff[i] = jj < n_lo ? (int)sLoList[jj] : -1;
       }
       for (int grp = 0; grp < NG; ++grp) {
-        float rc[16], zp[16];
+        float rc[16], nz[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int d = doff[i] < 0 ? 0 : doff[i];
-          rc[i] = doff[i] < 0 ? 0.f : sR[grp * kD + d];   // 0 gives code 0: the padding of the last word
-          zp[i] = sZ[grp * kD + d];
+          rc[i] = doff[i] < 0 ? 0.f : sR[grp * kD + d];   // (0, 0) gives code 0: the padding of the last word
+          nz[i] = doff[i] < 0 ? 0.f : sNZ[grp * kD + d];
         }
         for (int tt = tl; tt < Gk; tt += 32) {
           const int t = grp * Gk + tt;
           const __half* row = sT + t * kRowStride;
           float hw[2] = {0.f, 0.f};
-          bool near = false;
+          float dev = 0.f;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const float x = __half2float(row[doff[i] < 0 ? 0 : doff[i]]);
-            add_code<2>(hw, i, code_fast<3>(x, zp[i], rc[i], near));
-          }
-          unsigned w = join_halves(hw);
-          if (__any(near)) {     // rare: some quotient sits next to a rounding boundary
-            w = 0;
+          for (int i = 0; i < 16; ++i)
+            add_code<2>(hw, i, code_fast(row[doff[i] < 0 ? 0 : doff[i]], rc[i], nz[i], dev));
+          if (__any(dev > 0.5f - kEps2)) {     // some quotient sits next to a rounding boundary (exact ties are common)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
+            for (int i = 0; i < 16; ++i) {     // find the codes concerned and correct them
               const int d = doff[i] < 0 ? 0 : doff[i];
-              const float x = __half2float(row[d]);
-              w |= encode(x, zp[i], doff[i] < 0 ? 0.f : sS[grp * kD + d], 3.f) << (16 * (i & 1) + 2 * (i >> 1));
+              float dv = 0.f;
+              const float c = code_fast(row[d], rc[i], nz[i], dv);
+              if (__any(dv > 0.5f - kEps2))
+                add_code<2>(hw, i, code_exact(row[d], doff[i] < 0 ? 0u : sSZ[grp * kD + d], 3.f) - c);
             }
           }
+          const unsigned w = join_halves(hw);
           reinterpret_cast<unsigned*>(rec + off_klo)[t * Wlo + wd] = w;
         }
       }
@@ -611,25 +634,26 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
     if (t >= R) break;
     const int grp = t / Gk, it = t * W4 + wd;
     float hw[2] = {0.f, 0.f};
-    bool near = false;
+    float dev = 0.f;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const bool used = wd * 8 + i < n_4;                    // an unused entry gets reciprocal 0, i.e. code 0
+      const bool used = wd * 8 + i < n_4;                    // an unused entry gets (0, 0), i.e. code 0
       const int d = used ? sHiList[k16 + wd * 8 + i] : 0;
-      add_code<4>(hw, i, code_fast<15>(__half2float(sT[t * kRowStride + d]), sZ[grp * kD + d],
-                                       used ? sR[grp * kD + d] : 0.f, near));
+      add_code<4>(hw, i, code_fast(sT[t * kRowStride + d], used ? sR[grp * kD + d] : 0.f,
+                                   used ? sNZ[grp * kD + d] : 0.f, dev));
     }
-    unsigned w = join_halves(hw);
-    if (__any(near)) {     // rare: some quotient sits next to a rounding boundary
-      w = 0;
+    if (__any(dev > 0.5f - kEps4)) {     // some quotient sits next to a rounding boundary
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const bool used = wd * 8 + i < n_4;
         const int d = used ? sHiList[k16 + wd * 8 + i] : 0;
-        w |= encode(__half2float(sT[t * kRowStride + d]), sZ[grp * kD + d], used ? sS[grp * kD + d] : 0.f, 15.f)
-             << (16 * (i & 1) + 4 * (i >> 1));
+        float dv = 0.f;
+        const float c = code_fast(sT[t * kRowStride + d], used ? sR[grp * kD + d] : 0.f, used ? sNZ[grp * kD + d] : 0.f, dv);
+        if (__any(dv > 0.5f - kEps4))
+          add_code<4>(hw, i, code_exact(sT[t * kRowStride + d], used ? sSZ[grp * kD + d] : 0u, 15.f) - c);
       }
     }
+    const unsigned w = join_halves(hw);
     reinterpret_cast<unsigned*>(rec + off_k4)[it] = w;
   }
   // ---- fp16 tier: [token][k16] ------------------------------------------
@@ -644,8 +668,6 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   // The tile goes to LDS; on the way every thread reduces its 16-byte pieces (still in registers) to the minimum
   // and maximum per token and value group: 16 threads cover a row, a group is Gv/8 neighbouring threads, and the
   // pair (min, -max) is reduced with packed fp16 minima over DPP lane exchanges inside the row of 16.
-  float* sVS = sS;   // [token][NVG]
-  float* sVZ = sZ;
   {
     const int c = tid & 15, lpg = Gv / 8;                 // lpg = 2, 4, 8 or 16 (Gv divides 128)
     const int lpg_shift = 31 - __builtin_clz(lpg);
@@ -680,9 +702,8 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
     for (int it = tid; it < R * NVG; it += kFlushThreads) {
       const fh2 mm = as_h2(sRow[it]);
       const GroupParams gp = group_params((float)mm[0], -(float)mm[1], 3.f);
-      sVS[it] = gp.s;
-      sVZ[it] = gp.z;
-      sR[it] = safe_rcp(gp.s);
+      sSZ[it] = (unsigned)gp.s16 | ((unsigned)gp.z16 << 16);
+      fast_params(gp.s, gp.z, &sR[it], &sNZ[it]);
       vmax_t = gp.s16 > vmax_t ? gp.s16 : vmax_t;
       reinterpret_cast<unsigned short*>(rec + off_v_s)[it] = gp.s16;
       reinterpret_cast<unsigned short*>(rec + off_v_z)[it] = gp.z16;
@@ -703,39 +724,40 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
       const int tok0 = value_word_token(tg, 0, ilv), tok1 = tok0 + (ilv ? 32 : 8);
       const __half* const col0 = sT + tok0 * kRowStride + d;
       const __half* const col1 = sT + tok1 * kRowStride + d;
-      float rc[16], zp[16];
+      float rc[16], nz[16];
       if (NVG == 1) {
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
           const int t4 = (i4 >> 1 ? tok1 : tok0) + 4 * (i4 & 1);
           const float4 a = *reinterpret_cast<const float4*>(sR + t4);
-          const float4 b2 = *reinterpret_cast<const float4*>(sVZ + t4);
+          const float4 b2 = *reinterpret_cast<const float4*>(sNZ + t4);
           rc[4 * i4] = a.x; rc[4 * i4 + 1] = a.y; rc[4 * i4 + 2] = a.z; rc[4 * i4 + 3] = a.w;
-          zp[4 * i4] = b2.x; zp[4 * i4 + 1] = b2.y; zp[4 * i4 + 2] = b2.z; zp[4 * i4 + 3] = b2.w;
+          nz[4 * i4] = b2.x; nz[4 * i4 + 1] = b2.y; nz[4 * i4 + 2] = b2.z; nz[4 * i4 + 3] = b2.w;
         }
       } else {
         const float* const r0 = sR + tok0 * NVG + vg, * const r1 = sR + tok1 * NVG + vg;
-        const float* const z0 = sVZ + tok0 * NVG + vg, * const z1 = sVZ + tok1 * NVG + vg;
+        const float* const z0 = sNZ + tok0 * NVG + vg, * const z1 = sNZ + tok1 * NVG + vg;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           rc[i] = (i < 8 ? r0 : r1)[(i & 7) * NVG];
-          zp[i] = (i < 8 ? z0 : z1)[(i & 7) * NVG];
+          nz[i] = (i < 8 ? z0 : z1)[(i & 7) * NVG];
         }
       }
       float hw[2] = {0.f, 0.f};
-      bool near = false;
+      float dev = 0.f;
 #pragma unroll
       for (int i = 0; i < 16; ++i)
-        add_code<2>(hw, i, code_fast<3>(__half2float((i < 8 ? col0 : col1)[(i & 7) * kRowStride]), zp[i], rc[i], near));
-      unsigned w = join_halves(hw);
-      if (__any(near)) {     // rare: some quotient sits next to a rounding boundary
-        w = 0;
+        add_code<2>(hw, i, code_fast((i < 8 ? col0 : col1)[(i & 7) * kRowStride], rc[i], nz[i], dev));
+      if (__any(dev > 0.5f - kEps2)) {     // some quotient sits next to a rounding boundary
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int t = (i < 8 ? tok0 : tok1) + (i & 7);
-          w |= encode(__half2float(sT[t * kRowStride + d]), zp[i], sVS[t * NVG + vg], 3.f) << (16 * (i & 1) + 2 * (i >> 1));
+          float dv = 0.f;
+          const float c = code_fast(sT[t * kRowStride + d], rc[i], nz[i], dv);
+          if (__any(dv > 0.5f - kEps2)) add_code<2>(hw, i, code_exact(sT[t * kRowStride + d], sSZ[t * NVG + vg], 3.f) - c);
         }
       }
+      const unsigned w = join_halves(hw);
       reinterpret_cast<unsigned*>(rec + off_v)[tg * kD + d] = w;
     }
   }

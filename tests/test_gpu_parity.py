@@ -408,6 +408,34 @@ def test_quotients_on_rounding_boundaries(H):
     H.check_state(oc, gc)
 
 
+def test_groups_far_from_zero(H):
+    """Groups whose zero-point is many scale steps away from zero (channel / token offsets of up to +-2000 with a
+    spread of a few units, with and without exact ties): the quantize kernel's fused form of Eq. 2 loses accuracy
+    with |z/s| and must hand such groups to the exact division."""
+    rng = np.random.default_rng(43)
+    kw = dict(B=1, Hq=4, Hkv=2, D=128, T_max=512, Gk=64, Gv=64, R=128, k4=16, k16=0)
+    oc, gc = H.make_pair(**kw)
+    n = 400
+    offs = np.array([0, 3, -3, 8, -8, 16, -21, 40, -64, 100, -300, 1024, -2000, 0.5, -0.25, 7])
+    K = rng.standard_normal((1, 2, n, 128)) + offs[rng.integers(0, 16, (1, 2, 1, 128))]
+    K[..., 64:] = rng.integers(0, 7, (1, 2, n, 64)) + offs[rng.integers(0, 13, (1, 2, 1, 64))].round()   # ties
+    V = rng.standard_normal((1, 2, n, 128)) * 0.5 + offs[rng.integers(0, 16, (1, 2, n, 1))]
+    V[:, :, ::2] = rng.integers(-3, 4, (1, 2, (n + 1) // 2, 128)) + offs[rng.integers(0, 13, (1, 2, (n + 1) // 2, 1))].round()
+    K, V = K.astype(np.float16), V.astype(np.float16)
+    Qp = rng.standard_normal((1, 4, 8, 128)).astype(np.float16)
+    sel_ref = oc.select_channels(Qp, K)
+    sel = gc.select_channels(H.dev(Qp), H.dev(K))
+    assert np.array_equal(sel.cpu().numpy(), sel_ref)
+    oc.append(K, V, sel_ref)
+    gc.quantize_append(H.dev(K), H.dev(V), sel=sel)
+    H.check_state(oc, gc)
+    # the same data scored block by block inside the pack kernel
+    oc2, gc2 = H.make_pair(**kw)
+    oc2.append(K, V)
+    gc2.quantize_append(H.dev(K), H.dev(V))
+    H.check_state(oc2, gc2)
+
+
 def test_eager_mode_with_empty_window_and_single_block(H):
     rng = np.random.default_rng(10)
     kw = dict(B=1, Hq=7, Hkv=1, D=128, T_max=256, Gk=128, Gv=128, R=128, k4=16, k16=0, flush_mode=1)
