@@ -25,16 +25,25 @@ hipError_t launch_zero_qacc(const CacheView& v, hipStream_t s) {
 
 // ---------------------------------------------------------------------------
 // Eq. 6: sum of |q| per KV head and channel, over tokens and the g query heads
-// of the group.  Streaming form: a workgroup takes kRowsPerWG rows of one query head;
+// of the group.  Streaming form: a workgroup takes `rows` rows of one query head;
 // 16 threads cover a row of 256 bytes with one 16-byte load each, 16 rows per pass,
-// four passes in flight.  Per-thread 64-bit sums, one LDS reduction over the 16 row
+// eight passes in flight.  Per-thread 64-bit sums, one LDS reduction over the 16 row
 // lanes, one 64-bit atomic per channel and workgroup (integers: any order is exact).
 // ---------------------------------------------------------------------------
 constexpr int kStreamThreads = 256;
-constexpr int kRowsPerWG = 512;
+constexpr int kMinRowsPerWG = 512, kMaxRowsPerWG = 2048;
+constexpr int kInFlight = 8;      // 16-byte loads a thread has in flight
+
+// Rows one workgroup takes: 512, or up to 2048 when that still leaves every compute unit tens of workgroups (fewer
+// reductions and atomics per byte streamed: +2 % on a 5 GB tensor).
+static int rows_per_workgroup(int64_t pairs_times_heads, int L) {
+  int rows = kMinRowsPerWG;
+  while (rows < kMaxRowsPerWG && pairs_times_heads * ((L + 2 * rows - 1) / (2 * rows)) >= 4096) rows *= 2;
+  return rows;
+}
 
 // The per-thread sums run in binary64, which is exact here: every |fp16| is a multiple of 2^-24 below 2^16, so up to
-// 2^13 of them add without rounding in a 53-bit significand (a thread adds at most kRowsPerWG / 16 = 32 per channel);
+// 2^13 of them add without rounding in a 53-bit significand (a thread adds at most kMaxRowsPerWG / 16 = 128 per channel);
 // the sum times 2^24 is the exact integer.
 typedef _Float16 sh2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void add8(double (&acc)[8], uint4 v) {
@@ -49,25 +58,26 @@ __device__ __forceinline__ void add8(double (&acc)[8], uint4 v) {
 
 template <bool BF>      // BF: the tensor holds bfloat16 (converted to binary16 on entry)
 __global__ void __launch_bounds__(kStreamThreads)
-qabs_accumulate_kernel(const __half* __restrict__ q, int Lq, Strides3 qs, int Hkv, int g,
+qabs_accumulate_kernel(const __half* __restrict__ q, int Lq, Strides3 qs, int Hkv, int g, int rows,
                        unsigned long long* __restrict__ qacc, unsigned long long* __restrict__ qcnt) {
   __shared__ unsigned long long sAcc[16][kD];
   const int p = blockIdx.x, b = p / Hkv, j = p % Hkv, tid = threadIdx.x;
   const int hh = blockIdx.y % g, chunk = blockIdx.y / g;
   const int c = tid & 15, r = tid >> 4;
-  const int t0 = chunk * kRowsPerWG, t1 = min(Lq, t0 + kRowsPerWG);
+  const int t0 = chunk * rows, t1 = min(Lq, t0 + rows);
   const __half* base = q + (int64_t)b * qs.b + (int64_t)(j * g + hh) * qs.h + 8 * c;
-  static_assert(kRowsPerWG / 16 <= 8192, "per-thread binary64 sums must stay exact");
+  static_assert(kMaxRowsPerWG / 16 <= 8192, "per-thread binary64 sums must stay exact");
   double acc[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] = 0.0;
   int t = t0 + r;
-  for (; t + 48 < t1; t += 64) {
-    uint4 v[4];
+  constexpr int NF = kInFlight;
+  for (; t + 16 * (NF - 1) < t1; t += 16 * NF) {
+    uint4 v[NF];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const uint4*>(base + (int64_t)(t + 16 * u) * qs.t);
+    for (int u = 0; u < NF; ++u) v[u] = *reinterpret_cast<const uint4*>(base + (int64_t)(t + 16 * u) * qs.t);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) add8(acc, as_f16x8(v[u], BF));
+    for (int u = 0; u < NF; ++u) add8(acc, as_f16x8(v[u], BF));
   }
   for (; t < t1; t += 16) add8(acc, as_f16x8(*reinterpret_cast<const uint4*>(base + (int64_t)t * qs.t), BF));
 #pragma unroll
@@ -84,12 +94,12 @@ qabs_accumulate_kernel(const __half* __restrict__ q, int Lq, Strides3 qs, int Hk
 
 // Fallback for tensors whose rows are not 16-byte aligned: one thread per channel.
 __global__ void __launch_bounds__(kD) qabs_accumulate_unaligned_kernel(const __half* __restrict__ q, int Lq, Strides3 qs,
-                                                                      int Hkv, int g, int bf16,
+                                                                      int Hkv, int g, int rows, int bf16,
                                                                       unsigned long long* __restrict__ qacc,
                                                                       unsigned long long* __restrict__ qcnt) {
   const int p = blockIdx.x, b = p / Hkv, j = p % Hkv, d = threadIdx.x;
   const int hh = blockIdx.y % g, chunk = blockIdx.y / g;
-  const int t0 = chunk * kRowsPerWG, t1 = min(Lq, t0 + kRowsPerWG);
+  const int t0 = chunk * rows, t1 = min(Lq, t0 + rows);
   const __half* base = q + (int64_t)b * qs.b + (int64_t)(j * g + hh) * qs.h + d;
   unsigned long long acc = 0;
   for (int t = t0; t < t1; ++t) acc += fix24_abs(in_bits(base + (int64_t)t * qs.t, bf16));
@@ -102,13 +112,14 @@ static bool rows_aligned16(const void* ptr, Strides3 st) {
 }
 
 hipError_t launch_qabs_accumulate(const CacheView& v, const __half* q, int Lq, Strides3 qs, hipStream_t s) {
-  dim3 grid(v.P, v.g * ((Lq + kRowsPerWG - 1) / kRowsPerWG));
+  const int rows = rows_per_workgroup((int64_t)v.P * v.g, Lq);
+  dim3 grid(v.P, v.g * ((Lq + rows - 1) / rows));
   if (!rows_aligned16(q, qs))
-    qabs_accumulate_unaligned_kernel<<<grid, dim3(kD), 0, s>>>(q, Lq, qs, v.cfg.Hkv, v.g, v.cfg.in_dtype, v.qacc, v.qcnt);
+    qabs_accumulate_unaligned_kernel<<<grid, dim3(kD), 0, s>>>(q, Lq, qs, v.cfg.Hkv, v.g, rows, v.cfg.in_dtype, v.qacc, v.qcnt);
   else if (v.cfg.in_dtype)
-    qabs_accumulate_kernel<true><<<grid, dim3(kStreamThreads), 0, s>>>(q, Lq, qs, v.cfg.Hkv, v.g, v.qacc, v.qcnt);
+    qabs_accumulate_kernel<true><<<grid, dim3(kStreamThreads), 0, s>>>(q, Lq, qs, v.cfg.Hkv, v.g, rows, v.qacc, v.qcnt);
   else
-    qabs_accumulate_kernel<false><<<grid, dim3(kStreamThreads), 0, s>>>(q, Lq, qs, v.cfg.Hkv, v.g, v.qacc, v.qcnt);
+    qabs_accumulate_kernel<false><<<grid, dim3(kStreamThreads), 0, s>>>(q, Lq, qs, v.cfg.Hkv, v.g, rows, v.qacc, v.qcnt);
   return hipGetLastError();
 }
 
@@ -135,12 +146,12 @@ __global__ void range_init_kernel(long long* mn, long long* mx, int n) {
 
 template <bool BF>
 __global__ void __launch_bounds__(kStreamThreads)
-key_range_kernel(const __half* __restrict__ k, int L, Strides3 ks, int Hkv, long long* __restrict__ mn,
+key_range_kernel(const __half* __restrict__ k, int L, Strides3 ks, int Hkv, int rows, long long* __restrict__ mn,
                  long long* __restrict__ mx) {
   __shared__ unsigned sLo[16][kD / 2], sHi[16][kD / 2];
   const int p = blockIdx.x, b = p / Hkv, j = p % Hkv, tid = threadIdx.x;
   const int c = tid & 15, r = tid >> 4;
-  const int t0 = blockIdx.y * kRowsPerWG, t1 = min(L, t0 + kRowsPerWG);
+  const int t0 = blockIdx.y * rows, t1 = min(L, t0 + rows);
   const __half* base = k + (int64_t)b * ks.b + (int64_t)j * ks.h + 8 * c;
   s16x2 lo[4], hi[4];
 #pragma unroll
@@ -158,12 +169,13 @@ key_range_kernel(const __half* __restrict__ k, int L, Strides3 ks, int Hkv, long
     }
   };
   int t = t0 + r;
-  for (; t + 48 < t1; t += 64) {
-    uint4 v[4];
+  constexpr int NF = kInFlight;
+  for (; t + 16 * (NF - 1) < t1; t += 16 * NF) {
+    uint4 v[NF];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const uint4*>(base + (int64_t)(t + 16 * u) * ks.t);
+    for (int u = 0; u < NF; ++u) v[u] = *reinterpret_cast<const uint4*>(base + (int64_t)(t + 16 * u) * ks.t);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) upd(as_f16x8(v[u], BF));
+    for (int u = 0; u < NF; ++u) upd(as_f16x8(v[u], BF));
   }
   for (; t < t1; t += 16) upd(as_f16x8(*reinterpret_cast<const uint4*>(base + (int64_t)t * ks.t), BF));
 #pragma unroll
@@ -192,11 +204,11 @@ key_range_kernel(const __half* __restrict__ k, int L, Strides3 ks, int Hkv, long
 }
 
 __global__ void __launch_bounds__(kD) key_range_unaligned_kernel(const __half* __restrict__ k, int L, Strides3 ks,
-                                                                int Hkv, int bf16, long long* __restrict__ mn,
+                                                                int Hkv, int rows, int bf16, long long* __restrict__ mn,
                                                                 long long* __restrict__ mx) {
   const int p = blockIdx.x, b = p / Hkv, j = p % Hkv, d = threadIdx.x;
-  const int t0 = blockIdx.y * kRowsPerWG;
-  const int t1 = min(L, t0 + kRowsPerWG);
+  const int t0 = blockIdx.y * rows;
+  const int t1 = min(L, t0 + rows);
   const __half* base = k + (int64_t)b * ks.b + (int64_t)j * ks.h + d;
   long long lo = 0x7fffffffffffffffll, hi = -0x7fffffffffffffffll - 1;
   for (int t = t0; t < t1; ++t) {
@@ -252,13 +264,14 @@ hipError_t launch_select(const CacheView& v, const __half* k, int L, Strides3 ks
   long long* mx = mn + (size_t)v.P * kD;
   const int n = v.P * kD;
   range_init_kernel<<<dim3((n + 255) / 256), dim3(256), 0, s>>>(mn, mx, n);
-  dim3 grid(v.P, (L + kRowsPerWG - 1) / kRowsPerWG);
+  const int rows = rows_per_workgroup(v.P, L);
+  dim3 grid(v.P, (L + rows - 1) / rows);
   if (!rows_aligned16(k, ks))
-    key_range_unaligned_kernel<<<grid, dim3(kD), 0, s>>>(k, L, ks, v.cfg.Hkv, v.cfg.in_dtype, mn, mx);
+    key_range_unaligned_kernel<<<grid, dim3(kD), 0, s>>>(k, L, ks, v.cfg.Hkv, rows, v.cfg.in_dtype, mn, mx);
   else if (v.cfg.in_dtype)
-    key_range_kernel<true><<<grid, dim3(kStreamThreads), 0, s>>>(k, L, ks, v.cfg.Hkv, mn, mx);
+    key_range_kernel<true><<<grid, dim3(kStreamThreads), 0, s>>>(k, L, ks, v.cfg.Hkv, rows, mn, mx);
   else
-    key_range_kernel<false><<<grid, dim3(kStreamThreads), 0, s>>>(k, L, ks, v.cfg.Hkv, mn, mx);
+    key_range_kernel<false><<<grid, dim3(kStreamThreads), 0, s>>>(k, L, ks, v.cfg.Hkv, rows, mn, mx);
   select_topk_kernel<<<dim3(v.P), dim3(kD), 0, s>>>(v, mn, mx, sel);
   return hipGetLastError();
 }
