@@ -259,9 +259,11 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
 //   - minima and maxima are taken with packed fp16 instructions, two channels at a time, first per chunk of
 //     16 tokens (all threads), then per group / per block;
 //   - positions inside the tiers come from wavefront ballots;
-//   - in the encode loops a thread keeps the scale and zero-point of its channels (keys) or tokens (values)
-//     in registers and only the element itself comes from LDS.
-// Every rounding step is the one of flush_block_kernel: results are bit-identical.
+//   - in the encode loops a thread keeps the parameters of its channels (keys) or tokens (values) in registers
+//     and only the element itself comes from LDS; a code costs one fused multiply-add, a rounding and its share
+//     of the check that the shortcut is safe (see code_fast); the few codes that fail the check are redone with
+//     Eq. 2's division.
+// The codes, scales and zero-points are bit-identical to those of flush_block_kernel.
 // ---------------------------------------------------------------------------
 typedef _Float16 fh2 __attribute__((ext_vector_type(2)));
 
