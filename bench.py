@@ -33,6 +33,26 @@ LLC_BYTES = 256 << 20   # last-level (Infinity) cache
 MEASURED_TRAFFIC_BYTES = {("cfg1_gqa7b_b8_32k", 32768): 39552.3 * 1024 * 2.0 + 1868.3 * 1024 * 1.0}
 
 
+def copy_kernel_gbs():
+    """Bandwidth of a plain device copy (512 MiB read + 512 MiB written per call), the practical reference
+    beside the nominal 8 TB/s: GB/s of read + written bytes."""
+    import torch
+    n = 512 << 20
+    x = torch.empty(n, dtype=torch.uint8, device="cuda")
+    y = torch.empty_like(x)
+    for _ in range(3):
+        y.copy_(x)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(10):
+        y.copy_(x)
+    b.record()
+    torch.cuda.synchronize()
+    gbs = 10 * 2 * n / (a.elapsed_time(b) * 1e-3) / 1e9
+    del x, y
+    return gbs
+
+
 def algorithmic_bytes_thresholds(w, gc, r):
     """The same count under the threshold policy, where every block has its own tier sizes: they are read from
     the channel lists of the cache's block records (entries other than 255)."""
@@ -217,6 +237,10 @@ def bench_prefill(args, w, cfg_id):
                      "achieved": round((in_b + out_b) / el / 1e9, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round((in_b + out_b) / el / 1e9 / HBM_PEAK_GBS, 4), "traffic": None},
     }
+    del dq
+    copy_gbs = copy_kernel_gbs()
+    result["copy_kernel"] = {"value": round(copy_gbs, 1), "unit": "GB/s read+write, 512 MiB device copy on this box",
+                             "pct_of_copy_kernel": round(100 * (in_b + out_b) / el / 1e9 / copy_gbs, 2)}
     print(json.dumps(result))
 
 
@@ -396,6 +420,10 @@ def main():
         "amortised_with_flush_every_R": round((sum(ps_plain) / max(1, len(ps_plain)) * (w.R - 1)
                                                + (sum(ps_flush) / len(ps_flush) if ps_flush else 0.0)) / w.R, 2),
         "note": "each step between its own event pair (adds event overhead to every step)"}
+    copy_gbs = copy_kernel_gbs()
+    result["copy_kernel"] = {"value": round(copy_gbs, 1), "unit": "GB/s read+write, 512 MiB device copy on this box",
+                             "pct_of_copy_kernel": round(100 * value / copy_gbs, 2),
+                             "kernel_pct_of_copy_kernel": round(100 * achieved / copy_gbs, 2)}
     if tiers:
         result["config"]["threshold_policy"] = tiers
     result["config"]["selection"] = "per block" if (args.thresholds or args.per_block_selection) else "one per prompt"

@@ -22,6 +22,7 @@
 // product keeps ~22 bits of q*s at no extra matrix instruction; the two halves are
 // added after the product with one DPP add.
 #include <hip/hip_ext.h>
+#include <atomic>
 #include "mixkvq_internal.h"
 
 namespace mixkvq {
@@ -1105,11 +1106,15 @@ static hipError_t launch_one(const CacheView& v, const __half* q, float scale, i
                              hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
   auto kern = decode_fused_kernel<K4, K16, NVG, NKL, RG, THR, G32, PG>;
   const size_t lds = kHdrLds + (size_t)kWaves * kWaveLds;
-  static bool attr_set = false;
-  if (!attr_set) {
+  // the kernel's LDS limit is raised once per device (a repeated call from another thread does no harm)
+  static std::atomic<uint64_t> attr_set{0};
+  int device = 0;
+  if (hipError_t e = hipGetDevice(&device); e != hipSuccess) return e;
+  const uint64_t bit = 1ull << (device & 63);
+  if (!(attr_set.load(std::memory_order_acquire) & bit)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    attr_set.fetch_or(bit, std::memory_order_release);
   }
   if (ev_start && ev_stop) {
     // profiling aid: the two events take the start and the end time of this kernel itself (not of the launch call)
