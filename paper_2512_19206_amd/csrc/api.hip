@@ -2,6 +2,7 @@
 // cache state machine (residual window and lazy flush of Appendix D.1) and the
 // C ABI.  All device work is enqueued by the launchers in the kernel files.
 #include <new>
+#include <stdio.h>
 #include <string.h>
 #include "mixkvq_internal.h"
 
