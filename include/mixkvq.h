@@ -46,9 +46,10 @@ typedef struct {
   int32_t B, Hq, Hkv;   /* batch, query heads, KV heads; Hq % Hkv == 0, Hq/Hkv <= 8 */
   int32_t D;            /* head dimension; must be 128 */
   int32_t T_max;        /* capacity of the quantized part in tokens; multiple of R */
-  int32_t Gk;           /* key group: Gk consecutive tokens of one channel; R % Gk == 0, Gk % 16 == 0 */
+  int32_t Gk;           /* key group: Gk consecutive tokens of one channel; min(R, 128) % Gk == 0, Gk % 16 == 0 */
   int32_t Gv;           /* value group: Gv consecutive channels of one token; D % Gv == 0, Gv % 16 == 0 */
-  int32_t R;            /* residual window length == flush unit; multiple of 16, <= 128 */
+  int32_t R;            /* residual window length == flush unit; a multiple of 16 up to 128, or 256.  A block of R tokens
+                           is scored as a whole and stored as R / Rr records of Rr = min(R, 128) tokens with one channel list */
   int32_t k4, k16;      /* salient key channels kept at 4 bit / as fp16; k4 % 8 == 0, k16 % 4 == 0, k4+k16 < D */
   int32_t flush_mode;   /* 0 deferred: the newest <= R tokens stay fp16; 1 eager: flush as soon as R are buffered */
   int32_t score_mode;   /* 0: A_d = I_d * S_d (Eq. 8); 1: A_d = S_d (error-only ablation) */
@@ -70,7 +71,7 @@ typedef struct {
 
 /* Bytes of each caller-owned device buffer. */
 typedef struct {
-  uint64_t blocks;     /* [B*Hkv][T_max/R] block records, see mixkvq_block_layout */
+  uint64_t blocks;     /* [B*Hkv][T_max/Rr] block records (Rr = min(R, 128) tokens each), see mixkvq_block_layout */
   uint64_t res_k;      /* [B*Hkv][sink + R][D] fp16 keys: per pair the sink rows, then the residual window */
   uint64_t res_v;      /* [B*Hkv][sink + R][D] fp16 values likewise */
   uint64_t qacc;       /* [B*Hkv][D] u64 sums of |q| in units of 2^-24, then [B*Hkv] u64 counts */
@@ -81,8 +82,8 @@ typedef struct {
   void *blocks, *res_k, *res_v, *qacc, *workspace; /* DEVICE, 256-byte aligned */
 } mixkvq_buffers;
 
-/* Byte offsets of the planes inside one block record (R tokens of one
- * (batch, KV head) pair).  Every plane starts on a 16-byte boundary, padding is 0.
+/* Byte offsets of the planes inside one block record (Rr = min(R, 128) tokens of one
+ * (batch, KV head) pair; R below stands for Rr).  Every plane starts on a 16-byte boundary, padding is 0.
  *   idx    u8  [k16+k4]      fp16-tier channels ascending, then 4-bit-tier channels ascending; under policy 1 each
  *                            tier is filled up to its capacity with MIXKVQ_NO_CHANNEL and the unused entries of
  *                            every plane of that tier are 0
@@ -121,8 +122,8 @@ int mixkvq_cache_sizes(const mixkvq_config* cfg, mixkvq_sizes* out);
 int mixkvq_cache_create(const mixkvq_config* cfg, const mixkvq_buffers* bufs, mixkvq_cache** out);
 void mixkvq_cache_destroy(mixkvq_cache* c);
 
-/* Paged storage of the block records.  table: DEVICE int32 [B][T_max/R], owned by the caller; block i of sequence b
- * (its Hkv records, one after the other) then lives in slot table[b][i] of a pool, and bufs->blocks is that pool:
+/* Paged storage of the block records.  table: DEVICE int32 [B][T_max/Rr], owned by the caller; record i of sequence b
+ * (for its Hkv heads, one after the other) then lives in slot table[b][i] of a pool, and bufs->blocks is that pool:
  * slots * Hkv * rec_bytes bytes for as many slots as the caller's allocator hands out, instead of the size
  * mixkvq_cache_sizes reports.  The kernels read the table when a call runs: an entry must be set before the call that
  * flushes or reads its block, and must not change while the block is in use.  NULL returns to the contiguous layout.

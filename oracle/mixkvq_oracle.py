@@ -272,8 +272,18 @@ class BlockLayout:
     v_interleave: int   # 1: value words take their 16 tokens from both 32-token halves of a 64-token span
 
 
+MAX_REC_TOKENS = 128
+
+
+def rec_tokens(cfg: OracleConfig) -> int:
+    """Tokens one stored record holds.  A flushed block of R tokens is stored as R / rec_tokens records of
+    min(R, 128) tokens each, all with the block's channel selection (a storage choice: the quantization groups
+    never straddle a record because Gk divides 128 whenever R > 128)."""
+    return min(cfg.R, MAX_REC_TOKENS)
+
+
 def block_layout(cfg: OracleConfig) -> BlockLayout:
-    """Byte offsets of the planes inside one block record.  Every plane starts
+    """Byte offsets of the planes inside one block record (R below: rec_tokens(cfg)).  Every plane starts
     on a 16-byte boundary; padding bytes are zero.
       idx    u8  [ks]               fp16-tier channels ascending, then 4-bit tier ascending (threshold policy:
                                     each tier filled up to its capacity with NO_CHANNEL)
@@ -293,7 +303,7 @@ def block_layout(cfg: OracleConfig) -> BlockLayout:
       v_s    f16 [R][D/Gv]          value scales per (token, channel group)
       v_z    f16 [R][D/Gv]
     """
-    D, R = cfg.D, cfg.R
+    D, R = cfg.D, rec_tokens(cfg)
     NL = D if cfg.policy == 1 else D - cfg.ks     # threshold policy: room for every channel (tier sizes vary per block)
     Wlo = (NL + 15) // 16
     NLp = 16 * Wlo
@@ -363,8 +373,24 @@ def _pack_along_last(codes: np.ndarray, bits: int) -> np.ndarray:
     return np.bitwise_or.reduce(c << shifts, axis=-1).astype(np.uint32)
 
 
+def sub_block(cfg: OracleConfig, blk: QuantBlock, j: int) -> QuantBlock:
+    """Tokens [j * rec_tokens, (j + 1) * rec_tokens) of a block, with their groups."""
+    Rr = rec_tokens(cfg)
+    t = slice(j * Rr, (j + 1) * Rr)
+    g = slice(j * Rr // cfg.Gk, (j + 1) * Rr // cfg.Gk)
+    return QuantBlock(sel=blk.sel, lo_codes=blk.lo_codes[t], lo_s=blk.lo_s[g], lo_z=blk.lo_z[g], k4_codes=blk.k4_codes[t],
+                      k4_s=blk.k4_s[g], k4_z=blk.k4_z[g], k16=blk.k16[t], v_codes=blk.v_codes[t], v_s=blk.v_s[t],
+                      v_z=blk.v_z[t])
+
+
 def pack_block(cfg: OracleConfig, blk: QuantBlock) -> np.ndarray:
-    """Serialise one block into its record (uint8 [rec_bytes])."""
+    """Serialise one block into its records (uint8 [R / rec_tokens, rec_bytes])."""
+    n_rec = cfg.R // rec_tokens(cfg)
+    return np.stack([pack_record(cfg, sub_block(cfg, blk, j) if n_rec > 1 else blk) for j in range(n_rec)])
+
+
+def pack_record(cfg: OracleConfig, blk: QuantBlock) -> np.ndarray:
+    """Serialise rec_tokens tokens of a block into one record (uint8 [rec_bytes])."""
     lay = block_layout(cfg)
     rec = np.zeros(lay.rec_bytes, dtype=np.uint8)
 
@@ -391,7 +417,7 @@ def pack_block(cfg: OracleConfig, blk: QuantBlock) -> np.ndarray:
     if cfg.k16:
         put(lay.off_k16, np.pad(blk.k16, ((0, 0), (0, pad16))))
     # values: 16 codes per word along tokens, one word per (token group, channel)
-    tok = np.array([[value_word_token(tg, i, lay.v_interleave) for i in range(16)] for tg in range(cfg.R // 16)])
+    tok = np.array([[value_word_token(tg, i, lay.v_interleave) for i in range(16)] for tg in range(rec_tokens(cfg) // 16)])
     vc = blk.v_codes[tok].transpose(0, 2, 1)                              # [tg, d, 16]
     put(lay.off_v, _pack_along_last(vc, 2))
     put(lay.off_v_s, blk.v_s)
@@ -544,14 +570,15 @@ class OracleCache:
 
     # -- bytes ---------------------------------------------------------------
     def packed_blocks(self) -> np.ndarray:
-        """uint8 [P, n_blocks, rec_bytes]."""
+        """uint8 [P, n_records, rec_bytes]: the records of every flushed block, oldest first."""
         lay = block_layout(self.cfg)
         P = len(self.blocks)
+        per = self.cfg.R // rec_tokens(self.cfg)
         nb = self.n_quant // self.cfg.R
-        out = np.zeros((P, nb, lay.rec_bytes), dtype=np.uint8)
+        out = np.zeros((P, nb * per, lay.rec_bytes), dtype=np.uint8)
         for p in range(P):
             for i, blk in enumerate(self.blocks[p]):
-                out[p, i] = pack_block(self.cfg, blk)
+                out[p, i * per:(i + 1) * per] = pack_block(self.cfg, blk)
         return out
 
     # -- Eq. 1 over the mixed-precision cache ----------------------------------

@@ -161,14 +161,19 @@ class Cache:
         _check(self.lib.mixkvq_cache_state(self.handle, C.byref(nq), C.byref(r), None))
         return nq.value, r.value
 
+    @property
+    def rec_tokens(self) -> int:
+        """Tokens per block record: min(R, 128); a block of R = 256 tokens is stored as two records."""
+        return min(self.cfg.R, 128)
+
     def sink_count(self) -> int:
         n = C.c_int32()
         _check(self.lib.mixkvq_cache_state(self.handle, None, None, C.byref(n)))
         return n.value
 
     def set_block_table(self, table):
-        """table: int32 device tensor [B, T_max/R] (kept alive here) or None.  The block buffer becomes the pool:
-        B * T_max/R slots of Hkv records each."""
+        """table: int32 device tensor [B, T_max/rec_tokens] (kept alive here) or None.  The block buffer becomes the
+        pool: B * T_max/rec_tokens slots of Hkv records each."""
         if table is None:
             _check(self.lib.mixkvq_cache_set_block_table(self.handle, None))
         else:
@@ -178,7 +183,7 @@ class Cache:
 
     def pool_records(self) -> torch.Tensor:
         """uint8 [slots, Hkv, rec_bytes] view of the block buffer as a pool (paged layout)."""
-        slots = self.cfg.B * (self.cfg.T_max // self.cfg.R)
+        slots = self.cfg.B * (self.cfg.T_max // self.rec_tokens)
         n = slots * self.cfg.Hkv * self.layout.rec_bytes
         return self.blocks[:n].view(slots, self.cfg.Hkv, self.layout.rec_bytes)
 
@@ -255,9 +260,9 @@ class Cache:
 
     # helpers for tests: views of the raw buffers
     def block_records(self) -> torch.Tensor:
-        """uint8 [P, NB, rec_bytes] view of the quantized blocks."""
+        """uint8 [P, NB, rec_bytes] view of the block records (NB = T_max / rec_tokens)."""
         P = self.cfg.B * self.cfg.Hkv
-        NB = self.cfg.T_max // self.cfg.R
+        NB = self.cfg.T_max // self.rec_tokens
         n = P * NB * self.layout.rec_bytes
         return self.blocks[:n].view(P, NB, self.layout.rec_bytes)
 

@@ -23,18 +23,22 @@ static int hip_fail(hipError_t e) {
 
 static inline int al16(int n) { return (n + 15) / 16 * 16; }
 
+int rec_tokens(const mixkvq_config& c) { return c.R > kMaxR ? kMaxR : c.R; }
+
 int compute_layout(const mixkvq_config& c, Layout* out) {
   if (c.B < 1 || c.Hq < 1 || c.Hkv < 1 || c.Hq % c.Hkv != 0) return MIXKVQ_EINVAL;
   if (c.Hq / c.Hkv > 8) return MIXKVQ_EINVAL;
   if (c.D != kD) return MIXKVQ_EINVAL;
-  if (c.R < 16 || c.R > kMaxR || c.R % 16 != 0) return MIXKVQ_EINVAL;
-  if (c.Gk < 16 || c.Gk % 16 != 0 || c.R % c.Gk != 0) return MIXKVQ_EINVAL;
+  // residual length: a multiple of 16 up to 128, or 256 (stored as two records of 128 tokens per block)
+  if (c.R < 16 || c.R % 16 != 0 || (c.R > kMaxR && c.R != kMaxWindow)) return MIXKVQ_EINVAL;
+  const int Rr = rec_tokens(c);
+  if (c.Gk < 16 || c.Gk % 16 != 0 || Rr % c.Gk != 0) return MIXKVQ_EINVAL;
   if (c.Gv < 16 || c.Gv % 16 != 0 || c.D % c.Gv != 0) return MIXKVQ_EINVAL;
   if (c.k4 < 0 || c.k16 < 0 || c.k4 % 8 != 0 || c.k16 % 4 != 0 || c.k4 + c.k16 >= c.D) return MIXKVQ_EINVAL;
   if (c.T_max < c.R || c.T_max % c.R != 0) return MIXKVQ_EINVAL;
   if (c.flush_mode < 0 || c.flush_mode > 1 || c.score_mode < 0 || c.score_mode > 1) return MIXKVQ_EINVAL;
   if ((int64_t)c.B * c.Hkv > (1 << 20)) return MIXKVQ_EINVAL;
-  if ((int64_t)c.B * c.Hkv * (c.T_max / c.R) >= (1ll << 31)) return MIXKVQ_EINVAL;   // record indices are 32-bit
+  if ((int64_t)c.B * c.Hkv * (c.T_max / Rr) >= (1ll << 31)) return MIXKVQ_EINVAL;   // record indices are 32-bit
   if (c.policy < 0 || c.policy > 1) return MIXKVQ_EINVAL;
   if (c.policy == 1 && !(c.tau16 >= 0.0 && c.tau4 >= 0.0)) return MIXKVQ_EINVAL;   // also rejects NaN
   if (c.sink < 0 || c.sink > 128 || c.sink % 32 != 0) return MIXKVQ_EINVAL;
@@ -45,7 +49,7 @@ int compute_layout(const mixkvq_config& c, Layout* out) {
   l.NL = c.policy == 1 ? c.D : c.D - ks;
   l.Wlo = (l.NL + 15) / 16;
   l.NLp = 16 * l.Wlo;
-  l.NG = c.R / c.Gk;
+  l.NG = Rr / c.Gk;
   l.NVG = c.D / c.Gv;
   l.W4 = c.k4 / 8;
   int off = 0;
@@ -56,14 +60,14 @@ int compute_layout(const mixkvq_config& c, Layout* out) {
   plane(&l.off_klo_z, l.NG * l.NLp * 2);
   plane(&l.off_k4_s, l.NG * c.k4 * 2);
   plane(&l.off_k4_z, l.NG * c.k4 * 2);
-  plane(&l.off_klo, c.R * l.Wlo * 4);
-  plane(&l.off_k4, c.R * l.W4 * 4);
-  plane(&l.off_k16, c.R * c.k16 * 2);
-  plane(&l.off_v, (c.R / 16) * c.D * 4);
-  plane(&l.off_v_s, c.R * l.NVG * 2);
-  plane(&l.off_v_z, c.R * l.NVG * 2);
+  plane(&l.off_klo, Rr * l.Wlo * 4);
+  plane(&l.off_k4, Rr * l.W4 * 4);
+  plane(&l.off_k16, Rr * c.k16 * 2);
+  plane(&l.off_v, (Rr / 16) * c.D * 4);
+  plane(&l.off_v_s, Rr * l.NVG * 2);
+  plane(&l.off_v_z, Rr * l.NVG * 2);
   l.rec_bytes = off;
-  l.v_interleave = (c.Gk == 32 && c.R % 64 == 0) ? 1 : 0;
+  l.v_interleave = (c.Gk == 32 && Rr % 64 == 0) ? 1 : 0;
   if (l.rec_bytes > kMaxRec) return MIXKVQ_EINVAL;
   *out = l;
   return MIXKVQ_OK;
@@ -90,7 +94,8 @@ struct SeqState {
 };
 
 struct mixkvq_cache {
-  CacheView v;
+  CacheView v;       // v.cfg.R is the number of tokens per RECORD (what the kernels work on): min(R, 128)
+  int32_t Rw;        // the residual length R of the configuration: window size and flush unit, Rw / v.cfg.R records per block
   SeqState* seq;     // [B]: every sequence has its own counts (they are equal while the batch runs in lock-step)
   hipEvent_t ev_start = nullptr, ev_stop = nullptr;   // optional timing of the split kernel
 };
@@ -114,8 +119,8 @@ static CacheView sub_view(const mixkvq_cache* c, int b0, int nb) {
 
 // What an append of n_new tokens does to a sequence in state st: tokens for the sink, blocks flushed, what remains.
 struct AppendPlan { int take; int64_t F; int n_rest; int n_win; };
-static AppendPlan plan_append(const mixkvq_config& cfg, const SeqState& st, int n_new) {
-  const int R = cfg.R, S = cfg.sink;
+static AppendPlan plan_append(const mixkvq_config& cfg, int R, const SeqState& st, int n_new) {
+  const int S = cfg.sink;
   AppendPlan pl;
   // the first S tokens of the sequence go to the sink; the others take the window / flush path
   pl.take = st.n_sink < S ? (n_new < S - st.n_sink ? n_new : S - st.n_sink) : 0;
@@ -133,9 +138,9 @@ static AppendPlan plan_append(const mixkvq_config& cfg, const SeqState& st, int 
 static int append_range(mixkvq_cache* c, int b0, int nb, const __half* k_new, const __half* v_new, int n_new,
                         Strides3 kvs, const uint8_t* sel, hipStream_t s) {
   const mixkvq_config& cfg = c->v.cfg;
-  const int R = cfg.R, S = cfg.sink;
+  const int R = c->Rw, Rr = cfg.R, per = R / Rr, S = cfg.sink;      // a block of R tokens = `per` records of Rr
   const SeqState st = c->seq[b0];
-  const AppendPlan pl = plan_append(cfg, st, n_new);
+  const AppendPlan pl = plan_append(cfg, R, st, n_new);
   const CacheView v = sub_view(c, b0, nb);
   SeqState nx = st;
   if (pl.take > 0) {
@@ -148,7 +153,26 @@ static int append_range(mixkvq_cache* c, int b0, int nb, const __half* k_new, co
     const __half* kw = k_new + (int64_t)pl.take * kvs.t;
     const __half* vw = v_new + (int64_t)pl.take * kvs.t;
     const int r0 = st.n_res;
-    if (pl.F > 0) MIXKVQ_TRY_HIP(launch_flush(v, kw, vw, kvs, r0, (int)(st.n_quant / R), (int)pl.F, sel, s));
+    const int first_rec = (int)(st.n_quant / Rr);
+    if (pl.F > 0 && (sel || per == 1)) {
+      // one selection for the call, or blocks of one record each (the pack kernel scores those itself)
+      MIXKVQ_TRY_HIP(launch_flush(v, kw, vw, kvs, r0, first_rec, (int)pl.F * per, sel, s));
+    } else if (pl.F > 0) {
+      // blocks of several records without a given selection: every block is scored over all its R tokens first
+      // (they may lie partly in the window, partly in the new tokens), then its records are packed with that choice
+      uint8_t* sel_blk = select_scratch(v);
+      const Strides3 ws{(int64_t)cfg.Hkv * v.RW * kD, (int64_t)v.RW * kD, (int64_t)kD};
+      for (int64_t u = 0; u < pl.F; ++u) {
+        const int64_t p0 = u * R, p1 = p0 + R;                  // stream positions of (window ++ new tokens)
+        const int nA = p0 < r0 ? (int)((p1 < r0 ? p1 : r0) - p0) : 0;      // tokens taken from the window
+        const __half* kA = v.res_k + (size_t)(S + p0) * kD;
+        const __half* kB = kw + (p0 + nA - r0) * kvs.t;
+        MIXKVQ_TRY_HIP(launch_select2(v, kA, nA, ws, kB, R - nA, kvs, sel_blk, s));
+        // (stream origin shifted so that record 0 of this launch is record u * per of the call; r0 - u R <= 0 for u >= 1)
+        MIXKVQ_TRY_HIP(launch_flush(v, kw + (u ? (u * R - r0) * kvs.t : 0), vw + (u ? (u * R - r0) * kvs.t : 0), kvs,
+                                    u ? 0 : r0, first_rec + (int)u * per, per, sel_blk, s));
+      }
+    }
     // Tokens that stay in the window.  Stream position x of (old residual ++ new tokens) maps to
     // new-token index x - r0; after F flushes positions [F*R, total) remain.
     const int64_t rest_first = pl.F * R;
@@ -216,7 +240,7 @@ int mixkvq_cache_sizes(const mixkvq_config* cfg, mixkvq_sizes* out) {
   int rc = compute_layout(*cfg, &l);
   if (rc != MIXKVQ_OK) return rc;
   const uint64_t P = (uint64_t)cfg->B * cfg->Hkv;
-  out->blocks = al256(P * (uint64_t)(cfg->T_max / cfg->R) * (uint64_t)l.rec_bytes);
+  out->blocks = al256(P * (uint64_t)(cfg->T_max / rec_tokens(*cfg)) * (uint64_t)l.rec_bytes);
   out->res_k = al256(P * (uint64_t)(cfg->R + cfg->sink) * cfg->D * 2);
   out->res_v = out->res_k;
   out->qacc = al256(P * (uint64_t)(cfg->D + 1) * 8);
@@ -241,10 +265,12 @@ int mixkvq_cache_create(const mixkvq_config* cfg, const mixkvq_buffers* bufs, mi
     return MIXKVQ_ENOMEM;
   }
   c->v.cfg = *cfg;
+  c->v.cfg.R = rec_tokens(*cfg);      // what the kernels call R: the tokens of one record
+  c->Rw = cfg->R;
   c->v.lay = l;
   c->v.P = cfg->B * cfg->Hkv;
   c->v.g = cfg->Hq / cfg->Hkv;
-  c->v.NB = cfg->T_max / cfg->R;
+  c->v.NB = cfg->T_max / c->v.cfg.R;
   c->v.S = cfg->sink;
   c->v.RW = cfg->sink + cfg->R;
   c->v.blocks = (uint8_t*)bufs->blocks;
@@ -344,8 +370,8 @@ int mixkvq_quantize_append(mixkvq_cache* c, const void* k_new, const void* v_new
   if (rc != MIXKVQ_OK) return rc;
   const mixkvq_config& cfg = c->v.cfg;
   for (int b = 0; b < cfg.B; ++b) {     // nothing is touched unless every sequence has room
-    const AppendPlan pl = plan_append(cfg, c->seq[b], n_new);
-    if (c->seq[b].n_quant + pl.F * cfg.R > cfg.T_max) return MIXKVQ_ECAPACITY;
+    const AppendPlan pl = plan_append(cfg, c->Rw, c->seq[b], n_new);
+    if (c->seq[b].n_quant + pl.F * c->Rw > cfg.T_max) return MIXKVQ_ECAPACITY;
     if (pl.F > (1 << 24)) return MIXKVQ_EINVAL;
   }
   Strides3 kvs{kv_strides[0], kv_strides[1], kv_strides[2]};
@@ -369,8 +395,8 @@ int mixkvq_quantize_append_seq(mixkvq_cache* c, int32_t b, const void* k_new, co
   int rc = check_kv_args(k_new, v_new, kv_strides, 2);
   if (rc != MIXKVQ_OK) return rc;
   const mixkvq_config& cfg = c->v.cfg;
-  const AppendPlan pl = plan_append(cfg, c->seq[b], n_new);
-  if (c->seq[b].n_quant + pl.F * cfg.R > cfg.T_max) return MIXKVQ_ECAPACITY;
+  const AppendPlan pl = plan_append(cfg, c->Rw, c->seq[b], n_new);
+  if (c->seq[b].n_quant + pl.F * c->Rw > cfg.T_max) return MIXKVQ_ECAPACITY;
   if (pl.F > (1 << 24)) return MIXKVQ_EINVAL;
   Strides3 kvs{0, kv_strides[0], kv_strides[1]};
   return append_range(c, b, 1, (const __half*)k_new, (const __half*)v_new, n_new, kvs, sel, (hipStream_t)stream);
@@ -398,7 +424,7 @@ int mixkvq_decode_step(mixkvq_cache* c, const void* k_new, const void* v_new, co
   int rc = check_kv_args(k_new, v_new, kv_strides, 3);
   if (rc != MIXKVQ_OK) return rc;
   const mixkvq_config& cfg = c->v.cfg;
-  const int R = cfg.R;
+  const int R = c->Rw;
   // some sequence flushes a block or still feeds its sink, or the sequences differ in length: take the general path
   bool general = !lock_step(c);
   for (int b = 0; b < cfg.B; ++b) {

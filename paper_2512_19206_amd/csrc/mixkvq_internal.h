@@ -10,7 +10,8 @@ namespace mixkvq {
 __device__ __forceinline__ unsigned short h2bits(__half h) { return __half_as_ushort(h); }
 
 constexpr int kD = 128;             // head dimension of the hot path
-constexpr int kMaxR = 128;          // largest residual window / flush unit
+constexpr int kMaxR = 128;          // most tokens in one block record
+constexpr int kMaxWindow = 256;     // the one residual length above kMaxR: its blocks are stored as two records
 constexpr int kMaxSplits = 64;      // split-K ceiling per (batch, KV head) pair
 constexpr int kSplitTargetWGs = 1024;   // sizes the workspace: split ceiling = kSplitTargetWGs / pairs
 constexpr int kDecodeTargetWGs = 512;   // workgroups the decode launch aims for
@@ -61,12 +62,18 @@ __device__ __forceinline__ size_t record_index(const CacheView& cv, int p, int b
 }
 
 int compute_layout(const mixkvq_config& c, Layout* out);   // MIXKVQ_OK or MIXKVQ_EINVAL
+int rec_tokens(const mixkvq_config& c);                    // tokens per block record: min(R, kMaxR)
 int max_splits_for(int P);                                 // split-K ceiling used to size the workspace
 
 // ---- kernel launchers (each returns a hipError_t from the launch) ----
 hipError_t launch_zero_qacc(const CacheView& v, hipStream_t s);
 hipError_t launch_qabs_accumulate(const CacheView& v, const __half* q, int Lq, Strides3 qs, hipStream_t s);
 hipError_t launch_select(const CacheView& v, const __half* k, int L, Strides3 ks, uint8_t* sel, hipStream_t s);
+// The same over two runs of tokens: LA rows of the residual windows (binary16, kA = first row of the view's first pair,
+// strides of the fp16-row buffers) followed by LB rows of the caller's tensor (kB, its strides and dtype).
+hipError_t launch_select2(const CacheView& v, const __half* kA, int LA, Strides3 sA, const __half* kB, int LB, Strides3 sB,
+                          uint8_t* sel, hipStream_t s);
+uint8_t* select_scratch(const CacheView& v);   // room for one selection [P][k16 + k4] behind the range arrays in the workspace
 hipError_t launch_flush(const CacheView& v, const __half* k_new, const __half* v_new, Strides3 kvs,
                         int r0, int first_block, int n_flush, const uint8_t* sel, hipStream_t s);
 // n tokens starting at new-token index src_first go to fp16 rows dst_row.. of every pair (row 0 = first sink row,

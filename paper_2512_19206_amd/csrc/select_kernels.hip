@@ -257,23 +257,40 @@ __global__ void __launch_bounds__(kD) select_topk_kernel(CacheView cv, const lon
   }
 }
 
-size_t select_workspace_bytes(const mixkvq_config& c) { return (size_t)c.B * c.Hkv * kD * 2 * sizeof(long long); }
+size_t select_workspace_bytes(const mixkvq_config& c) {
+  // minima and maxima per (pair, channel), then one selection per pair
+  return (size_t)c.B * c.Hkv * kD * 2 * sizeof(long long) + (size_t)c.B * c.Hkv * kD;
+}
 
-hipError_t launch_select(const CacheView& v, const __half* k, int L, Strides3 ks, uint8_t* sel, hipStream_t s) {
+uint8_t* select_scratch(const CacheView& v) { return v.ws + (size_t)v.P * kD * 2 * sizeof(long long); }
+
+// One run of tokens into the range arrays.
+static void launch_key_range(const CacheView& v, const __half* k, int L, Strides3 ks, bool bf16, long long* mn, long long* mx,
+                             hipStream_t s) {
+  const int rows = rows_per_workgroup(v.P, L);
+  dim3 grid(v.P, (L + rows - 1) / rows);
+  if (!rows_aligned16(k, ks))
+    key_range_unaligned_kernel<<<grid, dim3(kD), 0, s>>>(k, L, ks, v.cfg.Hkv, rows, bf16 ? 1 : 0, mn, mx);
+  else if (bf16)
+    key_range_kernel<true><<<grid, dim3(kStreamThreads), 0, s>>>(k, L, ks, v.cfg.Hkv, rows, mn, mx);
+  else
+    key_range_kernel<false><<<grid, dim3(kStreamThreads), 0, s>>>(k, L, ks, v.cfg.Hkv, rows, mn, mx);
+}
+
+hipError_t launch_select2(const CacheView& v, const __half* kA, int LA, Strides3 sA, const __half* kB, int LB, Strides3 sB,
+                          uint8_t* sel, hipStream_t s) {
   long long* mn = (long long*)v.ws;
   long long* mx = mn + (size_t)v.P * kD;
   const int n = v.P * kD;
   range_init_kernel<<<dim3((n + 255) / 256), dim3(256), 0, s>>>(mn, mx, n);
-  const int rows = rows_per_workgroup(v.P, L);
-  dim3 grid(v.P, (L + rows - 1) / rows);
-  if (!rows_aligned16(k, ks))
-    key_range_unaligned_kernel<<<grid, dim3(kD), 0, s>>>(k, L, ks, v.cfg.Hkv, rows, v.cfg.in_dtype, mn, mx);
-  else if (v.cfg.in_dtype)
-    key_range_kernel<true><<<grid, dim3(kStreamThreads), 0, s>>>(k, L, ks, v.cfg.Hkv, rows, mn, mx);
-  else
-    key_range_kernel<false><<<grid, dim3(kStreamThreads), 0, s>>>(k, L, ks, v.cfg.Hkv, rows, mn, mx);
+  if (LA > 0) launch_key_range(v, kA, LA, sA, false, mn, mx, s);       // window rows are binary16 already
+  if (LB > 0) launch_key_range(v, kB, LB, sB, v.cfg.in_dtype != 0, mn, mx, s);
   select_topk_kernel<<<dim3(v.P), dim3(kD), 0, s>>>(v, mn, mx, sel);
   return hipGetLastError();
+}
+
+hipError_t launch_select(const CacheView& v, const __half* k, int L, Strides3 ks, uint8_t* sel, hipStream_t s) {
+  return launch_select2(v, nullptr, 0, Strides3{0, 0, 0}, k, L, ks, sel, s);
 }
 
 }  // namespace mixkvq

@@ -24,7 +24,7 @@ def check_state(oc: O.OracleCache, gc: M.Cache, check_qacc=True):
     torch.cuda.synchronize()
     nq, r = gc.state()
     assert (nq, r) == (oc.n_quant, oc.n_res)
-    nb = nq // oc.cfg.R
+    nb = nq // O.rec_tokens(oc.cfg)      # records
     if nb:
         got = gc.block_records()[:, :nb].cpu().numpy()
         ref = oc.packed_blocks()

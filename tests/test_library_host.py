@@ -50,6 +50,7 @@ CONFIGS = [
     dict(B=2, Hq=14, Hkv=2, D=128, T_max=512, Gk=32, Gv=32, R=128, k4=16, k16=0),
     dict(B=2, Hq=14, Hkv=2, D=128, T_max=512, Gk=32, Gv=32, R=128, k4=16, k16=0, sink=32),
     dict(B=1, Hq=5, Hkv=1, D=128, T_max=64, Gk=32, Gv=32, R=32, k4=8, k16=4, policy=1, tau16=0.0, tau4=float("inf")),
+    dict(B=2, Hq=14, Hkv=2, D=128, T_max=1024, Gk=64, Gv=128, R=256, k4=16, k16=0, sink=32),
 ]
 
 
@@ -66,7 +67,7 @@ def test_buffer_sizes(M, kw):
     cfg = M.make_config(**kw)
     sz, lay = M.cache_sizes(cfg), M.block_layout(cfg)
     P = kw["B"] * kw["Hkv"]
-    assert sz.blocks >= P * (kw["T_max"] // kw["R"]) * lay.rec_bytes
+    assert sz.blocks >= P * (kw["T_max"] // min(kw["R"], 128)) * lay.rec_bytes
     assert sz.res_k >= P * (kw["R"] + kw.get("sink", 0)) * 128 * 2 and sz.res_v == sz.res_k
     assert sz.qacc >= P * 129 * 8
     assert sz.workspace >= P * 128 * 16
@@ -75,7 +76,7 @@ def test_buffer_sizes(M, kw):
 
 
 @pytest.mark.parametrize("bad", [
-    dict(D=64), dict(Hq=3, Hkv=2), dict(Hq=18, Hkv=2), dict(R=24), dict(R=256, T_max=256), dict(Gk=48),
+    dict(D=64), dict(Hq=3, Hkv=2), dict(Hq=18, Hkv=2), dict(R=24), dict(R=192, T_max=384), dict(R=256, T_max=256, Gk=256), dict(Gk=48),
     dict(Gv=24), dict(k4=4), dict(k16=2), dict(k4=64, k16=64), dict(T_max=100), dict(flush_mode=2),
     dict(score_mode=-1), dict(B=0), dict(policy=2), dict(policy=1, tau16=-0.5, tau4=1.0),
     dict(policy=1, tau16=1.0, tau4=float("nan")), dict(sink=16), dict(sink=160), dict(sink=-32),

@@ -40,7 +40,7 @@ def brute_force_from_bytes(cfg, recs, res_k, res_v, n_res, q16, scale):
             sel = [int(raw[lay.off_idx + i]) for i in range(cfg.ks)]
             hi16, hi4 = sel[:cfg.k16], sel[cfg.k16:]      # 255 marks an unused entry (threshold policy)
             lo = [d for d in range(cfg.D) if d not in sel]
-            for t in range(cfg.R):
+            for t in range(O.rec_tokens(cfg)):
                 grp = t // cfg.Gk
                 krow = [0.0] * cfg.D
                 for i, d in enumerate(lo):
@@ -131,6 +131,41 @@ def test_brute_force_over_packed_bytes_with_interleaved_value_words_and_threshol
                                               cache.n_res, q, 1.0 / math.sqrt(cfg.D))
     assert np.allclose(out, ref_out, rtol=1e-11, atol=1e-12)
     assert np.allclose(lse, ref_lse, rtol=1e-12, atol=1e-12)
+
+
+def test_residual_length_256_is_stored_as_two_records_per_block():
+    """R = 256 (the largest residual length of the ablation in Appendix E): a block is scored over its 256 tokens and
+    stored as two records of 128 tokens with the same channel list; the bytes decode to what the oracle attends
+    over, and the counts follow the closed form n_q = R (ceil(n / R) - 1)."""
+    rng = np.random.default_rng(77)
+    B, Hq, Hkv, D, T = 1, 2, 1, 32, 600
+    cfg = O.OracleConfig(B=B, Hq=Hq, Hkv=Hkv, D=D, T_max=1024, Gk=64, Gv=16, R=256, k4=8, k16=0)
+    assert O.rec_tokens(cfg) == 128
+    K = rng.standard_normal((B, Hkv, T, D)).astype(np.float16)
+    V = rng.standard_normal((B, Hkv, T, D)).astype(np.float16)
+    # a channel that is wide only in the SECOND half of the first block: the block's one selection must see it
+    K[0, 0, 128:256, 5] *= np.float16(40.0)
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    cache = O.OracleCache(cfg)
+    cache.accumulate_queries(np.abs(rng.standard_normal((B, Hq, 8, D))).astype(np.float16) + np.float16(1.0))
+    cache.append(K, V)                                    # every block scored on its own 256 tokens
+    assert (cache.n_quant, cache.n_res) == (512, 88)
+    recs = cache.packed_blocks()
+    lay = O.block_layout(cfg)
+    assert recs.shape == (1, 4, lay.rec_bytes) and lay.NG == 2
+    idx = recs[0, :, lay.off_idx:lay.off_idx + cfg.ks]
+    assert np.array_equal(idx[0], idx[1]) and np.array_equal(idx[2], idx[3]) and 5 in idx[0]
+    assert not np.array_equal(recs[0, 0], recs[0, 1])
+    out, lse = cache.decode_attention(q)
+    ref_out, ref_lse = brute_force_from_bytes(cfg, recs, cache.res_k, cache.res_v, cache.n_res, q, 1.0 / math.sqrt(D))
+    assert np.allclose(out, ref_out, rtol=1e-11, atol=1e-12)
+    assert np.allclose(lse, ref_lse, rtol=1e-12, atol=1e-12)
+    # one token at a time gives the same bytes
+    step = O.OracleCache(cfg)
+    step.qacc[:], step.qcnt[:] = cache.qacc, cache.qcnt
+    for t in range(T):
+        step.append(K[:, :, t:t + 1], V[:, :, t:t + 1])
+    assert np.array_equal(step.packed_blocks(), recs)
 
 
 def _exact_attention(K, V, q, g, scale):

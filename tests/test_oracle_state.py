@@ -183,7 +183,7 @@ def test_value_words_hold_every_token_once(Gk, R, interleave):
     K = rng.standard_normal((R, 128)).astype(np.float16)
     V = rng.standard_normal((R, 128)).astype(np.float16)
     blk = O.quantize_block(cfg, K, V, np.arange(8, dtype=np.uint8))
-    rec = O.pack_block(cfg, blk)
+    rec = O.pack_record(cfg, blk)
     words = rec[lay.off_v:lay.off_v_s].view(np.uint32).reshape(R // 16, 128)
     seen = np.zeros(R, dtype=int)
     for tg in range(R // 16):

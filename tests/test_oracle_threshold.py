@@ -141,10 +141,10 @@ def test_block_with_thresholds_off_equals_plain_two_bit_block():
     b0 = O.quantize_block(cfg_0, K, V, np.zeros(0, dtype=np.uint8))
     assert np.array_equal(bt.lo_codes, b0.lo_codes) and np.array_equal(bt.lo_s, b0.lo_s)
     assert np.array_equal(O.dequant_block_keys(cfg_t, bt), O.dequant_block_keys(cfg_0, b0))
-    rec, lay = O.pack_block(cfg_t, bt), O.block_layout(cfg_t)
+    rec, lay = O.pack_record(cfg_t, bt), O.block_layout(cfg_t)
     assert lay.NL == 128 and np.all(rec[lay.off_idx:lay.off_idx + 24] == O.NO_CHANNEL)
     assert not rec[lay.off_k4_s:lay.off_klo].any() and not rec[lay.off_k4:lay.off_v].any()
-    rec0, lay0 = O.pack_block(cfg_0, b0), O.block_layout(cfg_0)
+    rec0, lay0 = O.pack_record(cfg_0, b0), O.block_layout(cfg_0)
     assert np.array_equal(rec[lay.off_klo:lay.off_k4], rec0[lay0.off_klo:lay0.off_k4])
 
 
@@ -169,7 +169,7 @@ def test_partly_filled_tiers_dequantize_within_their_error_bounds():
     rng2 = K64[:, lo].max(0) - K64[:, lo].min(0)
     assert np.all(np.abs(Kh - K64)[:, lo] <= rng2 / 3 / 2 * 1.002 + 1e-4)
     assert np.abs(Kh - K64)[:, [0, 5, 64, 100, 127]].max() < np.abs(Kh - K64)[:, lo].max()
-    rec, lay = O.pack_block(cfg, blk), O.block_layout(cfg)
+    rec, lay = O.pack_record(cfg, blk), O.block_layout(cfg)
     k4s = rec[lay.off_k4_s:lay.off_k4_z].view(np.float16).reshape(1, 16)
     assert not k4s[:, 5:].any()
     k16p = rec[lay.off_k16:lay.off_v].view(np.float16).reshape(32, 8)
