@@ -256,6 +256,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--group-size", type=int, default=0,
                     help="override the key and value group size of the configuration (32: the paper's accuracy setting)")
+    ap.add_argument("--residual-length", type=int, default=0,
+                    help="override the residual length R of the configuration (32 .. 128, or 256); key groups larger "
+                         "than a record are cut to it")
     ap.add_argument("--per-block-selection", action="store_true",
                     help="fill the cache with every block scored on its own tokens (as blocks flushed during decoding "
                          "are) instead of one selection for the whole prompt")
@@ -286,6 +289,11 @@ def main():
     if args.group_size:
         import dataclasses
         w = dataclasses.replace(w, name=w.name + "_g%d" % args.group_size, Gk=args.group_size, Gv=args.group_size)
+        args.no_cpu_baseline = True
+    if args.residual_length:
+        import dataclasses
+        R = args.residual_length
+        w = dataclasses.replace(w, name=w.name + "_r%d" % R, R=R, Gk=min(w.Gk, R, 128))
         args.no_cpu_baseline = True
     if args.thresholds:
         import dataclasses

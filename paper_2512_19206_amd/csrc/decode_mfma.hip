@@ -255,7 +255,7 @@ decode_merge_pair_kernel(CacheView cv, const float* __restrict__ part, int n_par
   }
 }
 
-template <int K4, int K16, int NVG, int NKL, int RG, int THR, int G32, int PG>
+template <int K4, int K16, int NVG, int NKL, int RG, int THR, int G32, int PG, int RH>
 __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __restrict__ q, float scale_log2e,
                                           int n_blocks, int n_res, int n_splits, float* __restrict__ part,
                                           int accumulate_q, const NewToken& nt, const SeqCounts& sc, unsigned char* smem) {
@@ -267,7 +267,11 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   // that group's scales), so tiles 0, 1 take the first 32 tokens of a 64-token span and tiles 2, 3 the second 32,
   // each lane group owning 8 tokens of either half; the value words of such a cache are interleaved to match
   // (codes 0..7 from the first half, 8..15 from the second: see the record layout).
+  // RH = 1: records of 32 tokens (R = Gk = 32): a record is HALF a 64-token span.  The lanes of token groups 2 and 3
+  // (kg >= 2) then have no tokens: their logits are -inf, and they load the value words and value scales of token
+  // group 0 instead (finite numbers that meet weights of exactly zero).
   static_assert(!(G32 && RG), "RG fixes Gk = 128");
+  static_assert(!(RH && (G32 || RG)), "RH is the plain tile order on a record of 32 tokens");
   const int R = RG ? 128 : cv.cfg.R, Gk = RG ? 128 : (G32 ? 32 : cv.cfg.Gk);
   const int g = cv.g, Hq = cv.cfg.Hq, Hkv = cv.cfg.Hkv, NB = cv.NB;
   const int rec_bytes = cv.lay.rec_bytes, off_idx = cv.lay.off_idx, off_klo_s = cv.lay.off_klo_s,
@@ -320,6 +324,8 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   // ---- per-lane constants -------------------------------------------------
   // token of A-row n in tile (h, x): 64h + tokbase + {0,1,8,9}[x]  (G32: 8 (n/4) + 2 (n%4) + {0,1,32,33}[x])
   const int tokbase = (G32 ? 8 : 16) * (n >> 2) + 2 * (n & 3);
+  const bool no_tokens = RH && kg >= 2;     // this lane's token group lies past the end of a 32-token record
+  const int kgv = no_tokens ? 0 : kg;       // the token group whose value words and scales it reads
   const int rec_chunks = rec_bytes >> 4;
   const int nvm = (rec_bytes - off_v_s) >> 4;     // 16-byte chunks of the value scale/zero planes
   // LDS byte offsets of this lane's words in token `tokbase` (clamped to existing words)
@@ -417,7 +423,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
     const unsigned char* rec_ = MIXKVQ_REC(REC);                                                             \
     const unsigned* vw_ = reinterpret_cast<const unsigned*>(rec_ + off_v);                                  \
     _Pragma("unroll") for (int h = 0; h < 2; ++h) _Pragma("unroll") for (int x = 0; x < 2; ++x)             \
-        MIXKVQ_LOAD_VWORDS(vreg[h][x], vw_ + (4 * (h * 64 < R ? h : 0) + kg) * kD, x)                       \
+        MIXKVQ_LOAD_VWORDS(vreg[h][x], vw_ + (4 * (h * 64 < R ? h : 0) + kgv) * kD, x)                      \
   }
 
   // The value words of one half (64 tokens) of a record: asked for as soon as the previous record's matrix
@@ -427,7 +433,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
     const unsigned char* rec_ = MIXKVQ_REC(REC);                                                             \
     const unsigned* vw_ = reinterpret_cast<const unsigned*>(rec_ + off_v);                                  \
     _Pragma("unroll") for (int x = 0; x < 2; ++x)                                                           \
-        MIXKVQ_LOAD_VWORDS(vreg[H][x], vw_ + (4 * (H) + kg) * kD, x)                                        \
+        MIXKVQ_LOAD_VWORDS(vreg[H][x], vw_ + (4 * (H) + kgv) * kD, x)                                       \
   }
 
   // q in slot order from the selection words SELW (wave-uniform): a table [head][slot] in LDS, slots 0..127 for the
@@ -898,6 +904,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
             xa[i] = fmaf(sa, Cx, zcx);
             xb[i] = fmaf(sb, Cx, zcx);
           }
+          if (RH && no_tokens) xa[i] = xb[i] = -INFINITY;
           mx = fmaxf(mx, fmaxf(xa[i], xb[i]));
         }
         mx = xkg_max(mx);
@@ -930,7 +937,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         u32x4 Bp[NVG == 4 ? 2 : NVG][2];   // NVG = 4: the two value groups of one xp at a time
         {
           // the 8 tokens this lane half pairs: 16 kg + 8 role .. (G32: 32 role + 8 kg ..), pair i = tokens 2i, 2i + 1
-          const int tv = 64 * hsg + (G32 ? 32 * role + 8 * kg : 16 * kg + 8 * role);
+          const int tv = 64 * hsg + (G32 ? 32 * role + 8 * kg : 16 * kgv + 8 * role);
           if (NVG == 1) {
             const uint4 sv = *reinterpret_cast<const uint4*>(sVm + 2 * tv);
             const uint4 zv = *reinterpret_cast<const uint4*>(sVm + 2 * R + 2 * tv);
@@ -966,7 +973,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         // element i of s4 / z4 holds tokens 2i and 2i + 1 of this lane half
         uint4 s4[NVG == 4 ? 4 : 1], z4[NVG == 4 ? 4 : 1];
         if (NVG == 4) {
-          const int tv = 64 * hsg + (G32 ? 32 * role + 8 * kg : 16 * kg + 8 * role);
+          const int tv = 64 * hsg + (G32 ? 32 * role + 8 * kg : 16 * kgv + 8 * role);
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             s4[i] = reinterpret_cast<const uint4*>(sVm + 8 * tv)[i];
@@ -1091,20 +1098,20 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 
 // One launch per decode step: the workgroups (pair, split) share the pair's block records and its
 // residual window.
-template <int K4, int K16, int NVG, int NKL, int RG, int THR, int G32, int PG>
+template <int K4, int K16, int NVG, int NKL, int RG, int THR, int G32, int PG, int RH>
 __global__ void __launch_bounds__(kMfmaThreads, 2)
 decode_fused_kernel(CacheView cv, const __half* __restrict__ q, float scale, int n_blocks, int n_res, int n_splits,
                     float* __restrict__ part, int accumulate_q, NewToken nt, SeqCounts sc) {
   extern __shared__ __align__(16) unsigned char smem[];
-  mfma_part<K4, K16, NVG, NKL, RG, THR, G32, PG>(cv, q, scale * 1.4426950408889634f, n_blocks, n_res, n_splits, part,
+  mfma_part<K4, K16, NVG, NKL, RG, THR, G32, PG, RH>(cv, q, scale * 1.4426950408889634f, n_blocks, n_res, n_splits, part,
                                              accumulate_q, nt, sc, smem);
 }
 
-template <int K4, int K16, int NVG, int NKL, int RG, int THR, int G32, int PG>
+template <int K4, int K16, int NVG, int NKL, int RG, int THR, int G32, int PG, int RH>
 static hipError_t launch_one(const CacheView& v, const __half* q, float scale, int n_blocks, int n_res, int n_splits,
                              float* part, __half* out, float* lse, int accumulate_q, NewToken nt, const SeqCounts& sc,
                              hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
-  auto kern = decode_fused_kernel<K4, K16, NVG, NKL, RG, THR, G32, PG>;
+  auto kern = decode_fused_kernel<K4, K16, NVG, NKL, RG, THR, G32, PG, RH>;
   const size_t lds = kHdrLds + (size_t)kWaves * kWaveLds;
   // the kernel's LDS limit is raised once per device (a repeated call from another thread does no harm)
   static std::atomic<uint64_t> attr_set{0};
@@ -1133,55 +1140,63 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
                             hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop, hipError_t* err) {
   const mixkvq_config& c = v.cfg;
   // key groups of 32 tokens take the G32 variants, multiples of 64 the others; value groups of 32, 64 or 128 channels
-  if (c.R % 64 != 0 || (c.Gk % 64 != 0 && c.Gk != 32) || (c.Gv % 64 != 0 && c.Gv != 32) || n_blocks < 1) return false;
+  // records of 32 tokens (one key group each) take the RH variants
+  const int rh = c.R == 32 && c.Gk == 32;
+  if ((c.R % 64 != 0 && !rh) || (c.Gk % 64 != 0 && c.Gk != 32) || (c.Gv % 64 != 0 && c.Gv != 32) || n_blocks < 1) return false;
   if (v.lay.off_v > kKPartMax || v.lay.rec_bytes - v.lay.off_v_s > kVMetaMax) return false;
   const int nvg = v.lay.NVG;
   const int nkl = (v.lay.off_v / 16 + 63) / 64;
-  const int g32 = c.Gk == 32;
+  const int g32 = c.Gk == 32 && !rh;
   const int paged = v.table != nullptr;
   hipError_t e = hipErrorInvalidValue;
   bool ok = true;
-#define MIXKVQ_CASE(K4_, K16_, NVG_, NKL_, RG_, THR_, G32_, PG_)                                                    \
+#define MIXKVQ_CASE(K4_, K16_, NVG_, NKL_, RG_, THR_, G32_, PG_, RH_)                                               \
   if (c.k4 == K4_ && c.k16 == K16_ && nvg == NVG_ && nkl <= NKL_ && c.policy == THR_ && g32 == G32_ && paged == PG_ && \
-      (RG_ == 0 || (c.R == 128 && c.Gk == 128)))                                                                    \
-    e = launch_one<K4_, K16_, NVG_, NKL_, RG_, THR_, G32_, PG_>(v, q, scale, n_blocks, n_res, n_splits, part, out, lse,  \
+      rh == RH_ && (RG_ == 0 || (c.R == 128 && c.Gk == 128)))                                                       \
+    e = launch_one<K4_, K16_, NVG_, NKL_, RG_, THR_, G32_, PG_, RH_>(v, q, scale, n_blocks, n_res, n_splits, part, out, lse,  \
                                                            accumulate_q, nt, sc, s, ev_start, ev_stop);             \
   else
-  MIXKVQ_CASE(16, 0, 1, 6, 1, 0, 0, 0)
-  MIXKVQ_CASE(0, 12, 1, 8, 1, 0, 0, 0)
-  MIXKVQ_CASE(8, 0, 1, 6, 1, 0, 0, 0)
-  MIXKVQ_CASE(16, 0, 1, 6, 0, 0, 0, 0)
-  MIXKVQ_CASE(0, 12, 1, 8, 0, 0, 0, 0)
-  MIXKVQ_CASE(0, 0, 1, 6, 0, 0, 0, 0)
-  MIXKVQ_CASE(8, 0, 1, 6, 0, 0, 0, 0)
-  MIXKVQ_CASE(24, 0, 1, 6, 0, 0, 0, 0)
-  MIXKVQ_CASE(32, 0, 1, 6, 0, 0, 0, 0)
-  MIXKVQ_CASE(16, 0, 2, 6, 0, 0, 0, 0)
-  MIXKVQ_CASE(0, 12, 2, 8, 0, 0, 0, 0)
-  MIXKVQ_CASE(8, 4, 1, 8, 0, 0, 0, 0)
-  MIXKVQ_CASE(0, 32, 1, 8, 0, 0, 0, 0)
+  MIXKVQ_CASE(16, 0, 1, 6, 1, 0, 0, 0, 0)
+  MIXKVQ_CASE(0, 12, 1, 8, 1, 0, 0, 0, 0)
+  MIXKVQ_CASE(8, 0, 1, 6, 1, 0, 0, 0, 0)
+  MIXKVQ_CASE(16, 0, 1, 6, 0, 0, 0, 0, 0)
+  MIXKVQ_CASE(0, 12, 1, 8, 0, 0, 0, 0, 0)
+  MIXKVQ_CASE(0, 0, 1, 6, 0, 0, 0, 0, 0)
+  MIXKVQ_CASE(8, 0, 1, 6, 0, 0, 0, 0, 0)
+  MIXKVQ_CASE(24, 0, 1, 6, 0, 0, 0, 0, 0)
+  MIXKVQ_CASE(32, 0, 1, 6, 0, 0, 0, 0, 0)
+  MIXKVQ_CASE(16, 0, 2, 6, 0, 0, 0, 0, 0)
+  MIXKVQ_CASE(0, 12, 2, 8, 0, 0, 0, 0, 0)
+  MIXKVQ_CASE(8, 4, 1, 8, 0, 0, 0, 0, 0)
+  MIXKVQ_CASE(0, 32, 1, 8, 0, 0, 0, 0, 0)
   // threshold policy: the capacities of the two side tiers
-  MIXKVQ_CASE(16, 8, 1, 8, 0, 1, 0, 0)
-  MIXKVQ_CASE(16, 0, 1, 6, 0, 1, 0, 0)
-  MIXKVQ_CASE(0, 12, 1, 8, 0, 1, 0, 0)
-  MIXKVQ_CASE(8, 4, 1, 8, 0, 1, 0, 0)
+  MIXKVQ_CASE(16, 8, 1, 8, 0, 1, 0, 0, 0)
+  MIXKVQ_CASE(16, 0, 1, 6, 0, 1, 0, 0, 0)
+  MIXKVQ_CASE(0, 12, 1, 8, 0, 1, 0, 0, 0)
+  MIXKVQ_CASE(8, 4, 1, 8, 0, 1, 0, 0, 0)
   // key groups of 32 tokens
-  MIXKVQ_CASE(16, 0, 1, 7, 0, 0, 1, 0)
-  MIXKVQ_CASE(8, 0, 1, 7, 0, 0, 1, 0)
-  MIXKVQ_CASE(0, 0, 1, 7, 0, 0, 1, 0)
-  MIXKVQ_CASE(16, 0, 2, 7, 0, 0, 1, 0)
-  MIXKVQ_CASE(16, 0, 1, 8, 0, 1, 1, 0)
+  MIXKVQ_CASE(16, 0, 1, 7, 0, 0, 1, 0, 0)
+  MIXKVQ_CASE(8, 0, 1, 7, 0, 0, 1, 0, 0)
+  MIXKVQ_CASE(0, 0, 1, 7, 0, 0, 1, 0, 0)
+  MIXKVQ_CASE(16, 0, 2, 7, 0, 0, 1, 0, 0)
+  MIXKVQ_CASE(16, 0, 1, 8, 0, 1, 1, 0, 0)
   // value groups of 32 channels (with key groups of 32 tokens: the group size of the paper's experiments)
-  MIXKVQ_CASE(16, 0, 4, 7, 0, 0, 1, 0)
-  MIXKVQ_CASE(8, 0, 4, 7, 0, 0, 1, 0)
-  MIXKVQ_CASE(16, 0, 4, 8, 0, 1, 1, 0)
-  MIXKVQ_CASE(16, 0, 4, 6, 0, 0, 0, 0)
+  MIXKVQ_CASE(16, 0, 4, 7, 0, 0, 1, 0, 0)
+  MIXKVQ_CASE(8, 0, 4, 7, 0, 0, 1, 0, 0)
+  MIXKVQ_CASE(16, 0, 4, 8, 0, 1, 1, 0, 0)
+  MIXKVQ_CASE(16, 0, 4, 6, 0, 0, 0, 0, 0)
   // paged layout (block table): the main tiers
-  MIXKVQ_CASE(16, 0, 1, 6, 0, 0, 0, 1)
-  MIXKVQ_CASE(0, 12, 1, 8, 0, 0, 0, 1)
-  MIXKVQ_CASE(8, 0, 1, 6, 0, 0, 0, 1)
-  MIXKVQ_CASE(16, 8, 1, 8, 0, 1, 0, 1)
-  MIXKVQ_CASE(16, 0, 4, 7, 0, 0, 1, 1)
+  MIXKVQ_CASE(16, 0, 1, 6, 0, 0, 0, 1, 0)
+  MIXKVQ_CASE(0, 12, 1, 8, 0, 0, 0, 1, 0)
+  MIXKVQ_CASE(8, 0, 1, 6, 0, 0, 0, 1, 0)
+  MIXKVQ_CASE(16, 8, 1, 8, 0, 1, 0, 1, 0)
+  MIXKVQ_CASE(16, 0, 4, 7, 0, 0, 1, 1, 0)
+  // records of 32 tokens (the shorter residual length of the paper's throughput runs), value groups of 32 or 128 channels
+  MIXKVQ_CASE(16, 0, 4, 2, 0, 0, 0, 0, 1)
+  MIXKVQ_CASE(8, 0, 4, 2, 0, 0, 0, 0, 1)
+  MIXKVQ_CASE(0, 0, 4, 2, 0, 0, 0, 0, 1)
+  MIXKVQ_CASE(16, 0, 1, 2, 0, 0, 0, 0, 1)
+  MIXKVQ_CASE(8, 4, 4, 2, 0, 0, 0, 0, 1)
   ok = false;
 #undef MIXKVQ_CASE
   if (!ok) return false;

@@ -247,6 +247,42 @@ def test_key_groups_of_32_tokens(H, R, Gv, k4, k16, g, policy):
     assert oc.n_flush_calls >= 4
 
 
+@pytest.mark.parametrize("Gv,k4,k16,g,sink,n_blocks", [(32, 16, 0, 7, 0, 40), (32, 8, 0, 1, 32, 9), (128, 16, 0, 5, 0, 130),
+                                                       (32, 0, 0, 8, 0, 17), (32, 8, 4, 3, 64, 25)])
+def test_records_of_32_tokens(H, Gv, k4, k16, g, sink, n_blocks):
+    """The shorter residual length of the paper's throughput runs (R = 32, with G = 32): one key group and half a
+    64-token span per record, on the matrix-core kernel."""
+    rng = np.random.default_rng(3200 + Gv + k4 + g + n_blocks)
+    B, Hkv, R = 2, 2, 32
+    kw = dict(B=B, Hq=Hkv * g, Hkv=Hkv, D=128, T_max=R * (n_blocks + 4), Gk=32, Gv=Gv, R=R, k4=k4, k16=k16, sink=sink)
+    oc, gc = H.make_pair(**kw)
+    n0 = sink + R * n_blocks + 13
+    grp_mag = np.repeat(rng.uniform(0.2, 1.25, (n0 + 31) // 32), 32)[:n0, None]     # a magnitude of its own per record
+    K = (rng.standard_normal((B, Hkv, n0, 128)) * rng.uniform(0.3, 8, 128) * grp_mag).astype(np.float16)
+    V = (rng.standard_normal((B, Hkv, n0, 128)) * rng.uniform(0.5, 2, (n0, 1))).astype(np.float16)
+    Qp = (rng.standard_normal((B, Hkv * g, 16, 128)) * rng.uniform(0.2, 5, 128)).astype(np.float16)
+    if k4 + k16:
+        oc.accumulate_queries(Qp)
+        gc.select_channels(H.dev(Qp), H.dev(K))
+    oc.append(K, V)                       # every record with its own channel list
+    gc.quantize_append(H.dev(K), H.dev(V))
+    H.check_state(oc, gc)
+    q = (rng.standard_normal((B, Hkv * g, 128)) * rng.uniform(0.2, 5, 128)).astype(np.float16)
+    H.check_attention(oc, gc, q)
+    for step in range(R + 5):
+        k1 = (rng.standard_normal((B, Hkv, 1, 128)) * rng.uniform(0.3, 8, 128)).astype(np.float16)
+        v1 = rng.standard_normal((B, Hkv, 1, 128)).astype(np.float16)
+        q1 = (rng.standard_normal((B, Hkv * g, 128)) * rng.uniform(0.2, 5, 128)).astype(np.float16)
+        oc.append(k1, v1)
+        ro, rl = oc.decode_attention(q1, accumulate_q=True)
+        out, lse = gc.decode_step(H.dev(k1), H.dev(v1), H.dev(q1), accumulate_q=True)
+        torch.cuda.synchronize()
+        err = np.abs(out.float().cpu().numpy() - ro)
+        assert np.all(err <= H.ATOL + H.RTOL * np.abs(ro)), (step, float(err.max()))
+        assert np.all(np.abs(lse.cpu().numpy() - rl) <= H.LSE_ATOL + 1e-4 * np.abs(rl))
+    H.check_state(oc, gc)
+
+
 @pytest.mark.parametrize("R,Gk,sink,k4,g,flush_mode", [(128, 128, 32, 16, 7, 0), (64, 64, 128, 16, 5, 0), (128, 32, 64, 8, 8, 1),
                                                       (32, 32, 32, 8, 3, 0), (128, 128, 128, 0, 2, 0)])
 def test_sink_tokens(H, R, Gk, sink, k4, g, flush_mode):
