@@ -257,7 +257,7 @@ def main():
     ap.add_argument("--group-size", type=int, default=0,
                     help="override the key and value group size of the configuration (32: the paper's accuracy setting)")
     ap.add_argument("--residual-length", type=int, default=0,
-                    help="override the residual length R of the configuration (32 .. 128, or 256); key groups larger "
+                    help="override the residual length R of the configuration (32, 64, 96, 128 or 256); key groups larger "
                          "than a record are cut to it")
     ap.add_argument("--per-block-selection", action="store_true",
                     help="fill the cache with every block scored on its own tokens (as blocks flushed during decoding "
@@ -293,7 +293,8 @@ def main():
     if args.residual_length:
         import dataclasses
         R = args.residual_length
-        w = dataclasses.replace(w, name=w.name + "_r%d" % R, R=R, Gk=min(w.Gk, R, 128))
+        # key groups must divide a record: 32 tokens for R = 32 and R = 96 (stored as three records of 32)
+        w = dataclasses.replace(w, name=w.name + "_r%d" % R, R=R, Gk=32 if R % 64 else min(w.Gk, R, 128))
         args.no_cpu_baseline = True
     if args.thresholds:
         import dataclasses

@@ -46,10 +46,11 @@ typedef struct {
   int32_t B, Hq, Hkv;   /* batch, query heads, KV heads; Hq % Hkv == 0, Hq/Hkv <= 8 */
   int32_t D;            /* head dimension; must be 128 */
   int32_t T_max;        /* capacity of the quantized part in tokens; multiple of R */
-  int32_t Gk;           /* key group: Gk consecutive tokens of one channel; min(R, 128) % Gk == 0, Gk % 16 == 0 */
+  int32_t Gk;           /* key group: Gk consecutive tokens of one channel; Rr % Gk == 0 (Rr below), Gk % 16 == 0 */
   int32_t Gv;           /* value group: Gv consecutive channels of one token; D % Gv == 0, Gv % 16 == 0 */
   int32_t R;            /* residual window length == flush unit; a multiple of 16 up to 128, or 256.  A block of R tokens
-                           is scored as a whole and stored as R / Rr records of Rr = min(R, 128) tokens with one channel list */
+                           is scored as a whole and stored as R / Rr records of Rr tokens with one channel list: Rr = R,
+                           except Rr = 128 for R = 256 and Rr = 32 for R = 96 with Gk = 16 or 32 */
   int32_t k4, k16;      /* salient key channels kept at 4 bit / as fp16; k4 % 8 == 0, k16 % 4 == 0, k4+k16 < D */
   int32_t flush_mode;   /* 0 deferred: the newest <= R tokens stay fp16; 1 eager: flush as soon as R are buffered */
   int32_t score_mode;   /* 0: A_d = I_d * S_d (Eq. 8); 1: A_d = S_d (error-only ablation) */
@@ -71,7 +72,7 @@ typedef struct {
 
 /* Bytes of each caller-owned device buffer. */
 typedef struct {
-  uint64_t blocks;     /* [B*Hkv][T_max/Rr] block records (Rr = min(R, 128) tokens each), see mixkvq_block_layout */
+  uint64_t blocks;     /* [B*Hkv][T_max/Rr] block records (Rr tokens each, see R above), see mixkvq_block_layout */
   uint64_t res_k;      /* [B*Hkv][sink + R][D] fp16 keys: per pair the sink rows, then the residual window */
   uint64_t res_v;      /* [B*Hkv][sink + R][D] fp16 values likewise */
   uint64_t qacc;       /* [B*Hkv][D] u64 sums of |q| in units of 2^-24, then [B*Hkv] u64 counts */
@@ -82,8 +83,8 @@ typedef struct {
   void *blocks, *res_k, *res_v, *qacc, *workspace; /* DEVICE, 256-byte aligned */
 } mixkvq_buffers;
 
-/* Byte offsets of the planes inside one block record (Rr = min(R, 128) tokens of one
- * (batch, KV head) pair; R below stands for Rr).  Every plane starts on a 16-byte boundary, padding is 0.
+/* Byte offsets of the planes inside one block record (Rr tokens of one (batch, KV head) pair, see mixkvq_config.R;
+ * R below stands for Rr).  Every plane starts on a 16-byte boundary, padding is 0.
  *   idx    u8  [k16+k4]      fp16-tier channels ascending, then 4-bit-tier channels ascending; under policy 1 each
  *                            tier is filled up to its capacity with MIXKVQ_NO_CHANNEL and the unused entries of
  *                            every plane of that tier are 0

@@ -276,10 +276,15 @@ MAX_REC_TOKENS = 128
 
 
 def rec_tokens(cfg: OracleConfig) -> int:
-    """Tokens one stored record holds.  A flushed block of R tokens is stored as R / rec_tokens records of
-    min(R, 128) tokens each, all with the block's channel selection (a storage choice: the quantization groups
-    never straddle a record because Gk divides 128 whenever R > 128)."""
-    return min(cfg.R, MAX_REC_TOKENS)
+    """Tokens one stored record holds.  A flushed block of R tokens is stored as R / rec_tokens records, all with
+    the block's channel selection: R = 256 as two records of 128 tokens, R = 96 with key groups that divide 32 as
+    three records of 32 tokens, every other R as one record.  (A storage choice: quantization groups never straddle
+    a record.)"""
+    if cfg.R > MAX_REC_TOKENS:
+        return MAX_REC_TOKENS
+    if cfg.R == 96 and 32 % cfg.Gk == 0:
+        return 32
+    return cfg.R
 
 
 def block_layout(cfg: OracleConfig) -> BlockLayout:

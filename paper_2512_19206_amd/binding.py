@@ -163,8 +163,14 @@ class Cache:
 
     @property
     def rec_tokens(self) -> int:
-        """Tokens per block record: min(R, 128); a block of R = 256 tokens is stored as two records."""
-        return min(self.cfg.R, 128)
+        """Tokens per block record: R, except 128 for R = 256 and 32 for R = 96 with Gk = 16 or 32 (a block is then
+        stored as two / three records with one channel list)."""
+        c = self.cfg
+        if c.R > 128:
+            return 128
+        if c.R == 96 and 32 % c.Gk == 0:
+            return 32
+        return c.R
 
     def sink_count(self) -> int:
         n = C.c_int32()

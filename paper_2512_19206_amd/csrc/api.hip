@@ -23,13 +23,19 @@ static int hip_fail(hipError_t e) {
 
 static inline int al16(int n) { return (n + 15) / 16 * 16; }
 
-int rec_tokens(const mixkvq_config& c) { return c.R > kMaxR ? kMaxR : c.R; }
+// Tokens per stored record.  A block of R tokens is one record, except: R = 256 is stored as two records of 128 tokens,
+// and R = 96 with key groups that divide 32 as three records of 32 (the sizes the matrix-core kernel takes).
+int rec_tokens(const mixkvq_config& c) {
+  if (c.R > kMaxR) return kMaxR;
+  if (c.R == 96 && c.Gk > 0 && 32 % c.Gk == 0) return 32;
+  return c.R;
+}
 
 int compute_layout(const mixkvq_config& c, Layout* out) {
   if (c.B < 1 || c.Hq < 1 || c.Hkv < 1 || c.Hq % c.Hkv != 0) return MIXKVQ_EINVAL;
   if (c.Hq / c.Hkv > 8) return MIXKVQ_EINVAL;
   if (c.D != kD) return MIXKVQ_EINVAL;
-  // residual length: a multiple of 16 up to 128, or 256 (stored as two records of 128 tokens per block)
+  // residual length: a multiple of 16 up to 128, or 256 (see rec_tokens)
   if (c.R < 16 || c.R % 16 != 0 || (c.R > kMaxR && c.R != kMaxWindow)) return MIXKVQ_EINVAL;
   const int Rr = rec_tokens(c);
   if (c.Gk < 16 || c.Gk % 16 != 0 || Rr % c.Gk != 0) return MIXKVQ_EINVAL;
@@ -94,7 +100,7 @@ struct SeqState {
 };
 
 struct mixkvq_cache {
-  CacheView v;       // v.cfg.R is the number of tokens per RECORD (what the kernels work on): min(R, 128)
+  CacheView v;       // v.cfg.R is the number of tokens per RECORD (what the kernels work on): rec_tokens()
   int32_t Rw;        // the residual length R of the configuration: window size and flush unit, Rw / v.cfg.R records per block
   SeqState* seq;     // [B]: every sequence has its own counts (they are equal while the batch runs in lock-step)
   hipEvent_t ev_start = nullptr, ev_stop = nullptr;   // optional timing of the split kernel

@@ -1,6 +1,7 @@
-"""GPU parity with the residual length R = 256 (the largest of the ablation in Appendix E): a block of 256 tokens is
-scored as a whole and stored as two records of 128 tokens.  Records, window and accumulator bit for bit against the
-oracle; attention within tolerance."""
+"""GPU parity for blocks that are stored as several records: the residual length R = 256 (the largest of the
+ablation in Appendix E; two records of 128 tokens) and R = 96 with G = 32 (three records of 32 tokens).  A block is
+scored as a whole; records, window and accumulator are compared bit for bit against the oracle, attention within
+tolerance."""
 import numpy as np
 import pytest
 import torch
@@ -23,16 +24,18 @@ def _kvq(rng, B, Hkv, g, n, ch):
     return K, V
 
 
-@pytest.mark.parametrize("Gk,Gv,k4,k16,g,sink,flush_mode", [(128, 128, 16, 0, 7, 0, 0), (64, 64, 16, 0, 5, 32, 0),
-                                                          (32, 32, 16, 0, 4, 0, 1), (128, 128, 0, 12, 8, 64, 0)])
-def test_prefill_then_decode_steps(H, Gk, Gv, k4, k16, g, sink, flush_mode):
-    rng = np.random.default_rng(2560 + Gk + k16 + sink)
+@pytest.mark.parametrize("R,Gk,Gv,k4,k16,g,sink,flush_mode", [(256, 128, 128, 16, 0, 7, 0, 0), (256, 64, 64, 16, 0, 5, 32, 0),
+                                                            (256, 32, 32, 16, 0, 4, 0, 1), (256, 128, 128, 0, 12, 8, 64, 0),
+                                                            (96, 32, 32, 16, 0, 7, 0, 0), (96, 32, 128, 16, 0, 5, 32, 1),
+                                                            (96, 16, 32, 8, 0, 2, 0, 0)])
+def test_prefill_then_decode_steps(H, R, Gk, Gv, k4, k16, g, sink, flush_mode):
+    rng = np.random.default_rng(2560 + R + Gk + k16 + sink)
     B, Hkv = 2, 2
-    kw = dict(B=B, Hq=Hkv * g, Hkv=Hkv, D=128, T_max=2048, Gk=Gk, Gv=Gv, R=256, k4=k4, k16=k16, sink=sink,
+    kw = dict(B=B, Hq=Hkv * g, Hkv=Hkv, D=128, T_max=8 * R, Gk=Gk, Gv=Gv, R=R, k4=k4, k16=k16, sink=sink,
               flush_mode=flush_mode)
     oc, gc = H.make_pair(**kw)
     ch = rng.uniform(0.3, 8, 128)
-    n0 = 3 * 256 + 77 + sink
+    n0 = 3 * R + 77 + sink
     K, V = _kvq(rng, B, Hkv, g, n0, ch)
     Qp = (rng.standard_normal((B, Hkv * g, 20, 128)) * rng.uniform(0.2, 5, 128)).astype(np.float16)
     sel_ref = oc.select_channels(Qp, K)
@@ -40,12 +43,12 @@ def test_prefill_then_decode_steps(H, Gk, Gv, k4, k16, g, sink, flush_mode):
     assert np.array_equal(sel.cpu().numpy(), sel_ref)
     oc.append(K, V, sel_ref)
     gc.quantize_append(H.dev(K), H.dev(V), sel=sel)
-    assert gc.rec_tokens == 128
+    assert gc.rec_tokens == (128 if R == 256 else 32) == O.rec_tokens(oc.cfg)
     H.check_state(oc, gc)
     q = (rng.standard_normal((B, Hkv * g, 128)) * rng.uniform(0.2, 5, 128)).astype(np.float16)
     H.check_attention(oc, gc, q)
-    # decode steps through the next flush: the block is scored over the 256 tokens of the window
-    for step in range(256 - oc.n_res + 40):
+    # decode steps through the next flush: the block is scored over the R tokens of the window
+    for step in range(R - oc.n_res + 40):
         k1, v1 = _kvq(rng, B, Hkv, g, 1, ch)
         q1 = (rng.standard_normal((B, Hkv * g, 128)) * rng.uniform(0.2, 5, 128)).astype(np.float16)
         oc.append(k1, v1)
@@ -55,16 +58,17 @@ def test_prefill_then_decode_steps(H, Gk, Gv, k4, k16, g, sink, flush_mode):
         err = np.abs(out.float().cpu().numpy() - ro)
         assert np.all(err <= H.ATOL + H.RTOL * np.abs(ro)), (step, float(err.max()))
         assert np.all(np.abs(lse.cpu().numpy() - rl) <= H.LSE_ATOL + 1e-4 * np.abs(rl))
-    assert oc.n_quant == 4 * 256
+    assert oc.n_quant == 4 * R
     H.check_state(oc, gc)
 
 
-def test_blocks_scored_one_by_one_across_window_and_new_tokens(H):
+@pytest.mark.parametrize("R,Gk,counts", [(256, 64, (1536, 21)), (96, 32, (1536, 21))])
+def test_blocks_scored_one_by_one_across_window_and_new_tokens(H, R, Gk, counts):
     """Appends without a given selection: the first block of the second call lies partly in the window, partly in
-    the new tokens, and each block takes its own channel list from its own 256 tokens."""
-    rng = np.random.default_rng(2561)
+    the new tokens, and each block takes its own channel list from its own R tokens."""
+    rng = np.random.default_rng(2561 + R)
     B, Hkv, g = 2, 2, 5
-    kw = dict(B=B, Hq=Hkv * g, Hkv=Hkv, D=128, T_max=2048, Gk=64, Gv=128, R=256, k4=16, k16=0)
+    kw = dict(B=B, Hq=Hkv * g, Hkv=Hkv, D=128, T_max=8 * R + 1536, Gk=Gk, Gv=128, R=R, k4=16, k16=0)
     oc, gc = H.make_pair(**kw)
     Qp = (rng.standard_normal((B, Hkv * g, 16, 128)) * rng.uniform(0.2, 5, 128)).astype(np.float16)
     Kd = rng.standard_normal((B, Hkv, 16, 128)).astype(np.float16)      # only to get the queries into the accumulator
@@ -76,7 +80,7 @@ def test_blocks_scored_one_by_one_across_window_and_new_tokens(H):
         oc.append(K, V)
         gc.quantize_append(H.dev(K), H.dev(V))
         H.check_state(oc, gc)
-    assert (oc.n_quant, oc.n_res) == (1536, 21)
+    assert oc.n_quant + oc.n_res == 1557 and oc.n_quant % R == 0 and 0 < oc.n_res <= R
     lists = {tuple(b.sel) for blocks in oc.blocks for b in blocks}
     assert len(lists) > 2                                   # the blocks really differ in their selection
     q = (rng.standard_normal((B, Hkv * g, 128)) * rng.uniform(0.2, 5, 128)).astype(np.float16)

@@ -51,6 +51,8 @@ CONFIGS = [
     dict(B=2, Hq=14, Hkv=2, D=128, T_max=512, Gk=32, Gv=32, R=128, k4=16, k16=0, sink=32),
     dict(B=1, Hq=5, Hkv=1, D=128, T_max=64, Gk=32, Gv=32, R=32, k4=8, k16=4, policy=1, tau16=0.0, tau4=float("inf")),
     dict(B=2, Hq=14, Hkv=2, D=128, T_max=1024, Gk=64, Gv=128, R=256, k4=16, k16=0, sink=32),
+    dict(B=2, Hq=14, Hkv=2, D=128, T_max=960, Gk=32, Gv=32, R=96, k4=16, k16=0),
+    dict(B=1, Hq=2, Hkv=1, D=128, T_max=192, Gk=48, Gv=64, R=96, k4=8, k16=0),
 ]
 
 
@@ -67,7 +69,7 @@ def test_buffer_sizes(M, kw):
     cfg = M.make_config(**kw)
     sz, lay = M.cache_sizes(cfg), M.block_layout(cfg)
     P = kw["B"] * kw["Hkv"]
-    assert sz.blocks >= P * (kw["T_max"] // min(kw["R"], 128)) * lay.rec_bytes
+    assert sz.blocks >= P * (kw["T_max"] // O.rec_tokens(O.OracleConfig(**kw))) * lay.rec_bytes
     assert sz.res_k >= P * (kw["R"] + kw.get("sink", 0)) * 128 * 2 and sz.res_v == sz.res_k
     assert sz.qacc >= P * 129 * 8
     assert sz.workspace >= P * 128 * 16

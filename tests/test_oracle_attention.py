@@ -1,5 +1,6 @@
 """Pins of the oracle's packed layout and of its attention (Section 3.1, Eq. 1,
 over keys/values dequantized by Eq. 3).  CPU only."""
+import dataclasses
 import math
 
 import numpy as np
@@ -166,6 +167,29 @@ def test_residual_length_256_is_stored_as_two_records_per_block():
     for t in range(T):
         step.append(K[:, :, t:t + 1], V[:, :, t:t + 1])
     assert np.array_equal(step.packed_blocks(), recs)
+
+
+def test_residual_length_96_with_groups_of_32_is_stored_as_three_records():
+    rng = np.random.default_rng(78)
+    B, Hq, Hkv, D, T = 1, 2, 1, 32, 250
+    cfg = O.OracleConfig(B=B, Hq=Hq, Hkv=Hkv, D=D, T_max=480, Gk=32, Gv=16, R=96, k4=8, k16=0)
+    assert O.rec_tokens(cfg) == 32 and O.rec_tokens(dataclasses.replace(cfg, Gk=96)) == 96
+    K = rng.standard_normal((B, Hkv, T, D)).astype(np.float16)
+    V = rng.standard_normal((B, Hkv, T, D)).astype(np.float16)
+    K[0, 0, 64:96, 7] *= np.float16(40.0)        # wide only in the LAST third of the first block
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    cache = O.OracleCache(cfg)
+    cache.accumulate_queries(np.abs(rng.standard_normal((B, Hq, 8, D))).astype(np.float16) + np.float16(1.0))
+    cache.append(K, V)
+    assert (cache.n_quant, cache.n_res) == (192, 58)
+    recs, lay = cache.packed_blocks(), O.block_layout(cfg)
+    assert recs.shape == (1, 6, lay.rec_bytes) and lay.NG == 1 and lay.v_interleave == 0
+    idx = recs[0, :, lay.off_idx:lay.off_idx + cfg.ks]
+    assert np.array_equal(idx[0], idx[1]) and np.array_equal(idx[0], idx[2]) and 7 in idx[0]
+    out, lse = cache.decode_attention(q)
+    ref_out, ref_lse = brute_force_from_bytes(cfg, recs, cache.res_k, cache.res_v, cache.n_res, q, 1.0 / math.sqrt(D))
+    assert np.allclose(out, ref_out, rtol=1e-11, atol=1e-12)
+    assert np.allclose(lse, ref_lse, rtol=1e-12, atol=1e-12)
 
 
 def _exact_attention(K, V, q, g, scale):
