@@ -1197,6 +1197,8 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
   MIXKVQ_CASE(0, 0, 4, 2, 0, 0, 0, 0, 1)
   MIXKVQ_CASE(16, 0, 1, 2, 0, 0, 0, 0, 1)
   MIXKVQ_CASE(8, 4, 4, 2, 0, 0, 0, 0, 1)
+  MIXKVQ_CASE(16, 8, 4, 3, 0, 1, 0, 0, 1)
+  MIXKVQ_CASE(16, 0, 4, 3, 0, 1, 0, 0, 1)
   ok = false;
 #undef MIXKVQ_CASE
   if (!ok) return false;

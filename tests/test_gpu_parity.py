@@ -247,14 +247,18 @@ def test_key_groups_of_32_tokens(H, R, Gv, k4, k16, g, policy):
     assert oc.n_flush_calls >= 4
 
 
-@pytest.mark.parametrize("Gv,k4,k16,g,sink,n_blocks", [(32, 16, 0, 7, 0, 40), (32, 8, 0, 1, 32, 9), (128, 16, 0, 5, 0, 130),
-                                                       (32, 0, 0, 8, 0, 17), (32, 8, 4, 3, 64, 25)])
-def test_records_of_32_tokens(H, Gv, k4, k16, g, sink, n_blocks):
+@pytest.mark.parametrize("Gv,k4,k16,g,sink,n_blocks,policy", [(32, 16, 0, 7, 0, 40, 0), (32, 8, 0, 1, 32, 9, 0),
+                                                              (128, 16, 0, 5, 0, 130, 0), (32, 0, 0, 8, 0, 17, 0),
+                                                              (32, 8, 4, 3, 64, 25, 0), (32, 16, 8, 7, 0, 30, 1),
+                                                              (32, 16, 0, 4, 32, 12, 1)])
+def test_records_of_32_tokens(H, Gv, k4, k16, g, sink, n_blocks, policy):
     """The shorter residual length of the paper's throughput runs (R = 32, with G = 32): one key group and half a
     64-token span per record, on the matrix-core kernel."""
     rng = np.random.default_rng(3200 + Gv + k4 + g + n_blocks)
     B, Hkv, R = 2, 2, 32
     kw = dict(B=B, Hq=Hkv * g, Hkv=Hkv, D=128, T_max=R * (n_blocks + 4), Gk=32, Gv=Gv, R=R, k4=k4, k16=k16, sink=sink)
+    if policy:
+        kw.update(policy=1, tau16=8.0 if k16 else np.inf, tau4=3.0)
     oc, gc = H.make_pair(**kw)
     n0 = sink + R * n_blocks + 13
     grp_mag = np.repeat(rng.uniform(0.2, 1.25, (n0 + 31) // 32), 32)[:n0, None]     # a magnitude of its own per record
