@@ -101,8 +101,8 @@ def _random_configs(n, seed):
             Gv = int(rng.choice([64, 128])) if (k4, k16) in ((16, 0), (0, 12)) else 128
         else:              # anything the layout allows
             k4, k16 = int(rng.choice([0, 8, 16, 40])), int(rng.choice([0, 4, 20]))
-            R = int(rng.choice([16, 32, 48, 80, 96, 112, 128]))
-            Gk = int(rng.choice([g for g in (16, 32, 48, 64, 80, 96, 112, 128) if R % g == 0]))
+            R = int(rng.choice([16, 32, 48, 80, 96, 112, 128, 256]))
+            Gk = int(rng.choice([g for g in (16, 32, 48, 64, 80, 96, 112, 128) if min(R, 128) % g == 0]))
             Gv = int(rng.choice([16, 32, 64, 128]))
         g = int(rng.integers(1, 9))
         out.append((g, k4, k16, Gk, Gv, R, int(rng.integers(1, 4)), int(rng.integers(0, R + 1)),
@@ -110,7 +110,7 @@ def _random_configs(n, seed):
     return out
 
 
-@pytest.mark.parametrize("g,k4,k16,Gk,Gv,R,n_blocks,n_extra,flush_mode,seed", _random_configs(24, 5))
+@pytest.mark.parametrize("g,k4,k16,Gk,Gv,R,n_blocks,n_extra,flush_mode,seed", _random_configs(30, 5))
 def test_random_configurations(H, g, k4, k16, Gk, Gv, R, n_blocks, n_extra, flush_mode, seed):
     rng = np.random.default_rng(seed)
     B, Hkv = 1, 2
