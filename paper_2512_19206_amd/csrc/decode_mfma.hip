@@ -310,7 +310,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   const int blk_step = n_gw;
   // fp16 rows (sink tokens, then the residual window; n_res counts both): sub-units of 32 tokens follow the
   // records in the same round-robin deal
-  const int n_sub = (n_res + 31) >> 5;     // <= 8 (sink + window <= 256 rows) and <= n_gw (the launcher sees to it)
+  const int n_sub = (n_res + 31) >> 5;     // <= 12 (sink + window <= 384 rows) and <= n_gw (the launcher sees to it)
   // unit n_blocks + j belongs to wavefront (n_blocks + j) % n_gw; n_sub <= n_gw, so one division serves them all
   const int first_sub_gw = n_blocks % n_gw;
   int my_sub = gw - first_sub_gw;
