@@ -283,6 +283,9 @@ def main():
         w = S.scaled_workload(args.config, T=args.tokens)
     if args.config == 4:
         args.steps, args.warmup = min(args.steps, 8), min(args.warmup, 2)
+        if args.group_size:
+            import dataclasses
+            w = dataclasses.replace(w, name=w.name + "_g%d" % args.group_size, Gk=args.group_size, Gv=args.group_size)
         bench_prefill(args, w, args.config)
         return
     policy_kw = {}
