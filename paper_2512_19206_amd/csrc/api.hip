@@ -160,8 +160,8 @@ static int append_range(mixkvq_cache* c, int b0, int nb, const __half* k_new, co
     const __half* vw = v_new + (int64_t)pl.take * kvs.t;
     const int r0 = st.n_res;
     const int first_rec = (int)(st.n_quant / Rr);
-    if (pl.F > 0 && (sel || per == 1)) {
-      // one selection for the call, or blocks of one record each (the pack kernel scores those itself)
+    if (pl.F > 0 && (sel || per == 1 || cfg.k4 + cfg.k16 == 0)) {
+      // one selection for the call, blocks of one record each (the pack kernel scores those itself), or nothing to select
       MIXKVQ_TRY_HIP(launch_flush(v, kw, vw, kvs, r0, first_rec, (int)pl.F * per, sel, s));
     } else if (pl.F > 0) {
       // blocks of several records without a given selection: every block is scored over all its R tokens first
