@@ -1169,6 +1169,12 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
   MIXKVQ_CASE(0, 12, 2, 8, 0, 0, 0, 0, 0)
   MIXKVQ_CASE(8, 4, 1, 8, 0, 0, 0, 0, 0)
   MIXKVQ_CASE(0, 32, 1, 8, 0, 0, 0, 0, 0)
+  MIXKVQ_CASE(0, 4, 1, 6, 0, 0, 0, 0, 0)
+  MIXKVQ_CASE(0, 8, 1, 7, 0, 0, 0, 0, 0)
+  MIXKVQ_CASE(0, 16, 1, 8, 0, 0, 0, 0, 0)
+  MIXKVQ_CASE(0, 24, 1, 8, 0, 0, 0, 0, 0)
+  MIXKVQ_CASE(16, 4, 1, 8, 0, 0, 0, 0, 0)
+  MIXKVQ_CASE(16, 8, 1, 8, 0, 0, 0, 0, 0)
   // threshold policy: the capacities of the two side tiers
   MIXKVQ_CASE(16, 8, 1, 8, 0, 1, 0, 0, 0)
   MIXKVQ_CASE(16, 0, 1, 6, 0, 1, 0, 0, 0)

@@ -91,7 +91,8 @@ def _random_configs(n, seed):
     """Seeded random valid configurations: every matrix-core kernel variant (tiers x value groups x R/Gk) and
     shapes that take the general kernels."""
     rng = np.random.default_rng(seed)
-    mfma_tiers = [(16, 0), (0, 12), (8, 0), (0, 0), (24, 0), (32, 0), (8, 4), (0, 32)]
+    mfma_tiers = [(16, 0), (0, 12), (8, 0), (0, 0), (24, 0), (32, 0), (8, 4), (0, 32), (0, 4), (0, 8), (0, 16), (0, 24),
+                  (16, 4), (16, 8)]
     out = []
     for i in range(n):
         if i % 3 != 2:     # matrix-core path: R, Gk, Gv multiples of 64
@@ -110,7 +111,7 @@ def _random_configs(n, seed):
     return out
 
 
-@pytest.mark.parametrize("g,k4,k16,Gk,Gv,R,n_blocks,n_extra,flush_mode,seed", _random_configs(30, 5))
+@pytest.mark.parametrize("g,k4,k16,Gk,Gv,R,n_blocks,n_extra,flush_mode,seed", _random_configs(42, 5))
 def test_random_configurations(H, g, k4, k16, Gk, Gv, R, n_blocks, n_extra, flush_mode, seed):
     rng = np.random.default_rng(seed)
     B, Hkv = 1, 2
