@@ -1172,7 +1172,7 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
   MIXKVQ_CASE(0, 4, 1, 6, 0, 0, 0, 0, 0)
   MIXKVQ_CASE(0, 8, 1, 7, 0, 0, 0, 0, 0)
   MIXKVQ_CASE(0, 16, 1, 8, 0, 0, 0, 0, 0)
-  MIXKVQ_CASE(0, 24, 1, 8, 0, 0, 0, 0, 0)
+  MIXKVQ_CASE(0, 24, 1, 10, 0, 0, 0, 0, 0)
   MIXKVQ_CASE(16, 4, 1, 8, 0, 0, 0, 0, 0)
   MIXKVQ_CASE(16, 8, 1, 8, 0, 0, 0, 0, 0)
   // threshold policy: the capacities of the two side tiers
@@ -1194,6 +1194,7 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
   MIXKVQ_CASE(8, 4, 4, 10, 0, 0, 1, 0, 0)
   MIXKVQ_CASE(0, 12, 1, 10, 0, 0, 1, 0, 0)
   MIXKVQ_CASE(16, 8, 1, 10, 0, 1, 1, 0, 0)
+  MIXKVQ_CASE(0, 12, 1, 10, 0, 1, 1, 0, 0)
   MIXKVQ_CASE(16, 0, 4, 7, 0, 0, 1, 0, 0)
   MIXKVQ_CASE(8, 0, 4, 7, 0, 0, 1, 0, 0)
   MIXKVQ_CASE(16, 0, 4, 8, 0, 1, 1, 0, 0)
