@@ -33,7 +33,7 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMfmaThreads = 256;
 constexpr int kWaves = kMfmaThreads / 64;
-constexpr int kKPartMax = 10240;                // bytes of a record before the value plane (staged in LDS)
+constexpr int kKPartMax = 12288;                // bytes of a record before the value plane (staged in LDS)
 constexpr int kVMetaMax = 2048;                 // value scales + zero-points of one block
 constexpr int kQsStride = 168;                  // halfs per head row of the slot-ordered q table (160 slots + padding)
 constexpr int kQsBytes = 8 * kQsStride * 2;
@@ -1168,7 +1168,7 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
   MIXKVQ_CASE(16, 0, 2, 6, 0, 0, 0, 0, 0)
   MIXKVQ_CASE(0, 12, 2, 8, 0, 0, 0, 0, 0)
   MIXKVQ_CASE(8, 4, 1, 8, 0, 0, 0, 0, 0)
-  MIXKVQ_CASE(0, 32, 1, 8, 0, 0, 0, 0, 0)
+  MIXKVQ_CASE(0, 32, 1, 12, 0, 0, 0, 0, 0)
   MIXKVQ_CASE(0, 4, 1, 6, 0, 0, 0, 0, 0)
   MIXKVQ_CASE(0, 8, 1, 7, 0, 0, 0, 0, 0)
   MIXKVQ_CASE(0, 16, 1, 8, 0, 0, 0, 0, 0)
@@ -1195,6 +1195,7 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
   MIXKVQ_CASE(0, 12, 1, 10, 0, 0, 1, 0, 0)
   MIXKVQ_CASE(16, 8, 1, 10, 0, 1, 1, 0, 0)
   MIXKVQ_CASE(0, 12, 1, 10, 0, 1, 1, 0, 0)
+  MIXKVQ_CASE(16, 16, 4, 12, 0, 1, 1, 0, 0)
   MIXKVQ_CASE(16, 0, 4, 7, 0, 0, 1, 0, 0)
   MIXKVQ_CASE(8, 0, 4, 7, 0, 0, 1, 0, 0)
   MIXKVQ_CASE(16, 0, 4, 8, 0, 1, 1, 0, 0)
