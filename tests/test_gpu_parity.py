@@ -211,7 +211,7 @@ def test_fused_decode_step(H, R, Gk, k4, k16, flush_mode):
 @pytest.mark.parametrize("R,Gv,k4,k16,g,policy", [(128, 128, 16, 0, 7, 0), (64, 64, 16, 0, 5, 0), (128, 128, 8, 0, 8, 0),
                                                   (128, 128, 0, 0, 3, 0), (128, 128, 16, 0, 4, 1), (128, 32, 16, 0, 7, 0), (128, 32, 16, 0, 5, 1),
                                                   (128, 32, 0, 12, 2, 0), (128, 32, 16, 8, 7, 1), (128, 128, 16, 8, 4, 1),
-                                                  (128, 32, 8, 4, 3, 0), (128, 32, 0, 12, 8, 1), (64, 32, 16, 8, 5, 1)])
+                                                  (128, 32, 8, 4, 3, 0), (128, 32, 0, 12, 8, 1), (64, 32, 16, 8, 5, 1), (128, 32, 16, 16, 7, 1)])
 def test_key_groups_of_32_tokens(H, R, Gv, k4, k16, g, policy):
     """The paper's group size (Section 5, "Settings": G = 32) with a residual length of 64 or 128: four (two) key
     groups per block, value words interleaved over the two key groups of a 64-token span."""
