@@ -413,7 +413,10 @@ def main():
                    "R": w.R, "k4": w.k4, "k16": w.k16, "cache_copies": copies,
                    "algorithmic_bytes_per_step": step_bytes,
                    "step": "decode_step = quantize_append(1 token, flush every R) + decode_attention(accumulate_q)"},
-        "roofline": {"bound": "hbm", "kernel": "decode_fused_kernel", "achieved": round(achieved, 2),
+        "roofline": {"bound": "hbm",
+                     "kernel": "decode_fused_kernel" if M.mixkvq_decode_path(caches[0]) == M.PATH_MATRIX
+                     else "decode_split_kernel (vector-ALU fallback: no matrix-core variant for this configuration)",
+                     "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "kernel_avg_us": round(k_avg_ms * 1e3, 2), "kernel_min_us": round(min(k_ms) * 1e3, 2),
                      "launches_timed": n_ev,

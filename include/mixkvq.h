@@ -202,6 +202,15 @@ int mixkvq_decode_step(mixkvq_cache* c, const void* k_new, const void* v_new, co
  * switch it off. */
 int mixkvq_set_timing_events(mixkvq_cache* c, void* start_event, void* stop_event);
 
+/* Profiling aid: which kernel the last mixkvq_decode_attention / mixkvq_decode_step on this cache launched.
+ * MIXKVQ_PATH_NONE (no attention call yet), MIXKVQ_PATH_MATRIX (the matrix-core kernel) or MIXKVQ_PATH_VECTOR (the
+ * vector-ALU kernel, which covers the configurations the matrix-core kernel has no variant for and is many times
+ * slower).  Host-only, no synchronisation; negative on a NULL handle. */
+#define MIXKVQ_PATH_NONE 0
+#define MIXKVQ_PATH_MATRIX 1
+#define MIXKVQ_PATH_VECTOR 2
+int mixkvq_decode_path(const mixkvq_cache* c);
+
 /* Message for a return code (for EHIP: the last HIP error string seen by this thread). */
 const char* mixkvq_strerror(int code);
 

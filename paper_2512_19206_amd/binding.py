@@ -15,10 +15,13 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmixkvq.so")
 
+PATH_NONE, PATH_MATRIX, PATH_VECTOR = 0, 1, 2
+
 EXPORTS = ("mixkvq_block_layout", "mixkvq_cache_sizes", "mixkvq_cache_create", "mixkvq_cache_destroy",
            "mixkvq_cache_set_block_table", "mixkvq_cache_reset", "mixkvq_cache_reset_seq", "mixkvq_cache_state", "mixkvq_cache_state_seq",
            "mixkvq_select_channels", "mixkvq_select_channels_seq", "mixkvq_quantize_append", "mixkvq_quantize_append_seq",
-           "mixkvq_decode_attention", "mixkvq_decode_step", "mixkvq_set_timing_events", "mixkvq_strerror")
+           "mixkvq_decode_attention", "mixkvq_decode_step", "mixkvq_set_timing_events", "mixkvq_decode_path",
+           "mixkvq_strerror")
 
 
 class Config(C.Structure):
@@ -78,6 +81,7 @@ def load_library() -> C.CDLL:
     lib.mixkvq_decode_attention.argtypes = [vp, vp, vp, vp, C.c_float, i32, vp]
     lib.mixkvq_decode_step.argtypes = [vp, vp, vp, i64p, vp, vp, vp, C.c_float, i32, vp]
     lib.mixkvq_set_timing_events.argtypes = [vp, vp, vp]
+    lib.mixkvq_decode_path.argtypes = [vp]
     lib.mixkvq_strerror.argtypes = [i32]
     lib.mixkvq_strerror.restype = C.c_char_p
     for name in EXPORTS:
@@ -263,6 +267,10 @@ class Cache:
     def set_timing_events(self, start_event, stop_event):
         """start_event, stop_event: raw hipEvent_t handles (ints) or None, None."""
         _check(self.lib.mixkvq_set_timing_events(self.handle, start_event, stop_event))
+
+    def decode_path(self) -> int:
+        """Kernel of the last attention call: PATH_NONE, PATH_MATRIX (matrix-core kernel) or PATH_VECTOR (fallback)."""
+        return int(self.lib.mixkvq_decode_path(self.handle))
 
     # helpers for tests: views of the raw buffers
     def block_records(self) -> torch.Tensor:

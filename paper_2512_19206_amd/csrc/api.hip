@@ -104,6 +104,7 @@ struct mixkvq_cache {
   int32_t Rw;        // the residual length R of the configuration: window size and flush unit, Rw / v.cfg.R records per block
   SeqState* seq;     // [B]: every sequence has its own counts (they are equal while the batch runs in lock-step)
   hipEvent_t ev_start = nullptr, ev_stop = nullptr;   // optional timing of the split kernel
+  int last_path = MIXKVQ_PATH_NONE;                   // kernel of the last attention launch
 };
 
 namespace mixkvq {
@@ -420,7 +421,7 @@ int mixkvq_decode_attention(mixkvq_cache* c, const void* q, void* out, float* ls
   if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)cfg.D);
   MIXKVQ_TRY_HIP(launch_decode(c->v, (const __half*)q, (__half*)out, lse, scale, n_blocks, n_fp16, accumulate_q,
                                NewToken{nullptr, nullptr, {0, 0, 0}, 0}, sc.enabled ? &sc : nullptr, s, c->ev_start,
-                               c->ev_stop));
+                               c->ev_stop, &c->last_path));
   return MIXKVQ_OK;
 }
 
@@ -452,7 +453,7 @@ int mixkvq_decode_step(mixkvq_cache* c, const void* k_new, const void* v_new, co
   NewToken nt{(const __half*)k_new, (const __half*)v_new, Strides3{kv_strides[0], kv_strides[1], kv_strides[2]},
               n_fp16 - 1};
   MIXKVQ_TRY_HIP(launch_decode(c->v, (const __half*)q, (__half*)out, lse, scale, n_blocks, n_fp16, accumulate_q, nt,
-                               sc.enabled ? &sc : nullptr, s, c->ev_start, c->ev_stop));
+                               sc.enabled ? &sc : nullptr, s, c->ev_start, c->ev_stop, &c->last_path));
   for (int b = 0; b < cfg.B; ++b) c->seq[b].n_res += 1;
   return MIXKVQ_OK;
 }
@@ -471,6 +472,8 @@ int mixkvq_set_timing_events(mixkvq_cache* c, void* start_event, void* stop_even
   c->ev_stop = (hipEvent_t)stop_event;
   return MIXKVQ_OK;
 }
+
+int mixkvq_decode_path(const mixkvq_cache* c) { return c ? c->last_path : MIXKVQ_EINVAL; }
 
 const char* mixkvq_strerror(int code) {
   switch (code) {

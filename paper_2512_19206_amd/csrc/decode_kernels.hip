@@ -238,7 +238,7 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
 
 hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float* lse, float scale, int n_blocks,
                          int n_fp16, int accumulate_q, NewToken nt, const SeqCounts* sc_in, hipStream_t s,
-                         hipEvent_t ev_start, hipEvent_t ev_stop) {
+                         hipEvent_t ev_start, hipEvent_t ev_stop, int* path) {
   static const SeqCounts kLockStep = [] { SeqCounts z; memset(&z, 0, sizeof(z)); return z; }();
   const SeqCounts& sc = sc_in ? *sc_in : kLockStep;
   // split count: enough workgroups to fill the chip (tunable through MIXKVQ_DECODE_WGS for experiments),
@@ -261,8 +261,11 @@ hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float
   if (n_splits_mc < min_splits) n_splits_mc = min_splits;
   if (n_splits_mc <= max_splits_for(v.P) &&
       try_launch_decode_mfma(v, q, scale, n_blocks, n_fp16, n_splits_mc, part, out, lse, accumulate_q, nt, sc, s,
-                             ev_start, ev_stop, &e))
+                             ev_start, ev_stop, &e)) {
+    *path = MIXKVQ_PATH_MATRIX;
     return e;
+  }
+  *path = MIXKVQ_PATH_VECTOR;
   if (nt.k) {   // this path does not move the new token itself
     e = launch_residual_copy(v, nt.k, nt.v, nt.st, 0, nt.row, 1, s);
     if (e != hipSuccess) return e;

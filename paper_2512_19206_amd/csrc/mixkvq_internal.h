@@ -86,7 +86,7 @@ hipError_t launch_residual_copy(const CacheView& v, const __half* k_new, const _
 // sequence without tokens is skipped (output 0, lse -inf), and a new token (nt) goes to the last fp16 row in use.
 hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float* lse, float scale,
                          int n_blocks, int n_fp16, int accumulate_q, NewToken nt, const SeqCounts* sc, hipStream_t s,
-                         hipEvent_t ev_start, hipEvent_t ev_stop);
+                         hipEvent_t ev_start, hipEvent_t ev_stop, int* path);   // *path: MIXKVQ_PATH_* of the launch
 
 size_t decode_workspace_bytes(const mixkvq_config& c);
 size_t decode_partials_bytes(const mixkvq_config& c);

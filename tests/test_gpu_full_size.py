@@ -60,6 +60,7 @@ def test_full_size_sampled_pairs(H, cfg_id, host_batch, samples, n_steps, over):
     outs = []
     for t in range(n_steps):
         out, lse = M.mixkvq_decode_step(gc, dk[:, :, t:t + 1], dv[:, :, t:t + 1], dq[t], accumulate_q=True)
+        assert M.mixkvq_decode_path(gc) == M.PATH_MATRIX      # the kernel bench.py times
         outs.append((out.float().cpu().numpy(), lse.cpu().numpy()))
     torch.cuda.synchronize()
     nq, r = gc.state()

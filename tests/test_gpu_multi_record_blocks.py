@@ -6,6 +6,8 @@ import numpy as np
 import pytest
 import torch
 
+import paper_2512_19206_amd as M
+
 from oracle import mixkvq_oracle as O
 
 pytestmark = pytest.mark.gpu
@@ -60,6 +62,7 @@ def test_prefill_then_decode_steps(H, R, Gk, Gv, k4, k16, g, sink, flush_mode):
         assert np.all(np.abs(lse.cpu().numpy() - rl) <= H.LSE_ATOL + 1e-4 * np.abs(rl))
     assert oc.n_quant == 4 * R
     H.check_state(oc, gc)
+    assert gc.decode_path() == (M.PATH_VECTOR if Gk == 16 else M.PATH_MATRIX)
 
 
 @pytest.mark.parametrize("R,Gk,counts", [(256, 64, (1536, 21)), (96, 32, (1536, 21))])

@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 import torch
 
+import paper_2512_19206_amd as M
 import synth_inputs as S
 
 pytestmark = pytest.mark.gpu
@@ -247,6 +248,7 @@ def test_key_groups_of_32_tokens(H, R, Gv, k4, k16, g, policy):
         assert np.all(np.abs(lse.cpu().numpy() - rl) <= H.LSE_ATOL + 1e-4 * np.abs(rl))
     H.check_state(oc, gc)
     assert oc.n_flush_calls >= 4
+    assert gc.decode_path() == M.PATH_MATRIX         # every listed combination has a matrix-core variant
 
 
 @pytest.mark.parametrize("Gv,k4,k16,g,sink,n_blocks,policy", [(32, 16, 0, 7, 0, 40, 0), (32, 8, 0, 1, 32, 9, 0),
@@ -287,6 +289,7 @@ def test_records_of_32_tokens(H, Gv, k4, k16, g, sink, n_blocks, policy):
         assert np.all(err <= H.ATOL + H.RTOL * np.abs(ro)), (step, float(err.max()))
         assert np.all(np.abs(lse.cpu().numpy() - rl) <= H.LSE_ATOL + 1e-4 * np.abs(rl))
     H.check_state(oc, gc)
+    assert gc.decode_path() == M.PATH_MATRIX         # not the fallback kernel
 
 
 @pytest.mark.parametrize("R,Gk,sink,k4,g,flush_mode", [(128, 128, 32, 16, 7, 0), (64, 64, 128, 16, 5, 0), (128, 32, 64, 8, 8, 1),

@@ -98,6 +98,7 @@ def test_null_arguments_and_error_strings(M):
     assert lib.mixkvq_block_layout(None, None) == -1
     assert lib.mixkvq_cache_state(None, None, None, None) == -1
     assert lib.mixkvq_decode_attention(None, None, None, None, 0.0, 0, None) == -1
+    assert lib.mixkvq_decode_path(None) == -1
     assert lib.mixkvq_quantize_append(None, None, None, 1, None, None, None) == -1
     for code in (0, -1, -2, -3, -4, -5, -99):
         assert len(lib.mixkvq_strerror(code)) > 0
