@@ -9,7 +9,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmixkvq.so")
-SOURCES = ["api.hip", "select_kernels.hip", "quantize_kernels.hip", "decode_kernels.hip", "decode_mfma.hip"]
+SOURCES = ["api.hip", "select_kernels.hip", "quantize_kernels.hip", "decode_kernels.hip", "decode_mfma.hip",
+           "decode_mfma_generic_plain.hip", "decode_mfma_generic_g32.hip", "decode_mfma_generic_rh.hip"]
+OBJ_DIR = os.path.join(HERE, "_build")      # object files (git-ignored)
 
 
 def hipcc_path() -> str:
@@ -19,20 +21,39 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile every HIP source for gfx950 and link the shared library."""
-    cmd = [hipcc_path(), "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wall", "-Wno-unused-function", "-fno-strict-aliasing",
-           "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+def _flags():
+    return ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
+            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+            "-Wall", "-Wno-unused-function", "-fno-strict-aliasing",
+            "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+
+
+def _compile(src: str, verbose: bool) -> str:
+    obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
+    cmd = [hipcc_path()] + _flags() + ["-c", os.path.join(CSRC, src), "-o", obj]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+        raise RuntimeError(f"hipcc failed on {src}:\n" + res.stdout + res.stderr)
     if verbose and res.stderr:
         print(res.stderr)
+    return obj
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile every HIP source for gfx950 (the translation units in parallel) and link the shared library."""
+    from concurrent.futures import ThreadPoolExecutor
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    jobs = min(len(SOURCES), max(1, min(os.cpu_count() or 1, int(os.environ.get("MAX_JOBS", "8")))))
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        objs = list(pool.map(lambda src: _compile(src, verbose), SOURCES))
+    cmd = [hipcc_path(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("link failed:\n" + res.stdout + res.stderr)
     return LIB
 
 
