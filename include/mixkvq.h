@@ -36,6 +36,7 @@ extern "C" {
 #define MIXKVQ_EHIP      (-3)  /* a HIP call failed; mixkvq_strerror gives the HIP message */
 #define MIXKVQ_ENOMEM    (-4)  /* host allocation of the handle failed */
 #define MIXKVQ_EEMPTY    (-5)  /* decode attention on a cache that holds no token */
+#define MIXKVQ_ESCRATCH  (-7)  /* mixkvq_decode_attention_noalloc: the launch needs more than the built-in scratch buffer */
 #define MIXKVQ_ERAGGED   (-6)  /* mixkvq_cache_state on a batch whose sequences differ: use mixkvq_cache_state_seq */
 
 typedef struct mixkvq_cache mixkvq_cache; /* opaque HOST handle: counts + the caller's device pointers */
@@ -186,6 +187,17 @@ int mixkvq_quantize_append_seq(mixkvq_cache* c, int32_t b, const void* k_new, co
  * 256 sequences then, else EINVAL); a sequence without tokens gets out = 0 and lse = -inf and its |q| is not accumulated. */
 int mixkvq_decode_attention(mixkvq_cache* c, const void* q, void* out, float* lse,
                             float scale, int32_t accumulate_q, void* stream);
+
+/* mixkvq_decode_attention for callers that cannot allocate device memory and hand over no workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, results and errors; the
+ * split-K partials go to a buffer built into the library (MIXKVQ_NOALLOC_SCRATCH_BYTES of device memory on every GPU
+ * the library runs on, held until the process ends) instead of the cache's workspace, and the call allocates nothing
+ * on the host or the device.  ESCRATCH if the launch would need more: pairs x splits x (Hq/Hkv) x 130 floats (any
+ * configuration of up to 512 (batch, KV head) pairs fits).  The buffer is shared by every call on a GPU and needs no
+ * clearing (a launch writes every partial it reads); calls that overlap on one GPU (two streams, two threads) race. */
+#define MIXKVQ_NOALLOC_SCRATCH_BYTES (8u << 20)
+int mixkvq_decode_attention_noalloc(mixkvq_cache* c, const void* q, void* out, float* lse,
+                                    float scale, int32_t accumulate_q, void* stream);
 
 /* One decode step in the fewest launches: the same result and cache state as
  * mixkvq_quantize_append(c, k_new, v_new, 1, kv_strides, NULL, stream) followed by

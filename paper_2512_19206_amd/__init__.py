@@ -22,3 +22,7 @@ def mixkvq_decode_attention(cache: Cache, q, out=None, lse=None, scale=0.0, accu
 
 def mixkvq_decode_path(cache: Cache) -> int:
     return cache.decode_path()
+
+
+def mixkvq_decode_attention_noalloc(cache: Cache, q, out, lse, scale=0.0, accumulate_q=False, stream=None):
+    return cache.decode_attention_noalloc(q, out, lse, scale=scale, accumulate_q=accumulate_q, stream=stream)

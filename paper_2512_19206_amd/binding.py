@@ -20,7 +20,7 @@ PATH_NONE, PATH_MATRIX, PATH_VECTOR = 0, 1, 2
 EXPORTS = ("mixkvq_block_layout", "mixkvq_cache_sizes", "mixkvq_cache_create", "mixkvq_cache_destroy",
            "mixkvq_cache_set_block_table", "mixkvq_cache_reset", "mixkvq_cache_reset_seq", "mixkvq_cache_state", "mixkvq_cache_state_seq",
            "mixkvq_select_channels", "mixkvq_select_channels_seq", "mixkvq_quantize_append", "mixkvq_quantize_append_seq",
-           "mixkvq_decode_attention", "mixkvq_decode_step", "mixkvq_set_timing_events", "mixkvq_decode_path",
+           "mixkvq_decode_attention", "mixkvq_decode_attention_noalloc", "mixkvq_decode_step", "mixkvq_set_timing_events", "mixkvq_decode_path",
            "mixkvq_strerror")
 
 
@@ -79,6 +79,7 @@ def load_library() -> C.CDLL:
     lib.mixkvq_select_channels.argtypes = [vp, vp, i32, i64p, vp, i32, i64p, vp, vp]
     lib.mixkvq_quantize_append.argtypes = [vp, vp, vp, i32, i64p, vp, vp]
     lib.mixkvq_decode_attention.argtypes = [vp, vp, vp, vp, C.c_float, i32, vp]
+    lib.mixkvq_decode_attention_noalloc.argtypes = [vp, vp, vp, vp, C.c_float, i32, vp]
     lib.mixkvq_decode_step.argtypes = [vp, vp, vp, i64p, vp, vp, vp, C.c_float, i32, vp]
     lib.mixkvq_set_timing_events.argtypes = [vp, vp, vp]
     lib.mixkvq_decode_path.argtypes = [vp]
@@ -250,6 +251,13 @@ class Cache:
             lse = torch.empty(q.shape[:2], dtype=torch.float32, device=self.device)
         _check(self.lib.mixkvq_decode_attention(self.handle, q.data_ptr(), out.data_ptr(), lse.data_ptr(),
                                                 float(scale), int(bool(accumulate_q)), _stream_ptr(stream)))
+        return out, lse
+
+    def decode_attention_noalloc(self, q, out, lse, scale=0.0, accumulate_q=False, stream=None):
+        """decode_attention through the entry point that allocates nothing: the caller passes every tensor."""
+        assert q.is_contiguous() and out.is_contiguous() and lse.is_contiguous()
+        _check(self.lib.mixkvq_decode_attention_noalloc(self.handle, q.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                                                        float(scale), int(bool(accumulate_q)), _stream_ptr(stream)))
         return out, lse
 
     def decode_step(self, k_new, v_new, q, out=None, lse=None, scale=0.0, accumulate_q=False, stream=None):

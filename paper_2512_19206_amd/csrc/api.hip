@@ -425,6 +425,25 @@ int mixkvq_decode_attention(mixkvq_cache* c, const void* q, void* out, float* ls
   return MIXKVQ_OK;
 }
 
+int mixkvq_decode_attention_noalloc(mixkvq_cache* c, const void* q, void* out, float* lse, float scale,
+                                    int32_t accumulate_q, void* stream) {
+  if (!c || !q || !out) return MIXKVQ_EINVAL;
+  const mixkvq_config& cfg = c->v.cfg;
+  int n_blocks, n_fp16;
+  SeqCounts sc;
+  if (!decode_counts(c, 0, &n_blocks, &n_fp16, &sc)) return MIXKVQ_EINVAL;
+  if (n_blocks == 0 && n_fp16 == 0) return MIXKVQ_EEMPTY;
+  if (decode_launch_partials_bytes(c->v, n_blocks, n_fp16) > kNoAllocScratchBytes) return MIXKVQ_ESCRATCH;
+  void* part = nullptr;
+  MIXKVQ_TRY_HIP(noalloc_scratch(&part));
+  hipStream_t s = (hipStream_t)stream;
+  if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)cfg.D);
+  MIXKVQ_TRY_HIP(launch_decode(c->v, (const __half*)q, (__half*)out, lse, scale, n_blocks, n_fp16, accumulate_q,
+                               NewToken{nullptr, nullptr, {0, 0, 0}, 0}, sc.enabled ? &sc : nullptr, s, c->ev_start,
+                               c->ev_stop, &c->last_path, (float*)part));
+  return MIXKVQ_OK;
+}
+
 int mixkvq_decode_step(mixkvq_cache* c, const void* k_new, const void* v_new, const int64_t kv_strides[3],
                        const void* q, void* out, float* lse, float scale, int32_t accumulate_q, void* stream) {
   if (!c || !q || !out) return MIXKVQ_EINVAL;
@@ -483,6 +502,7 @@ const char* mixkvq_strerror(int code) {
     case MIXKVQ_EHIP: return mixkvq::g_hip_msg;
     case MIXKVQ_ENOMEM: return "host allocation failed";
     case MIXKVQ_EEMPTY: return "the cache holds no token";
+    case MIXKVQ_ESCRATCH: return "the split-K partials of this launch exceed the library's built-in scratch buffer (8 MiB)";
     case MIXKVQ_ERAGGED: return "the sequences of the batch hold different numbers of tokens: ask per sequence";
     default: return "unknown mixkvq error code";
   }

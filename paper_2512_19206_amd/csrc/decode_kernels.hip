@@ -3,6 +3,7 @@
 // splits.
 #include <stdlib.h>
 #include <string.h>
+#include <mutex>
 #include "mixkvq_internal.h"
 
 namespace mixkvq {
@@ -236,13 +237,11 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
                             float* part, __half* out, float* lse, int accumulate_q, NewToken nt, const SeqCounts& sc,
                             hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop, hipError_t* err);
 
-hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float* lse, float scale, int n_blocks,
-                         int n_fp16, int accumulate_q, NewToken nt, const SeqCounts* sc_in, hipStream_t s,
-                         hipEvent_t ev_start, hipEvent_t ev_stop, int* path) {
-  static const SeqCounts kLockStep = [] { SeqCounts z; memset(&z, 0, sizeof(z)); return z; }();
-  const SeqCounts& sc = sc_in ? *sc_in : kLockStep;
-  // split count: enough workgroups to fill the chip (tunable through MIXKVQ_DECODE_WGS for experiments),
-  // never above the ceiling the workspace was sized for
+// Split count of a decode launch (one rule for every caller): enough workgroups to fill the chip (tunable through
+// MIXKVQ_DECODE_WGS for experiments), never above the ceiling the workspace was sized for.  *n_splits_mc is the count
+// the matrix-core kernel takes: its fp16 rows are cut into sub-units of 32 tokens and a wavefront takes at most one of
+// them, so a pair needs at least as many wavefronts (4 per workgroup) as it has sub-units.
+static void choose_splits(const CacheView& v, int n_blocks, int n_fp16, int* n_splits_out, int* n_splits_mc_out) {
   static const int target_wgs = [] {
     const char* e = getenv("MIXKVQ_DECODE_WGS");
     int t = e ? atoi(e) : 0;
@@ -252,13 +251,56 @@ hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float
   if (n_splits > max_splits_for(v.P)) n_splits = max_splits_for(v.P);
   if (n_splits > n_blocks) n_splits = n_blocks;
   if (n_splits < 1) n_splits = 1;
-  float* part = reinterpret_cast<float*>(v.ws);
-  hipError_t e = hipSuccess;
-  // matrix-core path: the fp16 rows are cut into sub-units of 32 tokens and a wavefront takes at most one of them,
-  // so a pair needs at least as many wavefronts (4 per workgroup) as it has sub-units
   int n_splits_mc = n_splits;
   const int min_splits = ((n_fp16 + 31) / 32 + 3) / 4;
   if (n_splits_mc < min_splits) n_splits_mc = min_splits;
+  *n_splits_out = n_splits;
+  *n_splits_mc_out = n_splits_mc;
+}
+
+size_t decode_launch_partials_bytes(const CacheView& v, int n_blocks, int n_fp16) {
+  int n_splits, n_splits_mc;
+  choose_splits(v, n_blocks, n_fp16, &n_splits, &n_splits_mc);
+  const int n = n_splits_mc > n_splits ? n_splits_mc : n_splits;
+  return (size_t)v.P * n * v.g * kPartStride * sizeof(float);
+}
+
+// ---------------------------------------------------------------------------
+// Split-K partials for callers that cannot allocate (and pass no workspace): one array per GPU, resident from the
+// moment the library is loaded until the process ends.  Every launch writes all the partials it later reads, so
+// nothing has to be cleared; launches that share it must not overlap on one GPU.
+// In host code the array's name is only a handle: the device address comes from hipGetSymbolAddress, once per
+// device with that device current, and is what the kernels get.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+
+hipError_t noalloc_scratch(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptrs[kMaxDevices] = {};
+  int device = 0;
+  if (hipError_t e = hipGetDevice(&device); e != hipSuccess) return e;
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptrs[device]) {
+    void* p = nullptr;
+    if (hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)); e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    ptrs[device] = p;
+  }
+  *out = ptrs[device];
+  return hipSuccess;
+}
+
+hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float* lse, float scale, int n_blocks,
+                         int n_fp16, int accumulate_q, NewToken nt, const SeqCounts* sc_in, hipStream_t s,
+                         hipEvent_t ev_start, hipEvent_t ev_stop, int* path, float* part) {
+  static const SeqCounts kLockStep = [] { SeqCounts z; memset(&z, 0, sizeof(z)); return z; }();
+  const SeqCounts& sc = sc_in ? *sc_in : kLockStep;
+  int n_splits, n_splits_mc;
+  choose_splits(v, n_blocks, n_fp16, &n_splits, &n_splits_mc);
+  if (!part) part = reinterpret_cast<float*>(v.ws);
+  hipError_t e = hipSuccess;
   if (n_splits_mc <= max_splits_for(v.P) &&
       try_launch_decode_mfma(v, q, scale, n_blocks, n_fp16, n_splits_mc, part, out, lse, accumulate_q, nt, sc, s,
                              ev_start, ev_stop, &e)) {

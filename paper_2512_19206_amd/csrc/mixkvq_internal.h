@@ -86,7 +86,14 @@ hipError_t launch_residual_copy(const CacheView& v, const __half* k_new, const _
 // sequence without tokens is skipped (output 0, lse -inf), and a new token (nt) goes to the last fp16 row in use.
 hipError_t launch_decode(const CacheView& v, const __half* q, __half* out, float* lse, float scale,
                          int n_blocks, int n_fp16, int accumulate_q, NewToken nt, const SeqCounts* sc, hipStream_t s,
-                         hipEvent_t ev_start, hipEvent_t ev_stop, int* path);   // *path: MIXKVQ_PATH_* of the launch
+                         hipEvent_t ev_start, hipEvent_t ev_stop, int* path,   // *path: MIXKVQ_PATH_* of the launch
+                         float* part = nullptr);   // split-K partials; nullptr: the cache's workspace
+// bytes of split-K partials that launch would write
+size_t decode_launch_partials_bytes(const CacheView& v, int n_blocks, int n_fp16);
+// The library's own partials buffer for callers that cannot allocate: a file-scope device array of
+// kNoAllocScratchBytes on every GPU; *out is its address on the current device (looked up once per device).
+constexpr size_t kNoAllocScratchBytes = 8u << 20;
+hipError_t noalloc_scratch(void** out);
 
 size_t decode_workspace_bytes(const mixkvq_config& c);
 size_t decode_partials_bytes(const mixkvq_config& c);
