@@ -18,6 +18,12 @@
  *   - Grouped-query mapping: query heads [j*g, (j+1)*g) use KV head j, g = Hq/Hkv.
  *   - "fp16" tensors below are IEEE binary16, or bfloat16 when cfg.in_dtype == 1 (same shapes and strides, in
  *     elements); Inf/NaN inputs are outside the contract.
+ *   - Precision of mixkvq_decode_attention / mixkvq_decode_step: fp16 operands, binary32 sums.  Against exact
+ *     arithmetic on the same dequantized cache, |out - exact| <= 2e-3 + 1e-2 |exact| per element as long as the
+ *     dequantized values stay within +-512; beyond, the absolute term is 2^-18 of the largest |value| (Eq. 3 is
+ *     evaluated as sum (p s) c + sum p z, two binary32 sums that cancel where a group's zero-point is far from its
+ *     values).  Scaled logits are binary32 numbers: a query/key pair that drives them beyond ~2^13 loses the
+ *     differences between tokens that binary32 cannot hold at that magnitude.
  *   - Calls on one cache must be issued from one host thread at a time.
  */
 #ifndef MIXKVQ_H

@@ -106,6 +106,19 @@ __device__ __forceinline__ float row_ror8(float v) {
   return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(v), 0x128, 0xF, 0xF, true));
 }
 
+// Small operands of the two value steps of one register of softmax weights: P*s as an fp16 head plus its exact fp16
+// remainder (one fused multiply-add), so that the value products carry ~22 bits of p*s like the key products do of
+// q*s.  In lanes 0..7 of a row `p` holds the token pair of step 0, in lanes 8..15 the pair of step 1.  Step 0 gets
+// the head in columns 0..7 and the tail of the same pairs in columns 8..15; step 1 gets the head of lanes 8..15
+// moved to columns 0..7 while columns 8..15 keep their own tail.  Columns 8..15 of the output accumulate the
+// tail products; the halves are added once, after the last record.
+__device__ __forceinline__ void ps_operands(unsigned p, unsigned sv, u32x4& b0, u32x4& b1, int i) {
+  const unsigned pm = pk_mul(p, sv);
+  const unsigned pt = pk_fma_neg(p, sv, pm);
+  b0[i] = __builtin_amdgcn_update_dpp(pm, pt, 0x118, 0xF, 0xC, false);   // row_shr:8 into lanes 8..15 only
+  b1[i] = __builtin_amdgcn_update_dpp(pt, pm, 0x108, 0xF, 0x3, false);   // row_shl:8 into lanes 0..7 only
+}
+
 // position exponent of code r%8 of a 16-code word after unpacking: value = c * 4^sc * 2^-24
 __device__ __host__ constexpr int sc2(int r) { return r < 5 ? r : r - 3; }
 // the same for nibble r%4 of an 8-nibble word: value = c * 4^sc * 2^-24
@@ -862,9 +875,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
             const unsigned sw[4] = {sv.x, sv.y, sv.z, sv.w}, zw[4] = {zv.x, zv.y, zv.z, zv.w};
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-              const unsigned pm = pk_mul(pk[i], sw[i]);
-              Bp[0][0][i] = pm;
-              Bp[0][1][i] = row_shl8u(pm);
+              ps_operands(pk[i], sw[i], Bp[0][0], Bp[0][1], i);
               zacc[0][i] = dot2(pk[i], zw[i], zacc[0][i]);
             }
           } else if (NVG == 2) {
@@ -879,9 +890,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 #pragma unroll
               for (int i = 0; i < 4; ++i) {
                 const unsigned selb = a ? 0x07060302u : 0x05040100u;
-                const unsigned pm = pk_mul(pk[i], __builtin_amdgcn_perm(sw[2 * i + 1], sw[2 * i], selb));
-                Bp[a][0][i] = pm;
-                Bp[a][1][i] = row_shl8u(pm);
+                ps_operands(pk[i], __builtin_amdgcn_perm(sw[2 * i + 1], sw[2 * i], selb), Bp[a][0], Bp[a][1], i);
                 zacc[a][i] = dot2(pk[i], __builtin_amdgcn_perm(zw[2 * i + 1], zw[2 * i], selb), zacc[a][i]);
               }
           }
@@ -911,9 +920,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 #pragma unroll
               for (int cc = 0; cc < 2; ++cc) {
                 const unsigned selb = cc ? 0x07060302u : 0x05040100u;
-                const unsigned pm = pk_mul(pk[i], __builtin_amdgcn_perm(s_b, s_a, selb));
-                Bp[cc][0][i] = pm;
-                Bp[cc][1][i] = row_shl8u(pm);
+                ps_operands(pk[i], __builtin_amdgcn_perm(s_b, s_a, selb), Bp[cc][0], Bp[cc][1], i);
                 zacc[2 * xp + cc][i] = dot2(pk[i], __builtin_amdgcn_perm(z_b, z_a, selb), zacc[2 * xp + cc][i]);
               }
             }
@@ -966,6 +973,14 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   }
   // each wavefront leaves its result in its own LDS region; after one barrier all threads merge the four
   // in a fixed order
+  // columns 8..15 of the value products hold the part that came from the remainders of P*s
+  f32x4 Ot[2][4];
+#pragma unroll
+  for (int xp = 0; xp < 2; ++xp)
+#pragma unroll
+    for (int qq = 0; qq < 4; ++qq)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) Ot[xp][qq][i] = O[xp][qq][i] + row_ror8(O[xp][qq][i]);
   float* wO = reinterpret_cast<float*>(wbase);        // [8][128] O, then [8] l
   float* sM = reinterpret_cast<float*>(smem + 2048 + 64);          // [waves][8]
   if (role == 0 && live) {
@@ -977,7 +992,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         for (int i = 0; i < 4; ++i) {
           const int ch = value_channel<NVG>(xp, qq, 4 * kg + i);
           const int a = value_group<NVG>(xp, qq);
-          wO[head * kD + ch] = fmaf(O[xp][qq][i], 16777216.f / (float)(1 << kPBoost), zsum[a]);
+          wO[head * kD + ch] = fmaf(Ot[xp][qq][i], 16777216.f / (float)(1 << kPBoost), zsum[a]);
         }
     if (kg == 0) {
       wO[8 * kD + head] = l_run;

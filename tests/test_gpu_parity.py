@@ -518,6 +518,14 @@ def test_degenerate_groups(H):
     oc.append(K, V, sel_ref)
     gc.quantize_append(H.dev(K), H.dev(V), sel=sel)
     H.check_state(oc, gc)
+    # attention over these blocks: a plain query, then one aligned with the token whose values are +-60000
+    # (values beyond 2048: the absolute term of the bar follows their magnitude, see value_atol)
+    atol = H.value_atol(60000.0)
+    q = rng.standard_normal((1, 2, 128)).astype(np.float16)
+    H.check_attention(oc, gc, q, atol=atol)
+    q[0, 0] = (K[0, 0, 6].astype(np.float32) * 0.6).astype(np.float16)
+    q[0, 1, 3] = 0.0      # (a query with weight on the 65504 channel would give logits near 4e7, beyond binary32's grain)
+    H.check_attention(oc, gc, q, atol=atol)
 
 
 def test_error_only_score_mode_and_ties(H):
