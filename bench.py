@@ -165,6 +165,25 @@ def cpu_baseline(cfg_id, w, host, budget_s=20.0):
                       f"{el / n * 1e3:.0f} ms per step"}
 
 
+def build_prefill_inputs(cfg_id, w, Lq):
+    """K, V [B, Hkv, T, D] and the prompt queries [B, Hq, Lq, D] of the prefill workload on the device: one batch
+    entry is drawn on the host, the others are device-side copies with the channel order rolled by 7 per entry."""
+    import torch
+    import synth_inputs as S
+    K, V, _ = S.heavy_tailed_kv(cfg_id, 1, w.Hkv, w.T)
+    Q = S.outlier_queries(cfg_id, 1, w.Hq, Lq)
+    dk = torch.empty((w.B, w.Hkv, w.T, w.D), dtype=torch.float16, device="cuda")
+    dv = torch.empty_like(dk)
+    dq = torch.empty((w.B, w.Hq, Lq, w.D), dtype=torch.float16, device="cuda")
+    hk, hv, hq = (torch.from_numpy(a).cuda() for a in (K, V, Q))
+    for b in range(w.B):
+        dk[b] = torch.roll(hk[0], 7 * b, dims=-1)
+        dv[b] = torch.roll(hv[0], 7 * b, dims=-1)
+        dq[b] = torch.roll(hq[0], 7 * b, dims=-1)
+    del hk, hv, hq
+    return dk, dv, dq, dict(K=K, V=V, Q=Q)
+
+
 def prefill_bytes(w, Lq):
     """(fp16 input bytes, bytes written) of one prefill pass: K, V and the prompt queries in; block records and the
     residual window out."""
@@ -181,20 +200,8 @@ def bench_prefill(args, w, cfg_id):
     mixkvq_select_channels(Q, K), mixkvq_quantize_append(K, V, sel) over the whole batch."""
     import torch
     import paper_2512_19206_amd as M
-    import synth_inputs as S
     Lq = w.T
-    hb = 1
-    K, V, _ = S.heavy_tailed_kv(cfg_id, hb, w.Hkv, w.T)
-    Q = S.outlier_queries(cfg_id, hb, w.Hq, Lq)
-    dk = torch.empty((w.B, w.Hkv, w.T, w.D), dtype=torch.float16, device="cuda")
-    dv = torch.empty_like(dk)
-    dq = torch.empty((w.B, w.Hq, Lq, w.D), dtype=torch.float16, device="cuda")
-    hk, hv, hq = (torch.from_numpy(a).cuda() for a in (K, V, Q))
-    for b in range(w.B):
-        dk[b] = torch.roll(hk[0], 7 * b, dims=-1)
-        dv[b] = torch.roll(hv[0], 7 * b, dims=-1)
-        dq[b] = torch.roll(hq[0], 7 * b, dims=-1)
-    del hk, hv, hq
+    dk, dv, dq, _ = build_prefill_inputs(cfg_id, w, Lq)
     kw = dict(B=w.B, Hq=w.Hq, Hkv=w.Hkv, D=w.D, T_max=-(-w.T // w.R) * w.R, Gk=w.Gk, Gv=w.Gv, R=w.R, k4=w.k4, k16=w.k16)
     gc = M.Cache(M.make_config(**kw))
     sel = torch.empty((w.B, w.Hkv, w.k4 + w.k16), dtype=torch.uint8, device="cuda")
