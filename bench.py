@@ -7,6 +7,11 @@ quantize-and-pack whenever the residual window is full) followed by
 mixkvq_decode_attention with |q| accumulation.  Inputs are synthetic and already
 resident in HBM when the timed region starts.
 
+Before the W counted warm-up steps every cache copy is stepped once and the GPU is kept busy with uncounted steps
+for about 20 ms; then exactly K steps are timed between two synchronisations.  With no --config the headline is
+configuration 1 (the metric's workload); configurations 2, 3 (decode) and 4 (prefill) are timed in the same run and
+reported under "other_workloads".
+
 Prints ONE JSON line (see the fields below).  `value` is effective bandwidth:
 algorithmic bytes of a decode step (minimal representation of the method: packed
 codes, fp16 scale/zero per group, fp16-tier values, index bytes, the fp16 residual
@@ -27,10 +32,24 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 LLC_BYTES = 256 << 20   # last-level (Infinity) cache
 
-# HBM bytes per launch of the decode kernel from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), each scaled by what
-# the same counter read for a 512 MiB device copy in the same run (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0);
-# the readings and commands are in profiles/decode_fused_kernel_cfg1.txt.  Only for the default workload.
-MEASURED_TRAFFIC_BYTES = {("cfg1_gqa7b_b8_32k", 32768): 39552.3 * 1024 * 2.0 + 1868.3 * 1024 * 1.0}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` on `workload` from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE in KiB per
+    dispatch, each scaled by what the same counter read for a plain device copy of known size in the same run), as
+    listed in profiles/hbm_traffic.txt beside the commands that measured them.  None when the table has no such row
+    (the counters are not read while the benchmark runs)."""
+    try:
+        with open(TRAFFIC_TABLE) as f:
+            for line in f:
+                col = line.split()
+                if len(col) >= 6 and not line.startswith("#") and col[0] == workload and col[1] == kernel:
+                    fetch_kib, write_kib, fetch_scale, write_scale = (float(x) for x in col[2:6])
+                    return round(fetch_kib * 1024 * fetch_scale + write_kib * 1024 * write_scale, 1)
+    except OSError:
+        pass
+    return None
 
 
 def copy_kernel_gbs():
@@ -219,17 +238,18 @@ def bench_prefill(args, w, cfg_id):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / n
 
-    for _ in range(args.warmup):
+    n_steps, n_warm = min(args.steps, 8), min(args.warmup, 2)
+    for _ in range(n_warm):
         step()
-    el = timed(args.steps)
-    el_noq = timed(args.steps, with_q=False)
-    el_pb = timed(args.steps, per_block=True)
+    el = timed(n_steps)
+    el_noq = timed(n_steps, with_q=False)
+    el_pb = timed(n_steps, per_block=True)
     in_b, out_b = prefill_bytes(w, Lq)
     in_noq = in_b - w.B * w.Hq * Lq * w.D * 2
     value = in_b / el / 1e9
     result = {
         "metric": "prefill quantization: GB/s of fp16 input consumed (K, V, prompt queries)", "value": round(value, 2),
-        "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(el * 1e3, 4),
+        "unit": "GB/s", "n_gpus": 1, "steps": n_steps, "warmup": n_warm, "ms_per_step": round(el * 1e3, 4),
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "T": w.T, "Lq": Lq, "Gk": w.Gk,
@@ -248,78 +268,45 @@ def bench_prefill(args, w, cfg_id):
     copy_gbs = copy_kernel_gbs()
     result["copy_kernel"] = {"value": round(copy_gbs, 1), "unit": "GB/s read+write, 512 MiB device copy on this box",
                              "pct_of_copy_kernel": round(100 * (in_b + out_b) / el / 1e9 / copy_gbs, 2)}
-    print(json.dumps(result))
+    return result
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1024)
-    ap.add_argument("--warmup", type=int, default=64)
-    ap.add_argument("--config", type=int, default=1, help="workload configuration (1, 2, 3: decode step; 4: prefill)")
-    ap.add_argument("--copies", type=int, default=0, help="independent cache copies rotated over (0 = enough for 2x LLC)")
-    ap.add_argument("--host-batch", type=int, default=2)
-    ap.add_argument("--tokens", type=int, default=0, help="override the context length of the configuration")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--group-size", type=int, default=0,
-                    help="override the key and value group size of the configuration (32: the paper's accuracy setting)")
-    ap.add_argument("--residual-length", type=int, default=0,
-                    help="override the residual length R of the configuration (32, 64, 96, 128 or 256); key groups larger "
-                         "than a record are cut to it")
-    ap.add_argument("--per-block-selection", action="store_true",
-                    help="fill the cache with every block scored on its own tokens (as blocks flushed during decoding "
-                         "are) instead of one selection for the whole prompt")
-    ap.add_argument("--thresholds", type=str, default="",
-                    help="'tau16,tau4': the three-tier threshold policy with room for 8 fp16 and 16 four-bit channels per "
-                         "block instead of the configuration's top-k budget (every block scored on its own tokens)")
-    ap.add_argument("--calibration-copy-mib", type=int, default=0,
-                    help="also run 4 plain device copies of this many MiB (reference reading for rocprofv3 --pmc byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the hot path has no collective); --gpus must be 1", file=sys.stderr)
-        sys.exit(2)
-
+def bench_decode(args, cfg_id, steps, warmup, with_cpu_baseline):
+    """Decode configurations 1-3: a step = mixkvq_decode_step (append one token per sequence, with the block flush and
+    channel re-selection whenever the window is full, then attention with |q| accumulation).  Returns the result dict."""
     import torch
     import paper_2512_19206_amd as M
     import synth_inputs as S
-    assert torch.cuda.is_available(), "bench.py needs the GPU (there is no CPU fallback)"
-    M.load_library()
+    import dataclasses
 
-    w = S.WORKLOADS[args.config]
+    w = S.WORKLOADS[cfg_id]
     if args.tokens:
-        w = S.scaled_workload(args.config, T=args.tokens)
-    if args.config == 4:
-        args.steps, args.warmup = min(args.steps, 8), min(args.warmup, 2)
-        if args.group_size:
-            import dataclasses
-            w = dataclasses.replace(w, name=w.name + "_g%d" % args.group_size, Gk=args.group_size, Gv=args.group_size)
-        bench_prefill(args, w, args.config)
-        return
+        w = S.scaled_workload(cfg_id, T=args.tokens)
     policy_kw = {}
     if args.group_size:
-        import dataclasses
         w = dataclasses.replace(w, name=w.name + "_g%d" % args.group_size, Gk=args.group_size, Gv=args.group_size)
-        args.no_cpu_baseline = True
+        with_cpu_baseline = False
     if args.residual_length:
-        import dataclasses
         R = args.residual_length
         # key groups must divide a record: 32 tokens for R = 32 and R = 96 (stored as three records of 32)
         w = dataclasses.replace(w, name=w.name + "_r%d" % R, R=R, Gk=32 if R % 64 else min(w.Gk, R, 128))
-        args.no_cpu_baseline = True
+        with_cpu_baseline = False
     if args.thresholds:
-        import dataclasses
         tau16, tau4 = (float(x) for x in args.thresholds.split(","))
         w = dataclasses.replace(w, name=w.name + "_thresholds", k4=16, k16=8)
         policy_kw = dict(policy=1, tau16=tau16, tau4=tau4)
-        args.no_cpu_baseline = True
+        with_cpu_baseline = False
     n_q0 = w.R * (-(-w.T // w.R) - 1)
     step_bytes = algorithmic_bytes(w, n_q0, w.T - n_q0)     # with thresholds: the capacity, refined below
     copies = args.copies or max(1, math.ceil(2 * LLC_BYTES / step_bytes))
-    total_steps = args.steps * 3 + args.warmup
+    n_ev = min(steps, 512)
+    n_ps = min(steps, 512)
+    n_settle = int(0.02 / (step_bytes / 6e12)) + 64      # steps the 20 ms settling phase can take at most (6 TB/s)
+    total_steps = steps + warmup + n_ev + n_ps + copies + n_settle
     per_copy = -(-total_steps // copies)
     T_max = (w.T + per_copy + 272 + 2 * w.R) // w.R * w.R     # + the single-copy pass on copy 0
 
-    dk, dv, dqp, dq, host = build_inputs(args.config, w, args.host_batch)
+    dk, dv, dqp, dq, host = build_inputs(cfg_id, w, args.host_batch)
     kw = dict(B=w.B, Hq=w.Hq, Hkv=w.Hkv, D=w.D, T_max=T_max, Gk=w.Gk, Gv=w.Gv, R=w.R, k4=w.k4, k16=w.k16, **policy_kw)
     caches = []
     for c in range(copies):
@@ -352,22 +339,35 @@ def main():
         t = i % 64
         M.mixkvq_decode_step(gc, k1[:, :, t:t + 1], v1[:, :, t:t + 1], dq[i % 8], out=out, lse=lse, accumulate_q=True)
 
+    # every cache copy is stepped once before anything is counted (a full prompt window is flushed by its first
+    # step, and a copy's first touch would otherwise land wherever the rotation first reaches it)
     i = 0
-    for _ in range(args.warmup):
+    for _ in range(copies):
+        step(i)
+        i += 1
+    # ... and the GPU is kept busy for about 20 ms (uncounted steps of the same kind), so that a short run
+    # (--steps 20 --warmup 5) is not timed on clocks that are still ramping up
+    torch.cuda.synchronize()
+    t_settle = time.perf_counter()
+    while time.perf_counter() - t_settle < 0.02:
+        for _ in range(8):
+            step(i)
+            i += 1
+        torch.cuda.synchronize()
+    for _ in range(warmup):
         step(i)
         i += 1
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step(i)
         i += 1
     torch.cuda.synchronize()
     el = time.perf_counter() - t0
-    ms_per_step = el / args.steps * 1e3
+    ms_per_step = el / steps * 1e3
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
     # second pass over the same kind of steps with HIP events around the split-K attention kernel
-    n_ev = min(args.steps, 512)
     ev = HipEvents(n_ev)
     for n in range(n_ev):
         gc = caches[i % copies]
@@ -382,7 +382,6 @@ def main():
 
     # third pass: every step between its own pair of events (whole step, flush steps included), for the
     # mean / worst step and the share of the block flushes
-    n_ps = min(args.steps, 512)
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_ps)]
     flushed = []
     for n in range(n_ps):
@@ -396,7 +395,7 @@ def main():
     ps = [a.elapsed_time(b) * 1e3 for a, b in evs]
 
     # fourth pass: one cache copy only (when it fits the last-level cache this is the cache-warm figure)
-    n_cw = min(args.steps, 256)
+    n_cw = min(steps, 256)
     for n in range(16):
         M.mixkvq_decode_step(caches[0], k1[:, :, :1], v1[:, :, :1], dq[n % 8], out=out, lse=lse, accumulate_q=True)
     torch.cuda.synchronize()
@@ -408,11 +407,11 @@ def main():
     ps_flush = [t for t, f in zip(ps, flushed) if f]
     ps_plain = [t for t, f in zip(ps, flushed) if not f]
     achieved = step_bytes / (k_avg_ms * 1e-3) / 1e9
-    nq_end, r_end = caches[0].state()
+    on_matrix_cores = M.mixkvq_decode_path(caches[0]) == M.PATH_MATRIX
 
     result = {
-        "metric": "quantized-KV decode attention: effective HBM GB/s at 32K ctx", "value": round(value, 2),
-        "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "metric": "quantized-KV decode attention: effective HBM GB/s at %dK ctx" % (w.T // 1024), "value": round(value, 2),
+        "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": round(ms_per_step, 5), "us_per_step": round(ms_per_step * 1e3, 2),
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
@@ -421,13 +420,14 @@ def main():
                    "algorithmic_bytes_per_step": step_bytes,
                    "step": "decode_step = quantize_append(1 token, flush every R) + decode_attention(accumulate_q)"},
         "roofline": {"bound": "hbm",
-                     "kernel": "decode_fused_kernel" if M.mixkvq_decode_path(caches[0]) == M.PATH_MATRIX
+                     "kernel": "decode_fused_kernel" if on_matrix_cores
                      else "decode_split_kernel (vector-ALU fallback: no matrix-core variant for this configuration)",
                      "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "kernel_avg_us": round(k_avg_ms * 1e3, 2), "kernel_min_us": round(min(k_ms) * 1e3, 2),
                      "launches_timed": n_ev,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, w.T)), "traffic_unit": "bytes per launch",
+                     "traffic": measured_traffic(w.name, "decode_fused_kernel") if (on_matrix_cores and w.T == S.WORKLOADS[cfg_id].T) else None,
+                     "traffic_unit": "bytes per launch (profiles/hbm_traffic.txt)",
                      "algorithmic_bytes_per_launch": step_bytes},
     }
     result["single_copy"] = {"us_per_step": round(single_copy_us, 2), "steps": n_cw,
@@ -442,15 +442,94 @@ def main():
         "amortised_with_flush_every_R": round((sum(ps_plain) / max(1, len(ps_plain)) * (w.R - 1)
                                                + (sum(ps_flush) / len(ps_flush) if ps_flush else 0.0)) / w.R, 2),
         "note": "each step between its own event pair (adds event overhead to every step)"}
+    if tiers:
+        result["config"]["threshold_policy"] = tiers
+    result["config"]["selection"] = "per block" if (args.thresholds or args.per_block_selection) else "one per prompt"
+    del caches, dk, dv, dqp, dq, k1, v1
+    torch.cuda.empty_cache()
     copy_gbs = copy_kernel_gbs()
     result["copy_kernel"] = {"value": round(copy_gbs, 1), "unit": "GB/s read+write, 512 MiB device copy on this box",
                              "pct_of_copy_kernel": round(100 * value / copy_gbs, 2),
                              "kernel_pct_of_copy_kernel": round(100 * achieved / copy_gbs, 2)}
-    if tiers:
-        result["config"]["threshold_policy"] = tiers
-    result["config"]["selection"] = "per block" if (args.thresholds or args.per_block_selection) else "one per prompt"
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(args.config, w, host)
+    if with_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg_id, w, host)
+    return result
+
+
+def summary_of(r):
+    """The figures of one more workload that ride along in the default run's JSON line."""
+    keep = {k: r[k] for k in ("metric", "value", "unit", "steps", "warmup", "ms_per_step", "pct_of_hbm_peak") if k in r}
+    keep["workload"] = r["config"]["workload"]
+    rf = r["roofline"]
+    keep["roofline"] = {k: rf[k] for k in ("bound", "kernel", "achieved", "peak", "unit", "frac", "kernel_avg_us", "traffic")
+                        if k in rf}
+    for k in ("per_step_us", "without_prompt_queries"):
+        if k in r:
+            keep[k] = r[k]
+    return keep
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1024)
+    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--config", type=int, default=0,
+                    help="time one workload configuration only (1, 2, 3: decode step; 4: prefill); default: configuration 1 "
+                         "as the headline, then 2, 3 and 4 under 'other_workloads'")
+    ap.add_argument("--copies", type=int, default=0, help="independent cache copies rotated over (0 = enough for 2x LLC)")
+    ap.add_argument("--host-batch", type=int, default=2)
+    ap.add_argument("--tokens", type=int, default=0, help="override the context length of the configuration")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--group-size", type=int, default=0,
+                    help="override the key and value group size of the configuration (32: the paper's accuracy setting)")
+    ap.add_argument("--residual-length", type=int, default=0,
+                    help="override the residual length R of the configuration (32, 64, 96, 128 or 256); key groups larger "
+                         "than a record are cut to it")
+    ap.add_argument("--per-block-selection", action="store_true",
+                    help="fill the cache with every block scored on its own tokens (as blocks flushed during decoding "
+                         "are) instead of one selection for the whole prompt")
+    ap.add_argument("--thresholds", type=str, default="",
+                    help="'tau16,tau4': the three-tier threshold policy with room for 8 fp16 and 16 four-bit channels per "
+                         "block instead of the configuration's top-k budget (every block scored on its own tokens)")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also run 4 plain device copies of this many MiB (reference reading for rocprofv3 --pmc byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the hot path has no collective); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2512_19206_amd as M
+    import synth_inputs as S
+    assert torch.cuda.is_available(), "bench.py needs the GPU (there is no CPU fallback)"
+    M.load_library()
+
+    def prefill(cfg_id):
+        w = S.WORKLOADS[cfg_id]
+        if args.tokens:
+            w = S.scaled_workload(cfg_id, T=args.tokens)
+        if args.group_size:
+            import dataclasses
+            w = dataclasses.replace(w, name=w.name + "_g%d" % args.group_size, Gk=args.group_size, Gv=args.group_size)
+        return bench_prefill(args, w, cfg_id)
+
+    if args.config == 4:
+        print(json.dumps(prefill(4)))
+        return
+    if args.config:
+        print(json.dumps(bench_decode(args, args.config, args.steps, args.warmup, not args.no_cpu_baseline)))
+        return
+    # default: the metric's workload (configuration 1) is the line's headline; the other configurations follow under
+    # one extra key, each timed the same way (configuration 3 always over its 512 consecutive steps)
+    result = bench_decode(args, 1, args.steps, args.warmup, not args.no_cpu_baseline)
+    others = {}
+    for cfg_id in (2, 3):
+        r = bench_decode(args, cfg_id, 512 if cfg_id == 3 else args.steps, args.warmup, False)
+        others[r["config"]["workload"]] = summary_of(r)
+    r = prefill(4)
+    others[r["config"]["workload"]] = summary_of(r)
+    result["other_workloads"] = others
     print(json.dumps(result))
 
 
