@@ -217,7 +217,8 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
     n_res = sc.n_fp16[b];
     skip_pair = n_blocks == 0 && n_res == 0;
   }
-  const int wave = tid >> 6, lane = tid & 63, n = lane & 15, kg = lane >> 4;
+  // (the wavefront index is the same in all lanes: as a scalar it keeps record indices and addresses off the vector ALU)
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, n = lane & 15, kg = lane >> 4;
   const int head = n & 7, role = n >> 3;     // role 0: head of q*s, role 1: tail
   const bool live = head < g;
 
@@ -295,7 +296,11 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 
   // q in slot order (rebuilt when the block's channel selection changes)
   unsigned qlo[2 * NU][4];            // [step][vgpr]: normalised q pairs of the 2-bit tier
-  unsigned qh4[4], q16[4];            // 4-bit tier pairs; fp16-tier pairs (role 0 only)
+  unsigned qh4[4];                    // 4-bit tier pairs
+  // fp16-tier pairs, zero beyond the tier, as two small operands: q16a is zero in columns 8..15 and q16b in columns
+  // 0..7.  A product of tile 0 (1) with q16a and one of tile 2 (3) with q16b into the SAME accumulator leave in
+  // every lane the tile its half keeps (lanes 0..7 of a row keep tiles 0 and 1, lanes 8..15 tiles 2 and 3).
+  unsigned q16a[4], q16b[4];
   constexpr int kSelWords = K4 + K16 > 0 ? (K4 + K16 + 3) / 4 : 1;
   unsigned sel_prev[kSelWords];     // wave-uniform: the selection q was last laid out for
 #pragma unroll
@@ -305,7 +310,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 #pragma unroll
     for (int e = 0; e < 4; ++e) qlo[s][e] = 0u;
 #pragma unroll
-  for (int e = 0; e < 4; ++e) { qh4[e] = 0u; q16[e] = 0u; }
+  for (int e = 0; e < 4; ++e) { qh4[e] = 0u; q16a[e] = 0u; q16b[e] = 0u; }
 
   // prefetch registers
   u32x4 kreg[NKL];
@@ -324,37 +329,40 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 #define MIXKVQ_REC(IDX) (blocks + (size_t)(IDX) * rec_bytes)     // (fewer than 2^31 records: the host checks)
   int slot_cur = 0, slot_nx = 0;
 
-  // Loads of one block.  Chunk indices are clamped to the record so that every lane loads and
-  // stores unconditionally (a clamped lane repeats the record's last chunk).
+  // Loads of one block.  A record's address is a scalar; every lane adds a 32-bit byte offset that is fixed for
+  // the whole kernel (so the loop spends no vector instruction on addresses).  Chunk indices are clamped to the
+  // record so that every lane loads and stores unconditionally (a clamped lane repeats the record's last chunk).
+  unsigned koff[NKL], vmoff[NVM];
+#pragma unroll
+  for (int c = 0; c < NKL; ++c) koff[c] = 16u * (unsigned)(c * 64 + lane < rec_chunks ? c * 64 + lane : rec_chunks - 1);
+#pragma unroll
+  for (int c = 0; c < NVM; ++c) vmoff[c] = (unsigned)off_v_s + 16u * (unsigned)(c * 64 + lane < nvm ? c * 64 + lane : nvm - 1);
+  // byte offset of this lane's value words in token group 0 of a record: channels value_channel(0, 0..3, n) of row kgv
+  const unsigned voff = (unsigned)off_v + 4u * (unsigned)(kgv * kD) + (NVG == 4 ? 8u : 16u) * (unsigned)n;
 #define MIXKVQ_ISSUE_K_LOADS(REC)                                                                           \
   {                                                                                                          \
     const unsigned char* rec_ = MIXKVQ_REC(REC);                                                             \
-    _Pragma("unroll") for (int c = 0; c < NKL; ++c) {                                                       \
-      const int idx_ = c * 64 + lane;                                                                        \
-      kreg[c] = reinterpret_cast<const u32x4*>(rec_)[idx_ < rec_chunks ? idx_ : rec_chunks - 1];            \
-    }                                                                                                        \
-    _Pragma("unroll") for (int c = 0; c < NVM; ++c) {                                                       \
-      const int idx_ = c * 64 + lane;                                                                        \
-      vmreg[c] = reinterpret_cast<const u32x4*>(rec_ + off_v_s)[idx_ < nvm ? idx_ : nvm - 1];               \
-    }                                                                                                        \
+    _Pragma("unroll") for (int c = 0; c < NKL; ++c)                                                         \
+        kreg[c] = *reinterpret_cast<const u32x4*>(rec_ + koff[c]);                                           \
+    _Pragma("unroll") for (int c = 0; c < NVM; ++c)                                                         \
+        vmreg[c] = *reinterpret_cast<const u32x4*>(rec_ + vmoff[c]);                                         \
   }
-  /* the four value words of vreg[.][X]: channels value_channel(X, 0..3, n) of one token group's row ROW_ */
-#define MIXKVQ_LOAD_VWORDS(DST, ROW_, X)                                                                     \
+  /* the four value words of vreg[.][X]: channels value_channel(X, 0..3, n) of the token group row at byte ROWB_ */
+#define MIXKVQ_LOAD_VWORDS(DST, ROWB_, X)                                                                    \
   {                                                                                                          \
     if (NVG == 4) {                                                                                          \
-      const uint2 lo_ = *reinterpret_cast<const uint2*>((ROW_) + 64 * (X) + 2 * n);                          \
-      const uint2 hi_ = *reinterpret_cast<const uint2*>((ROW_) + 64 * (X) + 32 + 2 * n);                     \
+      const uint2 lo_ = *reinterpret_cast<const uint2*>((ROWB_) + 256 * (X));                                \
+      const uint2 hi_ = *reinterpret_cast<const uint2*>((ROWB_) + 256 * (X) + 128);                          \
       DST = u32x4{lo_.x, lo_.y, hi_.x, hi_.y};                                                               \
     } else {                                                                                                 \
-      DST = *reinterpret_cast<const u32x4*>((ROW_) + 64 * (X) + 4 * n);                                      \
+      DST = *reinterpret_cast<const u32x4*>((ROWB_) + 256 * (X));                                            \
     }                                                                                                        \
   }
 #define MIXKVQ_ISSUE_V_LOADS(REC)                                                                           \
   {                                                                                                          \
     const unsigned char* rec_ = MIXKVQ_REC(REC);                                                             \
-    const unsigned* vw_ = reinterpret_cast<const unsigned*>(rec_ + off_v);                                  \
     _Pragma("unroll") for (int h = 0; h < 2; ++h) _Pragma("unroll") for (int x = 0; x < 2; ++x)             \
-        MIXKVQ_LOAD_VWORDS(vreg[h][x], vw_ + (4 * (h * 64 < R ? h : 0) + kgv) * kD, x)                      \
+        MIXKVQ_LOAD_VWORDS(vreg[h][x], rec_ + 2048 * (h * 64 < R ? h : 0) + voff, x)                        \
   }
 
   // The value words of one half (64 tokens) of a record: asked for as soon as the previous record's matrix
@@ -362,9 +370,8 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 #define MIXKVQ_ISSUE_V_HALF(REC, H)                                                                          \
   {                                                                                                          \
     const unsigned char* rec_ = MIXKVQ_REC(REC);                                                             \
-    const unsigned* vw_ = reinterpret_cast<const unsigned*>(rec_ + off_v);                                  \
     _Pragma("unroll") for (int x = 0; x < 2; ++x)                                                           \
-        MIXKVQ_LOAD_VWORDS(vreg[H][x], vw_ + (4 * (H) + kgv) * kD, x)                                       \
+        MIXKVQ_LOAD_VWORDS(vreg[H][x], rec_ + 2048 * (H) + voff, x)                                         \
   }
 
   // q in slot order from the selection words SELW (wave-uniform): a table [head][slot] in LDS, slots 0..127 for the
@@ -428,7 +435,11 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
     }                                                                                                          \
     if (K16 > 0) {                                                                                             \
       const u32x4 t_ = *reinterpret_cast<const u32x4*>(qrow + 128 + (8 * kg < K16 ? 8 * kg : 0));              \
-      _Pragma("unroll") for (int e = 0; e < 4; ++e) q16[e] = t_[e];                                            \
+      _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                                          \
+        const unsigned v_ = 8 * kg + 2 * e < K16 ? t_[e] : 0u;   /* (the table goes on with the 4-bit tier) */ \
+        q16a[e] = role ? 0u : v_;                                                                              \
+        q16b[e] = role ? v_ : 0u;                                                                              \
+      }                                                                                                        \
     }                                                                                                          \
   }
 
@@ -697,6 +708,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
     /* logits in the log2 domain: x2 = S * C + Z * Cz */                                                               \
     Cz = ldexpf(scale_log2e, Eq);                                                                                      \
     C = ldexpf(scale_log2e, 24 - e0 + Eq);                                                                             \
+    W = ldexpf(1.f, 24 - e0);                                                                                          \
     zc = zdot * Cz;                                                                                                    \
   }
 #define MIXKVQ_KEY_TILES(X0, X1)                                                                         \
@@ -724,19 +736,23 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
       for (int x = (X0); x < (X1); ++x) S[x] = mfma(unpack4(wh4[x]), Bh4, S[x]);                         \
     }                                                                                                    \
     if (K16 > 0) {                                                                                       \
-      const u32x4 bq = {q16[0], q16[1], q16[2], q16[3]};                                                 \
+      const u32x4 bqa = {q16a[0], q16a[1], q16a[2], q16a[3]}, bqb = {q16b[0], q16b[1], q16b[2], q16b[3]};   \
     _Pragma("unroll")                                                                                    \
       for (int x = (X0); x < (X1); ++x) {                                                                \
         const unsigned char* src = sK + k16_off + 2 * (64 * hsg + offx[x]) * K16;                        \
         const uint2 v0 = *reinterpret_cast<const uint2*>(src);                                           \
         const uint2 v1 = *reinterpret_cast<const uint2*>(src + 8);                                       \
-        /* entries beyond the tier are cleared: they belong to the next token's row or the next plane */ \
-        u32x4 a;                                                                                         \
-        a[0] = 8 * kg < K16 ? v0.x : 0u;                                                                 \
-        a[1] = 8 * kg + 2 < K16 ? v0.y : 0u;                                                             \
-        a[2] = 8 * kg + 4 < K16 ? v1.x : 0u;                                                             \
-        a[3] = 8 * kg + 6 < K16 ? v1.y : 0u;                                                             \
-        S16[x] = mfma(a, bq, f32x4{zdot, zdot, zdot, zdot});                                             \
+        /* Entries beyond the tier meet zeros in the small operand; they are another token's finite */   \
+        /* keys, except behind the last token of the plane (always in tile 3), where they are cleared */ \
+        u32x4 a = {v0.x, v0.y, v1.x, v1.y};                                                              \
+        if (x == 3 && K16 % 8 != 0) {                                                                    \
+          a[0] = 8 * kg < K16 ? v0.x : 0u;                                                               \
+          a[1] = 8 * kg + 2 < K16 ? v0.y : 0u;                                                           \
+          a[2] = 8 * kg + 4 < K16 ? v1.x : 0u;                                                           \
+          a[3] = 8 * kg + 6 < K16 ? v1.y : 0u;                                                           \
+        }                                                                                                \
+        /* tiles 0, 2 share one accumulator, tiles 1, 3 the other */                                     \
+        S16[x & 1] = mfma(a, x < 2 ? bqa : bqb, S16[x & 1]);                                             \
       }                                                                                                  \
     }                                                                                                    \
   }
@@ -792,52 +808,60 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 
     // operands that live across the super-groups of one key group
     u32x4 Blo[2 * NU], Bh4;
-    float zdot = 0.f, C = 0.f, Cz = 0.f, zc = 0.f;
+    float zdot = 0.f, C = 0.f, Cz = 0.f, zc = 0.f, W = 0.f;
 #pragma unroll
     for (int hsg = 0; hsg < 2; ++hsg) {       // super-groups of 64 tokens
       if (64 * hsg < R) {
         // ---- S^T tiles: tile x holds tokens 64*hsg + tokbase(row) + offx[x] ----
         constexpr int offx[4] = {0, 1, G32 ? 32 : 8, G32 ? 33 : 9};
         unsigned wlo[NU][4], wh4[4];
-        f32x4 S[4], S16[4];
+        f32x4 S[4], S16[2];
 #pragma unroll
         for (int x = 0; x < 4; ++x) S[x] = f32x4{0.f, 0.f, 0.f, 0.f};
-        float Cx = 0.f, zcx = 0.f;      // logit constants of this lane's tiles
+        S16[0] = S16[1] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // logit constants of this lane's tiles.  With y the sum of the code products of a token (plus, with an
+        // fp16 tier, its fp16 products brought to the same unit by the power of two Wx), the logit is
+        // x = y * Mx + zcx with Mx > 0, so the maximum is taken over y and the subtraction of the running maximum is
+        // folded into the constant of the fused multiply-add that feeds exp2.
+        float Mx = 0.f, zcx = 0.f, Wx = 0.f;
         if (G32) {
           // two key groups per super-group: tiles 0, 1 with the first group's operands, tiles 2, 3 with the second's
           MIXKVQ_GROUP_OPERANDS(2 * hsg)
           MIXKVQ_KEY_TILES(0, 2)
-          const float C0 = C, zc0 = zc;
+          const float C0 = C, zc0 = zc, W0 = W;
           MIXKVQ_GROUP_OPERANDS(2 * hsg + 1)
           MIXKVQ_KEY_TILES(2, 4)
-          Cx = role ? C : C0;            // lanes 0..7 of a row keep tiles 0, 1; lanes 8..15 tiles 2, 3
+          Mx = K16 > 0 ? Cz : (role ? C : C0);      // lanes 0..7 of a row keep tiles 0, 1; lanes 8..15 tiles 2, 3
           zcx = role ? zc : zc0;
+          Wx = role ? W : W0;
         } else {
           if ((64 * hsg) % Gk == 0) MIXKVQ_GROUP_OPERANDS((64 * hsg) / Gk)
           MIXKVQ_KEY_TILES(0, 4)
-          Cx = C;
+          Mx = K16 > 0 ? Cz : C;
           zcx = zc;
+          Wx = W;
         }
 
         // ---- logits.  Only columns 0..7 carry heads, so two tiles share one register: lanes 0..7 of a
         // row of 16 keep tile 0 (resp. 1), lanes 8..15 take tile 2 (resp. 3).  ror8 adds head and tail. ----
-        float xa[4], xb[4];     // packed logits: xa = tiles (0 | 2), xb = tiles (1 | 3)
-        float mx = -INFINITY;
+        float ya[4], yb[4];     // packed: ya = tiles (0 | 2), yb = tiles (1 | 3)
+        float ymax = -INFINITY;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const float c0 = S[0][i] + row_ror8(S[0][i]), c2 = S[2][i] + row_ror8(S[2][i]);
           const float c1 = S[1][i] + row_ror8(S[1][i]), c3 = S[3][i] + row_ror8(S[3][i]);
           const float sa = role ? c2 : c0, sb = role ? c3 : c1;
           if (K16 > 0) {
-            xa[i] = fmaf(sa, Cx, (role ? S16[2][i] : S16[0][i]) * Cz);
-            xb[i] = fmaf(sb, Cx, (role ? S16[3][i] : S16[1][i]) * Cz);
+            ya[i] = fmaf(sa, Wx, S16[0][i]);
+            yb[i] = fmaf(sb, Wx, S16[1][i]);
           } else {
-            xa[i] = fmaf(sa, Cx, zcx);
-            xb[i] = fmaf(sb, Cx, zcx);
+            ya[i] = sa;
+            yb[i] = sb;
           }
-          if (RH && no_tokens) xa[i] = xb[i] = -INFINITY;
-          mx = fmaxf(mx, fmaxf(xa[i], xb[i]));
+          ymax = fmaxf(ymax, fmaxf(ya[i], yb[i]));
         }
+        float mx = fmaf(ymax, Mx, zcx);
+        if (RH && no_tokens) mx = -INFINITY;
         mx = xkg_max(mx);
         mx = fmaxf(mx, row_ror8(mx));
         const float m_new = fmaxf(m_run, mx);
@@ -858,10 +882,13 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         // ---- p in fp16 with the position factor 4^-sc of the value code it meets.  In lanes 0..7 pair i is
         // (token 2i, token 2i+1) of this lane group's 16 tokens = PV step 0; in lanes 8..15 it is (8+2i, 9+2i) = step 1.
         unsigned pk[4];
+        const float zm = zcx - m_run;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const float msc = m_run + sc2f[i];
-          pk[i] = cvt_pk(__builtin_amdgcn_exp2f(xa[i] - msc), __builtin_amdgcn_exp2f(xb[i] - msc));
+          const float k = zm - sc2f[i];
+          float ea = fmaf(ya[i], Mx, k), eb = fmaf(yb[i], Mx, k);
+          if (RH && no_tokens) ea = eb = -INFINITY;
+          pk[i] = cvt_pk(__builtin_amdgcn_exp2f(ea), __builtin_amdgcn_exp2f(eb));
           l_run = dot2(pk[i], w4sc[i], l_run);
         }
         // value scales / zero-points of the tokens this lane half pairs
