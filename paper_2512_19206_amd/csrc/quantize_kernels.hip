@@ -380,48 +380,37 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   const int n_ch = R / 16;                 // chunks of 16 tokens
 
   MIXKVQ_FPHASE(0)
-  // ---- both tiles: every load in flight ------------------------------------------------------
+  // ---- the key tile first; the value tile is requested once the keys are staged in LDS, so that the wait for the
+  //      keys is a wait for 32 KiB and the values arrive while the keys are encoded ------------------------------
   uint4 kreg[8], vreg[8];
   const int64_t pair_off = (int64_t)(p / Hkv) * st.b + (int64_t)(p % Hkv) * st.h;
   const __half* res_kp = window_rows(cv, cv.res_k, p);
   const __half* res_vp = window_rows(cv, cv.res_v, p);
   const int pos0 = f * R;
-  bool v_pending = false;     // the value tile in registers still holds bfloat16
-  if (pos0 >= r0 || pos0 + R <= r0) {
-    // the usual case: the whole tile comes from one place, rows a constant stride apart
-    const bool from_res = pos0 + R <= r0;
-    const int64_t row_stride = from_res ? (int64_t)kD : st.t;
-    const int64_t first = (int64_t)(from_res ? pos0 : pos0 - r0) + (tid >> 4);
+  // the usual case: the whole tile comes from one place, rows a constant stride apart; else it straddles the end of
+  // the residual window (first block of an append onto a partly filled window)
+  const bool one_place = pos0 >= r0 || pos0 + R <= r0;
+  const bool from_res = pos0 + R <= r0;
+  const int64_t row_stride = from_res ? (int64_t)kD : st.t;
+  const int64_t first = (int64_t)(from_res ? pos0 : pos0 - r0) + (tid >> 4);
+  const bool v_pending = one_place && bf16 && !from_res;     // the value tile in registers still holds bfloat16
+  if (one_place) {
     const __half* kp = (from_res ? res_kp : k_new + pair_off) + first * row_stride + (tid & 15) * 8;
-    const __half* vp = (from_res ? res_vp : v_new + pair_off) + first * row_stride + (tid & 15) * 8;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       kreg[i] = make_uint4(0u, 0u, 0u, 0u);
       if (tid + kFlushThreads * i < n_chunks16) kreg[i] = *reinterpret_cast<const uint4*>(kp + 16 * i * row_stride);
     }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      vreg[i] = make_uint4(0u, 0u, 0u, 0u);
-      if (tid + kFlushThreads * i < n_chunks16) vreg[i] = *reinterpret_cast<const uint4*>(vp + 16 * i * row_stride);
-    }
     if (bf16 && !from_res) {     // rows of the caller's bfloat16 tensors enter as binary16 (the values when they are staged)
 #pragma unroll
       for (int i = 0; i < 8; ++i) kreg[i] = as_f16x8(kreg[i], true);
-      v_pending = true;
     }
   } else {
-    // the tile straddles the end of the residual window (first block of an append onto a partly filled window)
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int idx = tid + kFlushThreads * i;
       kreg[i] = make_uint4(0u, 0u, 0u, 0u);
       if (idx < n_chunks16) kreg[i] = load_chunk(res_kp, k_new + pair_off, st.t, r0, pos0, idx, bf16);
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int idx = tid + kFlushThreads * i;
-      vreg[i] = make_uint4(0u, 0u, 0u, 0u);
-      if (idx < n_chunks16) vreg[i] = load_chunk(res_vp, v_new + pair_off, st.t, r0, pos0, idx, bf16);
     }
   }
   // zero the small planes of the record (index bytes, tails of the scale/zero planes)
@@ -433,6 +422,21 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   for (int i = 0; i < 8; ++i) {
     const int idx = tid + kFlushThreads * i;
     if (idx < n_chunks16) *reinterpret_cast<uint4*>(sT + (idx >> 4) * kRowStride + (idx & 15) * 8) = kreg[i];
+  }
+  if (one_place) {
+    const __half* vp = (from_res ? res_vp : v_new + pair_off) + first * row_stride + (tid & 15) * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      vreg[i] = make_uint4(0u, 0u, 0u, 0u);
+      if (tid + kFlushThreads * i < n_chunks16) vreg[i] = *reinterpret_cast<const uint4*>(vp + 16 * i * row_stride);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int idx = tid + kFlushThreads * i;
+      vreg[i] = make_uint4(0u, 0u, 0u, 0u);
+      if (idx < n_chunks16) vreg[i] = load_chunk(res_vp, v_new + pair_off, st.t, r0, pos0, idx, bf16);
+    }
   }
   __syncthreads();
 
