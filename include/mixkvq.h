@@ -146,7 +146,17 @@ int mixkvq_cache_reset(mixkvq_cache* c, void* stream);
 int mixkvq_cache_state(const mixkvq_cache* c, int64_t* n_quantized, int32_t* n_residual, int32_t* n_sink);
 int mixkvq_cache_state_seq(const mixkvq_cache* c, int32_t b, int64_t* n_quantized, int32_t* n_residual, int32_t* n_sink);
 
-/* Empties sequence b only (its token counts and its rows of the |q| accumulator). */
+/* Resuming from a snapshot.  Everything a cache holds is in its five device buffers plus these token counts, so a
+ * snapshot is a copy of the buffers and of what mixkvq_cache_state(_seq) reports; to resume, copy the buffers back
+ * (into the same or another cache of the same configuration, with the same block table if one is in use) and set the
+ * counts here.  Host-only.  EINVAL for counts that no sequence of appends produces (n_quantized a multiple of R up to
+ * T_max; n_residual 1..R with the deferred flush once anything was flushed, 0..R-1 with the eager one; the window
+ * empty until the sink is full).  Appendix D.1 describes the cache as exactly this state. */
+int mixkvq_cache_set_state(mixkvq_cache* c, int64_t n_quantized, int32_t n_residual, int32_t n_sink);
+int mixkvq_cache_set_state_seq(mixkvq_cache* c, int32_t b, int64_t n_quantized, int32_t n_residual, int32_t n_sink);
+
+/* Empties sequence b only (its token counts and its rows of the |q| accumulator).  The per-sequence calls
+ * (mixkvq_cache_reset_seq, mixkvq_quantize_append_seq) are for batches of at most 256 sequences: EINVAL beyond. */
 int mixkvq_cache_reset_seq(mixkvq_cache* c, int32_t b, void* stream);
 
 /* Channel selection (Section 4.2, Eq. 6-8; top-k channel budget or thresholds, see mixkvq_config.policy).

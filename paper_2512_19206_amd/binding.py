@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libmixkvq.so")
 PATH_NONE, PATH_MATRIX, PATH_VECTOR = 0, 1, 2
 
 EXPORTS = ("mixkvq_block_layout", "mixkvq_cache_sizes", "mixkvq_cache_create", "mixkvq_cache_destroy",
-           "mixkvq_cache_set_block_table", "mixkvq_cache_reset", "mixkvq_cache_reset_seq", "mixkvq_cache_state", "mixkvq_cache_state_seq",
+           "mixkvq_cache_set_block_table", "mixkvq_cache_set_state", "mixkvq_cache_set_state_seq", "mixkvq_cache_reset", "mixkvq_cache_reset_seq", "mixkvq_cache_state", "mixkvq_cache_state_seq",
            "mixkvq_select_channels", "mixkvq_select_channels_seq", "mixkvq_quantize_append", "mixkvq_quantize_append_seq",
            "mixkvq_decode_attention", "mixkvq_decode_attention_noalloc", "mixkvq_decode_step", "mixkvq_set_timing_events", "mixkvq_decode_path",
            "mixkvq_strerror")
@@ -72,6 +72,8 @@ def load_library() -> C.CDLL:
     lib.mixkvq_cache_reset.argtypes = [vp, vp]
     lib.mixkvq_cache_state.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.mixkvq_cache_set_block_table.argtypes = [vp, vp]
+    lib.mixkvq_cache_set_state.argtypes = [vp, C.c_int64, i32, i32]
+    lib.mixkvq_cache_set_state_seq.argtypes = [vp, i32, C.c_int64, i32, i32]
     lib.mixkvq_cache_reset_seq.argtypes = [vp, i32, vp]
     lib.mixkvq_cache_state_seq.argtypes = [vp, i32, C.POINTER(C.c_int64), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.mixkvq_select_channels_seq.argtypes = [vp, i32, vp, i32, i64p, vp, i32, i64p, vp, vp]
@@ -165,6 +167,22 @@ class Cache:
         nq, r = C.c_int64(), C.c_int32()
         _check(self.lib.mixkvq_cache_state(self.handle, C.byref(nq), C.byref(r), None))
         return nq.value, r.value
+
+    def snapshot(self):
+        """Copies of the five device buffers and the token counts of every sequence (everything the cache holds)."""
+        bufs = [t.clone() for t in (self.blocks, self.res_k, self.res_v, self.qacc, self.workspace)]
+        return bufs, [self.state_seq(b) for b in range(self.cfg.B)]
+
+    def restore(self, snap):
+        """Takes a snapshot of a cache of the same configuration back in."""
+        bufs, states = snap
+        for dst, src in zip((self.blocks, self.res_k, self.res_v, self.qacc, self.workspace), bufs):
+            dst.copy_(src)
+        if all(st == states[0] for st in states):
+            _check(self.lib.mixkvq_cache_set_state(self.handle, *states[0]))
+        else:
+            for b, st in enumerate(states):
+                _check(self.lib.mixkvq_cache_set_state_seq(self.handle, b, *st))
 
     @property
     def rec_tokens(self) -> int:

@@ -307,6 +307,7 @@ int mixkvq_cache_reset(mixkvq_cache* c, void* stream) {
 
 int mixkvq_cache_reset_seq(mixkvq_cache* c, int32_t b, void* stream) {
   if (!c || b < 0 || b >= c->v.cfg.B) return MIXKVQ_EINVAL;
+  if (c->v.cfg.B > kMaxRaggedB) return MIXKVQ_EINVAL;     // such a batch could not be attended over once it is ragged
   MIXKVQ_TRY_HIP(launch_zero_qacc(sub_view(c, b, 1), (hipStream_t)stream));
   c->seq[b] = SeqState{0, 0, 0};
   return MIXKVQ_OK;
@@ -326,6 +327,30 @@ int mixkvq_cache_state_seq(const mixkvq_cache* c, int32_t b, int64_t* n_quantize
   if (n_quantized) *n_quantized = c->seq[b].n_quant;
   if (n_residual) *n_residual = c->seq[b].n_res;
   if (n_sink) *n_sink = c->seq[b].n_sink;
+  return MIXKVQ_OK;
+}
+
+// Is (nq, nr, ns) a state the append rules can produce?
+static bool reachable_state(const mixkvq_cache* c, int64_t nq, int32_t nr, int32_t ns) {
+  const mixkvq_config& cfg = c->v.cfg;
+  const int R = c->Rw;
+  if (nq < 0 || nr < 0 || ns < 0 || nq % R != 0 || nq > cfg.T_max || ns > cfg.sink) return false;
+  if (ns < cfg.sink && (nq != 0 || nr != 0)) return false;      // the window only fills once the sink is full
+  if (cfg.flush_mode == 0 ? nr > R : nr >= R) return false;     // deferred: up to R tokens wait; eager: fewer than R
+  if (cfg.flush_mode == 0 && nq > 0 && nr == 0) return false;   // a deferred flush always leaves the token that caused it
+  return true;
+}
+
+int mixkvq_cache_set_state(mixkvq_cache* c, int64_t n_quantized, int32_t n_residual, int32_t n_sink) {
+  if (!c || !reachable_state(c, n_quantized, n_residual, n_sink)) return MIXKVQ_EINVAL;
+  for (int b = 0; b < c->v.cfg.B; ++b) c->seq[b] = SeqState{n_quantized, n_residual, n_sink};
+  return MIXKVQ_OK;
+}
+
+int mixkvq_cache_set_state_seq(mixkvq_cache* c, int32_t b, int64_t n_quantized, int32_t n_residual, int32_t n_sink) {
+  if (!c || b < 0 || b >= c->v.cfg.B || !reachable_state(c, n_quantized, n_residual, n_sink)) return MIXKVQ_EINVAL;
+  if (c->v.cfg.B > kMaxRaggedB) return MIXKVQ_EINVAL;
+  c->seq[b] = SeqState{n_quantized, n_residual, n_sink};
   return MIXKVQ_OK;
 }
 
@@ -383,21 +408,31 @@ int mixkvq_quantize_append(mixkvq_cache* c, const void* k_new, const void* v_new
   }
   Strides3 kvs{kv_strides[0], kv_strides[1], kv_strides[2]};
   const int ks = cfg.k4 + cfg.k16;
-  // runs of neighbouring sequences in the same state are appended to together (one run while the batch is in lock-step)
-  for (int b0 = 0; b0 < cfg.B;) {
+  // Runs of neighbouring sequences in the same state are appended to together (one run while the batch is in
+  // lock-step).  The run boundaries are fixed before the first append (a run's append changes its sequences' state),
+  // and if a launch fails part-way the token counts of every sequence go back to what they were: the host state
+  // never describes an append that was not enqueued as a whole.
+  SeqState* before = new (std::nothrow) SeqState[cfg.B];
+  if (!before) return MIXKVQ_ENOMEM;
+  for (int b = 0; b < cfg.B; ++b) before[b] = c->seq[b];
+  rc = MIXKVQ_OK;
+  for (int b0 = 0; b0 < cfg.B && rc == MIXKVQ_OK;) {
     int b1 = b0 + 1;
-    while (b1 < cfg.B && c->seq[b1] == c->seq[b0]) ++b1;
+    while (b1 < cfg.B && before[b1] == before[b0]) ++b1;
     rc = append_range(c, b0, b1 - b0, (const __half*)k_new + (int64_t)b0 * kvs.b, (const __half*)v_new + (int64_t)b0 * kvs.b,
                       n_new, kvs, sel ? sel + (size_t)b0 * cfg.Hkv * ks : nullptr, (hipStream_t)stream);
-    if (rc != MIXKVQ_OK) return rc;
     b0 = b1;
   }
-  return MIXKVQ_OK;
+  if (rc != MIXKVQ_OK)
+    for (int b = 0; b < cfg.B; ++b) c->seq[b] = before[b];
+  delete[] before;
+  return rc;
 }
 
 int mixkvq_quantize_append_seq(mixkvq_cache* c, int32_t b, const void* k_new, const void* v_new, int32_t n_new,
                                const int64_t kv_strides[2], const uint8_t* sel, void* stream) {
   if (!c || b < 0 || b >= c->v.cfg.B || n_new < 0) return MIXKVQ_EINVAL;
+  if (c->v.cfg.B > kMaxRaggedB) return MIXKVQ_EINVAL;     // such a batch could not be attended over once it is ragged
   if (n_new == 0) return MIXKVQ_OK;
   int rc = check_kv_args(k_new, v_new, kv_strides, 2);
   if (rc != MIXKVQ_OK) return rc;
@@ -459,6 +494,9 @@ int mixkvq_decode_step(mixkvq_cache* c, const void* k_new, const void* v_new, co
     general |= (cfg.flush_mode == 0 ? total > R : total >= R) || st.n_sink < cfg.sink;
   }
   if (general) {
+    // everything the attention call could refuse is checked before the append changes the cache: a batch whose
+    // sequences differ in length can only be attended over up to kMaxRaggedB sequences (the counts go by value)
+    if (!lock_step(c) && cfg.B > kMaxRaggedB) return MIXKVQ_EINVAL;
     rc = mixkvq_quantize_append(c, k_new, v_new, 1, kv_strides, nullptr, stream);
     if (rc != MIXKVQ_OK) return rc;
     return mixkvq_decode_attention(c, q, out, lse, scale, accumulate_q, stream);

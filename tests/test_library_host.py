@@ -130,3 +130,37 @@ def test_header_is_plain_c(tmp_path):
     sizes = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
     import paper_2512_19206_amd.binding as Bd
     assert sizes == [C.sizeof(Bd.Config), C.sizeof(Bd.BlockLayout), C.sizeof(Bd.Sizes), C.sizeof(Bd.Buffers)]
+
+
+def test_host_state_machine_under_address_and_undefined_behaviour_sanitizers(M, tmp_path):
+    """csrc/api.hip (configuration checks, layout, handle, token-count state machine, error paths) compiled with
+    -fsanitize=address and -fsanitize=undefined on the HOST side, linked with the regular kernel objects and driven by
+    tests/host_shim_driver.c.  Host functions only: no kernel runs (without a GPU the launches fail inside HIP, and
+    the driver checks that such a failure leaves the token counts unchanged)."""
+    import subprocess
+    from paper_2512_19206_amd import build as B
+    objs = [os.path.join(B.OBJ_DIR, os.path.splitext(s)[0] + ".o") for s in B.SOURCES if s != "api.hip"]
+    if not all(os.path.exists(o) for o in objs):
+        B.build_library()
+    hipcc = B.hipcc_path()
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
+    api_o = str(tmp_path / "api_san.o")
+    drv_o = str(tmp_path / "driver.o")
+    exe = str(tmp_path / "host_shim_driver")
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", B.CSRC]
+    run = lambda cmd: subprocess.run(cmd, capture_output=True, text=True)
+    r = run([hipcc, "-O1", "-g", "-std=c++17", "--offload-arch=gfx950", "-fPIC"] + san + inc +
+            ["-c", os.path.join(B.CSRC, "api.hip"), "-o", api_o])
+    assert r.returncode == 0, r.stdout + r.stderr
+    r = run(["gcc", "-O1", "-g", "-std=c99", "-Wall", "-Werror", "-fsanitize=address", "-fsanitize=undefined",
+             "-fno-sanitize-recover=undefined"] + inc + ["-c", os.path.join(ROOT, "tests", "host_shim_driver.c"), "-o", drv_o])
+    assert r.returncode == 0, r.stdout + r.stderr
+    r = run([hipcc, "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize",
+             drv_o, api_o] + objs + ["-o", exe])
+    assert r.returncode == 0, r.stdout + r.stderr
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=120)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "host shim driver: ok" in r.stdout
+    assert "runtime error" not in r.stderr and "AddressSanitizer" not in r.stderr, r.stderr
