@@ -118,7 +118,10 @@ bool try_launch_decode_mfma(const CacheView& v, const __half* q, float scale, in
   bool ok = true;
 #define MIXKVQ_CASE(K4_, K16_, NVG_, NKL_, RG_, THR_, G32_, PG_, RH_)                                               \
   if (c.k4 == K4_ && c.k16 == K16_ && nvg == NVG_ && nkl <= NKL_ && c.policy == THR_ && g32 == G32_ && paged == PG_ && \
-      rh == RH_ && (RG_ == 0 || (c.R == 128 && c.Gk == 128)))                                                       \
+      rh == RH_ && (RG_ == 0 || (c.R == 128 && c.Gk == 128 && HalfSplit<K4_, K16_, THR_>::off_klo == v.lay.off_klo &&  \
+                                 HalfSplit<K4_, K16_, THR_>::off_k4 == v.lay.off_k4 &&                              \
+                                 HalfSplit<K4_, K16_, THR_>::off_k16 == v.lay.off_k16 &&                            \
+                                 HalfSplit<K4_, K16_, THR_>::off_v == v.lay.off_v)))                                \
     e = launch_one<K4_, K16_, NVG_, NKL_, RG_, THR_, G32_, PG_, RH_>(v, q, scale, n_blocks, n_res, n_splits, part, out, lse,  \
                                                            accumulate_q, nt, sc, s, ev_start, ev_stop);             \
   else

@@ -173,6 +173,25 @@ struct Tiers {
   static_assert(K16 <= 32, "the fp16 tier must fit one MFMA step");
 };
 
+// Which 1-KiB pieces of the key part the FIRST 64 tokens of a record of 128 tokens with one key group need
+// (the small planes, the first half of each code plane): a wavefront stages those, works on the first half while
+// the other pieces may still be on their way, and stages the rest before the second half.  The plane offsets
+// are those of mixkvq_block_layout for R = Gk = 128; the launcher checks them against the cache's layout.
+template <int K4, int K16, int THR>
+struct HalfSplit {
+  static constexpr int al(int n) { return (n + 15) / 16 * 16; }
+  static constexpr int ks = K4 + K16, NL = THR ? kD : kD - ks, Wlo = (NL + 15) / 16, NLp = 16 * Wlo, W4 = K4 / 8;
+  static constexpr int off_klo = al(ks) + al(4) + 2 * al(NLp * 2) + 2 * al(K4 * 2);
+  static constexpr int off_k4 = off_klo + al(128 * Wlo * 4);
+  static constexpr int off_k16 = off_k4 + al(128 * W4 * 4);
+  static constexpr int off_v = off_k16 + al(128 * K16 * 2);
+  static constexpr bool overlaps(int c, int lo, int hi) { return lo < hi && 1024 * c < hi && lo < 1024 * (c + 1); }
+  static constexpr bool early(int c) {
+    return overlaps(c, 0, off_klo + 64 * Wlo * 4) || overlaps(c, off_k4, off_k4 + 64 * W4 * 4) ||
+           overlaps(c, off_k16, off_k16 + 64 * K16 * 2);
+  }
+};
+
 // Contraction slots.  Every lane group runs the same code; a lane group whose word does not
 // exist reads a clamped address and meets a zero in the small operand.
 //   2-bit tier, step 2u+x (u < NU, x = 0,1): lane group kg unpacks half x of word c = 4u+kg;
@@ -339,13 +358,23 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   for (int c = 0; c < NVM; ++c) vmoff[c] = (unsigned)off_v_s + 16u * (unsigned)(c * 64 + lane < nvm ? c * 64 + lane : nvm - 1);
   // byte offset of this lane's value words in token group 0 of a record: channels value_channel(0, 0..3, n) of row kgv
   const unsigned voff = (unsigned)off_v + 4u * (unsigned)(kgv * kD) + (NVG == 4 ? 8u : 16u) * (unsigned)n;
-#define MIXKVQ_ISSUE_K_LOADS(REC)                                                                           \
+  /* RG variants split a record's key part in the pieces its first 64 tokens need (EARLY, with the value */       \
+  /* metadata) and the rest (LATE); elsewhere everything is EARLY */
+  using HS = HalfSplit<K4, K16, THR>;
+#define MIXKVQ_IS_EARLY(C) (!RG || HS::early(C))
+#define MIXKVQ_ISSUE_K_EARLY(REC)                                                                           \
   {                                                                                                          \
     const unsigned char* rec_ = MIXKVQ_REC(REC);                                                             \
     _Pragma("unroll") for (int c = 0; c < NKL; ++c)                                                         \
-        kreg[c] = *reinterpret_cast<const u32x4*>(rec_ + koff[c]);                                           \
+        if (MIXKVQ_IS_EARLY(c)) kreg[c] = *reinterpret_cast<const u32x4*>(rec_ + koff[c]);                   \
     _Pragma("unroll") for (int c = 0; c < NVM; ++c)                                                         \
         vmreg[c] = *reinterpret_cast<const u32x4*>(rec_ + vmoff[c]);                                         \
+  }
+#define MIXKVQ_ISSUE_K_LATE(REC)                                                                            \
+  {                                                                                                          \
+    const unsigned char* rec_ = MIXKVQ_REC(REC);                                                             \
+    _Pragma("unroll") for (int c = 0; c < NKL; ++c)                                                         \
+        if (!MIXKVQ_IS_EARLY(c)) kreg[c] = *reinterpret_cast<const u32x4*>(rec_ + koff[c]);                  \
   }
   /* the four value words of vreg[.][X]: channels value_channel(X, 0..3, n) of the token group row at byte ROWB_ */
 #define MIXKVQ_LOAD_VWORDS(DST, ROWB_, X)                                                                    \
@@ -503,7 +532,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
       vr[it] = *reinterpret_cast<const u32x4*>(src + 8 * (ci & 15));
     }
   }
-  if (blk < blk_hi) MIXKVQ_ISSUE_K_LOADS(rec_first)
+  if (blk < blk_hi) MIXKVQ_ISSUE_K_EARLY(rec_first)
 
   // ---- normalise q per head: qn = q * 2^-Eq with max|qn| in [1/2, 1) ----
   {
@@ -553,7 +582,13 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   // q in the slot order of the first record, while that record is still on its way (its value words are
   // asked for only now: the first answers come the sooner the less every wavefront asks for at once)
   if (blk < blk_hi) {
-    MIXKVQ_ISSUE_V_LOADS(rec_first)
+    if (RG) {      // in the order of use: first half of the values, rest of the keys, second half of the values
+      MIXKVQ_ISSUE_V_HALF(rec_first, 0)
+      MIXKVQ_ISSUE_K_LATE(rec_first)
+      MIXKVQ_ISSUE_V_HALF(rec_first, 1)
+    } else {
+      MIXKVQ_ISSUE_V_LOADS(rec_first)
+    }
 #pragma unroll
     for (int i = 0; i < kSelWords; ++i) sel_prev[i] = __builtin_amdgcn_readfirstlane(sel_first[i]);
     MIXKVQ_REBUILD_Q(sel_prev, true)
@@ -762,12 +797,13 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   for (; blk < blk_hi; blk += blk_step) {
     // ---- stage the key part and value metadata in LDS (wave-private: no barrier needed) ----
 #pragma unroll
-    for (int c = 0; c < NKL; ++c) reinterpret_cast<u32x4*>(sK)[c * 64 + lane] = kreg[c];
+    for (int c = 0; c < NKL; ++c)
+      if (MIXKVQ_IS_EARLY(c)) reinterpret_cast<u32x4*>(sK)[c * 64 + lane] = kreg[c];
 #pragma unroll
     for (int c = 0; c < NVM; ++c) reinterpret_cast<u32x4*>(sVm)[c * 64 + lane < nvm ? c * 64 + lane : nvm - 1] = vmreg[c];
     wave_lds_handoff();
     const unsigned rec_nx = MIXKVQ_REC_INDEX(blk + blk_step, slot_nx);     // the next record of this wavefront
-    if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_K_LOADS(rec_nx)
+    if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_K_EARLY(rec_nx)
     int slot_nn = 0;      // requested behind the record loads; needed only after they have arrived
     if (tab && blk + 2 * blk_step < blk_hi) slot_nn = tab[blk + 2 * blk_step];
     // Value scales above 255 (a group of values that spans more than 765) would overflow p' * s in fp16.  Such a
@@ -811,6 +847,13 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
     float zdot = 0.f, C = 0.f, Cz = 0.f, zc = 0.f, W = 0.f;
 #pragma unroll
     for (int hsg = 0; hsg < 2; ++hsg) {       // super-groups of 64 tokens
+      if (RG && hsg == 1) {     // the pieces of the key part that only the second half needs
+#pragma unroll
+        for (int c = 0; c < NKL; ++c)
+          if (!MIXKVQ_IS_EARLY(c)) reinterpret_cast<u32x4*>(sK)[c * 64 + lane] = kreg[c];
+        wave_lds_handoff();
+        if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_K_LATE(rec_nx)
+      }
       if (64 * hsg < R) {
         // ---- S^T tiles: tile x holds tokens 64*hsg + tokbase(row) + offx[x] ----
         constexpr int offx[4] = {0, 1, G32 ? 32 : 8, G32 ? 33 : 9};
@@ -975,7 +1018,9 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
     ++phase_i;
   }
   MIXKVQ_PHASE(14)
-#undef MIXKVQ_ISSUE_K_LOADS
+#undef MIXKVQ_ISSUE_K_EARLY
+#undef MIXKVQ_ISSUE_K_LATE
+#undef MIXKVQ_IS_EARLY
 #undef MIXKVQ_REC
 #undef MIXKVQ_REC_INDEX
 #undef MIXKVQ_ISSUE_V_LOADS
