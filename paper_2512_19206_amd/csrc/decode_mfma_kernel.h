@@ -36,6 +36,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMfmaThreads = 256;
+constexpr int kComputeUnits = 256;              // MI355X
 constexpr int kWaves = kMfmaThreads / 64;
 constexpr int kKPartMax = 12288;                // bytes of a record before the value plane (staged in LDS)
 constexpr int kVMetaMax = 2048;                 // value scales + zero-points of one block
@@ -238,6 +239,15 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   }
   // (the wavefront index is the same in all lanes: as a scalar it keeps record indices and addresses off the vector ALU)
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, n = lane & 15, kg = lane >> 4;
+  // Two workgroups share a compute unit, and among wavefronts of equal priority a SIMD issues from the OLDER one
+  // first.  With one round of workgroups (at most two per compute unit, all resident from the start) the workgroups
+  // of the second half of the grid are the younger ones everywhere: measured, their wavefronts finished 30 % later
+  // than their neighbours, which then left the SIMDs to a single wavefront each for the last quarter of the kernel.
+  // The younger wavefronts therefore raise their priority during every second half-record (s_setprio only reorders
+  // instruction issue): each of the two then wins about half of the time and both finish together.
+  const int n_wgs = gridDim.x * gridDim.y;
+  const bool younger = n_wgs > kComputeUnits && n_wgs <= 2 * kComputeUnits &&
+                       (int)(blockIdx.y * gridDim.x + blockIdx.x) >= kComputeUnits;
   const int head = n & 7, role = n >> 3;     // role 0: head of q*s, role 1: tail
   const bool live = head < g;
 
@@ -855,6 +865,10 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_K_LATE(rec_nx)
       }
       if (64 * hsg < R) {
+        if (younger) {      // (measured: raising the priority for more than half of the time is worse)
+          if (hsg) __builtin_amdgcn_s_setprio(1);
+          else __builtin_amdgcn_s_setprio(0);
+        }
         // ---- S^T tiles: tile x holds tokens 64*hsg + tokbase(row) + offx[x] ----
         constexpr int offx[4] = {0, 1, G32 ? 32 : 8, G32 ? 33 : 9};
         unsigned wlo[NU][4], wh4[4];
