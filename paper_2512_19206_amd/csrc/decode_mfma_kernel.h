@@ -289,11 +289,35 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   const int rec_chunks = rec_bytes >> 4;
   const int nvm = (rec_bytes - off_v_s) >> 4;     // 16-byte chunks of the value scale/zero planes
   // LDS byte offsets of this lane's words in token `tokbase` (clamped to existing words)
-  int lo_word_off[NU];
+  // With 8 two-bit words per token a token's row is 32 bytes, and the 16 tokens a lane group reads in one
+  // instruction (even or odd tokens, 2 apart, in four runs 16 apart) would share 4 of the 64 LDS banks.  Such a
+  // plane (SWZ) is staged with its 16-byte pieces permuted inside every aligned run of four: piece J goes to
+  // J ^ ((J >> 5) & 3), i.e. bits 4..5 of the token index are XORed into the two address bits that are the same for
+  // all lanes of an instruction; the 64 lanes then cover all banks.
+  constexpr bool SWZ = T::Wlo == 8;
+  constexpr int kOffx[4] = {0, 1, G32 ? 32 : 8, G32 ? 33 : 9};      // token offsets of the four tiles of a 64-token span
+  int lo_word_off[NU][SWZ ? 4 : 1];     // [round][tile] (one entry per round without the permutation)
 #pragma unroll
   for (int u = 0; u < NU; ++u) {
     const int c = 4 * u + kg < T::Wlo ? 4 * u + kg : T::Wlo - 1;
-    lo_word_off[u] = off_klo + 4 * (tokbase * T::Wlo + c);
+    if (SWZ) {
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        const int tk = tokbase + kOffx[x], piece = 2 * tk + (c >> 2);
+        lo_word_off[u][x] = off_klo + 16 * (piece ^ ((piece >> 5) & 3)) + 4 * (c & 3) - 4 * kOffx[x] * T::Wlo;
+      }
+    } else {
+      lo_word_off[u][0] = off_klo + 4 * (tokbase * T::Wlo + c);
+    }
+  }
+  // LDS piece a lane stages its c-th 16-byte piece of a record to
+  int kst[NKL];
+#pragma unroll
+  for (int c = 0; c < NKL; ++c) {
+    int piece = c * 64 + lane;
+    const int j = piece - (off_klo >> 4);
+    if (SWZ && j >= 0 && j < 2 * R) piece = (off_klo >> 4) + (j ^ ((j >> 5) & 3));
+    kst[c] = piece;
   }
   const int h4_word_off = off_k4 + 4 * (tokbase * T::W4 + (kg < T::W4 ? kg : 0));
   const int k16_off = off_k16 + 2 * (tokbase * K16 + (8 * kg < K16 ? 8 * kg : 0));
@@ -763,7 +787,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
       const int tk = 64 * hsg + offx[x];                                                                 \
     _Pragma("unroll")                                                                                    \
       for (int u = 0; u < NU; ++u)                                                                       \
-        wlo[u][x] = *reinterpret_cast<const unsigned*>(sK + lo_word_off[u] + 4 * tk * T::Wlo);           \
+        wlo[u][x] = *reinterpret_cast<const unsigned*>(sK + lo_word_off[u][SWZ ? x : 0] + 4 * tk * T::Wlo); \
       if (K4 > 0) wh4[x] = *reinterpret_cast<const unsigned*>(sK + h4_word_off + 4 * tk * T::W4);        \
     }                                                                                                    \
     _Pragma("unroll")                                                                                    \
@@ -808,7 +832,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
     // ---- stage the key part and value metadata in LDS (wave-private: no barrier needed) ----
 #pragma unroll
     for (int c = 0; c < NKL; ++c)
-      if (MIXKVQ_IS_EARLY(c)) reinterpret_cast<u32x4*>(sK)[c * 64 + lane] = kreg[c];
+      if (MIXKVQ_IS_EARLY(c)) reinterpret_cast<u32x4*>(sK)[SWZ ? kst[c] : c * 64 + lane] = kreg[c];
 #pragma unroll
     for (int c = 0; c < NVM; ++c) reinterpret_cast<u32x4*>(sVm)[c * 64 + lane < nvm ? c * 64 + lane : nvm - 1] = vmreg[c];
     wave_lds_handoff();
@@ -860,7 +884,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
       if (RG && hsg == 1) {     // the pieces of the key part that only the second half needs
 #pragma unroll
         for (int c = 0; c < NKL; ++c)
-          if (!MIXKVQ_IS_EARLY(c)) reinterpret_cast<u32x4*>(sK)[c * 64 + lane] = kreg[c];
+          if (!MIXKVQ_IS_EARLY(c)) reinterpret_cast<u32x4*>(sK)[SWZ ? kst[c] : c * 64 + lane] = kreg[c];
         wave_lds_handoff();
         if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_K_LATE(rec_nx)
       }
@@ -870,7 +894,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
           else __builtin_amdgcn_s_setprio(0);
         }
         // ---- S^T tiles: tile x holds tokens 64*hsg + tokbase(row) + offx[x] ----
-        constexpr int offx[4] = {0, 1, G32 ? 32 : 8, G32 ? 33 : 9};
+        constexpr int offx[4] = {kOffx[0], kOffx[1], kOffx[2], kOffx[3]};
         unsigned wlo[NU][4], wh4[4];
         f32x4 S[4], S16[2];
 #pragma unroll
