@@ -190,6 +190,15 @@ int mixkvq_select_channels_seq(mixkvq_cache* c, int32_t b, const void* q, int32_
 int mixkvq_quantize_append(mixkvq_cache* c, const void* k_new, const void* v_new, int32_t n_new,
                            const int64_t kv_strides[3], const uint8_t* sel, void* stream);
 
+/* A prompt in one call: the same selection, records and cache state as
+ *   mixkvq_select_channels(c, q, Lq, q_strides, k, L, kv_strides, sel, stream) followed by
+ *   mixkvq_quantize_append(c, k, v, L, kv_strides, sel, stream),
+ * with the same argument rules and errors, all of them checked before anything is enqueued: a prompt that does not
+ * fit (ECAPACITY) leaves the |q| accumulator untouched as well (Section 4.2 scores the prompt, Appendix D.1 stores
+ * it).  sel: DEVICE u8 [B][Hkv][k16+k4], written. */
+int mixkvq_prefill(mixkvq_cache* c, const void* q, int32_t Lq, const int64_t q_strides[3], const void* k, const void* v,
+                   int32_t L, const int64_t kv_strides[3], uint8_t* sel, void* stream);
+
 /* mixkvq_quantize_append for sequence b alone: k_new, v_new DEVICE [Hkv][n_new][D] with element strides
  * {head, token}, sel DEVICE u8 [Hkv][k16+k4] or NULL.  The other sequences are untouched. */
 int mixkvq_quantize_append_seq(mixkvq_cache* c, int32_t b, const void* k_new, const void* v_new, int32_t n_new,

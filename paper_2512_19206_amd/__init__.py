@@ -26,3 +26,7 @@ def mixkvq_decode_path(cache: Cache) -> int:
 
 def mixkvq_decode_attention_noalloc(cache: Cache, q, out, lse, scale=0.0, accumulate_q=False, stream=None):
     return cache.decode_attention_noalloc(q, out, lse, scale=scale, accumulate_q=accumulate_q, stream=stream)
+
+
+def mixkvq_prefill(cache: Cache, q, k, v, sel=None, stream=None):
+    return cache.prefill(q, k, v, sel=sel, stream=stream)

@@ -19,7 +19,7 @@ PATH_NONE, PATH_MATRIX, PATH_VECTOR = 0, 1, 2
 
 EXPORTS = ("mixkvq_block_layout", "mixkvq_cache_sizes", "mixkvq_cache_create", "mixkvq_cache_destroy",
            "mixkvq_cache_set_block_table", "mixkvq_cache_set_state", "mixkvq_cache_set_state_seq", "mixkvq_cache_reset", "mixkvq_cache_reset_seq", "mixkvq_cache_state", "mixkvq_cache_state_seq",
-           "mixkvq_select_channels", "mixkvq_select_channels_seq", "mixkvq_quantize_append", "mixkvq_quantize_append_seq",
+           "mixkvq_select_channels", "mixkvq_select_channels_seq", "mixkvq_quantize_append", "mixkvq_quantize_append_seq", "mixkvq_prefill",
            "mixkvq_decode_attention", "mixkvq_decode_attention_noalloc", "mixkvq_decode_step", "mixkvq_set_timing_events", "mixkvq_decode_path",
            "mixkvq_strerror")
 
@@ -80,6 +80,7 @@ def load_library() -> C.CDLL:
     lib.mixkvq_quantize_append_seq.argtypes = [vp, i32, vp, vp, i32, i64p, vp, vp]
     lib.mixkvq_select_channels.argtypes = [vp, vp, i32, i64p, vp, i32, i64p, vp, vp]
     lib.mixkvq_quantize_append.argtypes = [vp, vp, vp, i32, i64p, vp, vp]
+    lib.mixkvq_prefill.argtypes = [vp, vp, i32, i64p, vp, vp, i32, i64p, vp, vp]
     lib.mixkvq_decode_attention.argtypes = [vp, vp, vp, vp, C.c_float, i32, vp]
     lib.mixkvq_decode_attention_noalloc.argtypes = [vp, vp, vp, vp, C.c_float, i32, vp]
     lib.mixkvq_decode_step.argtypes = [vp, vp, vp, i64p, vp, vp, vp, C.c_float, i32, vp]
@@ -251,6 +252,17 @@ class Cache:
         qp, Lq, qs = (None, 0, None) if q is None else (q.data_ptr(), q.shape[2], _strides3(q))
         _check(self.lib.mixkvq_select_channels(self.handle, qp, Lq, qs, k.data_ptr(), k.shape[2], _strides3(k),
                                                sel.data_ptr(), _stream_ptr(stream)))
+        return sel
+
+    def prefill(self, q, k, v, sel=None, stream=None):
+        """q: fp16 [B, Hq, Lq, D] or None; k, v: fp16 [B, Hkv, L, D] with equal strides.  Scoring, selection and
+        append of a prompt in one call; returns the selection u8 [B, Hkv, ks]."""
+        assert k.stride() == v.stride() and k.shape == v.shape
+        if sel is None:
+            sel = torch.empty((self.cfg.B, self.cfg.Hkv, self.ks), dtype=torch.uint8, device=self.device)
+        qp, Lq, qs = (None, 0, None) if q is None else (q.data_ptr(), q.shape[2], _strides3(q))
+        _check(self.lib.mixkvq_prefill(self.handle, qp, Lq, qs, k.data_ptr(), v.data_ptr(), k.shape[2], _strides3(k),
+                                       sel.data_ptr(), _stream_ptr(stream)))
         return sel
 
     def quantize_append(self, k_new, v_new, sel=None, stream=None):

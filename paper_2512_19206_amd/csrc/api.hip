@@ -429,6 +429,30 @@ int mixkvq_quantize_append(mixkvq_cache* c, const void* k_new, const void* v_new
   return rc;
 }
 
+int mixkvq_prefill(mixkvq_cache* c, const void* q, int32_t Lq, const int64_t q_strides[3], const void* k, const void* v,
+                   int32_t L, const int64_t kv_strides[3], uint8_t* sel, void* stream) {
+  if (!c || !k || !v || !kv_strides || !sel || L < 1 || Lq < 0) return MIXKVQ_EINVAL;
+  if (Lq > 0 && (!q || !q_strides)) return MIXKVQ_EINVAL;
+  if (c->v.cfg.k4 + c->v.cfg.k16 == 0) return MIXKVQ_EINVAL;
+  // everything the append could refuse is checked before the scoring pass touches the accumulator
+  int rc = check_kv_args(k, v, kv_strides, 3);
+  if (rc != MIXKVQ_OK) return rc;
+  const mixkvq_config& cfg = c->v.cfg;
+  for (int b = 0; b < cfg.B; ++b) {
+    const AppendPlan pl = plan_append(cfg, c->Rw, c->seq[b], L);
+    if (c->seq[b].n_quant + pl.F * c->Rw > cfg.T_max) return MIXKVQ_ECAPACITY;
+    if (pl.F > (1 << 24)) return MIXKVQ_EINVAL;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  if (Lq > 0) {
+    Strides3 qs{q_strides[0], q_strides[1], q_strides[2]};
+    MIXKVQ_TRY_HIP(launch_qabs_accumulate(c->v, (const __half*)q, Lq, qs, s));
+  }
+  Strides3 ks{kv_strides[0], kv_strides[1], kv_strides[2]};
+  MIXKVQ_TRY_HIP(launch_select(c->v, (const __half*)k, L, ks, sel, s));
+  return mixkvq_quantize_append(c, k, v, L, kv_strides, sel, stream);
+}
+
 int mixkvq_quantize_append_seq(mixkvq_cache* c, int32_t b, const void* k_new, const void* v_new, int32_t n_new,
                                const int64_t kv_strides[2], const uint8_t* sel, void* stream) {
   if (!c || b < 0 || b >= c->v.cfg.B || n_new < 0) return MIXKVQ_EINVAL;

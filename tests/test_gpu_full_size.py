@@ -107,8 +107,7 @@ def test_prefill_configuration_at_its_own_shape(H):
     dk, dv, dq, host = bench.build_prefill_inputs(4, w, w.T)
     kw = dict(D=w.D, T_max=w.T, Gk=w.Gk, Gv=w.Gv, R=w.R, k4=w.k4, k16=w.k16)
     gc = M.Cache(M.make_config(B=w.B, Hq=w.Hq, Hkv=w.Hkv, **kw))
-    sel = M.mixkvq_select_channels(gc, dq, dk)
-    M.mixkvq_quantize_append(gc, dk, dv, sel=sel)
+    sel = M.mixkvq_prefill(gc, dq, dk, dv)      # scoring + selection + pack in one call, as bench.py's step
     torch.cuda.synchronize()
     del dq
     nq, r = gc.state()
