@@ -608,22 +608,30 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
           rc[i] = doff[i] < 0 ? 0.f : sR[grp * kD + d];   // (0, 0) gives code 0: the padding of the last word
           nz[i] = doff[i] < 0 ? 0.f : sNZ[grp * kD + d];
         }
-        for (int tt = tl; tt < Gk; tt += 32) {
-          const int t = grp * Gk + tt;
-          const __half* row = sT + t * kRowStride;
+        // LDS address of each of the 16 elements in this thread's first token of the group; its other tokens are 32
+        // rows further each, a compile-time distance once the loop is unrolled (no address arithmetic per element)
+        const __half* col[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) col[i] = sT + (grp * Gk + tl) * kRowStride + (doff[i] < 0 ? 0 : doff[i]);
+        const int n_it = (Gk - tl + 31) / 32;      // tokens tl, tl + 32, ... below Gk: at most 4 (Gk <= 128)
+#pragma unroll
+        for (int k = 0; k < kMaxR / 32; ++k) {
+          if (k >= n_it) break;
+          const int t = grp * Gk + tl + 32 * k;
           float hw[2] = {0.f, 0.f};
           float dev = 0.f;
 #pragma unroll
           for (int i = 0; i < 16; ++i)
-            add_code<2>(hw, i, code_fast(row[doff[i] < 0 ? 0 : doff[i]], rc[i], nz[i], dev));
+            add_code<2>(hw, i, code_fast(col[i][k * 32 * kRowStride], rc[i], nz[i], dev));
           if (__any(dev > 0.5f - kEps2)) {     // some quotient sits next to a rounding boundary (exact ties are common)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {     // find the codes concerned and correct them
               const int d = doff[i] < 0 ? 0 : doff[i];
+              const __half x = col[i][k * 32 * kRowStride];
               float dv = 0.f;
-              const float c = code_fast(row[d], rc[i], nz[i], dv);
+              const float c = code_fast(x, rc[i], nz[i], dv);
               if (__any(dv > 0.5f - kEps2))
-                add_code<2>(hw, i, code_exact(row[d], doff[i] < 0 ? 0u : sSZ[grp * kD + d], 3.f) - c);
+                add_code<2>(hw, i, code_exact(x, doff[i] < 0 ? 0u : sSZ[grp * kD + d], 3.f) - c);
             }
           }
           const unsigned w = join_halves(hw);
