@@ -243,8 +243,8 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   // first.  With one round of workgroups (at most two per compute unit, all resident from the start) the workgroups
   // of the second half of the grid are the younger ones everywhere: measured, their wavefronts finished 30 % later
   // than their neighbours, which then left the SIMDs to a single wavefront each for the last quarter of the kernel.
-  // The younger wavefronts therefore raise their priority during every second half-record (s_setprio only reorders
-  // instruction issue): each of the two then wins about half of the time and both finish together.
+  // The younger wavefronts therefore raise their priority during five of every eight half-records (s_setprio only
+  // reorders instruction issue): each of the two then wins about half of the time and both finish nearly together.
   const int n_wgs = gridDim.x * gridDim.y;
   const bool younger = n_wgs > kComputeUnits && n_wgs <= 2 * kComputeUnits &&
                        (int)(blockIdx.y * gridDim.x + blockIdx.x) >= kComputeUnits;
@@ -828,7 +828,8 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 
   MIXKVQ_PHASE(2)
   [[maybe_unused]] int phase_i = 3;
-  for (; blk < blk_hi; blk += blk_step) {
+  [[maybe_unused]] int prio_iter = 0;
+  for (; blk < blk_hi; blk += blk_step, ++prio_iter) {
     // ---- stage the key part and value metadata in LDS (wave-private: no barrier needed) ----
 #pragma unroll
     for (int c = 0; c < NKL; ++c)
@@ -889,8 +890,8 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         if (blk + blk_step < blk_hi) MIXKVQ_ISSUE_K_LATE(rec_nx)
       }
       if (64 * hsg < R) {
-        if (younger) {      // (measured: raising the priority for more than half of the time is worse)
-          if (hsg) __builtin_amdgcn_s_setprio(1);
+        if (younger) {      // 5 of 8 half-records (measured: 4 of 8 nearly as good, 3 of 8 and 6 of 8 and more worse)
+          if (hsg || (prio_iter & 3) == 0) __builtin_amdgcn_s_setprio(1);
           else __builtin_amdgcn_s_setprio(0);
         }
         // ---- S^T tiles: tile x holds tokens 64*hsg + tokbase(row) + offx[x] ----
