@@ -208,7 +208,8 @@ hipError_t launch_merge_pair(const CacheView& v, const float* part, int n_splits
 template <int K4, int K16, int NVG, int NKL, int RG, int THR, int G32, int PG, int RH>
 __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __restrict__ q, float scale_log2e,
                                           int n_blocks, int n_res, int n_splits, float* __restrict__ part,
-                                          int accumulate_q, const NewToken& nt, const SeqCounts& sc, unsigned char* smem) {
+                                          int accumulate_q, const NewToken& nt, const SeqCounts& sc, unsigned char* smem,
+                                          __half* __restrict__ fin_out, float* __restrict__ fin_lse) {
   using T = Tiers<K4, K16, THR>;
   constexpr int NU = T::NU;
   // scalars of the by-value view (kept in SGPRs; no references into the kernel argument)
@@ -1129,7 +1130,21 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 #pragma unroll
     for (int w = 0; w < kWaves; ++w)
       acc += mw[w] == -INFINITY ? 0.f : r0[w * kWaveF + src] * __builtin_amdgcn_exp2f(mw[w] - m_wg);
-    if (i < g * kD) {
+    if (fin_out) {
+      // the pair's only workgroup: the result is final (what the merge kernel would make of a single partial)
+      float lw = 0.f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w)
+        lw += mw[w] == -INFINITY ? 0.f : r0[w * kWaveF + 8 * kD + h] * __builtin_amdgcn_exp2f(mw[w] - m_wg);
+      const size_t bh = (size_t)b * Hq + (size_t)jkv * g + h;
+      if (i < g * kD) {
+        const float r = lw > 0.f ? acc / lw : 0.f;      // l == 0: a sequence without tokens
+        reinterpret_cast<unsigned short*>(fin_out)[bh * kD + (i % kD)] =
+            cv.cfg.in_dtype ? f32_to_bf16_bits(r) : __half_as_ushort(__float2half_rn(r));
+      } else if (fin_lse) {
+        fin_lse[bh] = lw > 0.f ? m_wg * 0.6931471805599453f + __logf(lw) : -INFINITY;
+      }
+    } else if (i < g * kD) {
       out[h * kPartStrideM + (i % kD)] = acc;
     } else {
       out[h * kPartStrideM + kD] = m_wg * 0.6931471805599453f;
@@ -1145,10 +1160,11 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
 template <int K4, int K16, int NVG, int NKL, int RG, int THR, int G32, int PG, int RH>
 __global__ void __launch_bounds__(kMfmaThreads, 2)
 decode_fused_kernel(CacheView cv, const __half* __restrict__ q, float scale, int n_blocks, int n_res, int n_splits,
-                    float* __restrict__ part, int accumulate_q, NewToken nt, SeqCounts sc) {
+                    float* __restrict__ part, int accumulate_q, NewToken nt, SeqCounts sc, __half* __restrict__ fin_out,
+                    float* __restrict__ fin_lse) {
   extern __shared__ __align__(16) unsigned char smem[];
   mfma_part<K4, K16, NVG, NKL, RG, THR, G32, PG, RH>(cv, q, scale * 1.4426950408889634f, n_blocks, n_res, n_splits, part,
-                                             accumulate_q, nt, sc, smem);
+                                             accumulate_q, nt, sc, smem, fin_out, fin_lse);
 }
 
 template <int K4, int K16, int NVG, int NKL, int RG, int THR, int G32, int PG, int RH>
@@ -1167,14 +1183,19 @@ static hipError_t launch_one(const CacheView& v, const __half* q, float scale, i
     if (e != hipSuccess) return e;
     attr_set.fetch_or(bit, std::memory_order_release);
   }
+  // a pair with a single workgroup needs no merge: that workgroup writes the output itself
+  __half* fin_out = n_splits == 1 ? out : nullptr;
+  float* fin_lse = n_splits == 1 ? lse : nullptr;
   if (ev_start && ev_stop) {
     // profiling aid: the two events take the start and the end time of this kernel itself (not of the launch call)
     hipExtLaunchKernelGGL(kern, dim3(v.P, n_splits), dim3(kMfmaThreads), (uint32_t)lds, s, ev_start, ev_stop, 0u, v, q,
-                          scale, n_blocks, n_res, n_splits, part, accumulate_q, nt, sc);
+                          scale, n_blocks, n_res, n_splits, part, accumulate_q, nt, sc, fin_out, fin_lse);
   } else {
-    kern<<<dim3(v.P, n_splits), dim3(kMfmaThreads), lds, s>>>(v, q, scale, n_blocks, n_res, n_splits, part, accumulate_q, nt, sc);
+    kern<<<dim3(v.P, n_splits), dim3(kMfmaThreads), lds, s>>>(v, q, scale, n_blocks, n_res, n_splits, part, accumulate_q, nt, sc,
+                                                             fin_out, fin_lse);
   }
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+  if (n_splits == 1) return hipSuccess;
   return launch_merge_pair(v, part, n_splits, out, lse, s);
 }
 
