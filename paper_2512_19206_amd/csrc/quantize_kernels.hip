@@ -619,19 +619,24 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
           if (k >= n_it) break;
           const int t = grp * Gk + tl + 32 * k;
           float hw[2] = {0.f, 0.f};
-          float dev = 0.f;
+          float dev[4] = {0.f, 0.f, 0.f, 0.f};     // per run of four codes: the search below stays short
 #pragma unroll
           for (int i = 0; i < 16; ++i)
-            add_code<2>(hw, i, code_fast(col[i][k * 32 * kRowStride], rc[i], nz[i], dev));
-          if (__any(dev > 0.5f - kEps2)) {     // some quotient sits next to a rounding boundary (exact ties are common)
+            add_code<2>(hw, i, code_fast(col[i][k * 32 * kRowStride], rc[i], nz[i], dev[i >> 2]));
+          // some quotient sits next to a rounding boundary (exact ties are common: about every other pass has one)
+          if (__any(fmaxf(fmaxf(dev[0], dev[1]), fmaxf(dev[2], dev[3])) > 0.5f - kEps2)) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {     // find the codes concerned and correct them
-              const int d = doff[i] < 0 ? 0 : doff[i];
-              const __half x = col[i][k * 32 * kRowStride];
-              float dv = 0.f;
-              const float c = code_fast(x, rc[i], nz[i], dv);
-              if (__any(dv > 0.5f - kEps2))
-                add_code<2>(hw, i, code_exact(x, doff[i] < 0 ? 0u : sSZ[grp * kD + d], 3.f) - c);
+            for (int i4 = 0; i4 < 4; ++i4) {
+              if (!__any(dev[i4] > 0.5f - kEps2)) continue;
+#pragma unroll
+              for (int i = 4 * i4; i < 4 * i4 + 4; ++i) {     // find the codes concerned and correct them
+                const int d = doff[i] < 0 ? 0 : doff[i];
+                const __half x = col[i][k * 32 * kRowStride];
+                float dv = 0.f;
+                const float c = code_fast(x, rc[i], nz[i], dv);
+                if (__any(dv > 0.5f - kEps2))
+                  add_code<2>(hw, i, code_exact(x, doff[i] < 0 ? 0u : sSZ[grp * kD + d], 3.f) - c);
+              }
             }
           }
           const unsigned w = join_halves(hw);
@@ -648,23 +653,27 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
     if (t >= R) break;
     const int grp = t / Gk, it = t * W4 + wd;
     float hw[2] = {0.f, 0.f};
-    float dev = 0.f;
+    float dev[2] = {0.f, 0.f};
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const bool used = wd * 8 + i < n_4;                    // an unused entry gets (0, 0), i.e. code 0
       const int d = used ? sHiList[k16 + wd * 8 + i] : 0;
       add_code<4>(hw, i, code_fast(sT[t * kRowStride + d], used ? sR[grp * kD + d] : 0.f,
-                                   used ? sNZ[grp * kD + d] : 0.f, dev));
+                                   used ? sNZ[grp * kD + d] : 0.f, dev[i >> 2]));
     }
-    if (__any(dev > 0.5f - kEps4)) {     // some quotient sits next to a rounding boundary
+    if (__any(fmaxf(dev[0], dev[1]) > 0.5f - kEps4)) {     // some quotient sits next to a rounding boundary
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const bool used = wd * 8 + i < n_4;
-        const int d = used ? sHiList[k16 + wd * 8 + i] : 0;
-        float dv = 0.f;
-        const float c = code_fast(sT[t * kRowStride + d], used ? sR[grp * kD + d] : 0.f, used ? sNZ[grp * kD + d] : 0.f, dv);
-        if (__any(dv > 0.5f - kEps4))
-          add_code<4>(hw, i, code_exact(sT[t * kRowStride + d], used ? sSZ[grp * kD + d] : 0u, 15.f) - c);
+      for (int i4 = 0; i4 < 2; ++i4) {
+        if (!__any(dev[i4] > 0.5f - kEps4)) continue;
+#pragma unroll
+        for (int i = 4 * i4; i < 4 * i4 + 4; ++i) {
+          const bool used = wd * 8 + i < n_4;
+          const int d = used ? sHiList[k16 + wd * 8 + i] : 0;
+          float dv = 0.f;
+          const float c = code_fast(sT[t * kRowStride + d], used ? sR[grp * kD + d] : 0.f, used ? sNZ[grp * kD + d] : 0.f, dv);
+          if (__any(dv > 0.5f - kEps4))
+            add_code<4>(hw, i, code_exact(sT[t * kRowStride + d], used ? sSZ[grp * kD + d] : 0u, 15.f) - c);
+        }
       }
     }
     const unsigned w = join_halves(hw);
@@ -758,17 +767,22 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
         }
       }
       float hw[2] = {0.f, 0.f};
-      float dev = 0.f;
+      float dev[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int i = 0; i < 16; ++i)
-        add_code<2>(hw, i, code_fast((i < 8 ? col0 : col1)[(i & 7) * kRowStride], rc[i], nz[i], dev));
-      if (__any(dev > 0.5f - kEps2)) {     // some quotient sits next to a rounding boundary
+        add_code<2>(hw, i, code_fast((i < 8 ? col0 : col1)[(i & 7) * kRowStride], rc[i], nz[i], dev[i >> 2]));
+      // some quotient sits next to a rounding boundary
+      if (__any(fmaxf(fmaxf(dev[0], dev[1]), fmaxf(dev[2], dev[3])) > 0.5f - kEps2)) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int t = (i < 8 ? tok0 : tok1) + (i & 7);
-          float dv = 0.f;
-          const float c = code_fast(sT[t * kRowStride + d], rc[i], nz[i], dv);
-          if (__any(dv > 0.5f - kEps2)) add_code<2>(hw, i, code_exact(sT[t * kRowStride + d], sSZ[t * NVG + vg], 3.f) - c);
+        for (int i4 = 0; i4 < 4; ++i4) {
+          if (!__any(dev[i4] > 0.5f - kEps2)) continue;
+#pragma unroll
+          for (int i = 4 * i4; i < 4 * i4 + 4; ++i) {
+            const int t = (i < 8 ? tok0 : tok1) + (i & 7);
+            float dv = 0.f;
+            const float c = code_fast(sT[t * kRowStride + d], rc[i], nz[i], dv);
+            if (__any(dv > 0.5f - kEps2)) add_code<2>(hw, i, code_exact(sT[t * kRowStride + d], sSZ[t * NVG + vg], 3.f) - c);
+          }
         }
       }
       const unsigned w = join_halves(hw);
