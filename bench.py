@@ -250,6 +250,12 @@ def bench_prefill(args, w, cfg_id):
     in_b, out_b = prefill_bytes(w, Lq)
     in_noq = in_b - w.B * w.Hq * Lq * w.D * 2
     value = in_b / el / 1e9
+    # measured HBM bytes of the step's three streaming kernels (the full-size workload only: that is what was profiled)
+    traffic = None
+    if w.T == S.WORKLOADS[cfg_id].T and w.B == S.WORKLOADS[cfg_id].B:
+        parts = [measured_traffic(w.name, k) for k in ("qabs_accumulate_kernel", "key_range_kernel", "flush_block_fast_kernel")]
+        if all(x is not None for x in parts):
+            traffic = round(sum(parts), 1)
     result = {
         "metric": "prefill quantization: GB/s of fp16 input consumed (K, V, prompt queries)", "value": round(value, 2),
         "unit": "GB/s", "n_gpus": 1, "steps": n_steps, "warmup": n_warm, "ms_per_step": round(el * 1e3, 4),
@@ -265,7 +271,7 @@ def bench_prefill(args, w, cfg_id):
                                         "(sel = NULL) instead of using the selection made over the whole prompt"},
         "roofline": {"bound": "hbm", "kernel": "whole step (qabs_accumulate, key_range, flush_block: streaming kernels)",
                      "achieved": round((in_b + out_b) / el / 1e9, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round((in_b + out_b) / el / 1e9 / HBM_PEAK_GBS, 4), "traffic": None},
+                     "frac": round((in_b + out_b) / el / 1e9 / HBM_PEAK_GBS, 4), "traffic": traffic},
     }
     del dq
     copy_gbs = copy_kernel_gbs()

@@ -295,7 +295,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   // plane (SWZ) is staged with its 16-byte pieces permuted inside every aligned run of four: piece J goes to
   // J ^ ((J >> 5) & 3), i.e. bits 4..5 of the token index are XORed into the two address bits that are the same for
   // all lanes of an instruction; the 64 lanes then cover all banks.
-  constexpr bool SWZ = T::Wlo == 8;
+  constexpr bool SWZ = T::Wlo == 8 && NKL <= 8;     // (variants that stage more pieces have no registers to spare for the permuted piece indices)
   constexpr int kOffx[4] = {0, 1, G32 ? 32 : 8, G32 ? 33 : 9};      // token offsets of the four tiles of a 64-token span
   int lo_word_off[NU][SWZ ? 4 : 1];     // [round][tile] (one entry per round without the permutation)
 #pragma unroll
@@ -330,6 +330,9 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   // p is rounded to fp16 once, as p' = p * 4^-sc * 2^kPBoost (p <= 1, so p' <= 2^kPBoost).  The boost keeps small
   // weights out of the fp16 subnormals: with it the weight of a token that meets a code at position 4 is resolved
   // down to 2^-25 of the wavefront's largest weight (2^-17 without).
+  // (the variants with the highest register pressure, both side tiers and four value groups, do not keep these eight
+  //  constants across the loop, where they would be spilled: they form them where they are used, two instructions each)
+  constexpr bool kLeanConstants = NVG == 4 && K4 > 0 && K16 > 0;
   float sc2f[4];        // 2 sc - kPBoost: exponent offset of p' for pair i
   unsigned w4sc[4];     // fp16 pair (4^sc 2^-kPBoost, same): turns p' back into p for the sum l
 #pragma unroll
@@ -386,9 +389,17 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   // Loads of one block.  A record's address is a scalar; every lane adds a 32-bit byte offset that is fixed for
   // the whole kernel (so the loop spends no vector instruction on addresses).  Chunk indices are clamped to the
   // record so that every lane loads and stores unconditionally (a clamped lane repeats the record's last chunk).
-  unsigned koff[NKL], vmoff[NVM];
+  // Variants that stage more than 8 KiB of key part, or have four value groups, or both side tiers with key groups of 32
+  // tokens, have no registers to spare for one offset per piece (kept, they are
+  // spilled and reloaded inside the loop, and a reload waits for every record load in flight before it): those form each
+  // offset where it is used, with an add and a minimum, from a copy of the lane's first offset that the compiler
+  // cannot see through (else it would hoist the ten to twelve results out of the loop again).
+  constexpr bool kKeepOffsets = NKL <= 8 && NVG != 4 && !(G32 && K4 > 0 && K16 > 0);
+  unsigned koff[kKeepOffsets ? NKL : 1], vmoff[NVM];
 #pragma unroll
-  for (int c = 0; c < NKL; ++c) koff[c] = 16u * (unsigned)(c * 64 + lane < rec_chunks ? c * 64 + lane : rec_chunks - 1);
+  for (int c = 0; c < (kKeepOffsets ? NKL : 1); ++c)
+    koff[c] = 16u * (unsigned)(c * 64 + lane < rec_chunks ? c * 64 + lane : rec_chunks - 1);
+  const unsigned koff_last = 16u * (unsigned)(rec_chunks - 1);
 #pragma unroll
   for (int c = 0; c < NVM; ++c) vmoff[c] = (unsigned)off_v_s + 16u * (unsigned)(c * 64 + lane < nvm ? c * 64 + lane : nvm - 1);
   // byte offset of this lane's value words in token group 0 of a record: channels value_channel(0, 0..3, n) of row kgv
@@ -397,19 +408,24 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   /* metadata) and the rest (LATE); elsewhere everything is EARLY */
   using HS = HalfSplit<K4, K16, THR>;
 #define MIXKVQ_IS_EARLY(C) (!RG || HS::early(C))
+#define MIXKVQ_KOFF(C) (kKeepOffsets ? koff[kKeepOffsets ? (C) : 0] : min(lane16_ + 1024u * (unsigned)(C), koff_last))
 #define MIXKVQ_ISSUE_K_EARLY(REC)                                                                           \
   {                                                                                                          \
     const unsigned char* rec_ = MIXKVQ_REC(REC);                                                             \
+    unsigned lane16_ = koff[0];                                                                              \
+    if (!kKeepOffsets) asm volatile("" : "+v"(lane16_));                                                     \
     _Pragma("unroll") for (int c = 0; c < NKL; ++c)                                                         \
-        if (MIXKVQ_IS_EARLY(c)) kreg[c] = *reinterpret_cast<const u32x4*>(rec_ + koff[c]);                   \
+        if (MIXKVQ_IS_EARLY(c)) kreg[c] = *reinterpret_cast<const u32x4*>(rec_ + MIXKVQ_KOFF(c));            \
     _Pragma("unroll") for (int c = 0; c < NVM; ++c)                                                         \
         vmreg[c] = *reinterpret_cast<const u32x4*>(rec_ + vmoff[c]);                                         \
   }
 #define MIXKVQ_ISSUE_K_LATE(REC)                                                                            \
   {                                                                                                          \
     const unsigned char* rec_ = MIXKVQ_REC(REC);                                                             \
+    unsigned lane16_ = koff[0];                                                                              \
+    if (!kKeepOffsets) asm volatile("" : "+v"(lane16_));                                                     \
     _Pragma("unroll") for (int c = 0; c < NKL; ++c)                                                         \
-        if (!MIXKVQ_IS_EARLY(c)) kreg[c] = *reinterpret_cast<const u32x4*>(rec_ + koff[c]);                  \
+        if (!MIXKVQ_IS_EARLY(c)) kreg[c] = *reinterpret_cast<const u32x4*>(rec_ + MIXKVQ_KOFF(c));           \
   }
   /* the four value words of vreg[.][X]: channels value_channel(X, 0..3, n) of the token group row at byte ROWB_ */
 #define MIXKVQ_LOAD_VWORDS(DST, ROWB_, X)                                                                    \
@@ -966,13 +982,22 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
         // (token 2i, token 2i+1) of this lane group's 16 tokens = PV step 0; in lanes 8..15 it is (8+2i, 9+2i) = step 1.
         unsigned pk[4];
         const float zm = zcx - m_run;
+        int role_here = role;
+        if (kLeanConstants) asm volatile("" : "+v"(role_here));
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const float k = zm - sc2f[i];
+          float sc2f_i = sc2f[i];
+          unsigned w4sc_i = w4sc[i];
+          if (kLeanConstants) {      // formed here from an opaque copy of the lane's role (see kLeanConstants)
+            const int sc_ = role_here ? sc2(4 + i) : i;
+            sc2f_i = 2.f * sc_ - (float)kPBoost;
+            w4sc_i = ((unsigned)(15 + 2 * sc_ - kPBoost) << 10) * 0x00010001u;
+          }
+          const float k = zm - sc2f_i;
           float ea = fmaf(ya[i], Mx, k), eb = fmaf(yb[i], Mx, k);
           if (RH && no_tokens) ea = eb = -INFINITY;
           pk[i] = cvt_pk(__builtin_amdgcn_exp2f(ea), __builtin_amdgcn_exp2f(eb));
-          l_run = dot2(pk[i], w4sc[i], l_run);
+          l_run = dot2(pk[i], w4sc_i, l_run);
         }
         // value scales / zero-points of the tokens this lane half pairs
         u32x4 Bp[NVG == 4 ? 2 : NVG][2];   // NVG = 4: the two value groups of one xp at a time
@@ -1060,6 +1085,7 @@ __device__ __forceinline__ void mfma_part(const CacheView& cv, const __half* __r
   MIXKVQ_PHASE(14)
 #undef MIXKVQ_ISSUE_K_EARLY
 #undef MIXKVQ_ISSUE_K_LATE
+#undef MIXKVQ_KOFF
 #undef MIXKVQ_IS_EARLY
 #undef MIXKVQ_REC
 #undef MIXKVQ_REC_INDEX
