@@ -219,6 +219,7 @@ def bench_prefill(args, w, cfg_id):
     mixkvq_prefill(Q, K, V) (= mixkvq_select_channels(Q, K), then mixkvq_quantize_append(K, V, sel)) over the whole batch."""
     import torch
     import paper_2512_19206_amd as M
+    import synth_inputs as S
     Lq = w.T
     dk, dv, dq, _ = build_prefill_inputs(cfg_id, w, Lq)
     kw = dict(B=w.B, Hq=w.Hq, Hkv=w.Hkv, D=w.D, T_max=-(-w.T // w.R) * w.R, Gk=w.Gk, Gv=w.Gv, R=w.R, k4=w.k4, k16=w.k16)
@@ -252,7 +253,7 @@ def bench_prefill(args, w, cfg_id):
     value = in_b / el / 1e9
     # measured HBM bytes of the step's three streaming kernels (the full-size workload only: that is what was profiled)
     traffic = None
-    if w.T == S.WORKLOADS[cfg_id].T and w.B == S.WORKLOADS[cfg_id].B:
+    if w == S.WORKLOADS[cfg_id]:
         parts = [measured_traffic(w.name, k) for k in ("qabs_accumulate_kernel", "key_range_kernel", "flush_block_fast_kernel")]
         if all(x is not None for x in parts):
             traffic = round(sum(parts), 1)
@@ -435,7 +436,7 @@ def bench_decode(args, cfg_id, steps, warmup, with_cpu_baseline):
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "kernel_avg_us": round(k_avg_ms * 1e3, 2), "kernel_min_us": round(min(k_ms) * 1e3, 2),
                      "launches_timed": n_ev,
-                     "traffic": measured_traffic(w.name, "decode_fused_kernel") if (on_matrix_cores and w.T == S.WORKLOADS[cfg_id].T) else None,
+                     "traffic": measured_traffic(w.name, "decode_fused_kernel") if (on_matrix_cores and w == S.WORKLOADS[cfg_id]) else None,
                      "traffic_unit": "bytes per launch (profiles/hbm_traffic.txt)",
                      "algorithmic_bytes_per_launch": step_bytes},
     }
