@@ -266,6 +266,10 @@ flush_block_kernel(CacheView cv, const __half* __restrict__ k_new, const __half*
 // The codes, scales and zero-points are bit-identical to those of flush_block_kernel.
 // ---------------------------------------------------------------------------
 typedef _Float16 fh2 __attribute__((ext_vector_type(2)));
+// Row stride of the staged tile in this kernel: 65 words, an odd number, so that the rows a wavefront reads in one
+// instruction (8 consecutive tokens x 8 word columns 8 words apart in the key loop, 64 tokens in the 4-bit loop) fall
+// into different LDS banks; rows are then only 4-byte aligned, and a 16-byte piece is staged with four 4-byte writes.
+constexpr int kFastStride = kD + 2;
 
 #ifdef MIXKVQ_PHASE_CLOCKS
 // Profiling aid, not part of the default build: 100 MHz timestamps of the phases of the first 1024 workgroups.
@@ -348,7 +352,7 @@ __device__ __forceinline__ uint4 load_chunk(const __half* res_p, const __half* f
 __global__ void __launch_bounds__(kFlushThreads, 3)   // three workgroups per CU (LDS) = three wavefronts per SIMD
 flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __half* __restrict__ v_new, Strides3 st,
                         int r0, int first_block, const uint8_t* __restrict__ sel_in) {
-  __shared__ __align__(16) __half sT[kMaxR * kRowStride];   // K tile, then V tile
+  __shared__ __align__(16) __half sT[kMaxR * kFastStride];   // K tile, then V tile
   __shared__ double sA[kD];
   __shared__ unsigned char sTier[kD];      // 0: 2 bit, 1: 4 bit, 2: fp16
   __shared__ unsigned char sPos[kD];       // position of the channel inside its tier
@@ -421,7 +425,10 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int idx = tid + kFlushThreads * i;
-    if (idx < n_chunks16) *reinterpret_cast<uint4*>(sT + (idx >> 4) * kRowStride + (idx & 15) * 8) = kreg[i];
+    if (idx < n_chunks16) {
+      unsigned* dst = reinterpret_cast<unsigned*>(sT + (idx >> 4) * kFastStride + (idx & 15) * 8);
+      dst[0] = kreg[i].x; dst[1] = kreg[i].y; dst[2] = kreg[i].z; dst[3] = kreg[i].w;
+    }
   }
   if (one_place) {
     const __half* vp = (from_res ? res_vp : v_new + pair_off) + first * row_stride + (tid & 15) * 8;
@@ -446,10 +453,10 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
     const int d2 = tid & 63;
     const unsigned* sT32 = reinterpret_cast<const unsigned*>(sT);
     for (int ch = tid >> 6; ch < n_ch; ch += 4) {
-      fh2 lo = as_h2(sT32[(16 * ch) * (kRowStride / 2) + d2]), hi = lo;
+      fh2 lo = as_h2(sT32[(16 * ch) * (kFastStride / 2) + d2]), hi = lo;
 #pragma unroll
       for (int t = 1; t < 16; ++t) {
-        const fh2 key = as_h2(sT32[(16 * ch + t) * (kRowStride / 2) + d2]);
+        const fh2 key = as_h2(sT32[(16 * ch + t) * (kFastStride / 2) + d2]);
         lo = __builtin_elementwise_min(lo, key);
         hi = __builtin_elementwise_max(hi, key);
       }
@@ -612,7 +619,7 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
         // rows further each, a compile-time distance once the loop is unrolled (no address arithmetic per element)
         const __half* col[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) col[i] = sT + (grp * Gk + tl) * kRowStride + (doff[i] < 0 ? 0 : doff[i]);
+        for (int i = 0; i < 16; ++i) col[i] = sT + (grp * Gk + tl) * kFastStride + (doff[i] < 0 ? 0 : doff[i]);
         const int n_it = (Gk - tl + 31) / 32;      // tokens tl, tl + 32, ... below Gk: at most 4 (Gk <= 128)
 #pragma unroll
         for (int k = 0; k < kMaxR / 32; ++k) {
@@ -622,7 +629,7 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
           float dev[4] = {0.f, 0.f, 0.f, 0.f};     // per run of four codes: the search below stays short
 #pragma unroll
           for (int i = 0; i < 16; ++i)
-            add_code<2>(hw, i, code_fast(col[i][k * 32 * kRowStride], rc[i], nz[i], dev[i >> 2]));
+            add_code<2>(hw, i, code_fast(col[i][k * 32 * kFastStride], rc[i], nz[i], dev[i >> 2]));
           // some quotient sits next to a rounding boundary (exact ties are common: about every other pass has one)
           if (__any(fmaxf(fmaxf(dev[0], dev[1]), fmaxf(dev[2], dev[3])) > 0.5f - kEps2)) {
 #pragma unroll
@@ -631,7 +638,7 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
 #pragma unroll
               for (int i = 4 * i4; i < 4 * i4 + 4; ++i) {     // find the codes concerned and correct them
                 const int d = doff[i] < 0 ? 0 : doff[i];
-                const __half x = col[i][k * 32 * kRowStride];
+                const __half x = col[i][k * 32 * kFastStride];
                 float dv = 0.f;
                 const float c = code_fast(x, rc[i], nz[i], dv);
                 if (__any(dv > 0.5f - kEps2))
@@ -658,7 +665,7 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
     for (int i = 0; i < 8; ++i) {
       const bool used = wd * 8 + i < n_4;                    // an unused entry gets (0, 0), i.e. code 0
       const int d = used ? sHiList[k16 + wd * 8 + i] : 0;
-      add_code<4>(hw, i, code_fast(sT[t * kRowStride + d], used ? sR[grp * kD + d] : 0.f,
+      add_code<4>(hw, i, code_fast(sT[t * kFastStride + d], used ? sR[grp * kD + d] : 0.f,
                                    used ? sNZ[grp * kD + d] : 0.f, dev[i >> 2]));
     }
     if (__any(fmaxf(dev[0], dev[1]) > 0.5f - kEps4)) {     // some quotient sits next to a rounding boundary
@@ -670,9 +677,9 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
           const bool used = wd * 8 + i < n_4;
           const int d = used ? sHiList[k16 + wd * 8 + i] : 0;
           float dv = 0.f;
-          const float c = code_fast(sT[t * kRowStride + d], used ? sR[grp * kD + d] : 0.f, used ? sNZ[grp * kD + d] : 0.f, dv);
+          const float c = code_fast(sT[t * kFastStride + d], used ? sR[grp * kD + d] : 0.f, used ? sNZ[grp * kD + d] : 0.f, dv);
           if (__any(dv > 0.5f - kEps4))
-            add_code<4>(hw, i, code_exact(sT[t * kRowStride + d], used ? sSZ[grp * kD + d] : 0u, 15.f) - c);
+            add_code<4>(hw, i, code_exact(sT[t * kFastStride + d], used ? sSZ[grp * kD + d] : 0u, 15.f) - c);
         }
       }
     }
@@ -682,7 +689,7 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
   // ---- fp16 tier: [token][k16] ------------------------------------------
   for (int i = tid >> 7; i < k16; i += 2) {
     const int t = tid & 127;
-    if (t < R) reinterpret_cast<__half*>(rec + off_k16)[t * k16 + i] = i < n_16 ? sT[t * kRowStride + sHiList[i]] : __ushort_as_half(0);
+    if (t < R) reinterpret_cast<__half*>(rec + off_k16)[t * k16 + i] = i < n_16 ? sT[t * kFastStride + sHiList[i]] : __ushort_as_half(0);
   }
   __syncthreads();
 
@@ -700,7 +707,8 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
       const int row = (tid >> 4) + 16 * i;
       if (row < R) {
         const uint4 v = as_f16x8(vreg[i], v_pending);
-        *reinterpret_cast<uint4*>(sT + row * kRowStride + c * 8) = v;
+        unsigned* dst = reinterpret_cast<unsigned*>(sT + row * kFastStride + c * 8);
+        dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
         const fh2 k0 = as_h2(v.x), k1 = as_h2(v.y), k2 = as_h2(v.z), k3 = as_h2(v.w);
         const fh2 lo2 = __builtin_elementwise_min(__builtin_elementwise_min(k0, k1), __builtin_elementwise_min(k2, k3));
         const fh2 hi2 = __builtin_elementwise_max(__builtin_elementwise_max(k0, k1), __builtin_elementwise_max(k2, k3));
@@ -745,8 +753,8 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
       // tokens of the word: two runs of 8 (tok0 .. tok0+7 and tok1 .. tok1+7), consecutive unless interleaved; each run
       // gets one base address, so that the elements sit at compile-time offsets from it
       const int tok0 = value_word_token(tg, 0, ilv), tok1 = tok0 + (ilv ? 32 : 8);
-      const __half* const col0 = sT + tok0 * kRowStride + d;
-      const __half* const col1 = sT + tok1 * kRowStride + d;
+      const __half* const col0 = sT + tok0 * kFastStride + d;
+      const __half* const col1 = sT + tok1 * kFastStride + d;
       float rc[16], nz[16];
       if (NVG == 1) {
 #pragma unroll
@@ -770,7 +778,7 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
       float dev[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int i = 0; i < 16; ++i)
-        add_code<2>(hw, i, code_fast((i < 8 ? col0 : col1)[(i & 7) * kRowStride], rc[i], nz[i], dev[i >> 2]));
+        add_code<2>(hw, i, code_fast((i < 8 ? col0 : col1)[(i & 7) * kFastStride], rc[i], nz[i], dev[i >> 2]));
       // some quotient sits next to a rounding boundary
       if (__any(fmaxf(fmaxf(dev[0], dev[1]), fmaxf(dev[2], dev[3])) > 0.5f - kEps2)) {
 #pragma unroll
@@ -780,8 +788,8 @@ flush_block_fast_kernel(CacheView cv, const __half* __restrict__ k_new, const __
           for (int i = 4 * i4; i < 4 * i4 + 4; ++i) {
             const int t = (i < 8 ? tok0 : tok1) + (i & 7);
             float dv = 0.f;
-            const float c = code_fast(sT[t * kRowStride + d], rc[i], nz[i], dv);
-            if (__any(dv > 0.5f - kEps2)) add_code<2>(hw, i, code_exact(sT[t * kRowStride + d], sSZ[t * NVG + vg], 3.f) - c);
+            const float c = code_fast(sT[t * kFastStride + d], rc[i], nz[i], dv);
+            if (__any(dv > 0.5f - kEps2)) add_code<2>(hw, i, code_exact(sT[t * kFastStride + d], sSZ[t * NVG + vg], 3.f) - c);
           }
         }
       }
